@@ -1,0 +1,421 @@
+/*
+ * RTN oracle -- TEST INFRASTRUCTURE, not the product.
+ *
+ * A plain, slow, obviously-correct CPU statement of what the reparameterized
+ * ternary conv/GEMM path computes (RTN, arxiv 1912.02057).  Only the tests,
+ * the smoke check and the benchmark's cpu_baseline leg may call it.  It shares
+ * no code with the HIP library and is never tuned for speed: plain loops,
+ * OpenMP on the outermost loop only.
+ *
+ * Notation (paper <-> here):  A^t = t_a, W^t = t_w (Section "Reparameterized
+ * Ternarization"); gamma = alpha_a, beta = beta_a (Eq.4); alpha = alpha_w;
+ * a weight offset beta_w is a generalisation (beta_w = 0 gives Eq.9);
+ * K = c*k*k is the length of one dot product (Section "Methodology").
+ *
+ * Every function below has an independent pin in tests/ (marked "not gpu").
+ */
+#include <stdint.h>
+#include <stddef.h>
+#include <stdlib.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+/* ------------------------------------------------------------------ O1 --
+ * Ternarizer.  Eq.1: t = sign(x) if |x| > 0.5 else 0, strict inequality.
+ * Eq.3 folds the affine k*x+b into two thresholds on x itself; both are the
+ * special cases  t = (x > hi) - (x < lo)  with (lo,hi) = (-D,+D) resp.
+ * ((-(0.5+b)/k), (0.5-b)/k).  Comparisons are on the stored fp32 value; no
+ * arithmetic touches x.  NaN compares false twice -> 0.
+ * x: [rows][cols]; lo/hi: one value (per_row = 0) or one per row.          */
+void orc_ternarize(const float *x, int64_t rows, int64_t cols,
+                   const float *lo, const float *hi, int per_row, int8_t *t)
+{
+#pragma omp parallel for
+    for (int64_t r = 0; r < rows; ++r) {
+        float l = per_row ? lo[r] : lo[0];
+        float h = per_row ? hi[r] : hi[0];
+        for (int64_t c = 0; c < cols; ++c) {
+            float v = x[r * cols + c];
+            t[r * cols + c] = (int8_t)((v > h) - (v < l));
+        }
+    }
+}
+
+/* ------------------------------------------------------------------ O2 --
+ * Table 1 encoding: 1st bit = "non-zero" (mask), 2nd bit = sign (1 <=> +1).
+ * 00 -> 0, 01 -> 0, 10 -> -1, 11 -> +1.  Canonical zero on encode is 00.
+ * The table's "2-bit network true value" column (01 -> 1, 10 -> 2) shows the
+ * 1st bit is the more significant one, so the 2-bit value is 2*mask + sign. */
+void orc_encode_2bit(const int8_t *t, int64_t n, uint8_t *v)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        unsigned m = (t[i] != 0), s = (t[i] == 1);
+        v[i] = (uint8_t)(2u * m + s);
+    }
+}
+
+void orc_decode_2bit(const uint8_t *v, int64_t n, int8_t *t)
+{
+    for (int64_t i = 0; i < n; ++i) {
+        unsigned m = (v[i] >> 1) & 1u, s = v[i] & 1u;
+        t[i] = (int8_t)(m ? (s ? 1 : -1) : 0);
+    }
+}
+
+/* Bit-plane split (W_1, W_2 / A_1, A_2 of the "Efficient Computation
+ * Pattern" section): plane 1 holds the first bits, plane 2 the second bits.
+ * Word w of a row, bit j (LSB = 0) <-> element k = 64*w + j; rows are padded
+ * with zeros up to `words` 64-bit words.  The paper leaves bit order open.  */
+void orc_encode_planes(const int8_t *t, int64_t rows, int64_t K, int64_t words,
+                       uint64_t *mask, uint64_t *sign)
+{
+    for (int64_t r = 0; r < rows; ++r) {
+        for (int64_t w = 0; w < words; ++w) {
+            uint64_t m = 0, s = 0;
+            for (int j = 0; j < 64; ++j) {
+                int64_t k = 64 * w + j;
+                if (k >= K) break;
+                int8_t v = t[r * K + k];
+                if (v != 0) m |= (uint64_t)1 << j;
+                if (v == 1) s |= (uint64_t)1 << j;
+            }
+            mask[r * words + w] = m;
+            sign[r * words + w] = s;
+        }
+    }
+}
+
+void orc_decode_planes(const uint64_t *mask, const uint64_t *sign, int64_t rows,
+                       int64_t K, int64_t words, int8_t *t)
+{
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t k = 0; k < K; ++k) {
+            uint64_t m = (mask[r * words + k / 64] >> (k % 64)) & 1u;
+            uint64_t s = (sign[r * words + k / 64] >> (k % 64)) & 1u;
+            t[r * K + k] = (int8_t)(m ? (s ? 1 : -1) : 0);
+        }
+}
+
+/* Layout only (no arithmetic): int8 codes, rows padded with code 0 to Kpad. */
+void orc_pad_rows_i8(const int8_t *t, int64_t rows, int64_t K, int64_t Kpad, int8_t *out)
+{
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t k = 0; k < Kpad; ++k)
+            out[r * Kpad + k] = (k < K) ? t[r * K + k] : 0;
+}
+
+/* Layout only: [N][C][H][W] codes -> channel-innermost [N][H][W][Cpad].     */
+void orc_nchw_to_nhwc_i8(const int8_t *t, int64_t N, int64_t C, int64_t H, int64_t W,
+                         int64_t Cpad, int8_t *out)
+{
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t h = 0; h < H; ++h)
+            for (int64_t w = 0; w < W; ++w)
+                for (int64_t c = 0; c < Cpad; ++c)
+                    out[((n * H + h) * W + w) * Cpad + c] =
+                        (c < C) ? t[((n * C + c) * H + h) * W + w] : 0;
+}
+
+/* ------------------------------------------------------------------ O4 --
+ * Side sums of Eq.9's constant: 1 (x) W^t = sum of a ternary vector.        */
+void orc_row_sums(const int8_t *t, int64_t rows, int64_t K, int32_t *s)
+{
+    for (int64_t r = 0; r < rows; ++r) {
+        int64_t a = 0;
+        for (int64_t k = 0; k < K; ++k) a += t[r * K + k];
+        s[r] = (int32_t)a;
+    }
+}
+
+/* Channel sum at every (n,h,w) of an [N][C][H][W] code tensor.  For a weight
+ * tensor [O][I][KH][KW] this is the per-tap sum over input channels.        */
+void orc_pixel_sums(const int8_t *t, int64_t N, int64_t C, int64_t H, int64_t W, int32_t *s)
+{
+    for (int64_t n = 0; n < N; ++n)
+        for (int64_t h = 0; h < H; ++h)
+            for (int64_t w = 0; w < W; ++w) {
+                int64_t a = 0;
+                for (int64_t c = 0; c < C; ++c) a += t[((n * C + c) * H + h) * W + w];
+                s[(n * H + h) * W + w] = (int32_t)a;
+            }
+}
+
+/* ------------------------------------------------------------------ O3 --
+ * D[m][n] = sum_k t_a[m][k] * t_w[n][k]: the ternary dot product W^t (x) A^t
+ * of Eq.8/Eq.9 by its definition.  int64 accumulate, |D| <= K checked, int32
+ * stored (the circuit of Fig.3(a) keeps 32-bit counters).  Returns 0, or -1
+ * if an accumulator left [-K, K].                                           */
+int orc_gemm_acc(const int8_t *ta, const int8_t *tw, int64_t M, int64_t N, int64_t K, int32_t *D)
+{
+    int bad = 0;
+#pragma omp parallel for
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            int64_t acc = 0;
+            for (int64_t k = 0; k < K; ++k)
+                acc += (int64_t)ta[m * K + k] * (int64_t)tw[n * K + k];
+            if (acc > K || acc < -K) bad = 1;
+            D[m * N + n] = (int32_t)acc;
+        }
+    return bad ? -1 : 0;
+}
+
+/* Second route to the same D, Eq.8 on the bit planes:
+ * c = W_1 AND A_1;  D = bC(c) - 2*bC((W_2 XOR A_2) AND c).                  */
+void orc_gemm_acc_popc(const uint64_t *ma, const uint64_t *sa, const uint64_t *mw,
+                       const uint64_t *sw, int64_t M, int64_t N, int64_t words, int32_t *D)
+{
+#pragma omp parallel for
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            int64_t nz = 0, df = 0;
+            for (int64_t w = 0; w < words; ++w) {
+                uint64_t c = ma[m * words + w] & mw[n * words + w];
+                nz += __builtin_popcountll(c);
+                df += __builtin_popcountll((sa[m * words + w] ^ sw[n * words + w]) & c);
+            }
+            D[m * N + n] = (int32_t)(nz - 2 * df);
+        }
+}
+
+/* ------------------------------------------------------------------ O5 --
+ * Four-term reparameterization (Eq.9 with a weight offset added), in double,
+ * rounded once to fp32:
+ *   y = aa*aw*D + aa*bw*Sa + ba*aw*Sw + Kv*ba*bw ;  then ReLU (phi of Eq.9)
+ *   if asked; then the BN affine that follows ReLU in RTN's layer order.
+ * stride_* = 0 broadcasts one scalar, 1 indexes per row (a) / per column (w).
+ * bw, bn_scale, bn_shift may be NULL (=> 0, 1, 0).                           */
+static double apply_tail(double y, int relu, const float *bs, const float *bh, int64_t n)
+{
+    if (relu && y < 0.0) y = 0.0;
+    if (bs) y = (double)bs[n] * y + (double)(bh ? bh[n] : 0.0f);
+    return y;
+}
+
+void orc_gemm_epilogue(const int32_t *D, int64_t M, int64_t N, int64_t K,
+                       const int32_t *Sa, const int32_t *Sw,
+                       const float *aa, const float *ba, int stride_a,
+                       const float *aw, const float *bw, int stride_w,
+                       int relu, const float *bn_scale, const float *bn_shift, float *y)
+{
+#pragma omp parallel for
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            double a_a = aa[m * stride_a], b_a = ba[m * stride_a];
+            double a_w = aw[n * stride_w], b_w = bw ? bw[n * stride_w] : 0.0;
+            double v = a_a * a_w * (double)D[m * N + n] + a_a * b_w * (double)Sa[m] +
+                       b_a * a_w * (double)Sw[n] + (double)K * b_a * b_w;
+            y[m * N + n] = (float)apply_tail(v, relu, bn_scale, bn_shift, n);
+        }
+}
+
+/* ------------------------------------------------------------------ O6 --
+ * Check of O3-O5, not part of them: the direct dot product of the
+ * reparameterized values, sum_k (aa*t_a+ba)*(aw*t_w+bw), in double.          */
+void orc_gemm_direct(const int8_t *ta, const int8_t *tw, int64_t M, int64_t N, int64_t K,
+                     const float *aa, const float *ba, int stride_a,
+                     const float *aw, const float *bw, int stride_w, double *y)
+{
+#pragma omp parallel for
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            double a_a = aa[m * stride_a], b_a = ba[m * stride_a];
+            double a_w = aw[n * stride_w], b_w = bw ? bw[n * stride_w] : 0.0;
+            double acc = 0.0;
+            for (int64_t k = 0; k < K; ++k)
+                acc += (a_a * ta[m * K + k] + b_a) * (a_w * tw[n * K + k] + b_w);
+            y[m * N + n] = acc;
+        }
+}
+
+/* --------------------------------------------------------------- conv ----
+ * Convolution as the dot product over a c*k*k patch (im2col view, footnote
+ * of Section "Methodology"); cross-correlation, zero padding:
+ *   ih = oh*stride - pad + kh,  iw = ow*stride - pad + kw,
+ *   OH = floor((H + 2*pad - KH)/stride) + 1.
+ * ta: [Nb][C][H][W], tw: [O][C][KH][KW], D: [Nb][O][OH][OW].
+ * A tap outside the image contributes nothing to D (code 0).               */
+typedef struct {
+    int64_t Nb, C, H, W, O, KH, KW, stride, pad, OH, OW;
+} orc_geom;
+
+static orc_geom make_geom(int64_t Nb, int64_t C, int64_t H, int64_t W, int64_t O,
+                          int64_t KH, int64_t KW, int64_t stride, int64_t pad)
+{
+    orc_geom g = {Nb, C, H, W, O, KH, KW, stride, pad,
+                  (H + 2 * pad - KH) / stride + 1, (W + 2 * pad - KW) / stride + 1};
+    return g;
+}
+
+void orc_conv_out_shape(int64_t H, int64_t W, int64_t KH, int64_t KW, int64_t stride,
+                        int64_t pad, int64_t *OH, int64_t *OW)
+{
+    orc_geom g = make_geom(1, 1, H, W, 1, KH, KW, stride, pad);
+    *OH = g.OH;
+    *OW = g.OW;
+}
+
+int orc_conv_acc(const int8_t *ta, const int8_t *tw, int64_t Nb, int64_t C, int64_t H,
+                 int64_t W, int64_t O, int64_t KH, int64_t KW, int64_t stride, int64_t pad,
+                 int32_t *D)
+{
+    orc_geom g = make_geom(Nb, C, H, W, O, KH, KW, stride, pad);
+    int64_t K = C * KH * KW;
+    int bad = 0;
+#pragma omp parallel for
+    for (int64_t nb = 0; nb < g.Nb; ++nb)
+        for (int64_t o = 0; o < g.O; ++o)
+            for (int64_t oh = 0; oh < g.OH; ++oh)
+                for (int64_t ow = 0; ow < g.OW; ++ow) {
+                    int64_t acc = 0;
+                    for (int64_t c = 0; c < g.C; ++c)
+                        for (int64_t kh = 0; kh < g.KH; ++kh)
+                            for (int64_t kw = 0; kw < g.KW; ++kw) {
+                                int64_t ih = oh * g.stride - g.pad + kh;
+                                int64_t iw = ow * g.stride - g.pad + kw;
+                                if (ih < 0 || ih >= g.H || iw < 0 || iw >= g.W) continue;
+                                acc += (int64_t)ta[((nb * g.C + c) * g.H + ih) * g.W + iw] *
+                                       (int64_t)tw[((o * g.C + c) * g.KH + kh) * g.KW + kw];
+                            }
+                    if (acc > K || acc < -K) bad = 1;
+                    D[((nb * g.O + o) * g.OH + oh) * g.OW + ow] = (int32_t)acc;
+                }
+    return bad ? -1 : 0;
+}
+
+/* Side sums for a padded conv.  pad_true_zero = 1: the padded border of the
+ * reparameterized activation is a true 0 (what a framework conv of
+ * gamma*t+beta does), so a padded tap contributes neither beta_a*w nor
+ * beta_a*beta_w: Sw and Kv count in-bounds taps only.  pad_true_zero = 0:
+ * the border holds code 0, i.e. the value beta_a; Sw is the whole filter
+ * sum and Kv = K at every pixel (Eq.9's "C is a constant" holds verbatim).
+ * Sa sums t_a over in-bounds taps in both modes (code 0 adds nothing).
+ * Sa: [Nb][OH][OW], Sw: [O][OH][OW], Kv: [OH][OW].                          */
+void orc_conv_sums(const int8_t *ta, const int8_t *tw, int64_t Nb, int64_t C, int64_t H,
+                   int64_t W, int64_t O, int64_t KH, int64_t KW, int64_t stride, int64_t pad,
+                   int pad_true_zero, int32_t *Sa, int32_t *Sw, int32_t *Kv)
+{
+    orc_geom g = make_geom(Nb, C, H, W, O, KH, KW, stride, pad);
+    for (int64_t oh = 0; oh < g.OH; ++oh)
+        for (int64_t ow = 0; ow < g.OW; ++ow) {
+            int64_t taps = 0;
+            for (int64_t kh = 0; kh < g.KH; ++kh)
+                for (int64_t kw = 0; kw < g.KW; ++kw) {
+                    int64_t ih = oh * g.stride - g.pad + kh, iw = ow * g.stride - g.pad + kw;
+                    int inb = !(ih < 0 || ih >= g.H || iw < 0 || iw >= g.W);
+                    if (inb || !pad_true_zero) ++taps;
+                }
+            Kv[oh * g.OW + ow] = (int32_t)(taps * g.C);
+            for (int64_t o = 0; o < g.O; ++o) {
+                int64_t s = 0;
+                for (int64_t c = 0; c < g.C; ++c)
+                    for (int64_t kh = 0; kh < g.KH; ++kh)
+                        for (int64_t kw = 0; kw < g.KW; ++kw) {
+                            int64_t ih = oh * g.stride - g.pad + kh;
+                            int64_t iw = ow * g.stride - g.pad + kw;
+                            int inb = !(ih < 0 || ih >= g.H || iw < 0 || iw >= g.W);
+                            if (inb || !pad_true_zero)
+                                s += tw[((o * g.C + c) * g.KH + kh) * g.KW + kw];
+                        }
+                Sw[(o * g.OH + oh) * g.OW + ow] = (int32_t)s;
+            }
+            for (int64_t nb = 0; nb < g.Nb; ++nb) {
+                int64_t s = 0;
+                for (int64_t c = 0; c < g.C; ++c)
+                    for (int64_t kh = 0; kh < g.KH; ++kh)
+                        for (int64_t kw = 0; kw < g.KW; ++kw) {
+                            int64_t ih = oh * g.stride - g.pad + kh;
+                            int64_t iw = ow * g.stride - g.pad + kw;
+                            if (ih < 0 || ih >= g.H || iw < 0 || iw >= g.W) continue;
+                            s += ta[((nb * g.C + c) * g.H + ih) * g.W + iw];
+                        }
+                Sa[(nb * g.OH + oh) * g.OW + ow] = (int32_t)s;
+            }
+        }
+}
+
+/* Conv form of O5.  alpha_a/beta_a are layer-wise scalars (Eq.4 and the note
+ * that the factors are designed layer-wise); alpha_w/beta_w are one scalar
+ * (stride_w = 0) or one per filter (stride_w = 1).  y: [Nb][O][OH][OW].      */
+void orc_conv_epilogue(const int32_t *D, const int32_t *Sa, const int32_t *Sw, const int32_t *Kv,
+                       int64_t Nb, int64_t O, int64_t OH, int64_t OW, float aa, float ba,
+                       const float *aw, const float *bw, int stride_w, int relu,
+                       const float *bn_scale, const float *bn_shift, float *y)
+{
+#pragma omp parallel for
+    for (int64_t nb = 0; nb < Nb; ++nb)
+        for (int64_t o = 0; o < O; ++o)
+            for (int64_t p = 0; p < OH * OW; ++p) {
+                double a_a = aa, b_a = ba;
+                double a_w = aw[o * stride_w], b_w = bw ? bw[o * stride_w] : 0.0;
+                int64_t i = (nb * O + o) * OH * OW + p;
+                double v = a_a * a_w * (double)D[i] + a_a * b_w * (double)Sa[nb * OH * OW + p] +
+                           b_a * a_w * (double)Sw[o * OH * OW + p] + (double)Kv[p] * b_a * b_w;
+                y[i] = (float)apply_tail(v, relu, bn_scale, bn_shift, o);
+            }
+}
+
+/* Conv form of O6: direct conv of the reparameterized values in double.
+ * pad_true_zero = 1 pads the value tensor (aa*t+ba) with 0.0;
+ * pad_true_zero = 0 pads the code tensor with 0, i.e. the value with ba.     */
+void orc_conv_direct(const int8_t *ta, const int8_t *tw, int64_t Nb, int64_t C, int64_t H,
+                     int64_t W, int64_t O, int64_t KH, int64_t KW, int64_t stride, int64_t pad,
+                     int pad_true_zero, float aa, float ba, const float *aw, const float *bw,
+                     int stride_w, double *y)
+{
+    orc_geom g = make_geom(Nb, C, H, W, O, KH, KW, stride, pad);
+#pragma omp parallel for
+    for (int64_t nb = 0; nb < g.Nb; ++nb)
+        for (int64_t o = 0; o < g.O; ++o)
+            for (int64_t oh = 0; oh < g.OH; ++oh)
+                for (int64_t ow = 0; ow < g.OW; ++ow) {
+                    double a_w = aw[o * stride_w], b_w = bw ? bw[o * stride_w] : 0.0;
+                    double acc = 0.0;
+                    for (int64_t c = 0; c < g.C; ++c)
+                        for (int64_t kh = 0; kh < g.KH; ++kh)
+                            for (int64_t kw = 0; kw < g.KW; ++kw) {
+                                int64_t ih = oh * g.stride - g.pad + kh;
+                                int64_t iw = ow * g.stride - g.pad + kw;
+                                double av;
+                                if (ih < 0 || ih >= g.H || iw < 0 || iw >= g.W)
+                                    av = pad_true_zero ? 0.0 : (double)ba;
+                                else
+                                    av = (double)aa * ta[((nb * g.C + c) * g.H + ih) * g.W + iw] +
+                                         (double)ba;
+                                acc += av * (a_w * tw[((o * g.C + c) * g.KH + kh) * g.KW + kw] + b_w);
+                            }
+                    y[((nb * g.O + o) * g.OH + oh) * g.OW + ow] = acc;
+                }
+}
+
+/* Rows-subset form of O3 for timing and sampled checks at sizes where the
+ * full triple loop would take minutes: D_sub[i][n] for m = rows[i].          */
+int orc_gemm_acc_rows(const int8_t *ta, const int8_t *tw, const int64_t *rows, int64_t R,
+                      int64_t N, int64_t K, int32_t *D)
+{
+    int bad = 0;
+#pragma omp parallel for
+    for (int64_t i = 0; i < R; ++i)
+        for (int64_t n = 0; n < N; ++n) {
+            int64_t m = rows[i], acc = 0;
+            for (int64_t k = 0; k < K; ++k)
+                acc += (int64_t)ta[m * K + k] * (int64_t)tw[n * K + k];
+            if (acc > K || acc < -K) bad = 1;
+            D[i * N + n] = (int32_t)acc;
+        }
+    return bad ? -1 : 0;
+}
+
+int orc_num_threads(void)
+{
+    int n = 1;
+#ifdef _OPENMP
+#pragma omp parallel
+    {
+#pragma omp master
+        n = omp_get_num_threads();
+    }
+#endif
+    return n;
+}

@@ -1,0 +1,296 @@
+"""ctypes wrapper around the C oracle (rtn_oracle.c) -- TEST INFRASTRUCTURE.
+
+Only tests/, __graft_entry__.smoke() and bench.py's cpu_baseline leg may import
+this.  It marshals numpy arrays to the C functions; all of the method's
+arithmetic is in the C file.  Nothing here touches the HIP library.
+"""
+import ctypes as C
+import os
+import subprocess
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "rtn_oracle.c")
+_LIB = os.path.join(_HERE, "librtn_oracle.so")
+_lib = None
+
+
+def build(force=False):
+    """Compile the oracle with gcc -O2 (OpenMP on outermost loops only)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        tmp = _LIB + ".tmp.%d" % os.getpid()
+        subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra",
+                               "-o", tmp, _SRC])
+        os.replace(tmp, _LIB)
+    return _LIB
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        _lib.orc_gemm_acc.restype = C.c_int
+        _lib.orc_gemm_acc_rows.restype = C.c_int
+        _lib.orc_conv_acc.restype = C.c_int
+        _lib.orc_num_threads.restype = C.c_int
+    return _lib
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _c(a, dt):
+    return None if a is None else np.ascontiguousarray(a, dtype=dt)
+
+
+_i64 = C.c_int64
+_f32 = C.c_float
+
+
+def num_threads():
+    return lib().orc_num_threads()
+
+
+def ternarize(x, lo, hi):
+    """O1.  x: float32 [..]; lo/hi scalars, or arrays with one entry per x.shape[0]."""
+    x = _c(x, np.float32)
+    lo = np.atleast_1d(np.asarray(lo, dtype=np.float32))
+    hi = np.atleast_1d(np.asarray(hi, dtype=np.float32))
+    per_row = int(lo.size > 1 or hi.size > 1)
+    rows = x.shape[0] if per_row else 1
+    if per_row:
+        assert lo.size == rows and hi.size == rows
+    cols = x.size // rows
+    t = np.empty(x.shape, dtype=np.int8)
+    lib().orc_ternarize(_p(x), _i64(rows), _i64(cols), _p(lo), _p(hi), C.c_int(per_row), _p(t))
+    return t
+
+
+def encode_2bit(t):
+    t = _c(t, np.int8)
+    v = np.empty(t.shape, dtype=np.uint8)
+    lib().orc_encode_2bit(_p(t), _i64(t.size), _p(v))
+    return v
+
+
+def decode_2bit(v):
+    v = _c(v, np.uint8)
+    t = np.empty(v.shape, dtype=np.int8)
+    lib().orc_decode_2bit(_p(v), _i64(v.size), _p(t))
+    return t
+
+
+def encode_planes(t, words=None):
+    """t: int8 [rows, K] -> (mask, sign) uint64 [rows, words]."""
+    t = _c(t, np.int8)
+    rows, K = t.shape
+    words = (K + 63) // 64 if words is None else words
+    mask = np.empty((rows, words), dtype=np.uint64)
+    sign = np.empty((rows, words), dtype=np.uint64)
+    lib().orc_encode_planes(_p(t), _i64(rows), _i64(K), _i64(words), _p(mask), _p(sign))
+    return mask, sign
+
+
+def decode_planes(mask, sign, K):
+    mask = _c(mask, np.uint64)
+    sign = _c(sign, np.uint64)
+    rows, words = mask.shape
+    t = np.empty((rows, K), dtype=np.int8)
+    lib().orc_decode_planes(_p(mask), _p(sign), _i64(rows), _i64(K), _i64(words), _p(t))
+    return t
+
+
+def pad_rows_i8(t, Kpad):
+    t = _c(t, np.int8)
+    rows, K = t.shape
+    out = np.empty((rows, Kpad), dtype=np.int8)
+    lib().orc_pad_rows_i8(_p(t), _i64(rows), _i64(K), _i64(Kpad), _p(out))
+    return out
+
+
+def nchw_to_nhwc_i8(t, Cpad):
+    t = _c(t, np.int8)
+    N, Cc, H, W = t.shape
+    out = np.empty((N, H, W, Cpad), dtype=np.int8)
+    lib().orc_nchw_to_nhwc_i8(_p(t), _i64(N), _i64(Cc), _i64(H), _i64(W), _i64(Cpad), _p(out))
+    return out
+
+
+def row_sums(t):
+    t = _c(t, np.int8)
+    rows, K = t.shape
+    s = np.empty(rows, dtype=np.int32)
+    lib().orc_row_sums(_p(t), _i64(rows), _i64(K), _p(s))
+    return s
+
+
+def pixel_sums(t):
+    t = _c(t, np.int8)
+    N, Cc, H, W = t.shape
+    s = np.empty((N, H, W), dtype=np.int32)
+    lib().orc_pixel_sums(_p(t), _i64(N), _i64(Cc), _i64(H), _i64(W), _p(s))
+    return s
+
+
+def gemm_acc(ta, tw):
+    """O3.  ta: int8 [M,K], tw: int8 [N,K] -> int32 D [M,N]."""
+    ta = _c(ta, np.int8)
+    tw = _c(tw, np.int8)
+    M, K = ta.shape
+    N, K2 = tw.shape
+    assert K == K2
+    D = np.empty((M, N), dtype=np.int32)
+    rc = lib().orc_gemm_acc(_p(ta), _p(tw), _i64(M), _i64(N), _i64(K), _p(D))
+    assert rc == 0, "accumulator left [-K, K]"
+    return D
+
+
+def gemm_acc_rows(ta, tw, rows):
+    ta = _c(ta, np.int8)
+    tw = _c(tw, np.int8)
+    rows = _c(rows, np.int64)
+    M, K = ta.shape
+    N = tw.shape[0]
+    assert rows.size == 0 or (rows.min() >= 0 and rows.max() < M)
+    D = np.empty((rows.size, N), dtype=np.int32)
+    rc = lib().orc_gemm_acc_rows(_p(ta), _p(tw), _p(rows), _i64(rows.size), _i64(N), _i64(K), _p(D))
+    assert rc == 0
+    return D
+
+
+def gemm_acc_popc(ma, sa, mw, sw):
+    ma, sa, mw, sw = (_c(a, np.uint64) for a in (ma, sa, mw, sw))
+    M, words = ma.shape
+    N = mw.shape[0]
+    D = np.empty((M, N), dtype=np.int32)
+    lib().orc_gemm_acc_popc(_p(ma), _p(sa), _p(mw), _p(sw), _i64(M), _i64(N), _i64(words), _p(D))
+    return D
+
+
+def _gran(a, n):
+    """scalar -> (array[1], stride 0); vector of n -> (array[n], stride 1)."""
+    a = np.atleast_1d(np.asarray(a, dtype=np.float32))
+    if a.size == 1:
+        return np.ascontiguousarray(a), 0
+    assert a.size == n
+    return np.ascontiguousarray(a), 1
+
+
+def gemm_epilogue(D, K, Sa, Sw, alpha_a, beta_a, alpha_w, beta_w=None, relu=False,
+                  bn_scale=None, bn_shift=None):
+    """O5.  D int32 [M,N]; Sa int32 [M]; Sw int32 [N] -> float32 y [M,N]."""
+    D = _c(D, np.int32)
+    M, N = D.shape
+    Sa = _c(Sa, np.int32)
+    Sw = _c(Sw, np.int32)
+    aa, sa_ = _gran(alpha_a, M)
+    ba, sb_ = _gran(beta_a, M)
+    assert sa_ == sb_
+    aw, sw_ = _gran(alpha_w, N)
+    bw = None
+    if beta_w is not None:
+        bw, s2 = _gran(beta_w, N)
+        assert s2 == sw_
+    bs = _c(bn_scale, np.float32)
+    bh = _c(bn_shift, np.float32)
+    y = np.empty((M, N), dtype=np.float32)
+    lib().orc_gemm_epilogue(_p(D), _i64(M), _i64(N), _i64(K), _p(Sa), _p(Sw), _p(aa), _p(ba),
+                            C.c_int(sa_), _p(aw), _p(bw), C.c_int(sw_), C.c_int(int(relu)),
+                            _p(bs), _p(bh), _p(y))
+    return y
+
+
+def gemm_direct(ta, tw, alpha_a, beta_a, alpha_w, beta_w=None):
+    """O6.  float64 [M,N]."""
+    ta = _c(ta, np.int8)
+    tw = _c(tw, np.int8)
+    M, K = ta.shape
+    N = tw.shape[0]
+    aa, sa_ = _gran(alpha_a, M)
+    ba, _ = _gran(beta_a, M)
+    aw, sw_ = _gran(alpha_w, N)
+    bw = None if beta_w is None else _gran(beta_w, N)[0]
+    y = np.empty((M, N), dtype=np.float64)
+    lib().orc_gemm_direct(_p(ta), _p(tw), _i64(M), _i64(N), _i64(K), _p(aa), _p(ba), C.c_int(sa_),
+                          _p(aw), _p(bw), C.c_int(sw_), _p(y))
+    return y
+
+
+def conv_out_shape(H, W, KH, KW, stride, pad):
+    oh, ow = _i64(), _i64()
+    lib().orc_conv_out_shape(_i64(H), _i64(W), _i64(KH), _i64(KW), _i64(stride), _i64(pad),
+                             C.byref(oh), C.byref(ow))
+    return oh.value, ow.value
+
+
+def _geom(ta, tw):
+    Nb, Cc, H, W = ta.shape
+    O, C2, KH, KW = tw.shape
+    assert Cc == C2
+    return Nb, Cc, H, W, O, KH, KW
+
+
+def conv_acc(ta, tw, stride, pad):
+    """O3 for conv.  ta int8 [Nb,C,H,W], tw int8 [O,C,KH,KW] -> int32 [Nb,O,OH,OW]."""
+    ta = _c(ta, np.int8)
+    tw = _c(tw, np.int8)
+    Nb, Cc, H, W, O, KH, KW = _geom(ta, tw)
+    OH, OW = conv_out_shape(H, W, KH, KW, stride, pad)
+    D = np.empty((Nb, O, OH, OW), dtype=np.int32)
+    rc = lib().orc_conv_acc(_p(ta), _p(tw), _i64(Nb), _i64(Cc), _i64(H), _i64(W), _i64(O),
+                            _i64(KH), _i64(KW), _i64(stride), _i64(pad), _p(D))
+    assert rc == 0
+    return D
+
+
+def conv_sums(ta, tw, stride, pad, pad_true_zero=True):
+    """O4 for conv -> Sa [Nb,OH,OW], Sw [O,OH,OW], Kv [OH,OW] (all int32)."""
+    ta = _c(ta, np.int8)
+    tw = _c(tw, np.int8)
+    Nb, Cc, H, W, O, KH, KW = _geom(ta, tw)
+    OH, OW = conv_out_shape(H, W, KH, KW, stride, pad)
+    Sa = np.empty((Nb, OH, OW), dtype=np.int32)
+    Sw = np.empty((O, OH, OW), dtype=np.int32)
+    Kv = np.empty((OH, OW), dtype=np.int32)
+    lib().orc_conv_sums(_p(ta), _p(tw), _i64(Nb), _i64(Cc), _i64(H), _i64(W), _i64(O), _i64(KH),
+                        _i64(KW), _i64(stride), _i64(pad), C.c_int(int(pad_true_zero)),
+                        _p(Sa), _p(Sw), _p(Kv))
+    return Sa, Sw, Kv
+
+
+def conv_epilogue(D, Sa, Sw, Kv, alpha_a, beta_a, alpha_w, beta_w=None, relu=False,
+                  bn_scale=None, bn_shift=None):
+    """O5 for conv.  alpha_a/beta_a scalars; alpha_w/beta_w scalar or per filter."""
+    D = _c(D, np.int32)
+    Nb, O, OH, OW = D.shape
+    Sa, Sw, Kv = _c(Sa, np.int32), _c(Sw, np.int32), _c(Kv, np.int32)
+    aw, sw_ = _gran(alpha_w, O)
+    bw = None
+    if beta_w is not None:
+        bw, s2 = _gran(beta_w, O)
+        assert s2 == sw_
+    bs = _c(bn_scale, np.float32)
+    bh = _c(bn_shift, np.float32)
+    y = np.empty((Nb, O, OH, OW), dtype=np.float32)
+    lib().orc_conv_epilogue(_p(D), _p(Sa), _p(Sw), _p(Kv), _i64(Nb), _i64(O), _i64(OH), _i64(OW),
+                            _f32(float(alpha_a)), _f32(float(beta_a)), _p(aw), _p(bw), C.c_int(sw_),
+                            C.c_int(int(relu)), _p(bs), _p(bh), _p(y))
+    return y
+
+
+def conv_direct(ta, tw, stride, pad, alpha_a, beta_a, alpha_w, beta_w=None, pad_true_zero=True):
+    """O6 for conv.  float64 [Nb,O,OH,OW]."""
+    ta = _c(ta, np.int8)
+    tw = _c(tw, np.int8)
+    Nb, Cc, H, W, O, KH, KW = _geom(ta, tw)
+    OH, OW = conv_out_shape(H, W, KH, KW, stride, pad)
+    aw, sw_ = _gran(alpha_w, O)
+    bw = None if beta_w is None else _gran(beta_w, O)[0]
+    y = np.empty((Nb, O, OH, OW), dtype=np.float64)
+    lib().orc_conv_direct(_p(ta), _p(tw), _i64(Nb), _i64(Cc), _i64(H), _i64(W), _i64(O), _i64(KH),
+                          _i64(KW), _i64(stride), _i64(pad), C.c_int(int(pad_true_zero)),
+                          _f32(float(alpha_a)), _f32(float(beta_a)), _p(aw), _p(bw), C.c_int(sw_),
+                          _p(y))
+    return y

@@ -1,0 +1,301 @@
+"""Pins for the CPU oracle (no GPU).  Each oracle function is checked against
+something other than itself: the paper's printed table, closed forms, brute
+force in pure Python, library routines (numpy integer matmul, torch conv2d on
+float codes -- exact, all partial sums are small integers), and the direct
+float dot product of the reparameterized values.
+"""
+import itertools
+import os
+
+import numpy as np
+import pytest
+import torch
+
+from oracle import rtn_oracle as orc
+
+GOLD = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _rand_t(rng, shape, p0=0.4):
+    return rng.choice(np.array([-1, 0, 1], dtype=np.int8), size=shape,
+                      p=[(1 - p0) / 2, p0, (1 - p0) / 2])
+
+
+# ------------------------------------------------------------------ O1 ----
+def test_ternarize_hand_listed_edges():
+    d = np.float32(0.5)
+    x = np.array([d, np.nextafter(d, np.float32(np.inf)), -d, np.nextafter(-d, np.float32(-np.inf)),
+                  0.0, -0.0, np.nan, np.inf, -np.inf, 0.49999997, -0.49999997, 3.0, -3.0],
+                 dtype=np.float32)
+    want = np.array([0, 1, 0, -1, 0, 0, 0, 1, -1, 0, 0, 1, -1], dtype=np.int8)
+    got = orc.ternarize(x[None, :], -d, d)[0]
+    assert (got == want).all()
+
+
+def test_ternarize_eq1_is_sign_where_abs_gt_half():
+    rng = np.random.default_rng(0)
+    x = rng.standard_normal((7, 1000)).astype(np.float32)
+    got = orc.ternarize(x, -0.5, 0.5)
+    want = np.where(np.abs(x) > 0.5, np.sign(x), 0).astype(np.int8)
+    assert (got == want).all()
+    assert set(np.unique(got)) == {-1, 0, 1}
+
+
+def test_ternarize_eq3_thresholds_equal_eq1_on_affine():
+    # Eq.3: Q(k*x+b) == [x > (0.5-b)/k] - [x < -(0.5+b)/k] for k > 0 (away from ties)
+    rng = np.random.default_rng(1)
+    x = rng.standard_normal((1, 20000)).astype(np.float64)
+    for k, b in [(1.3, 0.2), (0.4, -0.3), (2.0, 0.0)]:
+        hi, lo = (0.5 - b) / k, -(0.5 + b) / k
+        keep = (np.abs(x - hi) > 1e-4) & (np.abs(x - lo) > 1e-4)
+        xs = x[keep][None, :].astype(np.float32)
+        via_affine = orc.ternarize((k * xs.astype(np.float64) + b).astype(np.float32), -0.5, 0.5)
+        via_thr = orc.ternarize(xs, lo, hi)
+        assert (via_affine == via_thr).all()
+
+
+def test_ternarize_per_row_thresholds():
+    x = np.array([[0.3, -0.3, 0.6], [0.3, -0.3, 0.6]], dtype=np.float32)
+    got = orc.ternarize(x, np.array([-0.2, -0.5], np.float32), np.array([0.2, 0.5], np.float32))
+    assert got.tolist() == [[1, -1, 1], [0, 0, 1]]
+    # asymmetric thresholds (lo, hi) as in Eq.3
+    got = orc.ternarize(x[:1], np.float32(-0.4), np.float32(0.1))
+    assert got.tolist() == [[1, 0, 1]]
+
+
+# ------------------------------------------------------------------ O2 ----
+def _table1():
+    rows = []
+    for line in open(os.path.join(GOLD, "table1_encoding.txt")):
+        if line.startswith("#") or not line.strip():
+            continue
+        b1, b2, tv, qv = line.split()
+        rows.append((int(b1), int(b2), int(tv), int(qv)))
+    return rows
+
+
+def test_encoding_matches_paper_table1():
+    rows = _table1()
+    assert len(rows) == 4
+    for b1, b2, tv, qv in rows:
+        # decode: every printed row, including the second zero (01)
+        assert orc.decode_2bit(np.array([2 * b1 + b2], np.uint8))[0] == tv
+        # the 2-bit network value column fixes the bit significance
+        assert 2 * b1 + b2 == qv
+    # encode: canonical zero is 00; +-1 as printed
+    enc = orc.encode_2bit(np.array([0, -1, 1], np.int8)).tolist()
+    assert enc == [0b00, 0b10, 0b11]
+
+
+def test_bitplane_roundtrip_and_popcounts():
+    rng = np.random.default_rng(2)
+    for K in (1, 63, 64, 65, 200):
+        t = _rand_t(rng, (5, K))
+        mask, sign = orc.encode_planes(t)
+        assert mask.shape == (5, (K + 63) // 64)
+        assert (orc.decode_planes(mask, sign, K) == t).all()
+        for r in range(5):
+            nnz = sum(bin(int(w)).count("1") for w in mask[r])
+            npos = sum(bin(int(m) & int(s)).count("1") for m, s in zip(mask[r], sign[r]))
+            assert nnz == np.count_nonzero(t[r])
+            assert npos == np.count_nonzero(t[r] == 1)
+            # canonical zero: sign bit never set where mask is clear
+            assert all(int(s) & ~int(m) == 0 for m, s in zip(mask[r], sign[r]))
+
+
+def test_bitplane_bit_order():
+    t = np.zeros((1, 130), np.int8)
+    t[0, 0], t[0, 65], t[0, 129] = 1, -1, 1
+    mask, sign = orc.encode_planes(t)
+    assert [int(v) for v in mask[0]] == [1, 2, 2]
+    assert [int(v) for v in sign[0]] == [1, 0, 2]
+    # decoder accepts the non-canonical zero (mask 0, sign 1)
+    assert orc.decode_planes(np.array([[0]], np.uint64), np.array([[1]], np.uint64), 1)[0, 0] == 0
+
+
+def test_layout_helpers():
+    rng = np.random.default_rng(3)
+    t = _rand_t(rng, (3, 70))
+    p = orc.pad_rows_i8(t, 128)
+    assert (p[:, :70] == t).all() and (p[:, 70:] == 0).all()
+    t4 = _rand_t(rng, (2, 5, 3, 4))
+    q = orc.nchw_to_nhwc_i8(t4, 8)
+    assert (q[..., :5] == t4.transpose(0, 2, 3, 1)).all() and (q[..., 5:] == 0).all()
+
+
+# ------------------------------------------------------------------ O3 ----
+def test_dot_exhaustive_small_k_both_routes():
+    # every pair of ternary vectors for K <= 4 (3^K x 3^K), pure-Python sum as truth
+    for K in (1, 2, 3, 4):
+        vecs = np.array(list(itertools.product((-1, 0, 1), repeat=K)), dtype=np.int8)
+        truth = np.array([[sum(int(a) * int(b) for a, b in zip(u, v)) for v in vecs] for u in vecs])
+        D = orc.gemm_acc(vecs, vecs)
+        assert (D == truth).all()
+        ma, sa = orc.encode_planes(vecs)
+        assert (orc.gemm_acc_popc(ma, sa, ma, sa) == truth).all()
+
+
+def test_gemm_acc_vs_numpy_int_matmul_nonsquare():
+    rng = np.random.default_rng(4)
+    ta, tw = _rand_t(rng, (37, 131)), _rand_t(rng, (19, 131))
+    want = ta.astype(np.int64) @ tw.astype(np.int64).T
+    D = orc.gemm_acc(ta, tw)
+    assert D.shape == (37, 19) and (D == want).all()
+    ma, sa = orc.encode_planes(ta)
+    mw, sw = orc.encode_planes(tw)
+    assert (orc.gemm_acc_popc(ma, sa, mw, sw) == want).all()
+    rows = np.array([36, 0, 5], np.int64)
+    assert (orc.gemm_acc_rows(ta, tw, rows) == want[rows]).all()
+
+
+def test_gemm_acc_closed_forms():
+    rng = np.random.default_rng(5)
+    a = _rand_t(rng, (4, 300))
+    D = orc.gemm_acc(a, a)
+    assert (np.diag(D) == np.count_nonzero(a, axis=1)).all()          # a.a = nnz(a)
+    assert (np.diag(orc.gemm_acc(a, -a)) == -np.count_nonzero(a, axis=1)).all()
+    ones = np.ones((2, 300), np.int8)
+    assert (orc.gemm_acc(ones, ones) == 300).all()
+    assert (orc.gemm_acc(np.zeros((2, 300), np.int8), a) == 0).all()
+    assert (orc.gemm_acc(ones, a)[0] == a.sum(axis=1)).all()          # 1 (x) W^t = sum t_w
+
+
+def test_gemm_acc_statistics_at_p0_04():
+    # E[D] = 0, Var[D] = K * 0.6 * 0.6 for i.i.d. P(0) = 0.4
+    rng = np.random.default_rng(6)
+    K = 1024
+    D = orc.gemm_acc(_rand_t(rng, (64, K)), _rand_t(rng, (64, K))).astype(np.float64)
+    assert abs(D.mean()) < 4 * np.sqrt(K * 0.36 / D.size)
+    assert abs(D.var() / (K * 0.36) - 1) < 0.1
+
+
+def test_conv_acc_vs_torch_conv2d_exact():
+    rng = np.random.default_rng(7)
+    for (C, H, W, O, k, s, p) in [(5, 9, 7, 4, 3, 1, 1), (6, 10, 10, 3, 3, 2, 1), (4, 8, 8, 5, 1, 2, 0),
+                                  (3, 5, 6, 2, 1, 1, 0), (2, 2, 2, 2, 3, 1, 1)]:
+        ta, tw = _rand_t(rng, (2, C, H, W)), _rand_t(rng, (O, C, k, k))
+        want = torch.nn.functional.conv2d(torch.from_numpy(ta.astype(np.float64)),
+                                          torch.from_numpy(tw.astype(np.float64)),
+                                          stride=s, padding=p).numpy()
+        D = orc.conv_acc(ta, tw, s, p)
+        assert D.shape == want.shape
+        assert (D == want.astype(np.int64)).all()
+
+
+# ------------------------------------------------------------------ O4 ----
+def test_row_and_pixel_sums():
+    rng = np.random.default_rng(8)
+    t = _rand_t(rng, (6, 77))
+    assert (orc.row_sums(t) == t.astype(np.int64).sum(1)).all()
+    t4 = _rand_t(rng, (2, 5, 3, 4))
+    assert (orc.pixel_sums(t4) == t4.astype(np.int64).sum(1)).all()
+
+
+def test_conv_sums_border_classes_3x3_pad1():
+    ta = np.ones((1, 2, 5, 6), np.int8)
+    tw = np.ones((3, 2, 3, 3), np.int8)
+    Sa, Sw, Kv = orc.conv_sums(ta, tw, 1, 1, pad_true_zero=True)
+    # corner: 4 in-bounds taps, edge: 6, interior: 9 (times C = 2)
+    assert Kv[0, 0] == 8 and Kv[0, 2] == 12 and Kv[2, 0] == 12 and Kv[2, 2] == 18
+    assert Kv[4, 5] == 8
+    assert (Sa[0] == Kv).all() and (Sw == Kv[None]).all()
+    Sa2, Sw2, Kv2 = orc.conv_sums(ta, tw, 1, 1, pad_true_zero=False)
+    assert (Kv2 == 18).all() and (Sw2 == 18).all() and (Sa2 == Sa).all()
+
+
+def test_conv_sums_vs_torch():
+    rng = np.random.default_rng(9)
+    for (C, H, W, O, k, s, p) in [(5, 9, 7, 4, 3, 1, 1), (6, 10, 10, 3, 3, 2, 1), (4, 8, 8, 5, 1, 2, 0)]:
+        ta, tw = _rand_t(rng, (2, C, H, W)), _rand_t(rng, (O, C, k, k))
+        Sa, Sw, Kv = orc.conv_sums(ta, tw, s, p, pad_true_zero=True)
+        f = torch.nn.functional.conv2d
+        ones_w = torch.ones(1, C, k, k, dtype=torch.float64)
+        ones_a = torch.ones(1, C, H, W, dtype=torch.float64)
+        assert (Sa == f(torch.from_numpy(ta.astype(np.float64)), ones_w, stride=s, padding=p)
+                .numpy()[:, 0].astype(np.int64)).all()
+        assert (Sw == f(ones_a, torch.from_numpy(tw.astype(np.float64)), stride=s, padding=p)
+                .numpy()[0].astype(np.int64)).all()
+        assert (Kv == f(ones_a, ones_w, stride=s, padding=p).numpy()[0, 0].astype(np.int64)).all()
+
+
+# ------------------------------------------------------------------ O5 ----
+def _gemm_setup(seed, M=23, N=17, K=150):
+    rng = np.random.default_rng(seed)
+    ta, tw = _rand_t(rng, (M, K)), _rand_t(rng, (N, K))
+    aa = rng.uniform(0.5, 1.5, M).astype(np.float32)
+    ba = rng.uniform(-0.2, 0.2, M).astype(np.float32)
+    aw = rng.uniform(0.5, 1.5, N).astype(np.float32)
+    bw = rng.uniform(-0.2, 0.2, N).astype(np.float32)
+    return ta, tw, aa, ba, aw, bw
+
+
+def test_gemm_epilogue_equals_direct_float_product():
+    ta, tw, aa, ba, aw, bw = _gemm_setup(10)
+    K = ta.shape[1]
+    D, Sa, Sw = orc.gemm_acc(ta, tw), orc.row_sums(ta), orc.row_sums(tw)
+    y = orc.gemm_epilogue(D, K, Sa, Sw, aa, ba, aw, bw)
+    direct = orc.gemm_direct(ta, tw, aa, ba, aw, bw)
+    # independent numpy evaluation of the direct product as well
+    va = aa[:, None].astype(np.float64) * ta + ba[:, None].astype(np.float64)
+    vw = aw[:, None].astype(np.float64) * tw + bw[:, None].astype(np.float64)
+    assert np.allclose(direct, va @ vw.T, rtol=1e-12, atol=1e-12)
+    assert np.abs(y.astype(np.float64) - direct).max() <= 2e-7 * np.abs(direct).max() + 1e-6
+    # scalar granularity both sides
+    y0 = orc.gemm_epilogue(D, K, Sa, Sw, 1.25, -0.1, 0.75, 0.15)
+    d0 = orc.gemm_direct(ta, tw, 1.25, -0.1, 0.75, 0.15)
+    assert np.abs(y0 - d0).max() < 1e-5
+
+
+def test_gemm_epilogue_beta_w_zero_is_eq9():
+    ta, tw, aa, ba, aw, _ = _gemm_setup(11)
+    K = ta.shape[1]
+    D, Sa, Sw = orc.gemm_acc(ta, tw), orc.row_sums(ta), orc.row_sums(tw)
+    alpha, gamma, beta = np.float32(1.7), np.float32(0.9), np.float32(0.3)
+    y = orc.gemm_epilogue(D, K, Sa, Sw, gamma, beta, alpha, None, relu=True)
+    # Eq.9: z = relu(alpha*gamma*D + C), C = alpha*beta*(1 (x) W^t)
+    Cc = float(alpha) * float(beta) * Sw.astype(np.float64)
+    z9 = np.maximum(0.0, float(alpha) * float(gamma) * D + Cc[None, :])
+    assert np.allclose(y, z9, rtol=1e-6, atol=1e-6)
+    # Eq.10: z = alpha * max(0, gamma*D + T), T = beta*(1 (x) W^t)   (alpha > 0)
+    z10 = float(alpha) * np.maximum(0.0, float(gamma) * D + float(beta) * Sw[None, :].astype(np.float64))
+    assert np.allclose(z9, z10, rtol=1e-12, atol=1e-12)
+    # explicit beta_w = 0 equals beta_w = None
+    y2 = orc.gemm_epilogue(D, K, Sa, Sw, gamma, beta, alpha, 0.0, relu=True)
+    assert (y == y2).all()
+
+
+def test_gemm_epilogue_identity_params_return_D():
+    ta, tw, *_ = _gemm_setup(12)
+    D = orc.gemm_acc(ta, tw)
+    y = orc.gemm_epilogue(D, ta.shape[1], orc.row_sums(ta), orc.row_sums(tw), 1.0, 0.0, 1.0, 0.0)
+    assert (y == D.astype(np.float32)).all()
+
+
+def test_gemm_epilogue_relu_then_bn_order():
+    D = np.array([[-4, 3]], np.int32)
+    y = orc.gemm_epilogue(D, 8, np.zeros(1, np.int32), np.zeros(2, np.int32), 1.0, 0.0, 1.0, 0.0,
+                          relu=True, bn_scale=np.array([2.0, 2.0], np.float32),
+                          bn_shift=np.array([-1.0, 0.5], np.float32))
+    assert y.tolist() == [[-1.0, 6.5]]      # bn(relu(-4)) = 2*0-1 ; bn(relu(3)) = 6.5
+
+
+@pytest.mark.parametrize("true_zero", [True, False])
+def test_conv_epilogue_equals_direct_float_conv(true_zero):
+    rng = np.random.default_rng(13)
+    for (C, H, W, O, k, s, p) in [(5, 9, 7, 4, 3, 1, 1), (6, 10, 10, 3, 3, 2, 1), (4, 8, 8, 5, 1, 2, 0)]:
+        ta, tw = _rand_t(rng, (2, C, H, W)), _rand_t(rng, (O, C, k, k))
+        aw = rng.uniform(0.5, 1.5, O).astype(np.float32)
+        bw = rng.uniform(-0.2, 0.2, O).astype(np.float32)
+        aa, ba = np.float32(1.2), np.float32(-0.15)
+        D = orc.conv_acc(ta, tw, s, p)
+        Sa, Sw, Kv = orc.conv_sums(ta, tw, s, p, true_zero)
+        y = orc.conv_epilogue(D, Sa, Sw, Kv, aa, ba, aw, bw)
+        direct = orc.conv_direct(ta, tw, s, p, aa, ba, aw, bw, true_zero)
+        assert np.abs(y - direct).max() < 1e-5
+        if true_zero:
+            # library route: framework conv (zero padding) of the reparameterized values
+            va = torch.from_numpy(float(aa) * ta.astype(np.float64) + float(ba))
+            vw = torch.from_numpy(aw.astype(np.float64)[:, None, None, None] * tw +
+                                  bw.astype(np.float64)[:, None, None, None])
+            lib = torch.nn.functional.conv2d(va, vw, stride=s, padding=p).numpy()
+            assert np.allclose(direct, lib, rtol=1e-12, atol=1e-12)
