@@ -1,0 +1,255 @@
+"""Benchmark of the RTN ternary conv/GEMM hot path on one MI355X.
+
+A step = one pass of the whole hot path over one batch of synthetic input:
+for each of the 19 ternary conv layers of ResNet-18 at batch 256 (weights
+pre-packed offline, S0), ternarize+pack the fp32 NCHW input (S1), run the
+implicit-GEMM ternary convolution on the int8 matrix cores (S2+S3) with the
+fused four-term reparameterization + ReLU + BN epilogue (S4) writing fp32 NCHW.
+Inputs are resident in HBM before the timed region.
+
+Prints ONE JSON line (see README for the fields).
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+INT8_PEAK_TOPS = 5000.0   # MI355X dense int8 MFMA, TOP/s (2 ops per MAC)
+HBM_PEAK_GBS = 8000.0
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--batch", type=int, default=256)
+    ap.add_argument("--workload", default="resnet18_ternary_convs",
+                    choices=["resnet18_ternary_convs", "gemm4096"])
+    ap.add_argument("--tile", type=int, default=-1, help="force an MFMA tile configuration (tuning)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cpu-images", type=int, default=8,
+                    help="images per layer the oracle is timed on (cpu_baseline sample)")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU only (no collectives, no sharding); "
+              "re-run with --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import numpy as np
+    import torch
+    from paper_1912_02057_amd import binding as B
+    from paper_1912_02057_amd import workloads as wl
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    B.lib()  # raises if the HIP library is missing: there is no fallback
+    if args.tile >= 0:
+        B.set_tile_config(args.tile)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+
+    def to_dev(a):
+        return torch.from_numpy(np.ascontiguousarray(a)).to(dev)
+
+    def garg(v):
+        v = np.asarray(v, dtype=np.float32)
+        return float(v) if v.ndim == 0 else to_dev(v)
+
+    ev = torch.cuda.Event
+    if args.workload == "resnet18_ternary_convs":
+        shapes = wl.resnet18_ternary_layers()
+        layers = []
+        for i, sh in enumerate(shapes):
+            case = wl.conv_case(sh, batch=args.batch, seed=100 + i, per_channel=True, bn=True)
+            x = to_dev(case["x"])
+            w = to_dev(case["w"])
+            dw = np.asarray(case["delta_w"])
+            cw, pw = B.ternarize_pack(w, garg(-dw), garg(dw))            # S0, offline
+            Cp = B.padded_k(sh.C)
+            ca = torch.empty((args.batch, sh.H, sh.H, Cp), dtype=torch.int8, device=dev)
+            pa = torch.empty((args.batch, sh.H, sh.H), dtype=torch.int32, device=dev)
+            y = torch.empty((args.batch, sh.O, sh.OH, sh.OH), dtype=torch.float32, device=dev)
+            ws = torch.empty(B.conv2d_workspace_bytes(sh.O, sh.k, sh.k), dtype=torch.uint8, device=dev)
+            ep = B.Epilogue(garg(case["alpha_a"]), garg(case["beta_a"]), garg(case["alpha_w"]),
+                            garg(case["beta_w"]), pa, pw, relu=True,
+                            bn_scale=to_dev(case["bn_scale"]), bn_shift=to_dev(case["bn_shift"]))
+            layers.append(dict(sh=sh, x=x, cw=cw, pw=pw, ca=ca, pa=pa, y=y, ws=ws, ep=ep,
+                               da=float(case["delta_a"]), case=case if i < 0 else None))
+            del case
+        L = B.lib()
+        import ctypes as C
+
+        def pack(l):
+            sh = l["sh"]
+            lo, hi = C.c_float(-l["da"]), C.c_float(l["da"])
+            rc = L.rtn_ternarize_pack(l["x"].data_ptr(), B.RTN_NCHW, args.batch, sh.C, sh.H, sh.H,
+                                      C.addressof(lo), C.addressof(hi), B.RTN_SCALAR, B.RTN_CODE_I8,
+                                      l["ca"].data_ptr(), l["pa"].data_ptr(), stream)
+            assert rc == 0, rc
+
+        def conv(l):
+            sh = l["sh"]
+            B.ternary_conv2d(l["ca"], l["cw"], args.batch, sh.C, sh.H, sh.H, sh.O, sh.k, sh.k, sh.stride,
+                             sh.pad, B.RTN_PAD_TRUE_ZERO, ep=l["ep"], y_out=l["y"], workspace=l["ws"])
+
+        stream = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+        def step(timers=None):
+            for i, l in enumerate(layers):
+                if timers is not None:
+                    timers[i][0].record()
+                pack(l)
+                if timers is not None:
+                    timers[i][1].record()
+                conv(l)
+                if timers is not None:
+                    timers[i][2].record()
+
+        macs_step = sum(l["sh"].macs(args.batch) for l in layers)
+        workload = "ResNet-18 ternary conv stack (19 layers), batch %d, fp32 NCHW in/out" % args.batch
+        nlaunch = len(layers)
+    else:
+        case = wl.gemm_case(4096, 4096, 4096, 0.4, seed=1)
+        xa, xw = to_dev(case["xa"]), to_dev(case["xw"])
+        cw, sw = B.ternarize_pack(xw, -0.5, 0.5)                             # S0, offline
+        ca = torch.empty((4096, 4096), dtype=torch.int8, device=dev)
+        sa = torch.empty(4096, dtype=torch.int32, device=dev)
+        y = torch.empty((4096, 4096), dtype=torch.float32, device=dev)
+        ep = B.Epilogue(garg(case["alpha_a"]), garg(case["beta_a"]), garg(case["alpha_w"]),
+                        garg(case["beta_w"]), sa, sw)
+        import ctypes as C
+        L = B.lib()
+        stream = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+        lo, hi = C.c_float(-0.5), C.c_float(0.5)
+
+        def step(timers=None):
+            if timers is not None:
+                timers[0][0].record()
+            rc = L.rtn_ternarize_pack(xa.data_ptr(), B.RTN_ROWS_K_CONTIG, 4096, 4096, 1, 1, C.addressof(lo),
+                                      C.addressof(hi), B.RTN_SCALAR, B.RTN_CODE_I8, ca.data_ptr(),
+                                      sa.data_ptr(), stream)
+            assert rc == 0
+            if timers is not None:
+                timers[0][1].record()
+            B.ternary_gemm(ca, cw, 4096, 4096, 4096, ep=ep, y_out=y)
+            if timers is not None:
+                timers[0][2].record()
+
+        macs_step = 4096 ** 3
+        workload = "ternary GEMM M=N=K=4096, P(0)=0.4, fp32 in/out"
+        nlaunch = 1
+        layers = [dict(sh=None)]
+
+    # ---- timed region: exactly K steps, bracketed by synchronize ------------
+    for _ in range(args.warmup):
+        step()
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        step()
+    torch.cuda.synchronize()
+    t1 = time.perf_counter()
+    ms_per_step = (t1 - t0) * 1e3 / args.steps
+
+    # ---- per-kernel durations with HIP events on the launch stream ---------
+    reps = max(3, min(args.steps, 10))
+    pack_ms = np.zeros(nlaunch)
+    conv_ms = np.zeros(nlaunch)
+    for _ in range(reps):
+        timers = [[ev(enable_timing=True) for _ in range(3)] for _ in range(nlaunch)]
+        step(timers)
+        torch.cuda.synchronize()
+        for i in range(nlaunch):
+            pack_ms[i] += timers[i][0].elapsed_time(timers[i][1])
+            conv_ms[i] += timers[i][1].elapsed_time(timers[i][2])
+    pack_ms /= reps
+    conv_ms /= reps
+
+    per_layer = []
+    if args.workload == "resnet18_ternary_convs":
+        tot_bytes_conv = 0
+        for i, l in enumerate(layers):
+            sh = l["sh"]
+            macs = sh.macs(args.batch)
+            Cp = B.padded_k(sh.C)
+            in_b = args.batch * sh.H * sh.H * Cp + args.batch * sh.H * sh.H * 4     # codes + pixel sums
+            w_b = sh.O * sh.k * sh.k * Cp
+            out_b = args.batch * sh.O * sh.OH * sh.OH * 4
+            conv_bytes = in_b + w_b + out_b
+            pack_bytes = args.batch * sh.C * sh.H * sh.H * 4 + args.batch * sh.H * sh.H * (Cp + 4)
+            tot_bytes_conv += conv_bytes
+            per_layer.append(dict(
+                layer=sh.name, M=args.batch * sh.OH * sh.OH, N=sh.O, K=sh.K,
+                conv_us=round(conv_ms[i] * 1e3, 1), pack_us=round(pack_ms[i] * 1e3, 1),
+                conv_tops=round(2 * macs / (conv_ms[i] * 1e-3) / 1e12, 1),
+                conv_pct_int8_peak=round(100 * 2 * macs / (conv_ms[i] * 1e-3) / 1e12 / INT8_PEAK_TOPS, 1),
+                conv_gbs=round(conv_bytes / (conv_ms[i] * 1e-3) / 1e9, 0),
+                conv_pct_hbm=round(100 * conv_bytes / (conv_ms[i] * 1e-3) / 1e9 / HBM_PEAK_GBS, 1),
+                pack_gbs=round(pack_bytes / (pack_ms[i] * 1e-3) / 1e9, 0),
+                pack_pct_hbm=round(100 * pack_bytes / (pack_ms[i] * 1e-3) / 1e9 / HBM_PEAK_GBS, 1)))
+    conv_total_s = float(conv_ms.sum()) * 1e-3
+    achieved_tops = 2 * macs_step / conv_total_s / 1e12
+    roofline = dict(bound="mfma", kernel="k_tmm (int8 MFMA implicit-GEMM conv + fused epilogue)"
+                    if args.workload == "resnet18_ternary_convs" else "k_tmm (int8 MFMA GEMM + fused epilogue)",
+                    achieved=round(achieved_tops, 1), peak=INT8_PEAK_TOPS, unit="TOP/s",
+                    frac=round(achieved_tops / INT8_PEAK_TOPS, 4), traffic=None,
+                    launches_per_step=nlaunch, avg_launch_us=round(conv_total_s / nlaunch * 1e6, 1),
+                    ops_per_launch=2 * macs_step / nlaunch)
+
+    # ---- CPU baseline: the oracle, as it stands, on a bounded sample --------
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import rtn_oracle as orc
+        n_img = args.cpu_images
+        t_cpu, macs_cpu = 0.0, 0
+        if args.workload == "resnet18_ternary_convs":
+            for i, sh in enumerate(wl.resnet18_ternary_layers()):
+                case = wl.conv_case(sh, batch=n_img, seed=100 + i, per_channel=True, bn=True)
+                c0 = time.perf_counter()
+                ta = orc.ternarize(case["x"], -case["delta_a"], case["delta_a"])
+                tw = orc.ternarize(case["w"], -case["delta_w"], case["delta_w"])
+                D = orc.conv_acc(ta, tw, sh.stride, sh.pad)
+                Sa, Sw, Kv = orc.conv_sums(ta, tw, sh.stride, sh.pad, True)
+                orc.conv_epilogue(D, Sa, Sw, Kv, case["alpha_a"], case["beta_a"], case["alpha_w"],
+                                  case["beta_w"], relu=True, bn_scale=case["bn_scale"], bn_shift=case["bn_shift"])
+                t_cpu += time.perf_counter() - c0
+                macs_cpu += sh.macs(n_img)
+            sample = "all 19 layers, %d images each (of %d)" % (n_img, args.batch)
+        else:
+            rows = np.arange(0, 4096, 4096 // 64, dtype=np.int64)
+            c0 = time.perf_counter()
+            ta = orc.ternarize(case["xa"], -0.5, 0.5)
+            tw = orc.ternarize(case["xw"], -0.5, 0.5)
+            D = orc.gemm_acc_rows(ta, tw, rows)
+            orc.gemm_epilogue(D, 4096, orc.row_sums(ta)[rows], orc.row_sums(tw), case["alpha_a"][rows],
+                              case["beta_a"][rows], case["alpha_w"], case["beta_w"])
+            t_cpu = time.perf_counter() - c0
+            macs_cpu = rows.size * 4096 * 4096
+            sample = "64 of 4096 output rows, all columns"
+        cpu = dict(value=round(macs_cpu / t_cpu / 1e12, 6), unit="TMAC/s", cores=orc.num_threads(),
+                   kind="oracle", sample=sample, seconds=round(t_cpu, 2))
+
+    value = macs_step / (ms_per_step * 1e-3) / 1e12
+    out = {
+        "metric": "effective ternary MAC/s (dense MAC count, S1+S2+S3+S4 per layer), ResNet-18 ternary layers"
+        if args.workload == "resnet18_ternary_convs" else "effective ternary MAC/s, ternary GEMM",
+        "value": round(value, 3), "unit": "TMAC/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
+        "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
+        "vs_baseline": None, "dtype": "i8", "data": "synthetic",
+        "config": {"workload": workload, "batch": args.batch, "tile": args.tile},
+        "tops": round(2 * value, 1), "pct_int8_mfma_peak": round(100 * 2 * value / INT8_PEAK_TOPS, 2),
+        "contraction_only": {"tmacs": round(macs_step / conv_total_s / 1e12, 3),
+                             "pct_int8_mfma_peak": round(100 * achieved_tops / INT8_PEAK_TOPS, 2),
+                             "ms": round(conv_total_s * 1e3, 4)},
+        "pack_only_ms": round(float(pack_ms.sum()), 4),
+        "roofline": roofline, "cpu_baseline": cpu, "layers": per_layer,
+    }
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

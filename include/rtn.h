@@ -1,0 +1,191 @@
+/*
+ * librtn -- the inference hot path of RTN (Reparameterized Ternary Network,
+ * arxiv 1912.02057) for AMD MI355X (gfx950), behind a plain C ABI.
+ *
+ *   fp32 tensor --ternarize+pack--> ternary codes (+ side sums)
+ *   codes x codes --ternary contraction--> int32 accumulators D
+ *   D, side sums, scale/offset --four-term reparameterization--> fp32 output
+ *
+ * Notation.  t_a, t_w in {-1,0,+1} are the paper's fixed ternary activation
+ * A^t and weight W^t; the reparameterized values are alpha_a*t_a + beta_a
+ * (Eq.4: gamma, beta) and alpha_w*t_w + beta_w (the paper has alpha only; a
+ * NULL beta_w means 0 and gives Eq.9 verbatim).  K = c*k*k is the length of
+ * one dot product (Section "Methodology").
+ *
+ * Conventions for every entry point
+ *   - All tensor pointers are DEVICE pointers owned by the caller.  The
+ *     library never allocates, frees or keeps them.  Scratch memory, where an
+ *     entry point needs it, is a caller buffer sized by the matching
+ *     *_workspace_bytes() query.
+ *   - Parameters with a granularity switch (thresholds, alpha, beta): with
+ *     RTN_SCALAR the pointer is a HOST pointer to one float (read during the
+ *     call); with RTN_VECTOR it is a DEVICE pointer to one float per row /
+ *     column / channel as stated.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *     Work is enqueued asynchronously on it; nothing synchronizes.
+ *   - Return value: RTN_OK or a negative rtn_status.  All argument checks run
+ *     before anything is launched, so a rejected call has no side effects and
+ *     needs no GPU.  RTN_ERR_HIP means a launch failed; rtn_last_hip_error()
+ *     then returns the hipError_t as an int.
+ *   - Code tensors must be 16-byte aligned; fp32/int32 tensors 4-byte aligned.
+ *   - Sizes: every dimension and the products noted per function must be
+ *     below 2^31; K must be at most 2^24 so that D is exact in int32/fp32.
+ */
+#ifndef RTN_H
+#define RTN_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    RTN_OK = 0,
+    RTN_ERR_NULL = -1,        /* a required pointer is NULL */
+    RTN_ERR_SHAPE = -2,       /* non-positive or too large dimension, lo > hi ... */
+    RTN_ERR_ALIGN = -3,       /* pointer alignment */
+    RTN_ERR_UNSUPPORTED = -4, /* format/path/granularity/kernel size outside the list */
+    RTN_ERR_WORKSPACE = -5,   /* workspace NULL or too small */
+    RTN_ERR_HIP = -6          /* kernel launch failed */
+} rtn_status;
+
+/* Storage of ternary codes.
+ * RTN_CODE_I8: one signed byte per element holding t itself.
+ * RTN_CODE_BITPLANE: the 2-bit encoding of Table 1 split into its two bit
+ *   planes (W_1/A_1 = "non-zero" bits, W_2/A_2 = sign bits, 1 <=> +1; Section
+ *   "Efficient Computation Pattern").  Zero is always written as 00.  A plane
+ *   is uint64 words; bit j (LSB = 0) of word w of a row is element 64*w + j.
+ *   The buffer holds the whole mask plane [rows][Kpad/64] followed by the
+ *   whole sign plane [rows][Kpad/64].
+ * In both formats a row holds Kpad = rtn_padded_k(K) elements (K rounded up
+ * to a multiple of 64); the padding is code 0.                              */
+typedef enum { RTN_CODE_I8 = 0, RTN_CODE_BITPLANE = 1 } rtn_code_format;
+typedef enum { RTN_SCALAR = 0, RTN_VECTOR = 1 } rtn_gran;
+typedef enum { RTN_ROWS_K_CONTIG = 0, RTN_NCHW = 1 } rtn_layout;
+
+/* What the padded border of a convolution holds (the paper does not discuss
+ * padding).  RTN_PAD_TRUE_ZERO: the reparameterized activation alpha_a*t+beta_a
+ * is padded with the value 0, as a framework convolution of it would be; a
+ * padded tap then contributes nothing, so the sum of t_w and the count K of
+ * Eq.9's constant run over in-bounds taps only and differ per border pixel.
+ * RTN_PAD_CODE_ZERO: the code tensor is padded with code 0, i.e. the value
+ * beta_a; Eq.9's C is then one constant per filter.                          */
+typedef enum { RTN_PAD_TRUE_ZERO = 0, RTN_PAD_CODE_ZERO = 1 } rtn_pad_mode;
+
+/* Contraction strategy.  MFMA_I8: int8 matrix cores on RTN_CODE_I8 codes.
+ * POPC: Eq.8 (AND / XOR / popcount) on RTN_CODE_BITPLANE codes.
+ * AUTO picks the one that matches the code format.                           */
+typedef enum { RTN_PATH_AUTO = 0, RTN_PATH_MFMA_I8 = 1, RTN_PATH_POPC = 2 } rtn_path;
+
+/* Four-term reparameterization applied to an accumulator D (Eq.9 with a weight
+ * offset added; phi = ReLU; the BN affine follows ReLU in RTN's layer order):
+ *   y = alpha_a*alpha_w*D + alpha_a*beta_w*Sa + beta_a*alpha_w*Sw + Kv*beta_a*beta_w
+ *   if relu:      y = max(y, 0)
+ *   if bn_scale:  y = bn_scale[n]*y + bn_shift[n]
+ * evaluated in fp64 and rounded once to fp32.
+ * GEMM:  gran_a SCALAR or VECTOR over the M rows; gran_w SCALAR or VECTOR over
+ *        the N columns; sum_ta[M] = row sums of t_a, sum_tw[N] = row sums of
+ *        t_w; Kv = K.
+ * conv:  gran_a must be SCALAR (the paper's factors are layer-wise; a factor
+ *        per input channel cannot leave the integer sum); gran_w SCALAR or
+ *        VECTOR over the O filters; sum_ta[Nb][H][W] = channel sums of the
+ *        input codes at each input pixel; sum_tw[O][KH][KW] = channel sums of
+ *        the weight codes at each tap (both as written by rtn_ternarize_pack
+ *        with RTN_NCHW).  The library forms Sa, Sw and Kv per output pixel
+ *        from them according to the pad mode.
+ * beta_w, bn_scale, bn_shift may be NULL (0, 1, 0); bn_* are DEVICE pointers
+ * with one entry per output column / channel.                                */
+typedef struct {
+    const float *alpha_a, *beta_a;
+    rtn_gran gran_a;
+    const float *alpha_w, *beta_w;
+    rtn_gran gran_w;
+    const int32_t *sum_ta, *sum_tw;
+    int relu;
+    const float *bn_scale, *bn_shift;
+} rtn_epilogue;
+
+const char *rtn_status_string(int status);
+int rtn_last_hip_error(void);
+
+/* Tuning and testing aid for the matrix-core kernels.  The output tile a
+ * 256-thread block owns is BP x BQ (BP along M for the GEMM and along O for the
+ * conv; BQ along N resp. along output pixels).  Index: 0 = 64x64, 1 = 128x128,
+ * 2 = 256x256, 3 = 64x256, 4 = 128x256, 5 = 256x128; -1 (default) lets the
+ * library choose from the problem shape.  Every configuration computes the same
+ * result.  The setting is process-wide and not thread-safe.
+ * Returns RTN_ERR_UNSUPPORTED for an index outside -1 .. rtn_num_tile_configs()-1. */
+int rtn_num_tile_configs(void);
+int rtn_set_tile_config(int index);
+
+/* K rounded up to the row length of a code tensor (a multiple of 64). */
+int64_t rtn_padded_k(int64_t K);
+/* Bytes of a code tensor of `rows` rows of K elements in format `fmt`
+ * (0 on invalid arguments). */
+size_t rtn_codes_bytes(rtn_code_format fmt, int64_t rows, int64_t K);
+
+/* Ternarize + pack (Eq.1 / Eq.3, Table 1).
+ *   t = (x > hi) - (x < lo), compared on the stored fp32 value with strict
+ *   inequalities (x == threshold gives 0, NaN gives 0).  Eq.1 is lo = -Delta,
+ *   hi = +Delta; Eq.3's BN-folded form is lo = -(0.5+b)/k, hi = (0.5-b)/k,
+ *   computed by the caller.  lo <= hi is required for RTN_SCALAR thresholds.
+ * layout RTN_ROWS_K_CONTIG: x is [d0 = rows][d1 = K] row-major (d2 = d3 = 1).
+ *   codes: [rows][Kpad]; sum_t[rows] = sum of t over the row.
+ *   RTN_VECTOR thresholds: one (lo, hi) per row.
+ * layout RTN_NCHW: x is [d0 = N][d1 = C][d2 = H][d3 = W] (activations), or
+ *   [O][I][KH][KW] (weights).  codes are written channel-innermost,
+ *   [N][H][W][Cpad]; sum_t[N][H][W] = sum of t over the channels of a pixel
+ *   (for weights: per filter and tap).  RTN_VECTOR thresholds: one (lo, hi)
+ *   per d0 index (per filter).
+ * sum_t may be NULL.  d0*d2*d3 and d0*d1*d2*d3 must be below 2^31 resp. 2^40. */
+int rtn_ternarize_pack(const float *x, rtn_layout layout, int64_t d0, int64_t d1, int64_t d2,
+                       int64_t d3, const float *thr_lo, const float *thr_hi, rtn_gran thr_gran,
+                       rtn_code_format fmt, void *codes, int32_t *sum_t, void *stream);
+
+/* Ternary contraction D[m][n] = sum_k t_a[m][k]*t_w[n][k] (the dot product
+ * W^t (x) A^t of Eq.8/Eq.9), optionally followed by the fused epilogue.
+ *   a_codes: [M][Kpad], w_codes: [N][Kpad] in format `fmt`.
+ *   acc_out: int32 [M][N] row-major, or NULL.
+ *   ep + y_out: fp32 [M][N] row-major through the four-term formula, or both
+ *   NULL.  At least one of acc_out / (ep, y_out) must be given.
+ *   workspace: unused by the current kernels (pass NULL, 0).                 */
+int rtn_ternary_gemm(rtn_code_format fmt, rtn_path path, const void *a_codes, const void *w_codes,
+                     int64_t M, int64_t N, int64_t K, int32_t *acc_out, const rtn_epilogue *ep,
+                     float *y_out, void *workspace, size_t workspace_bytes, void *stream);
+
+/* Ternary 2-D convolution as an implicit GEMM (im2col view of the footnote in
+ * Section "Methodology"; the patch matrix is never materialised):
+ *   M = Nb*OH*OW, N = O, K = KH*KW*C, cross-correlation,
+ *   ih = oh*stride - pad + kh, iw = ow*stride - pad + kw,
+ *   OH = (H + 2*pad - KH)/stride + 1; a tap outside the image adds 0 to D.
+ *   a_codes: [Nb][H][W][Cpad]; w_codes: [O][KH][KW][Cpad] (RTN_CODE_I8 only).
+ *   acc_out: int32 [Nb][O][OH][OW] or NULL; y_out: fp32 [Nb][O][OH][OW] (NCHW).
+ *   KH, KW in 1..7, stride >= 1, 0 <= pad < KH, KW.
+ *   workspace: at least rtn_conv2d_workspace_bytes(O, KH, KW) bytes when an
+ *   epilogue is given (holds the per-border-class filter sums).
+ *   Nb*H*W and Nb*OH*OW must be below 2^31.                                  */
+size_t rtn_conv2d_workspace_bytes(int64_t O, int KH, int KW);
+int rtn_ternary_conv2d_implicit_gemm(rtn_code_format fmt, rtn_path path, const void *a_codes,
+                                     const void *w_codes, int64_t Nb, int64_t C, int64_t H,
+                                     int64_t W, int64_t O, int KH, int KW, int stride, int pad,
+                                     rtn_pad_mode pad_mode, int32_t *acc_out,
+                                     const rtn_epilogue *ep, float *y_out, void *workspace,
+                                     size_t workspace_bytes, void *stream);
+
+/* Stand-alone epilogue on stored accumulators (Eq.9 generalised, see
+ * rtn_epilogue).  GEMM form: acc, y_out are [M][N] row-major.               */
+int rtn_epilogue_reparam(const int32_t *acc, int64_t M, int64_t N, int64_t K,
+                         const rtn_epilogue *ep, float *y_out, void *stream);
+/* conv form: acc, y_out are [Nb][O][OH][OW]; geometry as in
+ * rtn_ternary_conv2d_implicit_gemm; needs no workspace.                      */
+int rtn_epilogue_reparam_conv2d(const int32_t *acc, int64_t Nb, int64_t C, int64_t H, int64_t W,
+                                int64_t O, int KH, int KW, int stride, int pad,
+                                rtn_pad_mode pad_mode, const rtn_epilogue *ep, float *y_out,
+                                void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RTN_H */

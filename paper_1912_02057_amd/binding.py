@@ -1,0 +1,233 @@
+"""Thin Python binding of librtn's C ABI (see include/rtn.h).
+
+Argument marshalling only: torch tensors supply device memory and the current
+HIP stream; every step of the path runs in the library's kernels.  There is no
+CPU fallback -- if librtn.so is missing or cannot be loaded this raises.
+"""
+import ctypes as C
+import os
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "librtn.so")
+
+RTN_OK = 0
+RTN_ERR_NULL, RTN_ERR_SHAPE, RTN_ERR_ALIGN, RTN_ERR_UNSUPPORTED, RTN_ERR_WORKSPACE, RTN_ERR_HIP = \
+    -1, -2, -3, -4, -5, -6
+RTN_CODE_I8, RTN_CODE_BITPLANE = 0, 1
+RTN_SCALAR, RTN_VECTOR = 0, 1
+RTN_ROWS_K_CONTIG, RTN_NCHW = 0, 1
+RTN_PAD_TRUE_ZERO, RTN_PAD_CODE_ZERO = 0, 1
+RTN_PATH_AUTO, RTN_PATH_MFMA_I8, RTN_PATH_POPC = 0, 1, 2
+
+EXPORTS = ["rtn_status_string", "rtn_last_hip_error", "rtn_num_tile_configs", "rtn_set_tile_config", "rtn_padded_k", "rtn_codes_bytes",
+           "rtn_ternarize_pack", "rtn_ternary_gemm", "rtn_conv2d_workspace_bytes",
+           "rtn_ternary_conv2d_implicit_gemm", "rtn_epilogue_reparam", "rtn_epilogue_reparam_conv2d"]
+
+
+class RtnEpilogue(C.Structure):
+    _fields_ = [("alpha_a", C.c_void_p), ("beta_a", C.c_void_p), ("gran_a", C.c_int),
+                ("alpha_w", C.c_void_p), ("beta_w", C.c_void_p), ("gran_w", C.c_int),
+                ("sum_ta", C.c_void_p), ("sum_tw", C.c_void_p), ("relu", C.c_int),
+                ("bn_scale", C.c_void_p), ("bn_shift", C.c_void_p)]
+
+
+class RtnError(RuntimeError):
+    def __init__(self, status, where):
+        self.status = status
+        msg = lib().rtn_status_string(status).decode()
+        if status == RTN_ERR_HIP:
+            msg += " [hipError %d]" % lib().rtn_last_hip_error()
+        super().__init__("%s: %s (%d)" % (where, msg, status))
+
+
+_lib = None
+
+
+def lib():
+    """Loads librtn.so (built by build.py).  Raises if it is not there."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("librtn.so not built: run `python -m paper_1912_02057_amd.build` "
+                               "(there is no fallback path)")
+        L = C.CDLL(LIB_PATH)
+        i64, vp, ci = C.c_int64, C.c_void_p, C.c_int
+        L.rtn_status_string.restype = C.c_char_p
+        L.rtn_status_string.argtypes = [ci]
+        L.rtn_last_hip_error.restype = ci
+        L.rtn_padded_k.restype = i64
+        L.rtn_padded_k.argtypes = [i64]
+        L.rtn_codes_bytes.restype = C.c_size_t
+        L.rtn_codes_bytes.argtypes = [ci, i64, i64]
+        L.rtn_ternarize_pack.restype = ci
+        L.rtn_ternarize_pack.argtypes = [vp, ci, i64, i64, i64, i64, vp, vp, ci, ci, vp, vp, vp]
+        L.rtn_ternary_gemm.restype = ci
+        L.rtn_ternary_gemm.argtypes = [ci, ci, vp, vp, i64, i64, i64, vp, vp, vp, vp, C.c_size_t, vp]
+        L.rtn_conv2d_workspace_bytes.restype = C.c_size_t
+        L.rtn_conv2d_workspace_bytes.argtypes = [i64, ci, ci]
+        L.rtn_ternary_conv2d_implicit_gemm.restype = ci
+        L.rtn_ternary_conv2d_implicit_gemm.argtypes = [ci, ci, vp, vp, i64, i64, i64, i64, i64, ci, ci,
+                                                       ci, ci, ci, vp, vp, vp, vp, C.c_size_t, vp]
+        L.rtn_epilogue_reparam.restype = ci
+        L.rtn_epilogue_reparam.argtypes = [vp, i64, i64, i64, vp, vp, vp]
+        L.rtn_epilogue_reparam_conv2d.restype = ci
+        L.rtn_epilogue_reparam_conv2d.argtypes = [vp, i64, i64, i64, i64, i64, ci, ci, ci, ci, ci, vp,
+                                                  vp, vp]
+        _lib = L
+    return _lib
+
+
+def _check(rc, where):
+    if rc != RTN_OK:
+        raise RtnError(rc, where)
+
+
+def _stream():
+    return C.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def _dev(t, dtype):
+    assert t.is_cuda and t.dtype == dtype and t.is_contiguous(), (t.device, t.dtype)
+    return C.c_void_p(t.data_ptr())
+
+
+class _Gran:
+    """A scalar (python float -> host float) or a device float32 vector."""
+
+    def __init__(self, v):
+        self.keep = None
+        if v is None:
+            self.ptr, self.gran = None, None
+        elif torch.is_tensor(v):
+            self.ptr, self.gran = _dev(v, torch.float32), RTN_VECTOR
+        else:
+            self.keep = C.c_float(float(v))
+            self.ptr, self.gran = C.cast(C.pointer(self.keep), C.c_void_p), RTN_SCALAR
+
+
+def num_tile_configs():
+    return lib().rtn_num_tile_configs()
+
+
+def set_tile_config(index):
+    _check(lib().rtn_set_tile_config(int(index)), "rtn_set_tile_config")
+
+
+def padded_k(K):
+    return lib().rtn_padded_k(K)
+
+
+def ternarize_pack(x, lo, hi, fmt=RTN_CODE_I8, layout=None, want_sum=True):
+    """x: cuda float32 [rows,K] (RTN_ROWS_K_CONTIG) or [N,C,H,W] (RTN_NCHW).
+    lo/hi: python floats, or cuda float32 vectors (per row / per leading index).
+    Returns (codes, sum_t).  codes: int8 [rows,Kpad] / [N,H,W,Cpad], or for
+    bit planes uint64-as-int64 [2, rows, Kpad/64] / [2, N,H,W, Cpad/64]."""
+    if layout is None:
+        layout = RTN_NCHW if x.dim() == 4 else RTN_ROWS_K_CONTIG
+    if layout == RTN_ROWS_K_CONTIG:
+        d = (x.shape[0], x.shape[1], 1, 1)
+        lead = (x.shape[0],)
+    else:
+        d = tuple(x.shape)
+        lead = (x.shape[0], x.shape[2], x.shape[3])
+    kp = padded_k(d[1])
+    if fmt == RTN_CODE_I8:
+        codes = torch.empty(lead + (kp,), dtype=torch.int8, device=x.device)
+    else:
+        codes = torch.empty((2,) + lead + (kp // 64,), dtype=torch.int64, device=x.device)
+    sum_t = torch.empty(lead, dtype=torch.int32, device=x.device) if want_sum else None
+    glo, ghi = _Gran(lo), _Gran(hi)
+    assert glo.gran == ghi.gran
+    rc = lib().rtn_ternarize_pack(_dev(x, torch.float32), layout, d[0], d[1], d[2], d[3], glo.ptr,
+                                  ghi.ptr, glo.gran, fmt, C.c_void_p(codes.data_ptr()),
+                                  None if sum_t is None else _dev(sum_t, torch.int32), _stream())
+    _check(rc, "rtn_ternarize_pack")
+    return codes, sum_t
+
+
+class Epilogue:
+    """Owns the marshalled rtn_epilogue (keeps host scalars alive)."""
+
+    def __init__(self, alpha_a, beta_a, alpha_w, beta_w, sum_ta, sum_tw, relu=False, bn_scale=None,
+                 bn_shift=None):
+        self._a, self._b = _Gran(alpha_a), _Gran(beta_a)
+        self._c, self._d = _Gran(alpha_w), _Gran(beta_w)
+        assert self._a.gran == self._b.gran
+        assert self._d.gran is None or self._c.gran == self._d.gran
+        self._tensors = (alpha_a, beta_a, alpha_w, beta_w, sum_ta, sum_tw, bn_scale, bn_shift)
+        self.s = RtnEpilogue(self._a.ptr, self._b.ptr, self._a.gran, self._c.ptr, self._d.ptr,
+                             self._c.gran, _dev(sum_ta, torch.int32), _dev(sum_tw, torch.int32),
+                             int(bool(relu)),
+                             None if bn_scale is None else _dev(bn_scale, torch.float32),
+                             None if bn_shift is None else _dev(bn_shift, torch.float32))
+
+    def ref(self):
+        return C.cast(C.pointer(self.s), C.c_void_p)
+
+
+def ternary_gemm(a_codes, w_codes, M, N, K, fmt=RTN_CODE_I8, path=RTN_PATH_AUTO, ep=None,
+                 want_acc=False, acc_out=None, y_out=None):
+    """Returns (acc or None, y or None)."""
+    dev = a_codes.device
+    if want_acc and acc_out is None:
+        acc_out = torch.empty((M, N), dtype=torch.int32, device=dev)
+    if ep is not None and y_out is None:
+        y_out = torch.empty((M, N), dtype=torch.float32, device=dev)
+    rc = lib().rtn_ternary_gemm(fmt, path, C.c_void_p(a_codes.data_ptr()), C.c_void_p(w_codes.data_ptr()),
+                                M, N, K, None if acc_out is None else _dev(acc_out, torch.int32),
+                                None if ep is None else ep.ref(),
+                                None if y_out is None else _dev(y_out, torch.float32), None, 0, _stream())
+    _check(rc, "rtn_ternary_gemm")
+    return acc_out, y_out
+
+
+def conv2d_workspace_bytes(O, KH, KW):
+    return lib().rtn_conv2d_workspace_bytes(O, KH, KW)
+
+
+def conv_out_hw(H, W, KH, KW, stride, pad):
+    return (H + 2 * pad - KH) // stride + 1, (W + 2 * pad - KW) // stride + 1
+
+
+def ternary_conv2d(a_codes, w_codes, Nb, Cc, H, W, O, KH, KW, stride, pad, pad_mode=RTN_PAD_TRUE_ZERO,
+                   ep=None, want_acc=False, acc_out=None, y_out=None, workspace=None,
+                   fmt=RTN_CODE_I8, path=RTN_PATH_AUTO):
+    """a_codes: int8 [Nb,H,W,Cpad]; w_codes: int8 [O,KH,KW,Cpad].  Returns (acc, y) in NCHW."""
+    dev = a_codes.device
+    OH, OW = conv_out_hw(H, W, KH, KW, stride, pad)
+    if want_acc and acc_out is None:
+        acc_out = torch.empty((Nb, O, OH, OW), dtype=torch.int32, device=dev)
+    if ep is not None and y_out is None:
+        y_out = torch.empty((Nb, O, OH, OW), dtype=torch.float32, device=dev)
+    if ep is not None and workspace is None:
+        workspace = torch.empty(conv2d_workspace_bytes(O, KH, KW), dtype=torch.uint8, device=dev)
+    rc = lib().rtn_ternary_conv2d_implicit_gemm(
+        fmt, path, C.c_void_p(a_codes.data_ptr()), C.c_void_p(w_codes.data_ptr()), Nb, Cc, H, W, O, KH, KW,
+        stride, pad, pad_mode, None if acc_out is None else _dev(acc_out, torch.int32),
+        None if ep is None else ep.ref(), None if y_out is None else _dev(y_out, torch.float32),
+        None if workspace is None else C.c_void_p(workspace.data_ptr()),
+        0 if workspace is None else workspace.numel() * workspace.element_size(), _stream())
+    _check(rc, "rtn_ternary_conv2d_implicit_gemm")
+    return acc_out, y_out
+
+
+def epilogue_reparam(acc, K, ep, y_out=None):
+    M, N = acc.shape
+    if y_out is None:
+        y_out = torch.empty((M, N), dtype=torch.float32, device=acc.device)
+    rc = lib().rtn_epilogue_reparam(_dev(acc, torch.int32), M, N, K, ep.ref(), _dev(y_out, torch.float32),
+                                    _stream())
+    _check(rc, "rtn_epilogue_reparam")
+    return y_out
+
+
+def epilogue_reparam_conv2d(acc, Cc, H, W, KH, KW, stride, pad, pad_mode, ep, y_out=None):
+    Nb, O, OH, OW = acc.shape
+    if y_out is None:
+        y_out = torch.empty_like(acc, dtype=torch.float32)
+    rc = lib().rtn_epilogue_reparam_conv2d(_dev(acc, torch.int32), Nb, Cc, H, W, O, KH, KW, stride, pad,
+                                           pad_mode, ep.ref(), _dev(y_out, torch.float32), _stream())
+    _check(rc, "rtn_epilogue_reparam_conv2d")
+    return y_out

@@ -1,0 +1,283 @@
+// C ABI of librtn: argument validation and dispatch.  Every check runs before
+// anything is launched, so a rejected call never touches the GPU.
+#include "../../include/rtn.h"
+
+#include <hip/hip_runtime.h>
+
+#include "rtn_kernels.h"
+
+namespace {
+
+thread_local int g_last_hip_error = 0;
+
+int hip_fail(hipError_t e)
+{
+    g_last_hip_error = (int)e;
+    return RTN_ERR_HIP;
+}
+
+constexpr int64_t kMaxDim = 0x7fffffffLL - 1024;
+constexpr int64_t kMaxK = 1LL << 24;
+
+bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
+int64_t pad64(int64_t k) { return (k + 63) / 64 * 64; }
+
+// Host scalar or device vector -> kernel parameter.
+int make_param(const float* p, rtn_gran gran, bool nullable, rtn::Param& out)
+{
+    out.ptr = nullptr;
+    out.s = 0.0f;
+    if (!p) return nullable ? RTN_OK : RTN_ERR_NULL;
+    if (gran == RTN_SCALAR) {
+        out.s = *p;
+    } else if (gran == RTN_VECTOR) {
+        if (!aligned(p, 4)) return RTN_ERR_ALIGN;
+        out.ptr = p;
+    } else {
+        return RTN_ERR_UNSUPPORTED;
+    }
+    return RTN_OK;
+}
+
+// Validates an rtn_epilogue for the GEMM (conv = false) or conv form.
+int make_epilogue(const rtn_epilogue* ep, bool conv, rtn::EpiArgs& out)
+{
+    if (!ep) return RTN_ERR_NULL;
+    if (ep->gran_a != RTN_SCALAR && ep->gran_a != RTN_VECTOR) return RTN_ERR_UNSUPPORTED;
+    if (ep->gran_w != RTN_SCALAR && ep->gran_w != RTN_VECTOR) return RTN_ERR_UNSUPPORTED;
+    if (conv && ep->gran_a != RTN_SCALAR) return RTN_ERR_UNSUPPORTED;
+    int rc;
+    if ((rc = make_param(ep->alpha_a, ep->gran_a, false, out.alpha_a)) != RTN_OK) return rc;
+    if ((rc = make_param(ep->beta_a, ep->gran_a, false, out.beta_a)) != RTN_OK) return rc;
+    if ((rc = make_param(ep->alpha_w, ep->gran_w, false, out.alpha_w)) != RTN_OK) return rc;
+    if ((rc = make_param(ep->beta_w, ep->gran_w, true, out.beta_w)) != RTN_OK) return rc;
+    if (!ep->sum_ta || !ep->sum_tw) return RTN_ERR_NULL;
+    if (!aligned(ep->sum_ta, 4) || !aligned(ep->sum_tw, 4)) return RTN_ERR_ALIGN;
+    if (ep->bn_shift && !ep->bn_scale) return RTN_ERR_NULL;
+    if (!aligned(ep->bn_scale, 4) || !aligned(ep->bn_shift, 4)) return RTN_ERR_ALIGN;
+    out.sum_ta = ep->sum_ta;
+    out.sum_tw = ep->sum_tw;
+    out.relu = ep->relu != 0;
+    out.bn_scale = ep->bn_scale;
+    out.bn_shift = ep->bn_shift;
+    return RTN_OK;
+}
+
+int make_geom(int64_t Nb, int64_t C, int64_t H, int64_t W, int64_t O, int KH, int KW, int stride,
+              int pad, rtn_pad_mode pad_mode, rtn::ConvGeom& g)
+{
+    if (Nb <= 0 || C <= 0 || H <= 0 || W <= 0 || O <= 0) return RTN_ERR_SHAPE;
+    if (Nb > kMaxDim || C > kMaxDim || H > kMaxDim || W > kMaxDim || O > kMaxDim) return RTN_ERR_SHAPE;
+    if (KH < 1 || KW < 1 || KH > 7 || KW > 7 || stride < 1 || stride > 64) return RTN_ERR_UNSUPPORTED;
+    if (pad < 0 || pad >= KH || pad >= KW) return RTN_ERR_UNSUPPORTED;
+    if (pad_mode != RTN_PAD_TRUE_ZERO && pad_mode != RTN_PAD_CODE_ZERO) return RTN_ERR_UNSUPPORTED;
+    if (H + 2 * pad < KH || W + 2 * pad < KW) return RTN_ERR_SHAPE;
+    const int64_t OH = (H + 2 * pad - KH) / stride + 1, OW = (W + 2 * pad - KW) / stride + 1;
+    const int64_t Cpad = pad64(C);
+    if (Cpad * KH * KW > kMaxK) return RTN_ERR_SHAPE;
+    if (Nb * H * W > kMaxDim || Nb * OH * OW > kMaxDim) return RTN_ERR_SHAPE;
+    g.Nb = (int)Nb, g.C = (int)C, g.Cpad = (int)Cpad, g.H = (int)H, g.W = (int)W, g.O = (int)O;
+    g.KH = KH, g.KW = KW, g.stride = stride, g.pad = pad, g.OH = (int)OH, g.OW = (int)OW;
+    g.code_zero_pad = pad_mode == RTN_PAD_CODE_ZERO;
+    return RTN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char* rtn_status_string(int status)
+{
+    switch (status) {
+        case RTN_OK: return "ok";
+        case RTN_ERR_NULL: return "required pointer is NULL";
+        case RTN_ERR_SHAPE: return "invalid shape or size";
+        case RTN_ERR_ALIGN: return "pointer not sufficiently aligned";
+        case RTN_ERR_UNSUPPORTED: return "unsupported format, path, granularity or kernel geometry";
+        case RTN_ERR_WORKSPACE: return "workspace missing or too small";
+        case RTN_ERR_HIP: return "HIP launch failed (see rtn_last_hip_error)";
+        default: return "unknown status";
+    }
+}
+
+int rtn_last_hip_error(void) { return g_last_hip_error; }
+
+int rtn_num_tile_configs(void) { return rtn::tile_config_count(); }
+
+int rtn_set_tile_config(int index)
+{
+    if (index < -1 || index >= rtn::tile_config_count()) return RTN_ERR_UNSUPPORTED;
+    rtn::force_tile_config(index);
+    return RTN_OK;
+}
+
+int64_t rtn_padded_k(int64_t K) { return K <= 0 ? 0 : pad64(K); }
+
+size_t rtn_codes_bytes(rtn_code_format fmt, int64_t rows, int64_t K)
+{
+    if (rows <= 0 || K <= 0) return 0;
+    const int64_t kp = pad64(K);
+    if (fmt == RTN_CODE_I8) return (size_t)rows * (size_t)kp;
+    if (fmt == RTN_CODE_BITPLANE) return (size_t)rows * (size_t)(kp / 64) * 8u * 2u;
+    return 0;
+}
+
+int rtn_ternarize_pack(const float* x, rtn_layout layout, int64_t d0, int64_t d1, int64_t d2,
+                       int64_t d3, const float* thr_lo, const float* thr_hi, rtn_gran thr_gran,
+                       rtn_code_format fmt, void* codes, int32_t* sum_t, void* stream)
+{
+    if (!x || !codes || !thr_lo || !thr_hi) return RTN_ERR_NULL;
+    if (layout != RTN_ROWS_K_CONTIG && layout != RTN_NCHW) return RTN_ERR_UNSUPPORTED;
+    if (fmt != RTN_CODE_I8 && fmt != RTN_CODE_BITPLANE) return RTN_ERR_UNSUPPORTED;
+    if (d0 <= 0 || d1 <= 0 || d2 <= 0 || d3 <= 0) return RTN_ERR_SHAPE;
+    if (d0 > kMaxDim || d1 > kMaxDim || d2 > kMaxDim || d3 > kMaxDim) return RTN_ERR_SHAPE;
+    if (layout == RTN_ROWS_K_CONTIG && (d2 != 1 || d3 != 1)) return RTN_ERR_SHAPE;
+    if (d2 * d3 > kMaxDim || d0 * d2 * d3 > kMaxDim) return RTN_ERR_SHAPE;
+    if ((double)d0 * (double)d1 * (double)d2 * (double)d3 >= 1099511627776.0) return RTN_ERR_SHAPE;
+    if (!aligned(x, 4) || !aligned(codes, 16) || !aligned(sum_t, 4)) return RTN_ERR_ALIGN;
+
+    rtn::PackArgs a = {};
+    int rc;
+    if ((rc = make_param(thr_lo, thr_gran, false, a.lo)) != RTN_OK) return rc;
+    if ((rc = make_param(thr_hi, thr_gran, false, a.hi)) != RTN_OK) return rc;
+    if (thr_gran == RTN_SCALAR && !(a.lo.s <= a.hi.s)) return RTN_ERR_SHAPE;
+    a.x = x;
+    a.codes = codes;
+    a.sum_t = sum_t;
+    a.K = d1;
+    a.Kpad = pad64(d1);
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t e;
+    if (layout == RTN_ROWS_K_CONTIG) {
+        a.rows = d0;
+        e = fmt == RTN_CODE_I8 ? rtn::launch_pack_rows_i8(a, st) : rtn::launch_pack_rows_planes(a, st);
+    } else {
+        a.N = d0;
+        a.HW = d2 * d3;
+        const int64_t tiles = (a.HW + 63) / 64;
+        if (tiles * a.N > kMaxDim) return RTN_ERR_SHAPE;
+        e = fmt == RTN_CODE_I8 ? rtn::launch_pack_nchw_i8(a, st) : rtn::launch_pack_nchw_planes(a, st);
+    }
+    return e == hipSuccess ? RTN_OK : hip_fail(e);
+}
+
+int rtn_ternary_gemm(rtn_code_format fmt, rtn_path path, const void* a_codes, const void* w_codes,
+                     int64_t M, int64_t N, int64_t K, int32_t* acc_out, const rtn_epilogue* ep,
+                     float* y_out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    (void)workspace;
+    (void)workspace_bytes;
+    if (!a_codes || !w_codes) return RTN_ERR_NULL;
+    if ((ep == nullptr) != (y_out == nullptr)) return RTN_ERR_NULL;
+    if (!acc_out && !y_out) return RTN_ERR_NULL;
+    if (fmt != RTN_CODE_I8 && fmt != RTN_CODE_BITPLANE) return RTN_ERR_UNSUPPORTED;
+    if (path != RTN_PATH_AUTO && path != RTN_PATH_MFMA_I8 && path != RTN_PATH_POPC)
+        return RTN_ERR_UNSUPPORTED;
+    if (path == RTN_PATH_AUTO) path = fmt == RTN_CODE_I8 ? RTN_PATH_MFMA_I8 : RTN_PATH_POPC;
+    if ((path == RTN_PATH_MFMA_I8) != (fmt == RTN_CODE_I8)) return RTN_ERR_UNSUPPORTED;
+    if (M <= 0 || N <= 0 || K <= 0 || M > kMaxDim || N > kMaxDim || K > kMaxK) return RTN_ERR_SHAPE;
+    if (!aligned(a_codes, 16) || !aligned(w_codes, 16) || !aligned(acc_out, 4) || !aligned(y_out, 4))
+        return RTN_ERR_ALIGN;
+    rtn::EpiArgs e = {};
+    if (ep) {
+        const int rc = make_epilogue(ep, false, e);
+        if (rc != RTN_OK) return rc;
+    }
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t he;
+    if (path == RTN_PATH_MFMA_I8) {
+        rtn::GemmArgs g = {};
+        g.a = (const int8_t*)a_codes;
+        g.w = (const int8_t*)w_codes;
+        g.M = M, g.N = N, g.K = K, g.Kpad = pad64(K);
+        g.acc = acc_out;
+        g.y = y_out;
+        g.ep = e;
+        he = rtn::launch_gemm_mfma(g, st);
+    } else {
+        rtn::PopcArgs p = {};
+        const int64_t words = pad64(K) / 64;
+        p.a_mask = (const uint64_t*)a_codes;
+        p.a_sign = p.a_mask + M * words;
+        p.w_mask = (const uint64_t*)w_codes;
+        p.w_sign = p.w_mask + N * words;
+        p.M = M, p.N = N, p.K = K, p.words = words;
+        p.acc = acc_out;
+        p.y = y_out;
+        p.ep = e;
+        he = rtn::launch_gemm_popc(p, st);
+    }
+    return he == hipSuccess ? RTN_OK : hip_fail(he);
+}
+
+size_t rtn_conv2d_workspace_bytes(int64_t O, int KH, int KW)
+{
+    if (O <= 0 || KH < 1 || KW < 1 || KH > 7 || KW > 7) return 0;
+    return (size_t)O * (size_t)(KH * KH * KW * KW) * sizeof(int32_t);
+}
+
+int rtn_ternary_conv2d_implicit_gemm(rtn_code_format fmt, rtn_path path, const void* a_codes,
+                                     const void* w_codes, int64_t Nb, int64_t C, int64_t H, int64_t W,
+                                     int64_t O, int KH, int KW, int stride, int pad,
+                                     rtn_pad_mode pad_mode, int32_t* acc_out, const rtn_epilogue* ep,
+                                     float* y_out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!a_codes || !w_codes) return RTN_ERR_NULL;
+    if ((ep == nullptr) != (y_out == nullptr)) return RTN_ERR_NULL;
+    if (!acc_out && !y_out) return RTN_ERR_NULL;
+    if (fmt != RTN_CODE_I8) return RTN_ERR_UNSUPPORTED;
+    if (path != RTN_PATH_AUTO && path != RTN_PATH_MFMA_I8) return RTN_ERR_UNSUPPORTED;
+    rtn::ConvArgs c = {};
+    int rc = make_geom(Nb, C, H, W, O, KH, KW, stride, pad, pad_mode, c.g);
+    if (rc != RTN_OK) return rc;
+    if (!aligned(a_codes, 16) || !aligned(w_codes, 16) || !aligned(acc_out, 4) || !aligned(y_out, 4))
+        return RTN_ERR_ALIGN;
+    if (ep) {
+        if ((rc = make_epilogue(ep, true, c.ep)) != RTN_OK) return rc;
+        if (!workspace || workspace_bytes < rtn_conv2d_workspace_bytes(O, KH, KW)) return RTN_ERR_WORKSPACE;
+        if (!aligned(workspace, 4)) return RTN_ERR_ALIGN;
+    }
+    c.a = (const int8_t*)a_codes;
+    c.w = (const int8_t*)w_codes;
+    c.acc = acc_out;
+    c.y = y_out;
+    c.sw_cls = (const int32_t*)workspace;
+    hipStream_t st = (hipStream_t)stream;
+    hipError_t he;
+    if (ep) {
+        he = rtn::launch_conv_class_sums(c.ep.sum_tw, c.g, (int32_t*)workspace, st);
+        if (he != hipSuccess) return hip_fail(he);
+    }
+    he = rtn::launch_conv_mfma(c, st);
+    return he == hipSuccess ? RTN_OK : hip_fail(he);
+}
+
+int rtn_epilogue_reparam(const int32_t* acc, int64_t M, int64_t N, int64_t K, const rtn_epilogue* ep,
+                         float* y_out, void* stream)
+{
+    if (!acc || !y_out) return RTN_ERR_NULL;
+    if (M <= 0 || N <= 0 || K <= 0 || M > kMaxDim || N > kMaxDim || K > kMaxK) return RTN_ERR_SHAPE;
+    if (!aligned(acc, 4) || !aligned(y_out, 4)) return RTN_ERR_ALIGN;
+    rtn::EpiArgs e = {};
+    const int rc = make_epilogue(ep, false, e);
+    if (rc != RTN_OK) return rc;
+    const hipError_t he = rtn::launch_epilogue_gemm(acc, M, N, K, e, y_out, (hipStream_t)stream);
+    return he == hipSuccess ? RTN_OK : hip_fail(he);
+}
+
+int rtn_epilogue_reparam_conv2d(const int32_t* acc, int64_t Nb, int64_t C, int64_t H, int64_t W,
+                                int64_t O, int KH, int KW, int stride, int pad, rtn_pad_mode pad_mode,
+                                const rtn_epilogue* ep, float* y_out, void* stream)
+{
+    if (!acc || !y_out) return RTN_ERR_NULL;
+    rtn::ConvGeom g = {};
+    int rc = make_geom(Nb, C, H, W, O, KH, KW, stride, pad, pad_mode, g);
+    if (rc != RTN_OK) return rc;
+    if (!aligned(acc, 4) || !aligned(y_out, 4)) return RTN_ERR_ALIGN;
+    rtn::EpiArgs e = {};
+    if ((rc = make_epilogue(ep, true, e)) != RTN_OK) return rc;
+    const hipError_t he = rtn::launch_epilogue_conv(acc, g, e, y_out, (hipStream_t)stream);
+    return he == hipSuccess ? RTN_OK : hip_fail(he);
+}
+
+}  // extern "C"

@@ -1,0 +1,89 @@
+// Internal launch interface between the C-ABI layer (rtn_api.hip) and the
+// gfx950 kernels.  Everything here takes validated arguments.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rtn {
+
+// A scalar-or-vector fp32 parameter: ptr != nullptr -> device vector, else `s`.
+struct Param {
+    const float* ptr;
+    float s;
+};
+
+struct PackArgs {
+    const float* x;
+    int64_t rows;     // ROWS: d0.  NCHW: unused
+    int64_t K, Kpad;  // ROWS: row length.  NCHW: C, Cpad
+    int64_t N, HW;    // NCHW only
+    Param lo, hi;     // vector: per row (ROWS) / per d0 (NCHW)
+    void* codes;
+    int32_t* sum_t;   // nullable
+};
+
+hipError_t launch_pack_rows_i8(const PackArgs& a, hipStream_t st);
+hipError_t launch_pack_rows_planes(const PackArgs& a, hipStream_t st);
+hipError_t launch_pack_nchw_i8(const PackArgs& a, hipStream_t st);
+hipError_t launch_pack_nchw_planes(const PackArgs& a, hipStream_t st);
+
+// Epilogue parameters as the kernels see them.
+struct EpiArgs {
+    Param alpha_a, beta_a;  // vector: per GEMM row m (GEMM only)
+    Param alpha_w, beta_w;  // vector: per output column / channel
+    const int32_t* sum_ta;  // GEMM: [M]; conv: [Nb][H][W] pixel sums
+    const int32_t* sum_tw;  // GEMM: [N]; conv: [O][KH][KW] tap sums
+    int relu;
+    const float* bn_scale;  // nullable, per output column / channel
+    const float* bn_shift;
+};
+
+struct ConvGeom {
+    int Nb, C, Cpad, H, W, O, KH, KW, stride, pad, OH, OW;
+    int code_zero_pad;  // 1: RTN_PAD_CODE_ZERO
+};
+
+struct GemmArgs {
+    const int8_t* a;  // [M][Kpad]
+    const int8_t* w;  // [N][Kpad]
+    int64_t M, N, K, Kpad;
+    int32_t* acc;  // nullable
+    float* y;      // nullable (then `ep` unused)
+    EpiArgs ep;
+};
+
+struct ConvArgs {
+    const int8_t* a;  // [Nb][H][W][Cpad]
+    const int8_t* w;  // [O][KH][KW][Cpad]
+    ConvGeom g;
+    int32_t* acc;          // nullable, [Nb][O][OH][OW]
+    float* y;              // nullable
+    const int32_t* sw_cls; // workspace: [KH*KH*KW*KW][O] class sums (when y)
+    EpiArgs ep;
+};
+
+hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t st);
+hipError_t launch_conv_mfma(const ConvArgs& a, hipStream_t st);
+// Tile configuration override for tuning and tests (-1 = heuristic).
+int tile_config_count();
+void force_tile_config(int index);
+
+hipError_t launch_conv_class_sums(const int32_t* tap_sums, const ConvGeom& g, int32_t* sw_cls,
+                                  hipStream_t st);
+
+struct PopcArgs {
+    const uint64_t *a_mask, *a_sign;  // [M][words]
+    const uint64_t *w_mask, *w_sign;  // [N][words]
+    int64_t M, N, K, words;
+    int32_t* acc;
+    float* y;
+    EpiArgs ep;
+};
+hipError_t launch_gemm_popc(const PopcArgs& a, hipStream_t st);
+
+hipError_t launch_epilogue_gemm(const int32_t* acc, int64_t M, int64_t N, int64_t K,
+                                const EpiArgs& ep, float* y, hipStream_t st);
+hipError_t launch_epilogue_conv(const int32_t* acc, const ConvGeom& g, const EpiArgs& ep, float* y,
+                                hipStream_t st);
+
+}  // namespace rtn

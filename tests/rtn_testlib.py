@@ -1,0 +1,103 @@
+"""Helpers shared by the GPU parity tests: run a workload through the oracle and
+through the HIP library (via the C-ABI binding) and compare."""
+import numpy as np
+import torch
+
+from oracle import rtn_oracle as orc
+from paper_1912_02057_amd import binding as B
+
+DEV = "cuda:0"
+
+
+def dev(a):
+    return torch.from_numpy(np.ascontiguousarray(a)).to(DEV)
+
+
+def thr_arg(v):
+    """numpy scalar -> python float; numpy vector -> cuda tensor."""
+    v = np.asarray(v, dtype=np.float32)
+    return float(v) if v.ndim == 0 else dev(v)
+
+
+def gran_arg(v):
+    return None if v is None else thr_arg(v)
+
+
+def planes_from_dev(codes):
+    """[2, rows.., words] int64 device tensor -> (mask, sign) uint64 numpy [rows, words]."""
+    c = codes.cpu().numpy().view(np.uint64)
+    words = c.shape[-1]
+    return c[0].reshape(-1, words), c[1].reshape(-1, words)
+
+
+def assert_y_close(y, yhat, what=""):
+    """The stated bar: 1e-5 relative on the reparameterized outputs.  The HIP
+    epilogue evaluates the four terms in fp64 and rounds once, so it sits within
+    about one fp32 ulp of the oracle; the absolute floor (1e-9 of the largest
+    output) only covers outputs where the four terms cancel to ~0."""
+    y = np.asarray(y, dtype=np.float64)
+    yhat = np.asarray(yhat, dtype=np.float64)
+    assert y.shape == yhat.shape, (y.shape, yhat.shape)
+    floor = 1e-9 * max(1.0, float(np.abs(yhat).max()))
+    err = np.abs(y - yhat)
+    bad = err > 1e-5 * np.abs(yhat) + floor
+    assert not bad.any(), "%s: %d outputs off; worst abs err %g at yhat=%g" % (
+        what, int(bad.sum()), float(err.max()), float(yhat.flat[int(err.argmax())]))
+
+
+def oracle_gemm(case, relu=False, bn=None):
+    """case from workloads.gemm_case*: returns dict of oracle results."""
+    da, dw = case["delta_a"], case["delta_w"]
+    ta = orc.ternarize(case["xa"], -da, da)
+    tw = orc.ternarize(case["xw"], -dw, dw)
+    D = orc.gemm_acc(ta, tw)
+    Sa, Sw = orc.row_sums(ta), orc.row_sums(tw)
+    y = orc.gemm_epilogue(D, case["K"], Sa, Sw, case["alpha_a"], case["beta_a"], case["alpha_w"],
+                          case["beta_w"], relu=relu,
+                          bn_scale=None if bn is None else bn[0], bn_shift=None if bn is None else bn[1])
+    return dict(ta=ta, tw=tw, D=D, Sa=Sa, Sw=Sw, y=y)
+
+
+def hip_gemm(case, fmt=B.RTN_CODE_I8, relu=False, bn=None, want_acc=True):
+    da, dw = case["delta_a"], case["delta_w"]
+    xa, xw = dev(case["xa"]), dev(case["xw"])
+    ca, sa = B.ternarize_pack(xa, thr_arg(-da), thr_arg(da), fmt)
+    cw, sw = B.ternarize_pack(xw, thr_arg(-dw), thr_arg(dw), fmt)
+    ep = B.Epilogue(gran_arg(case["alpha_a"]), gran_arg(case["beta_a"]), gran_arg(case["alpha_w"]),
+                    gran_arg(case["beta_w"]), sa, sw, relu=relu,
+                    bn_scale=None if bn is None else dev(bn[0]), bn_shift=None if bn is None else dev(bn[1]))
+    acc, y = B.ternary_gemm(ca, cw, case["M"], case["N"], case["K"], fmt=fmt, ep=ep, want_acc=want_acc)
+    torch.cuda.synchronize()
+    return dict(ca=ca, cw=cw, Sa=sa, Sw=sw, D=acc, y=y, ep=ep)
+
+
+def oracle_conv(case, pad_true_zero=True, relu=False, images=None):
+    """Oracle on the whole batch, or on the listed images only."""
+    sh = case["shape"]
+    x = case["x"] if images is None else case["x"][images]
+    da, dw = case["delta_a"], case["delta_w"]
+    ta = orc.ternarize(x, -da, da)
+    tw = orc.ternarize(case["w"], -np.asarray(dw), dw)
+    D = orc.conv_acc(ta, tw, sh.stride, sh.pad)
+    Sa, Sw, Kv = orc.conv_sums(ta, tw, sh.stride, sh.pad, pad_true_zero)
+    y = orc.conv_epilogue(D, Sa, Sw, Kv, case["alpha_a"], case["beta_a"], case["alpha_w"], case["beta_w"],
+                          relu=relu, bn_scale=case.get("bn_scale"), bn_shift=case.get("bn_shift"))
+    return dict(ta=ta, tw=tw, D=D, y=y)
+
+
+def hip_conv(case, pad_true_zero=True, relu=False, want_acc=True):
+    sh = case["shape"]
+    da, dw = case["delta_a"], case["delta_w"]
+    x, w = dev(case["x"]), dev(case["w"])
+    ca, pa = B.ternarize_pack(x, thr_arg(-da), thr_arg(da))
+    cw, pw = B.ternarize_pack(w, thr_arg(-np.asarray(dw)), thr_arg(dw))
+    ep = B.Epilogue(gran_arg(case["alpha_a"]), gran_arg(case["beta_a"]), gran_arg(case["alpha_w"]),
+                    gran_arg(case["beta_w"]), pa, pw, relu=relu,
+                    bn_scale=None if "bn_scale" not in case else dev(case["bn_scale"]),
+                    bn_shift=None if "bn_shift" not in case else dev(case["bn_shift"]))
+    Nb, Cc, H, W = case["x"].shape
+    acc, y = B.ternary_conv2d(ca, cw, Nb, Cc, H, W, sh.O, sh.k, sh.k, sh.stride, sh.pad,
+                              B.RTN_PAD_TRUE_ZERO if pad_true_zero else B.RTN_PAD_CODE_ZERO,
+                              ep=ep, want_acc=want_acc)
+    torch.cuda.synchronize()
+    return dict(ca=ca, cw=cw, pa=pa, pw=pw, D=acc, y=y, ep=ep)

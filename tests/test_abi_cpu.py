@@ -1,0 +1,151 @@
+"""Host-side checks of the C ABI (no GPU): the library loads, exports every
+symbol the header declares, and rejects bad arguments with the documented
+status before anything is launched."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from paper_1912_02057_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def L():
+    if not os.path.exists(B.LIB_PATH):
+        from paper_1912_02057_amd.build import build_lib
+        build_lib()
+    return B.lib()
+
+
+def _declared():
+    txt = open(os.path.join(ROOT, "include", "rtn.h")).read()
+    txt = re.sub(r"/\*.*?\*/", "", txt, flags=re.S)
+    return sorted(set(re.findall(r"\b(rtn_[a-z0-9_]+)\s*\(", txt)))
+
+
+def test_header_symbols_exported(L):
+    names = _declared()
+    assert set(names) == set(B.EXPORTS)
+    for n in names:
+        assert getattr(L, n) is not None
+
+
+def test_helpers(L):
+    assert L.rtn_padded_k(1) == 64 and L.rtn_padded_k(64) == 64 and L.rtn_padded_k(65) == 128
+    assert L.rtn_padded_k(0) == 0
+    assert L.rtn_codes_bytes(B.RTN_CODE_I8, 3, 70) == 3 * 128
+    assert L.rtn_codes_bytes(B.RTN_CODE_BITPLANE, 3, 70) == 3 * 2 * 8 * 2
+    assert L.rtn_codes_bytes(7, 3, 70) == 0
+    assert L.rtn_conv2d_workspace_bytes(64, 3, 3) == 64 * 81 * 4
+    assert L.rtn_status_string(0) == b"ok"
+    for s in range(-6, 0):
+        assert len(L.rtn_status_string(s)) > 3
+
+
+FAKE = C.c_void_p(0x10000)       # never dereferenced: validation fails first
+ODD = C.c_void_p(0x10002)
+
+
+def _f(v):
+    return C.cast(C.pointer(C.c_float(v)), C.c_void_p)
+
+
+def test_ternarize_pack_rejects(L):
+    lo, hi = _f(-0.5), _f(0.5)
+    call = L.rtn_ternarize_pack
+    ok_args = [FAKE, B.RTN_ROWS_K_CONTIG, 4, 64, 1, 1, lo, hi, B.RTN_SCALAR, B.RTN_CODE_I8, FAKE, None, None]
+
+    def with_(i, v):
+        a = list(ok_args)
+        a[i] = v
+        return call(*a)
+    assert with_(0, None) == B.RTN_ERR_NULL
+    assert with_(10, None) == B.RTN_ERR_NULL
+    assert with_(6, None) == B.RTN_ERR_NULL
+    assert with_(2, 0) == B.RTN_ERR_SHAPE
+    assert with_(3, -5) == B.RTN_ERR_SHAPE
+    assert with_(4, 2) == B.RTN_ERR_SHAPE            # rows layout needs d2 = d3 = 1
+    assert with_(1, 9) == B.RTN_ERR_UNSUPPORTED
+    assert with_(9, 5) == B.RTN_ERR_UNSUPPORTED
+    assert with_(8, 3) == B.RTN_ERR_UNSUPPORTED
+    assert with_(0, ODD) == B.RTN_ERR_ALIGN
+    assert with_(10, ODD) == B.RTN_ERR_ALIGN
+    assert with_(6, _f(0.7)) == B.RTN_ERR_SHAPE      # lo > hi
+
+
+def _ep(gran_a=B.RTN_SCALAR, gran_w=B.RTN_SCALAR, sums=True):
+    e = B.RtnEpilogue(_f(1.0), _f(0.0), gran_a, _f(1.0), None, gran_w,
+                      FAKE if sums else None, FAKE if sums else None, 0, None, None)
+    return e
+
+
+def test_gemm_rejects(L):
+    call = L.rtn_ternary_gemm
+    ok = [B.RTN_CODE_I8, B.RTN_PATH_AUTO, FAKE, FAKE, 8, 8, 64, FAKE, None, None, None, 0, None]
+
+    def with_(**kw):
+        a = list(ok)
+        for i, v in kw.items():
+            a[int(i[1:])] = v
+        return call(*a)
+    assert with_(_2=None) == B.RTN_ERR_NULL
+    assert with_(_7=None) == B.RTN_ERR_NULL                     # neither acc nor y
+    e = _ep()
+    assert with_(_8=C.byref(e)) == B.RTN_ERR_NULL               # ep without y_out
+    assert with_(_4=0) == B.RTN_ERR_SHAPE
+    assert with_(_6=(1 << 24) + 1) == B.RTN_ERR_SHAPE
+    assert with_(_0=3) == B.RTN_ERR_UNSUPPORTED
+    assert with_(_1=B.RTN_PATH_POPC) == B.RTN_ERR_UNSUPPORTED   # int8 codes on the popcount path
+    assert with_(_0=B.RTN_CODE_BITPLANE, _1=B.RTN_PATH_MFMA_I8) == B.RTN_ERR_UNSUPPORTED
+    assert with_(_2=ODD) == B.RTN_ERR_ALIGN
+    e2 = _ep(sums=False)
+    assert with_(_8=C.byref(e2), _9=FAKE) == B.RTN_ERR_NULL     # epilogue without side sums
+    e3 = _ep(gran_a=5)
+    assert with_(_8=C.byref(e3), _9=FAKE) == B.RTN_ERR_UNSUPPORTED
+
+
+def test_conv_rejects(L):
+    call = L.rtn_ternary_conv2d_implicit_gemm
+    ok = [B.RTN_CODE_I8, B.RTN_PATH_AUTO, FAKE, FAKE, 1, 64, 8, 8, 64, 3, 3, 1, 1, B.RTN_PAD_TRUE_ZERO,
+          FAKE, None, None, None, 0, None]
+
+    def with_(**kw):
+        a = list(ok)
+        for i, v in kw.items():
+            a[int(i[1:])] = v
+        return call(*a)
+    assert with_(_3=None) == B.RTN_ERR_NULL
+    assert with_(_0=B.RTN_CODE_BITPLANE) == B.RTN_ERR_UNSUPPORTED
+    assert with_(_9=8) == B.RTN_ERR_UNSUPPORTED                 # kernel size
+    assert with_(_11=0) == B.RTN_ERR_UNSUPPORTED                # stride
+    assert with_(_12=3) == B.RTN_ERR_UNSUPPORTED                # pad >= kernel
+    assert with_(_13=4) == B.RTN_ERR_UNSUPPORTED
+    assert with_(_4=0) == B.RTN_ERR_SHAPE
+    assert with_(_6=1, _7=1, _12=0) == B.RTN_ERR_SHAPE          # image smaller than the kernel
+    e = _ep()
+    assert with_(_15=C.byref(e), _16=FAKE) == B.RTN_ERR_WORKSPACE
+    assert with_(_15=C.byref(e), _16=FAKE, _17=FAKE, _18=16) == B.RTN_ERR_WORKSPACE
+    ev = _ep(gran_a=B.RTN_VECTOR)
+    assert with_(_15=C.byref(ev), _16=FAKE, _17=FAKE, _18=1 << 20) == B.RTN_ERR_UNSUPPORTED
+
+
+def test_epilogue_rejects(L):
+    e = _ep()
+    assert L.rtn_epilogue_reparam(None, 4, 4, 64, C.byref(e), FAKE, None) == B.RTN_ERR_NULL
+    assert L.rtn_epilogue_reparam(FAKE, 4, 4, 64, None, FAKE, None) == B.RTN_ERR_NULL
+    assert L.rtn_epilogue_reparam(FAKE, 0, 4, 64, C.byref(e), FAKE, None) == B.RTN_ERR_SHAPE
+    assert L.rtn_epilogue_reparam(FAKE, 4, 4, 64, C.byref(e), ODD, None) == B.RTN_ERR_ALIGN
+    assert L.rtn_epilogue_reparam_conv2d(FAKE, 1, 64, 8, 8, 64, 3, 3, 1, 1, 0, None, FAKE, None) \
+        == B.RTN_ERR_NULL
+    assert L.rtn_epilogue_reparam_conv2d(FAKE, 1, 64, 8, 8, 64, 9, 3, 1, 1, 0, C.byref(e), FAKE, None) \
+        == B.RTN_ERR_UNSUPPORTED
+
+
+def test_binding_refuses_missing_library(monkeypatch, tmp_path):
+    monkeypatch.setattr(B, "_lib", None)
+    monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
+    with pytest.raises(RuntimeError):
+        B.lib()

@@ -1,0 +1,295 @@
+"""GPU parity: the HIP library (through the C ABI) against the CPU oracle on the
+same seeded inputs.  Integer results (codes, side sums, accumulators) must be
+bit-exact; reparameterized outputs within 1e-5 relative."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import rtn_oracle as orc
+from paper_1912_02057_amd import binding as B
+from paper_1912_02057_amd import workloads as wl
+
+import rtn_testlib as T
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print("[case] " + msg, flush=True)
+
+
+# ------------------------------------------------------------ S1: pack ------
+@pytest.mark.parametrize("rows,K", [(1, 1), (5, 63), (4, 64), (7, 65), (9, 200), (37, 1000), (3, 4096),
+                                    (130, 258)])
+@pytest.mark.parametrize("per_row", [False, True])
+def test_pack_rows(rows, K, per_row):
+    _say("pack_rows rows=%d K=%d per_row=%s" % (rows, K, per_row))
+    rng = np.random.default_rng(rows * 1000 + K)
+    x = rng.standard_normal((rows, K)).astype(np.float32)
+    if per_row:
+        hi = rng.uniform(0.1, 1.0, rows).astype(np.float32)
+        lo = -rng.uniform(0.1, 1.0, rows).astype(np.float32)
+        x[:, 0] = hi            # ties -> 0
+        x[:, -1] = lo
+    else:
+        hi, lo = np.float32(0.62), np.float32(-0.31)   # asymmetric, as Eq.3 allows
+        x.flat[:: max(1, x.size // 7)] = hi
+    special = np.array([np.nan, np.inf, -np.inf, 0.0, -0.0], np.float32)
+    x.flat[1:1 + min(5, x.size - 1)] = special[: min(5, x.size - 1)]
+    t = orc.ternarize(x, lo, hi)
+    Kp = (K + 63) // 64 * 64
+    xd = T.dev(x)
+    codes, s = B.ternarize_pack(xd, T.thr_arg(lo), T.thr_arg(hi), B.RTN_CODE_I8)
+    assert codes.shape == (rows, Kp)
+    assert (codes.cpu().numpy() == orc.pad_rows_i8(t, Kp)).all()
+    assert (s.cpu().numpy() == orc.row_sums(t)).all()
+    planes, s2 = B.ternarize_pack(xd, T.thr_arg(lo), T.thr_arg(hi), B.RTN_CODE_BITPLANE)
+    m, sg = T.planes_from_dev(planes)
+    em, es = orc.encode_planes(t, Kp // 64)
+    assert (m == em).all() and (sg == es).all()
+    assert (s2.cpu().numpy() == orc.row_sums(t)).all()
+
+
+def test_pack_rows_unaligned_base():
+    # a view whose base is only 4-byte aligned takes the scalar-load variant
+    _say("pack_rows unaligned base")
+    rng = np.random.default_rng(5)
+    buf = T.dev(rng.standard_normal(1 + 6 * 128).astype(np.float32))
+    x = buf[1:].view(6, 128)
+    t = orc.ternarize(x.cpu().numpy(), -0.5, 0.5)
+    codes, s = B.ternarize_pack(x, -0.5, 0.5)
+    assert (codes.cpu().numpy() == t).all() and (s.cpu().numpy() == orc.row_sums(t)).all()
+
+
+@pytest.mark.parametrize("shape", [(2, 5, 7, 9), (3, 64, 8, 8), (2, 130, 5, 5), (1, 64, 56, 56),
+                                   (8, 70, 3, 3), (4, 256, 1, 1)])
+@pytest.mark.parametrize("per_lead", [False, True])
+def test_pack_nchw(shape, per_lead):
+    _say("pack_nchw %s per_lead=%s" % (shape, per_lead))
+    rng = np.random.default_rng(sum(shape))
+    x = rng.standard_normal(shape).astype(np.float32)
+    if per_lead:
+        hi = rng.uniform(0.1, 1.0, shape[0]).astype(np.float32)
+        lo = -hi
+        x[:, 0, 0, 0] = hi
+    else:
+        hi, lo = np.float32(0.4), np.float32(-0.9)
+    x.flat[3] = np.nan
+    t = orc.ternarize(x, lo, hi)
+    Cp = (shape[1] + 63) // 64 * 64
+    xd = T.dev(x)
+    codes, s = B.ternarize_pack(xd, T.thr_arg(lo), T.thr_arg(hi), B.RTN_CODE_I8)
+    assert tuple(codes.shape) == (shape[0], shape[2], shape[3], Cp)
+    assert (codes.cpu().numpy() == orc.nchw_to_nhwc_i8(t, Cp)).all()
+    assert (s.cpu().numpy() == orc.pixel_sums(t)).all()
+    planes, s2 = B.ternarize_pack(xd, T.thr_arg(lo), T.thr_arg(hi), B.RTN_CODE_BITPLANE)
+    m, sg = T.planes_from_dev(planes)
+    em, es = orc.encode_planes(orc.nchw_to_nhwc_i8(t, shape[1]).reshape(-1, shape[1]), Cp // 64)
+    assert (m == em).all() and (sg == es).all()
+    assert (s2.cpu().numpy() == orc.pixel_sums(t)).all()
+
+
+# ------------------------------------------------------ S2 + S4: GEMM -------
+GEMM_SHAPES = [(1, 1, 1), (37, 19, 131), (64, 64, 64), (65, 33, 64), (300, 200, 576), (129, 257, 1000),
+               (512, 384, 2048), (1024, 1024, 512)]
+
+
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES)
+def test_gemm_mfma_vs_oracle(M, N, K):
+    _say("gemm_mfma M=%d N=%d K=%d" % (M, N, K))
+    case = wl.gemm_case(M, N, K, p_zero=0.4, seed=M + N + K)
+    ref = T.oracle_gemm(case)
+    got = T.hip_gemm(case)
+    assert (got["Sa"].cpu().numpy() == ref["Sa"]).all() and (got["Sw"].cpu().numpy() == ref["Sw"]).all()
+    assert (got["D"].cpu().numpy() == ref["D"]).all()
+    T.assert_y_close(got["y"].cpu().numpy(), ref["y"], "gemm y")
+    # the accumulator equals sum t_a*t_w by an independent library route too
+    assert (ref["D"] == ref["ta"].astype(np.int64) @ ref["tw"].astype(np.int64).T).all()
+
+
+def test_gemm_real_inputs_relu_bn_scalar_params():
+    _say("gemm real inputs, relu+bn, scalar/vector mixes")
+    case = wl.gemm_case_real(200, 150, 700, seed=3)
+    rng = np.random.default_rng(0)
+    bn = (rng.uniform(0.5, 1.5, 150).astype(np.float32), rng.normal(0, 0.1, 150).astype(np.float32))
+    ref = T.oracle_gemm(case, relu=True, bn=bn)
+    got = T.hip_gemm(case, relu=True, bn=bn)
+    assert (got["D"].cpu().numpy() == ref["D"]).all()
+    T.assert_y_close(got["y"].cpu().numpy(), ref["y"], "gemm relu+bn")
+    # scalar alpha/beta on both sides, beta_w = NULL (Eq.9 as printed)
+    c2 = dict(case, alpha_a=np.float32(1.3), beta_a=np.float32(0.4), alpha_w=np.float32(0.8), beta_w=None)
+    ref2, got2 = T.oracle_gemm(c2), T.hip_gemm(c2)
+    T.assert_y_close(got2["y"].cpu().numpy(), ref2["y"], "gemm scalar params")
+    # identity parameters return D itself
+    c3 = dict(case, alpha_a=np.float32(1), beta_a=np.float32(0), alpha_w=np.float32(1), beta_w=np.float32(0))
+    got3 = T.hip_gemm(c3)
+    assert (got3["y"].cpu().numpy() == got3["D"].cpu().numpy().astype(np.float32)).all()
+
+
+def test_gemm_acc_only_and_y_only_and_deterministic():
+    _say("gemm acc-only / y-only / determinism")
+    case = wl.gemm_case(260, 300, 640, seed=9)
+    ref = T.oracle_gemm(case)
+    g1 = T.hip_gemm(case)
+    acc_only, none_y = B.ternary_gemm(g1["ca"], g1["cw"], 260, 300, 640, want_acc=True)
+    assert none_y is None and (acc_only.cpu().numpy() == ref["D"]).all()
+    none_acc, y_only = B.ternary_gemm(g1["ca"], g1["cw"], 260, 300, 640, ep=g1["ep"])
+    assert none_acc is None
+    assert torch.equal(y_only, g1["y"])
+    g2 = T.hip_gemm(case)
+    assert torch.equal(g1["D"], g2["D"]) and torch.equal(g1["y"], g2["y"])
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (37, 19, 131), (130, 70, 1000), (256, 256, 4096)])
+def test_gemm_popc_vs_oracle(M, N, K):
+    _say("gemm_popc M=%d N=%d K=%d" % (M, N, K))
+    case = wl.gemm_case(M, N, K, p_zero=0.5, seed=M + K)
+    ref = T.oracle_gemm(case)
+    got = T.hip_gemm(case, fmt=B.RTN_CODE_BITPLANE)
+    assert (got["D"].cpu().numpy() == ref["D"]).all()
+    T.assert_y_close(got["y"].cpu().numpy(), ref["y"], "popc y")
+
+
+def test_standalone_epilogue_gemm():
+    _say("standalone epilogue (gemm form)")
+    case = wl.gemm_case(100, 90, 300, seed=4, table4=True)
+    ref = T.oracle_gemm(case, relu=True)
+    got = T.hip_gemm(case, relu=True)
+    y = B.epilogue_reparam(got["D"], 300, got["ep"])
+    torch.cuda.synchronize()
+    T.assert_y_close(y.cpu().numpy(), ref["y"], "standalone epilogue")
+    assert torch.equal(y, got["y"])
+
+
+# ------------------------------------------------- S3: implicit-GEMM conv ----
+CONV_SHAPES = [
+    wl.ConvShape("c3x3s1", 64, 12, 64, 3, 1, 1),
+    wl.ConvShape("c3x3s2", 64, 14, 128, 3, 2, 1),
+    wl.ConvShape("c1x1s2", 64, 14, 128, 1, 2, 0),
+    wl.ConvShape("c1x1s1", 128, 7, 64, 1, 1, 0),
+    wl.ConvShape("ragged_c", 5, 9, 7, 3, 1, 1),          # C and O far from tile sizes
+    wl.ConvShape("c130", 130, 6, 70, 3, 1, 1),           # C pads to 192
+    wl.ConvShape("tiny", 3, 2, 2, 3, 1, 1),              # image smaller than the kernel
+    wl.ConvShape("nopad", 64, 9, 32, 3, 1, 0),
+    wl.ConvShape("k5", 16, 11, 24, 5, 2, 2),
+    wl.ConvShape("wide_o", 64, 7, 320, 3, 1, 1),
+]
+
+
+@pytest.mark.parametrize("shape", CONV_SHAPES, ids=lambda s: s.name)
+@pytest.mark.parametrize("true_zero", [True, False])
+def test_conv_vs_oracle(shape, true_zero):
+    _say("conv %s true_zero=%s" % (shape, true_zero))
+    case = wl.conv_case(shape, batch=3, seed=len(shape.name), per_channel=True, bn=True)
+    ref = T.oracle_conv(case, true_zero, relu=True)
+    got = T.hip_conv(case, true_zero, relu=True)
+    Cp = (shape.C + 63) // 64 * 64
+    assert (got["ca"].cpu().numpy() == orc.nchw_to_nhwc_i8(ref["ta"], Cp)).all()
+    assert (got["cw"].cpu().numpy() == orc.nchw_to_nhwc_i8(ref["tw"], Cp)).all()
+    assert (got["D"].cpu().numpy() == ref["D"]).all()
+    T.assert_y_close(got["y"].cpu().numpy(), ref["y"], "conv y")
+    y2 = B.epilogue_reparam_conv2d(got["D"], shape.C, case["H"], case["W"], shape.k, shape.k, shape.stride,
+                                   shape.pad, B.RTN_PAD_TRUE_ZERO if true_zero else B.RTN_PAD_CODE_ZERO,
+                                   got["ep"])
+    torch.cuda.synchronize()
+    assert torch.equal(y2, got["y"])
+
+
+def test_conv_rectangular_image():
+    _say("conv rectangular image 10x23")
+    shape = wl.ConvShape("rect", 64, 10, 96, 3, 1, 1)
+    case = wl.conv_case(shape, batch=2, seed=77, Hx=10, Wx=23)
+    ref, got = T.oracle_conv(case), T.hip_conv(case)
+    assert (got["D"].cpu().numpy() == ref["D"]).all()
+    T.assert_y_close(got["y"].cpu().numpy(), ref["y"], "rect conv")
+
+
+def test_config1_single_layer():
+    """3x3 s1 p1, batch 1, 64->64 @ 56x56, Delta_a = 0.5, per-layer scalars."""
+    _say("config 1")
+    case = wl.config1_case()
+    ref, got = T.oracle_conv(case), T.hip_conv(case)
+    assert (got["D"].cpu().numpy() == ref["D"]).all()
+    T.assert_y_close(got["y"].cpu().numpy(), ref["y"], "config1")
+    # direct float conv of the reparameterized values (zero padding)
+    direct = orc.conv_direct(ref["ta"], ref["tw"], 1, 1, case["alpha_a"], case["beta_a"], case["alpha_w"],
+                             case["beta_w"], True)
+    assert np.abs(got["y"].cpu().numpy() - direct).max() <= 1e-5 * np.abs(direct).max()
+
+
+def test_conv_beta_w_null_is_eq9():
+    _say("conv beta_w = NULL")
+    shape = wl.ConvShape("eq9", 64, 8, 64, 3, 1, 1)
+    case = dict(wl.conv_case(shape, batch=2, seed=5), beta_w=None)
+    ref, got = T.oracle_conv(case, False, relu=True), T.hip_conv(case, False, relu=True)
+    T.assert_y_close(got["y"].cpu().numpy(), ref["y"], "eq9")
+    # Eq.9 as printed: z = relu(alpha*gamma*D + alpha*beta*sum(t_w)), code-zero padding
+    Sw = ref["tw"].reshape(shape.O, -1).sum(1).astype(np.float64)
+    aw = np.asarray(case["alpha_w"], np.float64)
+    z = np.maximum(0.0, float(case["alpha_a"]) * aw[None, :, None, None] * ref["D"] +
+                   (aw * float(case["beta_a"]) * Sw)[None, :, None, None])
+    assert np.abs(got["y"].cpu().numpy() - z).max() <= 1e-5 * np.abs(z).max()
+
+
+# ------------------------------------------ every tile configuration ---------
+@pytest.fixture
+def tile_reset():
+    yield
+    B.set_tile_config(-1)
+
+
+@pytest.mark.parametrize("cfg", range(6))
+def test_all_tile_configs_gemm_and_conv(cfg, tile_reset):
+    _say("tile config %d" % cfg)
+    assert B.num_tile_configs() == 6
+    B.set_tile_config(cfg)
+    case = wl.gemm_case(300, 530, 320, seed=cfg)          # several tiles + ragged tails in M and N
+    ref, got = T.oracle_gemm(case), T.hip_gemm(case)
+    assert (got["D"].cpu().numpy() == ref["D"]).all()
+    T.assert_y_close(got["y"].cpu().numpy(), ref["y"], "gemm cfg %d" % cfg)
+    shape = wl.ConvShape("t", 64, 13, 200, 3, 2, 1)
+    ccase = wl.conv_case(shape, batch=7, seed=cfg)         # 7*49 = 343 pixels, O = 200
+    cref, cgot = T.oracle_conv(ccase, True, relu=True), T.hip_conv(ccase, True, relu=True)
+    assert (cgot["D"].cpu().numpy() == cref["D"]).all()
+    T.assert_y_close(cgot["y"].cpu().numpy(), cref["y"], "conv cfg %d" % cfg)
+
+
+# ----------------------------------------------------- full-size checks ------
+def test_config2_gemm_4096_sampled_rows():
+    """M = N = K = 4096 in the launch configuration the benchmark times; the
+    oracle computes 48 sampled rows (all columns) plus every code and side sum."""
+    _say("config 2: 4096^3, sampled rows")
+    case = wl.gemm_case(4096, 4096, 4096, p_zero=0.4, seed=1)
+    got = T.hip_gemm(case)
+    ta = orc.ternarize(case["xa"], -0.5, 0.5)
+    tw = orc.ternarize(case["xw"], -0.5, 0.5)
+    assert (got["ca"].cpu().numpy() == ta).all() and (got["cw"].cpu().numpy() == tw).all()
+    Sa, Sw = orc.row_sums(ta), orc.row_sums(tw)
+    assert (got["Sa"].cpu().numpy() == Sa).all() and (got["Sw"].cpu().numpy() == Sw).all()
+    rows = np.sort(np.random.default_rng(0).choice(4096, 48, replace=False)).astype(np.int64)
+    rows[0], rows[-1] = 0, 4095
+    D = orc.gemm_acc_rows(ta, tw, rows)
+    assert (got["D"].cpu().numpy()[rows] == D).all()
+    y = orc.gemm_epilogue(D, 4096, Sa[rows], Sw, case["alpha_a"][rows], case["beta_a"][rows],
+                          case["alpha_w"], case["beta_w"])
+    T.assert_y_close(got["y"].cpu().numpy()[rows], y, "config2 y")
+    # statistics the i.i.d. P(0) = 0.4 draw fixes: E[D] = 0, Var[D] = 0.36 K
+    Dall = got["D"].double()
+    assert abs(float(Dall.mean())) < 0.05
+    assert abs(float(Dall.var()) / (0.36 * 4096) - 1) < 0.01
+
+
+@pytest.mark.parametrize("idx", range(19))
+def test_resnet18_layers_batch256_sampled_images(idx):
+    """Each ternary ResNet-18 layer at batch 256 (the benchmark's shape and launch
+    configuration); the oracle recomputes two whole images of the batch."""
+    shape = wl.resnet18_ternary_layers()[idx]
+    _say("resnet18 b256 %s" % (shape,))
+    case = wl.conv_case(shape, batch=256, seed=100 + idx, per_channel=True, bn=True)
+    got = T.hip_conv(case, True, relu=True)
+    imgs = [0, 255]
+    ref = T.oracle_conv(case, True, relu=True, images=imgs)
+    assert (got["D"][imgs].cpu().numpy() == ref["D"]).all()
+    T.assert_y_close(got["y"][imgs].cpu().numpy(), ref["y"], shape.name)
+    # properties that hold at any size: |D| <= K, D has the parity pattern of an integer sum
+    assert int(got["D"].abs().max()) <= shape.K
