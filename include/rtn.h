@@ -164,7 +164,8 @@ int rtn_ternary_gemm(rtn_code_format fmt, rtn_path path, const void *a_codes, co
  *   acc_out: int32 [Nb][O][OH][OW] or NULL; y_out: fp32 [Nb][O][OH][OW] (NCHW).
  *   KH, KW in 1..7, stride >= 1, 0 <= pad < KH, KW.
  *   workspace: at least rtn_conv2d_workspace_bytes(O, KH, KW) bytes when an
- *   epilogue is given (holds the per-border-class filter sums).
+ *   epilogue is given (holds Eq.9's constant per border class and
+ *   filter), 8-byte aligned.
  *   Nb*H*W and Nb*OH*OW must be below 2^31.                                  */
 size_t rtn_conv2d_workspace_bytes(int64_t O, int KH, int KW);
 int rtn_ternary_conv2d_implicit_gemm(rtn_code_format fmt, rtn_path path, const void *a_codes,

@@ -213,7 +213,7 @@ int rtn_ternary_gemm(rtn_code_format fmt, rtn_path path, const void* a_codes, co
 size_t rtn_conv2d_workspace_bytes(int64_t O, int KH, int KW)
 {
     if (O <= 0 || KH < 1 || KW < 1 || KH > 7 || KW > 7) return 0;
-    return (size_t)O * (size_t)(KH * KH * KW * KW) * sizeof(int32_t);
+    return (size_t)O * (size_t)(KH * KH * KW * KW) * sizeof(double);
 }
 
 int rtn_ternary_conv2d_implicit_gemm(rtn_code_format fmt, rtn_path path, const void* a_codes,
@@ -235,17 +235,17 @@ int rtn_ternary_conv2d_implicit_gemm(rtn_code_format fmt, rtn_path path, const v
     if (ep) {
         if ((rc = make_epilogue(ep, true, c.ep)) != RTN_OK) return rc;
         if (!workspace || workspace_bytes < rtn_conv2d_workspace_bytes(O, KH, KW)) return RTN_ERR_WORKSPACE;
-        if (!aligned(workspace, 4)) return RTN_ERR_ALIGN;
+        if (!aligned(workspace, 8)) return RTN_ERR_ALIGN;
     }
     c.a = (const int8_t*)a_codes;
     c.w = (const int8_t*)w_codes;
     c.acc = acc_out;
     c.y = y_out;
-    c.sw_cls = (const int32_t*)workspace;
+    c.cst_cls = (const double*)workspace;
     hipStream_t st = (hipStream_t)stream;
     hipError_t he;
     if (ep) {
-        he = rtn::launch_conv_class_sums(c.ep.sum_tw, c.g, (int32_t*)workspace, st);
+        he = rtn::launch_conv_class_consts(c, (double*)workspace, st);
         if (he != hipSuccess) return hip_fail(he);
     }
     he = rtn::launch_conv_mfma(c, st);

@@ -58,7 +58,7 @@ struct ConvArgs {
     ConvGeom g;
     int32_t* acc;          // nullable, [Nb][O][OH][OW]
     float* y;              // nullable
-    const int32_t* sw_cls; // workspace: [KH*KH*KW*KW][O] class sums (when y)
+    const double* cst_cls; // workspace: [KH*KH*KW*KW][O] per-border-class constants (when y)
     EpiArgs ep;
 };
 
@@ -68,8 +68,7 @@ hipError_t launch_conv_mfma(const ConvArgs& a, hipStream_t st);
 int tile_config_count();
 void force_tile_config(int index);
 
-hipError_t launch_conv_class_sums(const int32_t* tap_sums, const ConvGeom& g, int32_t* sw_cls,
-                                  hipStream_t st);
+hipError_t launch_conv_class_consts(const ConvArgs& a, double* cst, hipStream_t st);
 
 struct PopcArgs {
     const uint64_t *a_mask, *a_sign;  // [M][words]

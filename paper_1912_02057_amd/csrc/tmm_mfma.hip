@@ -11,16 +11,20 @@
 //          m = (nb, oh, ow), column = (kh, kw, c)); output NCHW, lanes run
 //          along pixels.  A 64-byte K-step never straddles a tap because
 //          Cpad % 64 == 0, so a Q row of a K-step is 64 contiguous bytes of one
-//          input pixel, or zeros when the tap falls outside the image.
+//          input pixel, or 64 zero bytes when the tap falls outside the image.
 //
 // Tiling (wave64, v_mfma_i32_32x32x32_i8): a 256-thread block owns a BP x BQ
 // output tile, its 4 waves a WGP x WGQ grid of (BP/WGP) x (BQ/WGQ) sub-tiles
 // made of 32x32 MFMA tiles.  K advances 64 bytes per step (two MFMA k-slices).
-// Operand tiles are staged global -> registers -> LDS with the next step's
-// global loads in flight during the current step's MFMAs; two LDS stages, one
-// barrier per step.  LDS rows are 64 bytes; the four 16-byte chunks of a row
-// are XOR-swizzled by a function of the row so that both the 16-byte stores
-// and the 16-byte fragment reads spread over all banks.
+//
+// Data movement: operand tiles go global -> LDS directly (global_load_lds,
+// 16 bytes per lane, no register staging) into NS ring stages, NS steps ahead
+// of the MFMAs; completion is tracked by hand with s_waitcnt vmcnt and ONE
+// workgroup barrier per K-step placed between the two k-slices, so that the
+// fragments of the next slice are always in flight behind 16 MFMAs.  A wave's
+// direct load writes 1 KiB of LDS, lane l at +16*l, i.e. 16 rows of 64 bytes;
+// which global 16-byte chunk a lane fetches is permuted (XOR swizzle by row) so
+// that the 16-byte fragment reads of 16 consecutive rows hit all 64 banks.
 #include "epilogue_math.h"
 #include "rtn_kernels.h"
 
@@ -30,6 +34,9 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+
+// 16 zero bytes every out-of-image tap reads from.
+__device__ __attribute__((aligned(16))) int g_zero16[4] = {0, 0, 0, 0};
 
 struct TmmParams {
     const int8_t* P;
@@ -42,47 +49,57 @@ struct TmmParams {
     ConvGeom g;        // conv only
     int32_t* acc;
     float* y;
-    const int32_t* sw_cls;
+    const double* cst_cls;  // conv: [class][O] constants (see k_conv_class_consts)
     EpiArgs ep;
 };
 
+// chunk swizzle of a 64-byte LDS row (depends on row & 15 only)
 __device__ __forceinline__ int swz(int row) { return ((row >> 1) & 3) ^ ((row >> 3) & 1); }
 
-// Per output pixel: Sa = sum of the input-pixel channel sums over the in-bounds
-// taps, Kv = C * (number of taps that count), cls = index of the border class
-// whose filter sums apply.  With code-zero padding every tap counts.
-__device__ __forceinline__ void pixel_terms(const ConvGeom& g, const int32_t* pix_sums, int nb, int pix,
-                                         int& Sa, int& Kv, int& cls)
+// Direct global -> LDS load: every lane fetches 16 bytes at gptr; the wave's
+// 1 KiB lands at LDS byte offset lds_off (wave-uniform) + 16 * lane.
+__device__ __forceinline__ void dma16(const void* gptr, unsigned lds_off)
 {
-    const int oh = pix / g.OW, ow = pix - oh * g.OW;
-    int khl, khh, kwl, kwh;
-    tap_range(oh, g.stride, g.pad, g.KH, g.H, khl, khh);
-    tap_range(ow, g.stride, g.pad, g.KW, g.W, kwl, kwh);
-    const int32_t* ps = pix_sums + (int64_t)nb * g.H * g.W;
-    int s = 0;
-    for (int kh = khl; kh <= khh; ++kh)
-        for (int kw = kwl; kw <= kwh; ++kw)
-            s += ps[(oh * g.stride - g.pad + kh) * g.W + (ow * g.stride - g.pad + kw)];
-    if (g.code_zero_pad) {
-        khl = 0, khh = g.KH - 1, kwl = 0, kwh = g.KW - 1;
-    }
-    Sa = s;
-    Kv = g.C * (khh - khl + 1) * (kwh - kwl + 1);
-    cls = ((khl * g.KH + khh) * g.KW + kwl) * g.KW + kwh;
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_off), "v"(gptr) : "memory");
 }
 
-template <int BP, int BQ, int WGP, int WGQ, bool CONV>
+template <int N>
+__device__ __forceinline__ void wait_vm()
+{
+    asm volatile("s_waitcnt vmcnt(%0)" ::"n"(N) : "memory");
+}
+__device__ __forceinline__ void wait_lgkm0() { asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory"); }
+// Workgroup barrier that the compiler may not move memory accesses across.
+__device__ __forceinline__ void block_barrier() { asm volatile("s_barrier" ::: "memory"); }
+
+// Wait until at most `groups` of this wave's K-step load groups (DPS loads
+// each) are still in flight.
+template <int DPS>
+__device__ __forceinline__ void wait_groups(int groups)
+{
+    if (groups <= 0)
+        wait_vm<0>();
+    else if (groups == 1)
+        wait_vm<DPS>();
+    else if (groups == 2)
+        wait_vm<2 * DPS>();
+    else
+        wait_vm<3 * DPS>();
+}
+
+template <int BP, int BQ, int WGP, int WGQ, int NS, bool CONV>
 __global__ __launch_bounds__(256) void k_tmm(TmmParams prm)
 {
     static_assert(WGP * WGQ == 4, "4 waves per block");
     constexpr int WP = BP / WGP, WQ = BQ / WGQ, TP = WP / 32, TQ = WQ / 32;
-    constexpr int LP = BP / 64, LQ = BQ / 64;  // 16-byte chunks per thread per K-step
+    constexpr int LP = BP / 64, LQ = BQ / 64;  // direct loads per wave per K-step
+    constexpr int DPS = LP + LQ;
     static_assert(TP >= 1 && TQ >= 1 && LP >= 1 && LQ >= 1, "tile too small");
-    constexpr int STAGE_P = BP * 64, STAGE_Q = BQ * 64;
+    static_assert(NS >= 2 && NS <= 4 && 3 * DPS < 64, "vmcnt range");
+    constexpr int STAGE = (BP + BQ) * 64;  // bytes; P tile first, then Q tile
 
     extern __shared__ __attribute__((aligned(16))) int8_t smem[];
-    int8_t* sP = smem;
-    int8_t* sQ = smem + 2 * STAGE_P;
+    const unsigned lds0 = (unsigned)(uintptr_t)smem;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wp = wave / WGQ, wq = wave % WGQ;
@@ -91,55 +108,55 @@ __global__ __launch_bounds__(256) void k_tmm(TmmParams prm)
     const ConvGeom& g = prm.g;
 
     // ---- loader state ------------------------------------------------------
+    // Load j of a wave covers tile rows 16*(wave + 4*j) .. +15; lane l fetches
+    // row (l >> 2), logical chunk (l & 3) ^ swz(row) and lands at physical
+    // chunk (l & 3) of that row.
+    const int lrow = lane >> 2;
+    const int lchunk = (lane & 3) ^ swz(lrow);
     const int8_t* gP[LP];
-    bool okP[LP];
-    int ldsP[LP];
 #pragma unroll
-    for (int i = 0; i < LP; ++i) {
-        const int cid = tid + 256 * i, row = cid >> 2, c = cid & 3;
-        okP[i] = p0 + row < prm.RP;
-        gP[i] = prm.P + (int64_t)(p0 + row) * prm.ldP + c * 16;
-        ldsP[i] = row * 64 + ((c ^ swz(row)) << 4);
+    for (int j = 0; j < LP; ++j) {
+        int row = p0 + 16 * (wave + 4 * j) + lrow;
+        row = row < prm.RP ? row : prm.RP - 1;  // tail rows: any valid data, never stored
+        gP[j] = prm.P + (int64_t)row * prm.ldP + lchunk * 16;
     }
     const int8_t* gQ[LQ];
-    bool okQ[LQ];
-    int ldsQ[LQ];
-    int ih0[LQ], iw0[LQ];  // conv: input coordinates of tap (0,0)
+    int vmask[LQ];  // conv: bit kh = row tap valid, bit (8 + kw) = column tap valid
 #pragma unroll
-    for (int i = 0; i < LQ; ++i) {
-        const int cid = tid + 256 * i, row = cid >> 2, c = cid & 3;
-        okQ[i] = q0 + row < prm.RQ;
-        ldsQ[i] = row * 64 + ((c ^ swz(row)) << 4);
+    for (int j = 0; j < LQ; ++j) {
+        int row = q0 + 16 * (wave + 4 * j) + lrow;
+        row = row < prm.RQ ? row : prm.RQ - 1;
         if (CONV) {
-            const int m = okQ[i] ? q0 + row : 0;
             const int ohw = g.OH * g.OW;
-            const int nb = m / ohw, pix = m - nb * ohw;
+            const int nb = row / ohw, pix = row - nb * ohw;
             const int oh = pix / g.OW, ow = pix - oh * g.OW;
-            ih0[i] = oh * g.stride - g.pad;
-            iw0[i] = ow * g.stride - g.pad;
-            gQ[i] = prm.Q + (int64_t)nb * g.H * g.W * g.Cpad + c * 16;
+            const int ih0 = oh * g.stride - g.pad, iw0 = ow * g.stride - g.pad;
+            int m = 0;
+            for (int k = 0; k < g.KH; ++k) m |= ((unsigned)(ih0 + k) < (unsigned)g.H) << k;
+            for (int k = 0; k < g.KW; ++k) m |= ((unsigned)(iw0 + k) < (unsigned)g.W) << (8 + k);
+            vmask[j] = m;
+            gQ[j] = prm.Q + (((int64_t)nb * g.H + ih0) * g.W + iw0) * g.Cpad + lchunk * 16;
         } else {
-            ih0[i] = iw0[i] = 0;
-            gQ[i] = prm.Q + (int64_t)(q0 + row) * prm.ldQ + c * 16;
+            vmask[j] = 0;
+            gQ[j] = prm.Q + (int64_t)row * prm.ldQ + lchunk * 16;
         }
     }
-    // conv: position of the next K-step to load, as (kh, kw, channel offset)
+    // conv: position of the next K-step to issue, as (kh, kw, channel offset)
     int l_kh = 0, l_kw = 0, l_cc = 0;
+    const int8_t* zero_page = (const int8_t*)g_zero16;
 
-    v4i rP[LP], rQ[LQ];
-    const v4i zero4 = {0, 0, 0, 0};
-
-    auto load_step = [&](int kt) {
+    auto issue = [&](int kt) {
+        const unsigned sbase = lds0 + (unsigned)((kt % NS) * STAGE);
 #pragma unroll
-        for (int i = 0; i < LP; ++i)
-            rP[i] = okP[i] ? *(const v4i*)(gP[i] + (int64_t)kt * 64) : zero4;
+        for (int j = 0; j < LP; ++j)
+            dma16(gP[j] + (int64_t)kt * 64, __builtin_amdgcn_readfirstlane(sbase + (wave + 4 * j) * 1024));
         if (CONV) {
+            const int64_t koff = ((int64_t)l_kh * g.W + l_kw) * g.Cpad + l_cc;
 #pragma unroll
-            for (int i = 0; i < LQ; ++i) {
-                const int ih = ih0[i] + l_kh, iw = iw0[i] + l_kw;
-                const bool ok = okQ[i] && (unsigned)ih < (unsigned)g.H && (unsigned)iw < (unsigned)g.W;
-                const int64_t off = ((int64_t)ih * g.W + iw) * g.Cpad + l_cc;
-                rQ[i] = ok ? *(const v4i*)(gQ[i] + off) : zero4;
+            for (int j = 0; j < LQ; ++j) {
+                const bool ok = ((vmask[j] >> l_kh) & (vmask[j] >> (8 + l_kw)) & 1) != 0;
+                const int8_t* src = ok ? gQ[j] + koff : zero_page;
+                dma16(src, __builtin_amdgcn_readfirstlane(sbase + BP * 64 + (wave + 4 * j) * 1024));
             }
             l_cc += 64;
             if (l_cc == g.Cpad) {
@@ -151,15 +168,10 @@ __global__ __launch_bounds__(256) void k_tmm(TmmParams prm)
             }
         } else {
 #pragma unroll
-            for (int i = 0; i < LQ; ++i)
-                rQ[i] = okQ[i] ? *(const v4i*)(gQ[i] + (int64_t)kt * 64) : zero4;
+            for (int j = 0; j < LQ; ++j)
+                dma16(gQ[j] + (int64_t)kt * 64,
+                      __builtin_amdgcn_readfirstlane(sbase + BP * 64 + (wave + 4 * j) * 1024));
         }
-    };
-    auto store_step = [&](int stage) {
-#pragma unroll
-        for (int i = 0; i < LP; ++i) *(v4i*)(sP + stage * STAGE_P + ldsP[i]) = rP[i];
-#pragma unroll
-        for (int i = 0; i < LQ; ++i) *(v4i*)(sQ + stage * STAGE_Q + ldsQ[i]) = rQ[i];
     };
 
     // ---- fragment addressing ------------------------------------------------
@@ -176,8 +188,17 @@ __global__ __launch_bounds__(256) void k_tmm(TmmParams prm)
     for (int t = 0; t < TQ; ++t) {
         const int row = wq * WQ + t * 32 + (lane & 31);
 #pragma unroll
-        for (int ks = 0; ks < 2; ++ks) fragQ[t][ks] = row * 64 + (((ks * 2 + (lane >> 5)) ^ swz(row)) << 4);
+        for (int ks = 0; ks < 2; ++ks)
+            fragQ[t][ks] = BP * 64 + row * 64 + (((ks * 2 + (lane >> 5)) ^ swz(row)) << 4);
     }
+    v4i fa[2][TP], fb[2][TQ];
+    auto load_frags = [&](int kt, int ks) {
+        const int8_t* st = smem + (kt % NS) * STAGE;
+#pragma unroll
+        for (int t = 0; t < TP; ++t) fa[ks][t] = *(const v4i*)(st + fragP[t][ks]);
+#pragma unroll
+        for (int t = 0; t < TQ; ++t) fb[ks][t] = *(const v4i*)(st + fragQ[t][ks]);
+    };
 
     v16i acc[TP][TQ];
 #pragma unroll
@@ -186,53 +207,77 @@ __global__ __launch_bounds__(256) void k_tmm(TmmParams prm)
         for (int j = 0; j < TQ; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
+    auto mma = [&](int ks) {
+#pragma unroll
+        for (int i = 0; i < TP; ++i)
+#pragma unroll
+            for (int j = 0; j < TQ; ++j)
+                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[ks][i], fb[ks][j], acc[i][j], 0, 0, 0);
+    };
 
     // ---- main loop ------------------------------------------------------------
-    load_step(0);
-    store_step(0);
-    __syncthreads();
-    for (int kt = 0; kt < prm.nk; ++kt) {
-        const int cur = kt & 1;
-        const bool more = kt + 1 < prm.nk;
-        if (more) load_step(kt + 1);
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-            v4i fa[TP], fb[TQ];
-#pragma unroll
-            for (int t = 0; t < TP; ++t) fa[t] = *(const v4i*)(sP + cur * STAGE_P + fragP[t][ks]);
-#pragma unroll
-            for (int t = 0; t < TQ; ++t) fb[t] = *(const v4i*)(sQ + cur * STAGE_Q + fragQ[t][ks]);
-#pragma unroll
-            for (int i = 0; i < TP; ++i)
-#pragma unroll
-                for (int j = 0; j < TQ; ++j)
-                    acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[i], fb[j], acc[i][j], 0, 0, 0);
+    // Steps kt .. kt+NS-1 are in flight or resident while step kt is multiplied.
+    const int nk = prm.nk;
+    const int npro = nk < NS ? nk : NS;
+    for (int s = 0; s < npro; ++s) issue(s);
+    wait_groups<DPS>(npro - 1);
+    block_barrier();
+    load_frags(0, 0);
+    for (int kt = 0; kt < nk; ++kt) {
+        load_frags(kt, 1);
+        mma(0);
+        if (kt + 1 < nk) {
+            // Stage kt is fully in registers once the slice-1 fragments arrive;
+            // step kt+1 must have landed for every wave before anyone reads it.
+            wait_lgkm0();
+            const int inflight = nk - 2 - kt;  // groups issued after step kt+1
+            wait_groups<DPS>(inflight < NS - 2 ? inflight : NS - 2);
+            block_barrier();
+            if (kt + NS < nk) issue(kt + NS);  // refills the stage just freed
+            load_frags(kt + 1, 0);
         }
-        if (more) store_step(cur ^ 1);
-        __syncthreads();
+        mma(1);
     }
 
     // ---- epilogue ---------------------------------------------------------------
     // acc[i][j][r] is D at P-row  wp*WP + i*32 + 8*(r/4) + 4*(lane/32) + r%4
     //                  and Q-row  wq*WQ + j*32 + lane%32.
+    // Per-P-row factors are staged once per block in LDS as doubles.
     const EpiArgs& ep = prm.ep;
     const bool has_bn = ep.bn_scale != nullptr;
+    double* tab = (double*)smem;  // [5][BP]
+    __syncthreads();              // all waves are done with the operand stages
     if (!CONV) {
+        // y = aw*(aa*D + ba*Sw) + bw*(aa*Sa + K*ba); per row m: aa, ba, r2 = aa*Sa + K*ba
+        if (prm.y) {
+            for (int t = tid; t < BP; t += 256) {
+                const int m = p0 + t;
+                double aa = 0.0, ba = 0.0, r2 = 0.0;
+                if (m < prm.RP) {
+                    aa = pval(ep.alpha_a, m);
+                    ba = pval(ep.beta_a, m);
+                    r2 = aa * (double)ep.sum_ta[m] + (double)prm.Klogical * ba;
+                }
+                tab[t] = aa;
+                tab[BP + t] = ba;
+                tab[2 * BP + t] = r2;
+            }
+        }
+        __syncthreads();
         const int64_t N = prm.RQ;
         int ncol[TQ];
         bool nok[TQ];
-        double aw[TQ], bw[TQ], bs[TQ], bh[TQ];
-        int Sw[TQ];
+        double aw[TQ], bw[TQ], bs[TQ], bh[TQ], sw[TQ];
 #pragma unroll
         for (int j = 0; j < TQ; ++j) {
             ncol[j] = q0 + wq * WQ + j * 32 + (lane & 31);
             nok[j] = ncol[j] < prm.RQ;
-            aw[j] = bw[j] = bs[j] = bh[j] = 0.0;
-            Sw[j] = 0;
+            aw[j] = bw[j] = bh[j] = sw[j] = 0.0;
+            bs[j] = 1.0;
             if (prm.y && nok[j]) {
                 aw[j] = pval(ep.alpha_w, ncol[j]);
                 bw[j] = pval(ep.beta_w, ncol[j]);
-                Sw[j] = ep.sum_tw[ncol[j]];
+                sw[j] = (double)ep.sum_tw[ncol[j]];
                 if (has_bn) {
                     bs[j] = ep.bn_scale[ncol[j]];
                     bh[j] = ep.bn_shift ? (double)ep.bn_shift[ncol[j]] : 0.0;
@@ -243,32 +288,55 @@ __global__ __launch_bounds__(256) void k_tmm(TmmParams prm)
         for (int i = 0; i < TP; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int m = p0 + wp * WP + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                const int t = wp * WP + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                const int m = p0 + t;
                 const bool mok = m < prm.RP;
-                double aa = 0.0, ba = 0.0;
-                int Sa = 0;
-                if (prm.y && mok) {
-                    aa = pval(ep.alpha_a, m);
-                    ba = pval(ep.beta_a, m);
-                    Sa = ep.sum_ta[m];
-                }
+                const double aa = tab[t], ba = tab[BP + t], r2 = tab[2 * BP + t];
 #pragma unroll
                 for (int j = 0; j < TQ; ++j) {
                     if (mok && nok[j]) {
                         const int D = acc[i][j][r];
                         const int64_t idx = (int64_t)m * N + ncol[j];
                         if (prm.acc) prm.acc[idx] = D;
-                        if (prm.y)
-                            prm.y[idx] = reparam(aa, ba, aw[j], bw[j], D, Sa, Sw[j], prm.Klogical,
-                                                 ep.relu, has_bn, bs[j], bh[j]);
+                        if (prm.y) {
+                            double v = aw[j] * (aa * (double)D + ba * sw[j]) + bw[j] * r2;
+                            if (ep.relu) v = v < 0.0 ? 0.0 : v;
+                            if (has_bn) v = bs[j] * v + bh[j];
+                            prm.y[idx] = (float)v;
+                        }
                     }
                 }
             }
     } else {
+        // y = g1[o]*D + c2[o]*Sa[m] + Cst[class(m)][o]
+        //   g1 = aa*aw, c2 = aa*bw, Cst = ba*aw*Sw[class] + Kv[class]*ba*bw
         const int ohw = g.OH * g.OW;
-        const double aa = (double)ep.alpha_a.s, ba = (double)ep.beta_a.s;
+        const int full_cls = (g.KH - 1) * g.KW * g.KW + (g.KW - 1);  // taps [0..KH-1] x [0..KW-1]
+        if (prm.y) {
+            const double aa = (double)ep.alpha_a.s;
+            for (int t = tid; t < BP; t += 256) {
+                const int o = p0 + t;
+                double g1 = 0.0, c2 = 0.0, cf = 0.0, bs = 1.0, bh = 0.0;
+                if (o < prm.RP) {
+                    g1 = aa * pval(ep.alpha_w, o);
+                    c2 = aa * pval(ep.beta_w, o);
+                    cf = prm.cst_cls[(int64_t)full_cls * g.O + o];
+                    if (has_bn) {
+                        bs = (double)ep.bn_scale[o];
+                        bh = ep.bn_shift ? (double)ep.bn_shift[o] : 0.0;
+                    }
+                }
+                tab[t] = g1;
+                tab[BP + t] = c2;
+                tab[2 * BP + t] = cf;
+                tab[3 * BP + t] = bs;
+                tab[4 * BP + t] = bh;
+            }
+        }
+        __syncthreads();
         bool mok[TQ];
-        int Sa[TQ], Kv[TQ], cls[TQ];
+        double Sa[TQ];
+        int cls[TQ];
         int64_t obase[TQ];
 #pragma unroll
         for (int j = 0; j < TQ; ++j) {
@@ -277,24 +345,31 @@ __global__ __launch_bounds__(256) void k_tmm(TmmParams prm)
             const int mm = mok[j] ? m : 0;
             const int nb = mm / ohw, pix = mm - nb * ohw;
             obase[j] = (int64_t)nb * g.O * ohw + pix;
-            Sa[j] = Kv[j] = cls[j] = 0;
-            if (prm.y) pixel_terms(g, ep.sum_ta, nb, pix, Sa[j], Kv[j], cls[j]);
+            Sa[j] = 0.0;
+            cls[j] = full_cls;
+            if (prm.y) {
+                const int oh = pix / g.OW, ow = pix - oh * g.OW;
+                int khl, khh, kwl, kwh;
+                tap_range(oh, g.stride, g.pad, g.KH, g.H, khl, khh);
+                tap_range(ow, g.stride, g.pad, g.KW, g.W, kwl, kwh);
+                const int32_t* ps = ep.sum_ta + (int64_t)nb * g.H * g.W;
+                int s = 0;
+                for (int kh = khl; kh <= khh; ++kh)
+                    for (int kw = kwl; kw <= kwh; ++kw)
+                        s += ps[(oh * g.stride - g.pad + kh) * g.W + (ow * g.stride - g.pad + kw)];
+                Sa[j] = (double)s;
+                if (!g.code_zero_pad) cls[j] = ((khl * g.KH + khh) * g.KW + kwl) * g.KW + kwh;
+            }
         }
 #pragma unroll
         for (int i = 0; i < TP; ++i)
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int o = p0 + wp * WP + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                const int t = wp * WP + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                const int o = p0 + t;
                 const bool ook = o < prm.RP;
-                double aw = 0.0, bw = 0.0, bs = 1.0, bh = 0.0;
-                if (prm.y && ook) {
-                    aw = pval(ep.alpha_w, o);
-                    bw = pval(ep.beta_w, o);
-                    if (has_bn) {
-                        bs = (double)ep.bn_scale[o];
-                        bh = ep.bn_shift ? (double)ep.bn_shift[o] : 0.0;
-                    }
-                }
+                const double g1 = tab[t], c2 = tab[BP + t], cf = tab[2 * BP + t];
+                const double bs = tab[3 * BP + t], bh = tab[4 * BP + t];
 #pragma unroll
                 for (int j = 0; j < TQ; ++j) {
                     if (ook && mok[j]) {
@@ -302,8 +377,12 @@ __global__ __launch_bounds__(256) void k_tmm(TmmParams prm)
                         const int64_t idx = obase[j] + (int64_t)o * ohw;
                         if (prm.acc) prm.acc[idx] = D;
                         if (prm.y) {
-                            const int Sw = prm.sw_cls[(int64_t)cls[j] * g.O + o];
-                            prm.y[idx] = reparam(aa, ba, aw, bw, D, Sa[j], Sw, Kv[j], ep.relu, has_bn, bs, bh);
+                            double c = cf;
+                            if (cls[j] != full_cls) c = prm.cst_cls[(int64_t)cls[j] * g.O + o];
+                            double v = g1 * (double)D + c2 * Sa[j] + c;
+                            if (ep.relu) v = v < 0.0 ? 0.0 : v;
+                            if (has_bn) v = bs * v + bh;
+                            prm.y[idx] = (float)v;
                         }
                     }
                 }
@@ -311,10 +390,13 @@ __global__ __launch_bounds__(256) void k_tmm(TmmParams prm)
     }
 }
 
-// Filter sums per border class.  A class is the in-bounds tap rectangle
-// [khl..khh] x [kwl..kwh] of an output pixel; sw_cls[class][o] is the sum of
-// the per-tap channel sums of filter o over that rectangle (0 if empty).
-__global__ __launch_bounds__(256) void k_conv_class_sums(const int32_t* tap, ConvGeom g, int32_t* sw_cls)
+// Constants of the reparameterization per border class.  A class is the
+// in-bounds tap rectangle [khl..khh] x [kwl..kwh] of an output pixel;
+//   cst[class][o] = ba*aw[o]*Sw + Kv*ba*bw[o]
+// with Sw the sum of filter o's per-tap channel sums over the rectangle and
+// Kv = C * (number of taps in it): Eq.9's pre-stored constant C, one per class.
+__global__ __launch_bounds__(256) void k_conv_class_consts(const int32_t* tap, ConvGeom g, Param alpha_w,
+                                                           Param beta_w, float beta_a, double* cst)
 {
     const int ncls = g.KH * g.KH * g.KW * g.KW;
     const int64_t total = (int64_t)ncls * g.O;
@@ -327,18 +409,23 @@ __global__ __launch_bounds__(256) void k_conv_class_sums(const int32_t* tap, Con
     const int kwl = cls % g.KW;
     cls /= g.KW;
     const int khh = cls % g.KH, khl = cls / g.KH;
-    int s = 0;
+    int s = 0, taps = 0;
     for (int kh = khl; kh <= khh; ++kh)
-        for (int kw = kwl; kw <= kwh; ++kw) s += tap[((int64_t)o * g.KH + kh) * g.KW + kw];
-    sw_cls[i] = s;
+        for (int kw = kwl; kw <= kwh; ++kw) {
+            s += tap[((int64_t)o * g.KH + kh) * g.KW + kw];
+            ++taps;
+        }
+    const double ba = (double)beta_a;
+    cst[i] = ba * pval(alpha_w, o) * (double)s + (double)(g.C * taps) * ba * pval(beta_w, o);
 }
 
-template <int BP, int BQ, int WGP, int WGQ, bool CONV>
+template <int BP, int BQ, int WGP, int WGQ, int NS, bool CONV>
 hipError_t launch_cfg(TmmParams& prm, hipStream_t st)
 {
-    constexpr int smem = 2 * (BP + BQ) * 64;
+    constexpr int stage_bytes = NS * (BP + BQ) * 64, tab_bytes = 5 * BP * 8;
+    constexpr int smem = stage_bytes > tab_bytes ? stage_bytes : tab_bytes;
     static bool attr_done = false;
-    auto kern = k_tmm<BP, BQ, WGP, WGQ, CONV>;
+    auto kern = k_tmm<BP, BQ, WGP, WGQ, NS, CONV>;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
         if (e != hipSuccess) return e;
@@ -365,12 +452,12 @@ template <bool CONV>
 hipError_t launch_index(int cfg, TmmParams& prm, hipStream_t st)
 {
     switch (cfg) {
-        case 0: return launch_cfg<64, 64, 2, 2, CONV>(prm, st);
-        case 1: return launch_cfg<128, 128, 2, 2, CONV>(prm, st);
-        case 2: return launch_cfg<256, 256, 2, 2, CONV>(prm, st);
-        case 3: return launch_cfg<64, 256, 1, 4, CONV>(prm, st);
-        case 4: return launch_cfg<128, 256, 2, 2, CONV>(prm, st);
-        case 5: return launch_cfg<256, 128, 2, 2, CONV>(prm, st);
+        case 0: return launch_cfg<64, 64, 2, 2, 4, CONV>(prm, st);
+        case 1: return launch_cfg<128, 128, 2, 2, 4, CONV>(prm, st);
+        case 2: return launch_cfg<256, 256, 2, 2, 4, CONV>(prm, st);
+        case 3: return launch_cfg<64, 256, 1, 4, 3, CONV>(prm, st);
+        case 4: return launch_cfg<128, 256, 2, 2, 3, CONV>(prm, st);
+        case 5: return launch_cfg<256, 128, 2, 2, 3, CONV>(prm, st);
         default: return hipErrorInvalidValue;
     }
 }
@@ -393,12 +480,12 @@ int pick_tile(int64_t rp, int64_t rq)
 int tile_config_count() { return kNumTileConfigs; }
 void force_tile_config(int index) { g_forced_tile = index; }
 
-hipError_t launch_conv_class_sums(const int32_t* tap_sums, const ConvGeom& g, int32_t* sw_cls,
-                                  hipStream_t st)
+hipError_t launch_conv_class_consts(const ConvArgs& a, double* cst, hipStream_t st)
 {
+    const ConvGeom& g = a.g;
     const int64_t total = (int64_t)g.KH * g.KH * g.KW * g.KW * g.O;
-    hipLaunchKernelGGL(k_conv_class_sums, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                       tap_sums, g, sw_cls);
+    hipLaunchKernelGGL(k_conv_class_consts, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
+                       a.ep.sum_tw, g, a.ep.alpha_w, a.ep.beta_w, a.ep.beta_a.s, cst);
     return hipGetLastError();
 }
 
@@ -434,7 +521,7 @@ hipError_t launch_conv_mfma(const ConvArgs& a, hipStream_t st)
     prm.g = g;
     prm.acc = a.acc;
     prm.y = a.y;
-    prm.sw_cls = a.sw_cls;
+    prm.cst_cls = a.cst_cls;
     prm.ep = a.ep;
     const int cfg = g_forced_tile >= 0 ? g_forced_tile : pick_tile(g.O, prm.RQ);
     return launch_index<true>(cfg, prm, st);

@@ -39,7 +39,7 @@ def test_helpers(L):
     assert L.rtn_codes_bytes(B.RTN_CODE_I8, 3, 70) == 3 * 128
     assert L.rtn_codes_bytes(B.RTN_CODE_BITPLANE, 3, 70) == 3 * 2 * 8 * 2
     assert L.rtn_codes_bytes(7, 3, 70) == 0
-    assert L.rtn_conv2d_workspace_bytes(64, 3, 3) == 64 * 81 * 4
+    assert L.rtn_conv2d_workspace_bytes(64, 3, 3) == 64 * 81 * 8
     assert L.rtn_status_string(0) == b"ok"
     for s in range(-6, 0):
         assert len(L.rtn_status_string(s)) > 3
