@@ -101,7 +101,8 @@ __global__ __launch_bounds__(256) void k_tmm(TmmParams prm)
     extern __shared__ __attribute__((aligned(16))) int8_t smem[];
     const unsigned lds0 = (unsigned)(uintptr_t)smem;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, lives in an SGPR
     const int wp = wave / WGQ, wq = wave % WGQ;
     const int tileP = blockIdx.x % prm.tilesP, tileQ = blockIdx.x / prm.tilesP;
     const int p0 = tileP * BP, q0 = tileQ * BQ;
@@ -223,21 +224,34 @@ __global__ __launch_bounds__(256) void k_tmm(TmmParams prm)
     wait_groups<DPS>(npro - 1);
     block_barrier();
     load_frags(0, 0);
-    for (int kt = 0; kt < nk; ++kt) {
+    int kt = 0;
+    // Steady state: between the two k-slices, stage kt is fully in registers
+    // (slice-1 fragments waited for), step kt+1 has landed for this wave
+    // (all but the NS-2 younger load groups done) and, after the barrier, for
+    // every wave; the freed stage is refilled with step kt+NS.
+    for (; kt + NS < nk; ++kt) {
         load_frags(kt, 1);
         mma(0);
-        if (kt + 1 < nk) {
-            // Stage kt is fully in registers once the slice-1 fragments arrive;
-            // step kt+1 must have landed for every wave before anyone reads it.
-            wait_lgkm0();
-            const int inflight = nk - 2 - kt;  // groups issued after step kt+1
-            wait_groups<DPS>(inflight < NS - 2 ? inflight : NS - 2);
-            block_barrier();
-            if (kt + NS < nk) issue(kt + NS);  // refills the stage just freed
-            load_frags(kt + 1, 0);
-        }
+        wait_lgkm0();
+        wait_vm<(NS - 2) * DPS>();
+        block_barrier();
+        issue(kt + NS);
+        load_frags(kt + 1, 0);
         mma(1);
     }
+    // Drain: nothing left to issue.
+    for (; kt + 1 < nk; ++kt) {
+        load_frags(kt, 1);
+        mma(0);
+        wait_lgkm0();
+        wait_vm<0>();
+        block_barrier();
+        load_frags(kt + 1, 0);
+        mma(1);
+    }
+    load_frags(kt, 1);
+    mma(0);
+    mma(1);
 
     // ---- epilogue ---------------------------------------------------------------
     // acc[i][j][r] is D at P-row  wp*WP + i*32 + 8*(r/4) + 4*(lane/32) + r%4
