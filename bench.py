@@ -73,7 +73,7 @@ def main():
             ca = torch.empty((args.batch, sh.H, sh.H, Cp), dtype=torch.int8, device=dev)
             pa = torch.empty((args.batch, sh.H, sh.H), dtype=torch.int32, device=dev)
             y = torch.empty((args.batch, sh.O, sh.OH, sh.OH), dtype=torch.float32, device=dev)
-            ws = torch.empty(B.conv2d_workspace_bytes(sh.O, sh.k, sh.k), dtype=torch.uint8, device=dev)
+            ws = torch.empty(B.conv2d_workspace_bytes(sh.O, sh.k, sh.k, sh.pad), dtype=torch.uint8, device=dev)
             ep = B.Epilogue(garg(case["alpha_a"]), garg(case["beta_a"]), garg(case["alpha_w"]),
                             garg(case["beta_w"]), pa, pw, relu=True,
                             bn_scale=to_dev(case["bn_scale"]), bn_shift=to_dev(case["bn_shift"]))

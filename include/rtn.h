@@ -29,7 +29,7 @@
  *     then returns the hipError_t as an int.
  *   - Code tensors must be 16-byte aligned; fp32/int32 tensors 4-byte aligned.
  *   - Sizes: every dimension and the products noted per function must be
- *     below 2^31; K must be at most 2^24 so that D is exact in int32/fp32.
+ *     below 2^31; K (padded) must be at most 2^22, so D is exact in int32 and fp32.
  */
 #ifndef RTN_H
 #define RTN_H
@@ -162,12 +162,12 @@ int rtn_ternary_gemm(rtn_code_format fmt, rtn_path path, const void *a_codes, co
  *   OH = (H + 2*pad - KH)/stride + 1; a tap outside the image adds 0 to D.
  *   a_codes: [Nb][H][W][Cpad]; w_codes: [O][KH][KW][Cpad] (RTN_CODE_I8 only).
  *   acc_out: int32 [Nb][O][OH][OW] or NULL; y_out: fp32 [Nb][O][OH][OW] (NCHW).
- *   KH, KW in 1..7, stride >= 1, 0 <= pad < KH, KW.
- *   workspace: at least rtn_conv2d_workspace_bytes(O, KH, KW) bytes when an
+ *   KH, KW in 1..7, stride in 1..64, 0 <= pad < min(KH, KW), pad <= 3.
+ *   workspace: at least rtn_conv2d_workspace_bytes(O, KH, KW, pad) bytes when an
  *   epilogue is given (holds Eq.9's constant per border class and
  *   filter), 8-byte aligned.
  *   Nb*H*W and Nb*OH*OW must be below 2^31.                                  */
-size_t rtn_conv2d_workspace_bytes(int64_t O, int KH, int KW);
+size_t rtn_conv2d_workspace_bytes(int64_t O, int KH, int KW, int pad);
 int rtn_ternary_conv2d_implicit_gemm(rtn_code_format fmt, rtn_path path, const void *a_codes,
                                      const void *w_codes, int64_t Nb, int64_t C, int64_t H,
                                      int64_t W, int64_t O, int KH, int KW, int stride, int pad,

@@ -66,7 +66,7 @@ def lib():
         L.rtn_ternary_gemm.restype = ci
         L.rtn_ternary_gemm.argtypes = [ci, ci, vp, vp, i64, i64, i64, vp, vp, vp, vp, C.c_size_t, vp]
         L.rtn_conv2d_workspace_bytes.restype = C.c_size_t
-        L.rtn_conv2d_workspace_bytes.argtypes = [i64, ci, ci]
+        L.rtn_conv2d_workspace_bytes.argtypes = [i64, ci, ci, ci]
         L.rtn_ternary_conv2d_implicit_gemm.restype = ci
         L.rtn_ternary_conv2d_implicit_gemm.argtypes = [ci, ci, vp, vp, i64, i64, i64, i64, i64, ci, ci,
                                                        ci, ci, ci, vp, vp, vp, vp, C.c_size_t, vp]
@@ -183,8 +183,8 @@ def ternary_gemm(a_codes, w_codes, M, N, K, fmt=RTN_CODE_I8, path=RTN_PATH_AUTO,
     return acc_out, y_out
 
 
-def conv2d_workspace_bytes(O, KH, KW):
-    return lib().rtn_conv2d_workspace_bytes(O, KH, KW)
+def conv2d_workspace_bytes(O, KH, KW, pad):
+    return lib().rtn_conv2d_workspace_bytes(O, KH, KW, pad)
 
 
 def conv_out_hw(H, W, KH, KW, stride, pad):
@@ -202,7 +202,7 @@ def ternary_conv2d(a_codes, w_codes, Nb, Cc, H, W, O, KH, KW, stride, pad, pad_m
     if ep is not None and y_out is None:
         y_out = torch.empty((Nb, O, OH, OW), dtype=torch.float32, device=dev)
     if ep is not None and workspace is None:
-        workspace = torch.empty(conv2d_workspace_bytes(O, KH, KW), dtype=torch.uint8, device=dev)
+        workspace = torch.empty(conv2d_workspace_bytes(O, KH, KW, pad), dtype=torch.uint8, device=dev)
     rc = lib().rtn_ternary_conv2d_implicit_gemm(
         fmt, path, C.c_void_p(a_codes.data_ptr()), C.c_void_p(w_codes.data_ptr()), Nb, Cc, H, W, O, KH, KW,
         stride, pad, pad_mode, None if acc_out is None else _dev(acc_out, torch.int32),

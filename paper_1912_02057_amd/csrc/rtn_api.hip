@@ -17,7 +17,8 @@ int hip_fail(hipError_t e)
 }
 
 constexpr int64_t kMaxDim = 0x7fffffffLL - 1024;
-constexpr int64_t kMaxK = 1LL << 24;
+constexpr int64_t kMaxK = 1LL << 22;
+constexpr int kMaxPad = 3;
 
 bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 int64_t pad64(int64_t k) { return (k + 63) / 64 * 64; }
@@ -69,7 +70,7 @@ int make_geom(int64_t Nb, int64_t C, int64_t H, int64_t W, int64_t O, int KH, in
     if (Nb <= 0 || C <= 0 || H <= 0 || W <= 0 || O <= 0) return RTN_ERR_SHAPE;
     if (Nb > kMaxDim || C > kMaxDim || H > kMaxDim || W > kMaxDim || O > kMaxDim) return RTN_ERR_SHAPE;
     if (KH < 1 || KW < 1 || KH > 7 || KW > 7 || stride < 1 || stride > 64) return RTN_ERR_UNSUPPORTED;
-    if (pad < 0 || pad >= KH || pad >= KW) return RTN_ERR_UNSUPPORTED;
+    if (pad < 0 || pad >= KH || pad >= KW || pad > kMaxPad) return RTN_ERR_UNSUPPORTED;
     if (pad_mode != RTN_PAD_TRUE_ZERO && pad_mode != RTN_PAD_CODE_ZERO) return RTN_ERR_UNSUPPORTED;
     if (H + 2 * pad < KH || W + 2 * pad < KW) return RTN_ERR_SHAPE;
     const int64_t OH = (H + 2 * pad - KH) / stride + 1, OW = (W + 2 * pad - KW) / stride + 1;
@@ -210,10 +211,12 @@ int rtn_ternary_gemm(rtn_code_format fmt, rtn_path path, const void* a_codes, co
     return he == hipSuccess ? RTN_OK : hip_fail(he);
 }
 
-size_t rtn_conv2d_workspace_bytes(int64_t O, int KH, int KW)
+size_t rtn_conv2d_workspace_bytes(int64_t O, int KH, int KW, int pad)
 {
     if (O <= 0 || KH < 1 || KW < 1 || KH > 7 || KW > 7) return 0;
-    return (size_t)O * (size_t)(KH * KH * KW * KW) * sizeof(double);
+    if (pad < 0 || pad >= KH || pad >= KW || pad > kMaxPad) return 0;
+    const int p1 = pad + 1;
+    return (size_t)O * (size_t)(p1 * p1 * p1 * p1) * sizeof(double);
 }
 
 int rtn_ternary_conv2d_implicit_gemm(rtn_code_format fmt, rtn_path path, const void* a_codes,
@@ -234,7 +237,7 @@ int rtn_ternary_conv2d_implicit_gemm(rtn_code_format fmt, rtn_path path, const v
         return RTN_ERR_ALIGN;
     if (ep) {
         if ((rc = make_epilogue(ep, true, c.ep)) != RTN_OK) return rc;
-        if (!workspace || workspace_bytes < rtn_conv2d_workspace_bytes(O, KH, KW)) return RTN_ERR_WORKSPACE;
+        if (!workspace || workspace_bytes < rtn_conv2d_workspace_bytes(O, KH, KW, pad)) return RTN_ERR_WORKSPACE;
         if (!aligned(workspace, 8)) return RTN_ERR_ALIGN;
     }
     c.a = (const int8_t*)a_codes;

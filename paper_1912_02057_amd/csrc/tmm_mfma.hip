@@ -25,6 +25,8 @@
 // direct load writes 1 KiB of LDS, lane l at +16*l, i.e. 16 rows of 64 bytes;
 // which global 16-byte chunk a lane fetches is permuted (XOR swizzle by row) so
 // that the 16-byte fragment reads of 16 consecutive rows hit all 64 banks.
+#include <type_traits>
+
 #include "epilogue_math.h"
 #include "rtn_kernels.h"
 
@@ -94,6 +96,7 @@ __global__ __launch_bounds__(256) void k_tmm(TmmParams prm)
     constexpr int WP = BP / WGP, WQ = BQ / WGQ, TP = WP / 32, TQ = WQ / 32;
     constexpr int LP = BP / 64, LQ = BQ / 64;  // direct loads per wave per K-step
     constexpr int DPS = LP + LQ;
+    constexpr int NM = TP * TQ;  // MFMAs per k-slice
     static_assert(TP >= 1 && TQ >= 1 && LP >= 1 && LQ >= 1, "tile too small");
     static_assert(NS >= 2 && NS <= 4 && 3 * DPS < 64, "vmcnt range");
     constexpr int STAGE = (BP + BQ) * 64;  // bytes; P tile first, then Q tile
@@ -142,23 +145,21 @@ __global__ __launch_bounds__(256) void k_tmm(TmmParams prm)
             gQ[j] = prm.Q + (int64_t)row * prm.ldQ + lchunk * 16;
         }
     }
-    // conv: position of the next K-step to issue, as (kh, kw, channel offset)
+    // K position of the step being issued: byte offset into a dense row, or for
+    // the conv's Q operand the tap (kh, kw) and the offset of its 64 channels.
     int l_kh = 0, l_kw = 0, l_cc = 0;
+    int64_t is_koffP = 0, is_koffQ = 0;
+    unsigned is_sbase = 0;
+    int is_kh = 0, is_kw = 0;
     const int8_t* zero_page = (const int8_t*)g_zero16;
 
-    auto issue = [&](int kt) {
-        const unsigned sbase = lds0 + (unsigned)((kt % NS) * STAGE);
-#pragma unroll
-        for (int j = 0; j < LP; ++j)
-            dma16(gP[j] + (int64_t)kt * 64, __builtin_amdgcn_readfirstlane(sbase + (wave + 4 * j) * 1024));
+    auto issue_begin = [&](int kt) {
+        is_sbase = lds0 + (unsigned)((kt % NS) * STAGE);
+        is_koffP = (int64_t)kt * 64;
         if (CONV) {
-            const int64_t koff = ((int64_t)l_kh * g.W + l_kw) * g.Cpad + l_cc;
-#pragma unroll
-            for (int j = 0; j < LQ; ++j) {
-                const bool ok = ((vmask[j] >> l_kh) & (vmask[j] >> (8 + l_kw)) & 1) != 0;
-                const int8_t* src = ok ? gQ[j] + koff : zero_page;
-                dma16(src, __builtin_amdgcn_readfirstlane(sbase + BP * 64 + (wave + 4 * j) * 1024));
-            }
+            is_kh = l_kh;
+            is_kw = l_kw;
+            is_koffQ = ((int64_t)l_kh * g.W + l_kw) * g.Cpad + l_cc;
             l_cc += 64;
             if (l_cc == g.Cpad) {
                 l_cc = 0;
@@ -168,11 +169,27 @@ __global__ __launch_bounds__(256) void k_tmm(TmmParams prm)
                 }
             }
         } else {
-#pragma unroll
-            for (int j = 0; j < LQ; ++j)
-                dma16(gQ[j] + (int64_t)kt * 64,
-                      __builtin_amdgcn_readfirstlane(sbase + BP * 64 + (wave + 4 * j) * 1024));
+            is_koffQ = is_koffP;
         }
+    };
+    // the idx-th of the DPS direct loads of the step set up by issue_begin()
+    auto issue_one = [&](int idx) {
+        if (idx < LP) {
+            dma16(gP[idx] + is_koffP, is_sbase + (wave + 4 * idx) * 1024);
+        } else {
+            const int j = idx - LP;
+            const int8_t* src = gQ[j] + is_koffQ;
+            if (CONV) {
+                const bool ok = ((vmask[j] >> is_kh) & (vmask[j] >> (8 + is_kw)) & 1) != 0;
+                src = ok ? src : zero_page;
+            }
+            dma16(src, is_sbase + BP * 64 + (wave + 4 * j) * 1024);
+        }
+    };
+    auto issue = [&](int kt) {
+        issue_begin(kt);
+#pragma unroll
+        for (int i = 0; i < DPS; ++i) issue_one(i);
     };
 
     // ---- fragment addressing ------------------------------------------------
@@ -215,12 +232,70 @@ __global__ __launch_bounds__(256) void k_tmm(TmmParams prm)
             for (int j = 0; j < TQ; ++j)
                 acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[ks][i], fb[ks][j], acc[i][j], 0, 0, 0);
     };
+    // The MFMAs of a k-slice with the DPS direct loads of step kt spread evenly
+    // between them, so that load issue hides behind matrix-core time.
+    auto mma_issue = [&](int ks, int kt) {
+        issue_begin(kt);
+#pragma unroll
+        for (int n = 0; n < NM; ++n) {
+            acc[n / TQ][n % TQ] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[ks][n / TQ], fb[ks][n % TQ],
+                                                                        acc[n / TQ][n % TQ], 0, 0, 0);
+#pragma unroll
+            for (int d = n * DPS / NM; d < (n + 1) * DPS / NM; ++d) issue_one(d);
+        }
+    };
 
-    // ---- main loop ------------------------------------------------------------
-    // Steps kt .. kt+NS-1 are in flight or resident while step kt is multiplied.
+    // ---- prologue: start the first NS steps, then per-lane epilogue terms -----
     const int nk = prm.nk;
     const int npro = nk < NS ? nk : NS;
     for (int s = 0; s < npro; ++s) issue(s);
+
+    // conv: for each of this lane's TQ output pixels, Sa (sum of the input-pixel
+    // channel sums over the in-bounds taps) and the border class, packed as
+    // (Sa << 8) | class.  Computed here so that the pixel-sum loads overlap the
+    // latency of the first operand loads.
+    //   class = rid * (pad+1)^2 + cid,  rid = khl + (pad+1)*(KH-1-khh), cid likewise;
+    //   class 0 is the interior (all taps in bounds).
+    int pixinfo[TQ];
+#pragma unroll
+    for (int j = 0; j < TQ; ++j) pixinfo[j] = 0;
+    if (CONV && prm.y) {
+        const int ohw = g.OH * g.OW, p1 = g.pad + 1;
+#pragma unroll
+        for (int j = 0; j < TQ; ++j) {
+            int m = q0 + wq * WQ + j * 32 + (lane & 31);
+            m = m < prm.RQ ? m : prm.RQ - 1;
+            const int nb = m / ohw, pix = m - nb * ohw;
+            const int oh = pix / g.OW, ow = pix - oh * g.OW;
+            const int ih0 = oh * g.stride - g.pad, iw0 = ow * g.stride - g.pad;
+            int khl, khh, kwl, kwh;
+            tap_range(oh, g.stride, g.pad, g.KH, g.H, khl, khh);
+            tap_range(ow, g.stride, g.pad, g.KW, g.W, kwl, kwh);
+            const int32_t* ps = prm.ep.sum_ta + ((int64_t)nb * g.H + ih0) * g.W + iw0;
+            int s = 0;
+            if (g.KH == 3 && g.KW == 3) {
+                int v[9];
+#pragma unroll
+                for (int t = 0; t < 9; ++t) {
+                    const int kh = t / 3, kw = t % 3;
+                    const bool ok = kh >= khl && kh <= khh && kw >= kwl && kw <= kwh;
+                    v[t] = ok ? ps[kh * g.W + kw] : 0;
+                }
+#pragma unroll
+                for (int t = 0; t < 9; ++t) s += v[t];
+            } else {
+                for (int kh = khl; kh <= khh; ++kh)
+                    for (int kw = kwl; kw <= kwh; ++kw) s += ps[kh * g.W + kw];
+            }
+            int cls = 0;
+            if (!g.code_zero_pad)
+                cls = (khl + p1 * (g.KH - 1 - khh)) * p1 * p1 + (kwl + p1 * (g.KW - 1 - kwh));
+            pixinfo[j] = s * 256 + cls;
+        }
+    }
+
+    // ---- main loop ------------------------------------------------------------
+    // Steps kt .. kt+NS-1 are in flight or resident while step kt is multiplied.
     wait_groups<DPS>(npro - 1);
     block_barrier();
     load_frags(0, 0);
@@ -235,9 +310,8 @@ __global__ __launch_bounds__(256) void k_tmm(TmmParams prm)
         wait_lgkm0();
         wait_vm<(NS - 2) * DPS>();
         block_barrier();
-        issue(kt + NS);
         load_frags(kt + 1, 0);
-        mma(1);
+        mma_issue(1, kt + NS);
     }
     // Drain: nothing left to issue.
     for (; kt + 1 < nk; ++kt) {
@@ -256,13 +330,17 @@ __global__ __launch_bounds__(256) void k_tmm(TmmParams prm)
     // ---- epilogue ---------------------------------------------------------------
     // acc[i][j][r] is D at P-row  wp*WP + i*32 + 8*(r/4) + 4*(lane/32) + r%4
     //                  and Q-row  wq*WQ + j*32 + lane%32.
-    // Per-P-row factors are staged once per block in LDS as doubles.
+    // Per-P-row factors (and the conv's per-class constants) are staged once per
+    // block in LDS as doubles; a block whose tile lies fully inside the output
+    // takes the branch-free variant.
     const EpiArgs& ep = prm.ep;
     const bool has_bn = ep.bn_scale != nullptr;
-    double* tab = (double*)smem;  // [5][BP]
-    __syncthreads();              // all waves are done with the operand stages
+    const bool relu = ep.relu != 0;
+    double* tab = (double*)smem;
+    const bool full_tile = p0 + BP <= prm.RP && q0 + BQ <= prm.RQ;
+    __syncthreads();  // all waves are done with the operand stages
     if (!CONV) {
-        // y = aw*(aa*D + ba*Sw) + bw*(aa*Sa + K*ba); per row m: aa, ba, r2 = aa*Sa + K*ba
+        // y = aw*(aa*D + ba*Sw) + bw*r2 with r2 = aa*Sa + K*ba per row m; tab = [3][BP]
         if (prm.y) {
             for (int t = tid; t < BP; t += 256) {
                 const int m = p0 + t;
@@ -298,43 +376,49 @@ __global__ __launch_bounds__(256) void k_tmm(TmmParams prm)
                 }
             }
         }
+        auto run = [&](auto full) {
+            constexpr bool FULL = decltype(full)::value;
 #pragma unroll
-        for (int i = 0; i < TP; ++i)
+            for (int i = 0; i < TP; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int t = wp * WP + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                const int m = p0 + t;
-                const bool mok = m < prm.RP;
-                const double aa = tab[t], ba = tab[BP + t], r2 = tab[2 * BP + t];
+                for (int r = 0; r < 16; ++r) {
+                    const int t = wp * WP + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                    const int m = p0 + t;
+                    const bool mok = FULL || m < prm.RP;
+                    const double aa = tab[t], ba = tab[BP + t], r2 = tab[2 * BP + t];
 #pragma unroll
-                for (int j = 0; j < TQ; ++j) {
-                    if (mok && nok[j]) {
-                        const int D = acc[i][j][r];
-                        const int64_t idx = (int64_t)m * N + ncol[j];
-                        if (prm.acc) prm.acc[idx] = D;
-                        if (prm.y) {
-                            double v = aw[j] * (aa * (double)D + ba * sw[j]) + bw[j] * r2;
-                            if (ep.relu) v = v < 0.0 ? 0.0 : v;
-                            if (has_bn) v = bs[j] * v + bh[j];
-                            prm.y[idx] = (float)v;
+                    for (int j = 0; j < TQ; ++j) {
+                        if (FULL || (mok && nok[j])) {
+                            const int D = acc[i][j][r];
+                            const int64_t idx = (int64_t)m * N + ncol[j];
+                            if (prm.acc) prm.acc[idx] = D;
+                            if (prm.y) {
+                                double v = aw[j] * (aa * (double)D + ba * sw[j]) + bw[j] * r2;
+                                if (relu) v = __builtin_fmax(v, 0.0);
+                                if (has_bn) v = bs[j] * v + bh[j];
+                                prm.y[idx] = (float)v;
+                            }
                         }
                     }
                 }
-            }
+        };
+        if (full_tile)
+            run(std::true_type{});
+        else
+            run(std::false_type{});
     } else {
-        // y = g1[o]*D + c2[o]*Sa[m] + Cst[class(m)][o]
-        //   g1 = aa*aw, c2 = aa*bw, Cst = ba*aw*Sw[class] + Kv[class]*ba*bw
+        // y = g1[o]*D + c2[o]*Sa[m] + Cst[class(m)][o],  g1 = aa*aw, c2 = aa*bw;
+        // tab = [4 + ncls][BP]: g1, c2, bn scale, bn shift, then the class constants.
         const int ohw = g.OH * g.OW;
-        const int full_cls = (g.KH - 1) * g.KW * g.KW + (g.KW - 1);  // taps [0..KH-1] x [0..KW-1]
+        const int p1 = g.pad + 1, ncls = p1 * p1 * p1 * p1;
         if (prm.y) {
             const double aa = (double)ep.alpha_a.s;
             for (int t = tid; t < BP; t += 256) {
                 const int o = p0 + t;
-                double g1 = 0.0, c2 = 0.0, cf = 0.0, bs = 1.0, bh = 0.0;
+                double g1 = 0.0, c2 = 0.0, bs = 1.0, bh = 0.0;
                 if (o < prm.RP) {
                     g1 = aa * pval(ep.alpha_w, o);
                     c2 = aa * pval(ep.beta_w, o);
-                    cf = prm.cst_cls[(int64_t)full_cls * g.O + o];
                     if (has_bn) {
                         bs = (double)ep.bn_scale[o];
                         bh = ep.bn_shift ? (double)ep.bn_shift[o] : 0.0;
@@ -342,15 +426,19 @@ __global__ __launch_bounds__(256) void k_tmm(TmmParams prm)
                 }
                 tab[t] = g1;
                 tab[BP + t] = c2;
-                tab[2 * BP + t] = cf;
-                tab[3 * BP + t] = bs;
-                tab[4 * BP + t] = bh;
+                tab[2 * BP + t] = bs;
+                tab[3 * BP + t] = bh;
+            }
+            for (int e = tid; e < ncls * BP; e += 256) {
+                const int c = e / BP, t = e - c * BP;
+                const int o = p0 + t;
+                tab[(4 + c) * BP + t] = o < prm.RP ? prm.cst_cls[(int64_t)c * g.O + o] : 0.0;
             }
         }
         __syncthreads();
         bool mok[TQ];
         double Sa[TQ];
-        int cls[TQ];
+        const double* ctab[TQ];
         int64_t obase[TQ];
 #pragma unroll
         for (int j = 0; j < TQ; ++j) {
@@ -359,70 +447,63 @@ __global__ __launch_bounds__(256) void k_tmm(TmmParams prm)
             const int mm = mok[j] ? m : 0;
             const int nb = mm / ohw, pix = mm - nb * ohw;
             obase[j] = (int64_t)nb * g.O * ohw + pix;
-            Sa[j] = 0.0;
-            cls[j] = full_cls;
-            if (prm.y) {
-                const int oh = pix / g.OW, ow = pix - oh * g.OW;
-                int khl, khh, kwl, kwh;
-                tap_range(oh, g.stride, g.pad, g.KH, g.H, khl, khh);
-                tap_range(ow, g.stride, g.pad, g.KW, g.W, kwl, kwh);
-                const int32_t* ps = ep.sum_ta + (int64_t)nb * g.H * g.W;
-                int s = 0;
-                for (int kh = khl; kh <= khh; ++kh)
-                    for (int kw = kwl; kw <= kwh; ++kw)
-                        s += ps[(oh * g.stride - g.pad + kh) * g.W + (ow * g.stride - g.pad + kw)];
-                Sa[j] = (double)s;
-                if (!g.code_zero_pad) cls[j] = ((khl * g.KH + khh) * g.KW + kwl) * g.KW + kwh;
-            }
+            Sa[j] = (double)(pixinfo[j] >> 8);
+            ctab[j] = tab + (4 + (pixinfo[j] & 255)) * BP;
         }
+        auto run = [&](auto full) {
+            constexpr bool FULL = decltype(full)::value;
 #pragma unroll
-        for (int i = 0; i < TP; ++i)
+            for (int i = 0; i < TP; ++i)
 #pragma unroll
-            for (int r = 0; r < 16; ++r) {
-                const int t = wp * WP + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
-                const int o = p0 + t;
-                const bool ook = o < prm.RP;
-                const double g1 = tab[t], c2 = tab[BP + t], cf = tab[2 * BP + t];
-                const double bs = tab[3 * BP + t], bh = tab[4 * BP + t];
+                for (int r = 0; r < 16; ++r) {
+                    const int t = wp * WP + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                    const int o = p0 + t;
+                    const bool ook = FULL || o < prm.RP;
+                    const double g1 = tab[t], c2 = tab[BP + t];
+                    const double bs = tab[2 * BP + t], bh = tab[3 * BP + t];
 #pragma unroll
-                for (int j = 0; j < TQ; ++j) {
-                    if (ook && mok[j]) {
-                        const int D = acc[i][j][r];
-                        const int64_t idx = obase[j] + (int64_t)o * ohw;
-                        if (prm.acc) prm.acc[idx] = D;
-                        if (prm.y) {
-                            double c = cf;
-                            if (cls[j] != full_cls) c = prm.cst_cls[(int64_t)cls[j] * g.O + o];
-                            double v = g1 * (double)D + c2 * Sa[j] + c;
-                            if (ep.relu) v = v < 0.0 ? 0.0 : v;
-                            if (has_bn) v = bs * v + bh;
-                            prm.y[idx] = (float)v;
+                    for (int j = 0; j < TQ; ++j) {
+                        if (FULL || (ook && mok[j])) {
+                            const int D = acc[i][j][r];
+                            const int64_t idx = obase[j] + (int64_t)o * ohw;
+                            if (prm.acc) prm.acc[idx] = D;
+                            if (prm.y) {
+                                double v = g1 * (double)D + (c2 * Sa[j] + ctab[j][t]);
+                                if (relu) v = __builtin_fmax(v, 0.0);
+                                if (has_bn) v = bs * v + bh;
+                                prm.y[idx] = (float)v;
+                            }
                         }
                     }
                 }
-            }
+        };
+        if (full_tile)
+            run(std::true_type{});
+        else
+            run(std::false_type{});
     }
 }
 
 // Constants of the reparameterization per border class.  A class is the
-// in-bounds tap rectangle [khl..khh] x [kwl..kwh] of an output pixel;
-//   cst[class][o] = ba*aw[o]*Sw + Kv*ba*bw[o]
+// in-bounds tap rectangle [khl..khh] x [kwl..kwh] of an output pixel, indexed
+//   class = rid * (pad+1)^2 + cid,  rid = khl + (pad+1)*(KH-1-khh),  cid = kwl + (pad+1)*(KW-1-kwh)
+// (both cuts are at most pad, so there are (pad+1)^4 classes; class 0 is the
+// interior).    cst[class][o] = ba*aw[o]*Sw + Kv*ba*bw[o]
 // with Sw the sum of filter o's per-tap channel sums over the rectangle and
 // Kv = C * (number of taps in it): Eq.9's pre-stored constant C, one per class.
 __global__ __launch_bounds__(256) void k_conv_class_consts(const int32_t* tap, ConvGeom g, Param alpha_w,
                                                            Param beta_w, float beta_a, double* cst)
 {
-    const int ncls = g.KH * g.KH * g.KW * g.KW;
+    const int p1 = g.pad + 1;
+    const int ncls = p1 * p1 * p1 * p1;
     const int64_t total = (int64_t)ncls * g.O;
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= total) return;
     const int o = (int)(i % g.O);
-    int cls = (int)(i / g.O);
-    const int kwh = cls % g.KW;
-    cls /= g.KW;
-    const int kwl = cls % g.KW;
-    cls /= g.KW;
-    const int khh = cls % g.KH, khl = cls / g.KH;
+    const int cls = (int)(i / g.O);
+    const int rid = cls / (p1 * p1), cid = cls % (p1 * p1);
+    const int khl = rid % p1, khh = g.KH - 1 - rid / p1;
+    const int kwl = cid % p1, kwh = g.KW - 1 - cid / p1;
     int s = 0, taps = 0;
     for (int kh = khl; kh <= khh; ++kh)
         for (int kw = kwl; kw <= kwh; ++kw) {
@@ -433,15 +514,26 @@ __global__ __launch_bounds__(256) void k_conv_class_consts(const int32_t* tap, C
     cst[i] = ba * pval(alpha_w, o) * (double)s + (double)(g.C * taps) * ba * pval(beta_w, o);
 }
 
+// LDS bytes of the epilogue tables of a BP-row tile.
+inline int64_t table_bytes(int bp, bool conv, int pad)
+{
+    const int p1 = pad + 1;
+    return conv ? (int64_t)(4 + p1 * p1 * p1 * p1) * bp * 8 : (int64_t)3 * bp * 8;
+}
+constexpr int64_t kMaxLds = 160 * 1024;
+
 template <int BP, int BQ, int WGP, int WGQ, int NS, bool CONV>
 hipError_t launch_cfg(TmmParams& prm, hipStream_t st)
 {
-    constexpr int stage_bytes = NS * (BP + BQ) * 64, tab_bytes = 5 * BP * 8;
-    constexpr int smem = stage_bytes > tab_bytes ? stage_bytes : tab_bytes;
+    constexpr int stage_bytes = NS * (BP + BQ) * 64;
+    const int64_t tb = table_bytes(BP, CONV, prm.g.pad);
+    const int64_t smem = stage_bytes > tb ? stage_bytes : tb;
+    if (smem > kMaxLds) return hipErrorInvalidValue;
     static bool attr_done = false;
     auto kern = k_tmm<BP, BQ, WGP, WGQ, NS, CONV>;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize, smem);
+        hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
+                                           (int)kMaxLds);
         if (e != hipSuccess) return e;
         attr_done = true;
     }
@@ -449,7 +541,7 @@ hipError_t launch_cfg(TmmParams& prm, hipStream_t st)
     const int64_t tilesQ = ((int64_t)prm.RQ + BQ - 1) / BQ;
     const int64_t blocks = (int64_t)prm.tilesP * tilesQ;
     if (blocks <= 0 || blocks > 0x7fffffff) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), smem, st, prm);
+    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), (size_t)smem, st, prm);
     return hipGetLastError();
 }
 
@@ -460,11 +552,15 @@ inline int64_t nblocks(int64_t rp, int64_t rq, int bp, int bq)
 
 // Tile configurations, indexed as rtn_set_tile_config() documents.
 constexpr int kNumTileConfigs = 6;
+const int kTileBP[kNumTileConfigs] = {64, 128, 256, 64, 128, 256};
 int g_forced_tile = -1;
 
 template <bool CONV>
 hipError_t launch_index(int cfg, TmmParams& prm, hipStream_t st)
 {
+    // conv with a large pad: the per-class constant table of a tall tile does
+    // not fit in LDS; fall back to the tile of the same width class with BP = 64.
+    if (CONV && table_bytes(kTileBP[cfg], true, prm.g.pad) > kMaxLds) cfg = 0;
     switch (cfg) {
         case 0: return launch_cfg<64, 64, 2, 2, 4, CONV>(prm, st);
         case 1: return launch_cfg<128, 128, 2, 2, 4, CONV>(prm, st);
@@ -497,7 +593,8 @@ void force_tile_config(int index) { g_forced_tile = index; }
 hipError_t launch_conv_class_consts(const ConvArgs& a, double* cst, hipStream_t st)
 {
     const ConvGeom& g = a.g;
-    const int64_t total = (int64_t)g.KH * g.KH * g.KW * g.KW * g.O;
+    const int p1 = g.pad + 1;
+    const int64_t total = (int64_t)p1 * p1 * p1 * p1 * g.O;
     hipLaunchKernelGGL(k_conv_class_consts, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
                        a.ep.sum_tw, g, a.ep.alpha_w, a.ep.beta_w, a.ep.beta_a.s, cst);
     return hipGetLastError();

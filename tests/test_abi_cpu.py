@@ -39,7 +39,9 @@ def test_helpers(L):
     assert L.rtn_codes_bytes(B.RTN_CODE_I8, 3, 70) == 3 * 128
     assert L.rtn_codes_bytes(B.RTN_CODE_BITPLANE, 3, 70) == 3 * 2 * 8 * 2
     assert L.rtn_codes_bytes(7, 3, 70) == 0
-    assert L.rtn_conv2d_workspace_bytes(64, 3, 3) == 64 * 81 * 8
+    assert L.rtn_conv2d_workspace_bytes(64, 3, 3, 1) == 64 * 16 * 8
+    assert L.rtn_conv2d_workspace_bytes(64, 1, 1, 0) == 64 * 8
+    assert L.rtn_conv2d_workspace_bytes(64, 3, 3, 3) == 0
     assert L.rtn_status_string(0) == b"ok"
     for s in range(-6, 0):
         assert len(L.rtn_status_string(s)) > 3
@@ -96,7 +98,7 @@ def test_gemm_rejects(L):
     e = _ep()
     assert with_(_8=C.byref(e)) == B.RTN_ERR_NULL               # ep without y_out
     assert with_(_4=0) == B.RTN_ERR_SHAPE
-    assert with_(_6=(1 << 24) + 1) == B.RTN_ERR_SHAPE
+    assert with_(_6=(1 << 22) + 1) == B.RTN_ERR_SHAPE
     assert with_(_0=3) == B.RTN_ERR_UNSUPPORTED
     assert with_(_1=B.RTN_PATH_POPC) == B.RTN_ERR_UNSUPPORTED   # int8 codes on the popcount path
     assert with_(_0=B.RTN_CODE_BITPLANE, _1=B.RTN_PATH_MFMA_I8) == B.RTN_ERR_UNSUPPORTED
