@@ -89,8 +89,9 @@ __device__ __forceinline__ void wait_groups(int groups)
         wait_vm<3 * DPS>();
 }
 
-template <int BP, int BQ, int WGP, int WGQ, int NS, bool CONV>
-__global__ __launch_bounds__(256) void k_tmm(TmmParams prm)
+// MINW = waves per SIMD the register allocation must leave room for.
+template <int BP, int BQ, int WGP, int WGQ, int NS, int MINW, bool CONV>
+__global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
 {
     static_assert(WGP * WGQ == 4, "4 waves per block");
     constexpr int WP = BP / WGP, WQ = BQ / WGQ, TP = WP / 32, TQ = WQ / 32;
@@ -335,9 +336,30 @@ __global__ __launch_bounds__(256) void k_tmm(TmmParams prm)
     // takes the branch-free variant.
     const EpiArgs& ep = prm.ep;
     const bool has_bn = ep.bn_scale != nullptr;
-    const bool relu = ep.relu != 0;
+    // ReLU and BN are applied unconditionally with neutral parameters when off:
+    // max(v, -inf) = v and 1*v + 0 = v exactly, so the element code has no selects.
+    const double relu_floor = ep.relu ? 0.0 : -__builtin_inf();
     double* tab = (double*)smem;
     const bool full_tile = p0 + BP <= prm.RP && q0 + BQ <= prm.RQ;
+    // The element loops exist in 6 straight-line variants (interior / ragged
+    // tile) x (acc only / y only / both), picked once per block.
+    auto dispatch = [&](auto&& run) {
+        if (full_tile) {
+            if (!prm.y)
+                run(std::true_type{}, std::true_type{}, std::false_type{});
+            else if (!prm.acc)
+                run(std::true_type{}, std::false_type{}, std::true_type{});
+            else
+                run(std::true_type{}, std::true_type{}, std::true_type{});
+        } else {
+            if (!prm.y)
+                run(std::false_type{}, std::true_type{}, std::false_type{});
+            else if (!prm.acc)
+                run(std::false_type{}, std::false_type{}, std::true_type{});
+            else
+                run(std::false_type{}, std::true_type{}, std::true_type{});
+        }
+    };
     __syncthreads();  // all waves are done with the operand stages
     if (!CONV) {
         // y = aw*(aa*D + ba*Sw) + bw*r2 with r2 = aa*Sa + K*ba per row m; tab = [3][BP]
@@ -376,8 +398,9 @@ __global__ __launch_bounds__(256) void k_tmm(TmmParams prm)
                 }
             }
         }
-        auto run = [&](auto full) {
-            constexpr bool FULL = decltype(full)::value;
+        dispatch([&](auto full, auto want_acc, auto want_y) {
+            constexpr bool FULL = decltype(full)::value, ACC = decltype(want_acc)::value,
+                           Y = decltype(want_y)::value;
 #pragma unroll
             for (int i = 0; i < TP; ++i)
 #pragma unroll
@@ -385,27 +408,30 @@ __global__ __launch_bounds__(256) void k_tmm(TmmParams prm)
                     const int t = wp * WP + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
                     const int m = p0 + t;
                     const bool mok = FULL || m < prm.RP;
-                    const double aa = tab[t], ba = tab[BP + t], r2 = tab[2 * BP + t];
+                    double aa = 0.0, ba = 0.0, r2 = 0.0;
+                    if (Y) {
+                        aa = tab[t];
+                        ba = tab[BP + t];
+                        r2 = tab[2 * BP + t];
+                    }
+                    const int64_t rowoff = (int64_t)m * N;
 #pragma unroll
                     for (int j = 0; j < TQ; ++j) {
                         if (FULL || (mok && nok[j])) {
                             const int D = acc[i][j][r];
-                            const int64_t idx = (int64_t)m * N + ncol[j];
-                            if (prm.acc) prm.acc[idx] = D;
-                            if (prm.y) {
+                            const int64_t idx = rowoff + ncol[j];
+                            if (ACC) prm.acc[idx] = D;
+                            if (Y) {
                                 double v = aw[j] * (aa * (double)D + ba * sw[j]) + bw[j] * r2;
-                                if (relu) v = __builtin_fmax(v, 0.0);
-                                if (has_bn) v = bs[j] * v + bh[j];
-                                prm.y[idx] = (float)v;
+                                v = __builtin_fmax(v, relu_floor);
+                                prm.y[idx] = (float)(bs[j] * v + bh[j]);
                             }
                         }
                     }
+                    // keep the scheduler from hoisting every later load up here
+                    if ((r & 3) == 3) __builtin_amdgcn_sched_barrier(0);
                 }
-        };
-        if (full_tile)
-            run(std::true_type{});
-        else
-            run(std::false_type{});
+        });
     } else {
         // y = g1[o]*D + c2[o]*Sa[m] + Cst[class(m)][o],  g1 = aa*aw, c2 = aa*bw;
         // tab = [4 + ncls][BP]: g1, c2, bn scale, bn shift, then the class constants.
@@ -450,8 +476,9 @@ __global__ __launch_bounds__(256) void k_tmm(TmmParams prm)
             Sa[j] = (double)(pixinfo[j] >> 8);
             ctab[j] = tab + (4 + (pixinfo[j] & 255)) * BP;
         }
-        auto run = [&](auto full) {
-            constexpr bool FULL = decltype(full)::value;
+        dispatch([&](auto full, auto want_acc, auto want_y) {
+            constexpr bool FULL = decltype(full)::value, ACC = decltype(want_acc)::value,
+                           Y = decltype(want_y)::value;
 #pragma unroll
             for (int i = 0; i < TP; ++i)
 #pragma unroll
@@ -459,28 +486,32 @@ __global__ __launch_bounds__(256) void k_tmm(TmmParams prm)
                     const int t = wp * WP + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
                     const int o = p0 + t;
                     const bool ook = FULL || o < prm.RP;
-                    const double g1 = tab[t], c2 = tab[BP + t];
-                    const double bs = tab[2 * BP + t], bh = tab[3 * BP + t];
+                    double g1 = 0.0, c2 = 0.0, bs = 1.0, bh = 0.0, cc[TQ];
+                    if (Y) {
+                        g1 = tab[t];
+                        c2 = tab[BP + t];
+                        bs = tab[2 * BP + t];
+                        bh = tab[3 * BP + t];
+#pragma unroll
+                        for (int j = 0; j < TQ; ++j) cc[j] = ctab[j][t];
+                    }
+                    const int64_t rowoff = (int64_t)o * ohw;
 #pragma unroll
                     for (int j = 0; j < TQ; ++j) {
                         if (FULL || (ook && mok[j])) {
                             const int D = acc[i][j][r];
-                            const int64_t idx = obase[j] + (int64_t)o * ohw;
-                            if (prm.acc) prm.acc[idx] = D;
-                            if (prm.y) {
-                                double v = g1 * (double)D + (c2 * Sa[j] + ctab[j][t]);
-                                if (relu) v = __builtin_fmax(v, 0.0);
-                                if (has_bn) v = bs * v + bh;
-                                prm.y[idx] = (float)v;
+                            const int64_t idx = obase[j] + rowoff;
+                            if (ACC) prm.acc[idx] = D;
+                            if (Y) {
+                                double v = g1 * (double)D + (c2 * Sa[j] + cc[j]);
+                                v = __builtin_fmax(v, relu_floor);
+                                prm.y[idx] = (float)(bs * v + bh);
                             }
                         }
                     }
+                    if ((r & 3) == 3) __builtin_amdgcn_sched_barrier(0);
                 }
-        };
-        if (full_tile)
-            run(std::true_type{});
-        else
-            run(std::false_type{});
+        });
     }
 }
 
@@ -522,7 +553,7 @@ inline int64_t table_bytes(int bp, bool conv, int pad)
 }
 constexpr int64_t kMaxLds = 160 * 1024;
 
-template <int BP, int BQ, int WGP, int WGQ, int NS, bool CONV>
+template <int BP, int BQ, int WGP, int WGQ, int NS, int MINW, bool CONV>
 hipError_t launch_cfg(TmmParams& prm, hipStream_t st)
 {
     constexpr int stage_bytes = NS * (BP + BQ) * 64;
@@ -530,7 +561,7 @@ hipError_t launch_cfg(TmmParams& prm, hipStream_t st)
     const int64_t smem = stage_bytes > tb ? stage_bytes : tb;
     if (smem > kMaxLds) return hipErrorInvalidValue;
     static bool attr_done = false;
-    auto kern = k_tmm<BP, BQ, WGP, WGQ, NS, CONV>;
+    auto kern = k_tmm<BP, BQ, WGP, WGQ, NS, MINW, CONV>;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)kMaxLds);
@@ -562,12 +593,12 @@ hipError_t launch_index(int cfg, TmmParams& prm, hipStream_t st)
     // not fit in LDS; fall back to the tile of the same width class with BP = 64.
     if (CONV && table_bytes(kTileBP[cfg], true, prm.g.pad) > kMaxLds) cfg = 0;
     switch (cfg) {
-        case 0: return launch_cfg<64, 64, 2, 2, 4, CONV>(prm, st);
-        case 1: return launch_cfg<128, 128, 2, 2, 4, CONV>(prm, st);
-        case 2: return launch_cfg<256, 256, 2, 2, 4, CONV>(prm, st);
-        case 3: return launch_cfg<64, 256, 1, 4, 3, CONV>(prm, st);
-        case 4: return launch_cfg<128, 256, 2, 2, 3, CONV>(prm, st);
-        case 5: return launch_cfg<256, 128, 2, 2, 3, CONV>(prm, st);
+        case 0: return launch_cfg<64, 64, 2, 2, 4, 4, CONV>(prm, st);
+        case 1: return launch_cfg<128, 128, 2, 2, 4, 2, CONV>(prm, st);
+        case 2: return launch_cfg<256, 256, 2, 2, 4, 1, CONV>(prm, st);
+        case 3: return launch_cfg<64, 256, 1, 4, 3, 3, CONV>(prm, st);
+        case 4: return launch_cfg<128, 256, 2, 2, 3, 2, CONV>(prm, st);
+        case 5: return launch_cfg<256, 128, 2, 2, 3, 2, CONV>(prm, st);
         default: return hipErrorInvalidValue;
     }
 }
