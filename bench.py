@@ -77,6 +77,7 @@ def main():
             ep = B.Epilogue(garg(case["alpha_a"]), garg(case["beta_a"]), garg(case["alpha_w"]),
                             garg(case["beta_w"]), pa, pw, relu=True,
                             bn_scale=to_dev(case["bn_scale"]), bn_shift=to_dev(case["bn_shift"]))
+            B.conv2d_prepare_constants(sh.C, sh.O, sh.k, sh.k, sh.pad, ep, ws)   # S0, offline
             layers.append(dict(sh=sh, x=x, cw=cw, pw=pw, ca=ca, pa=pa, y=y, ws=ws, ep=ep,
                                da=float(case["delta_a"]), case=case if i < 0 else None))
             del case

@@ -138,7 +138,7 @@ size_t rtn_codes_bytes(rtn_code_format fmt, int64_t rows, int64_t K);
  *   [O][I][KH][KW] (weights).  codes are written channel-innermost,
  *   [N][H][W][Cpad]; sum_t[N][H][W] = sum of t over the channels of a pixel
  *   (for weights: per filter and tap).  RTN_VECTOR thresholds: one (lo, hi)
- *   per d0 index (per filter).
+ *   per d0 index (per filter).  RTN_CODE_I8 needs C <= 2048 in this layout.
  * sum_t may be NULL.  d0*d2*d3 and d0*d1*d2*d3 must be below 2^31 resp. 2^40. */
 int rtn_ternarize_pack(const float *x, rtn_layout layout, int64_t d0, int64_t d1, int64_t d2,
                        int64_t d3, const float *thr_lo, const float *thr_hi, rtn_gran thr_gran,
@@ -163,11 +163,21 @@ int rtn_ternary_gemm(rtn_code_format fmt, rtn_path path, const void *a_codes, co
  *   a_codes: [Nb][H][W][Cpad]; w_codes: [O][KH][KW][Cpad] (RTN_CODE_I8 only).
  *   acc_out: int32 [Nb][O][OH][OW] or NULL; y_out: fp32 [Nb][O][OH][OW] (NCHW).
  *   KH, KW in 1..7, stride in 1..64, 0 <= pad < min(KH, KW), pad <= 3.
- *   workspace: at least rtn_conv2d_workspace_bytes(O, KH, KW, pad) bytes when an
- *   epilogue is given (holds Eq.9's constant per border class and
- *   filter), 8-byte aligned.
+ *   workspace (needed when an epilogue is given): the table written by
+ *   rtn_conv2d_prepare_constants() for the same filters, pad and epilogue
+ *   parameters; it is only read here, so one prepared table serves any number
+ *   of calls, batch sizes and image sizes.
  *   Nb*H*W and Nb*OH*OW must be below 2^31.                                  */
 size_t rtn_conv2d_workspace_bytes(int64_t O, int KH, int KW, int pad);
+/* Weight-side preparation of the conv epilogue (offline, once per layer): fills
+ * `workspace` (>= rtn_conv2d_workspace_bytes(O, KH, KW, pad) bytes, 8-byte
+ * aligned) with Eq.9's pre-stored constant  C = beta_a*alpha_w*Sw + Kv*beta_a*beta_w
+ * for every filter and every border class of output pixels (the in-bounds tap
+ * rectangle decides which taps enter Sw and Kv).  Reads ep->sum_tw (the per-tap
+ * sums [O][KH][KW]), alpha_w, beta_w and beta_a; ep->sum_ta must be non-NULL but
+ * is not read.  C is the number of input channels.                           */
+int rtn_conv2d_prepare_constants(int64_t C, int64_t O, int KH, int KW, int pad, const rtn_epilogue *ep,
+                                 void *workspace, size_t workspace_bytes, void *stream);
 int rtn_ternary_conv2d_implicit_gemm(rtn_code_format fmt, rtn_path path, const void *a_codes,
                                      const void *w_codes, int64_t Nb, int64_t C, int64_t H,
                                      int64_t W, int64_t O, int KH, int KW, int stride, int pad,

@@ -23,6 +23,7 @@ RTN_PATH_AUTO, RTN_PATH_MFMA_I8, RTN_PATH_POPC = 0, 1, 2
 
 EXPORTS = ["rtn_status_string", "rtn_last_hip_error", "rtn_num_tile_configs", "rtn_set_tile_config", "rtn_padded_k", "rtn_codes_bytes",
            "rtn_ternarize_pack", "rtn_ternary_gemm", "rtn_conv2d_workspace_bytes",
+           "rtn_conv2d_prepare_constants",
            "rtn_ternary_conv2d_implicit_gemm", "rtn_epilogue_reparam", "rtn_epilogue_reparam_conv2d"]
 
 
@@ -67,6 +68,8 @@ def lib():
         L.rtn_ternary_gemm.argtypes = [ci, ci, vp, vp, i64, i64, i64, vp, vp, vp, vp, C.c_size_t, vp]
         L.rtn_conv2d_workspace_bytes.restype = C.c_size_t
         L.rtn_conv2d_workspace_bytes.argtypes = [i64, ci, ci, ci]
+        L.rtn_conv2d_prepare_constants.restype = ci
+        L.rtn_conv2d_prepare_constants.argtypes = [i64, i64, ci, ci, ci, vp, vp, C.c_size_t, vp]
         L.rtn_ternary_conv2d_implicit_gemm.restype = ci
         L.rtn_ternary_conv2d_implicit_gemm.argtypes = [ci, ci, vp, vp, i64, i64, i64, i64, i64, ci, ci,
                                                        ci, ci, ci, vp, vp, vp, vp, C.c_size_t, vp]
@@ -187,6 +190,17 @@ def conv2d_workspace_bytes(O, KH, KW, pad):
     return lib().rtn_conv2d_workspace_bytes(O, KH, KW, pad)
 
 
+def conv2d_prepare_constants(Cc, O, KH, KW, pad, ep, workspace=None):
+    """Offline: fills (and returns) the per-border-class constant table of a conv layer."""
+    if workspace is None:
+        workspace = torch.empty(conv2d_workspace_bytes(O, KH, KW, pad), dtype=torch.uint8,
+                                device=torch.device("cuda", torch.cuda.current_device()))
+    rc = lib().rtn_conv2d_prepare_constants(Cc, O, KH, KW, pad, ep.ref(), C.c_void_p(workspace.data_ptr()),
+                                            workspace.numel() * workspace.element_size(), _stream())
+    _check(rc, "rtn_conv2d_prepare_constants")
+    return workspace
+
+
 def conv_out_hw(H, W, KH, KW, stride, pad):
     return (H + 2 * pad - KH) // stride + 1, (W + 2 * pad - KW) // stride + 1
 
@@ -202,7 +216,7 @@ def ternary_conv2d(a_codes, w_codes, Nb, Cc, H, W, O, KH, KW, stride, pad, pad_m
     if ep is not None and y_out is None:
         y_out = torch.empty((Nb, O, OH, OW), dtype=torch.float32, device=dev)
     if ep is not None and workspace is None:
-        workspace = torch.empty(conv2d_workspace_bytes(O, KH, KW, pad), dtype=torch.uint8, device=dev)
+        workspace = conv2d_prepare_constants(Cc, O, KH, KW, pad, ep)
     rc = lib().rtn_ternary_conv2d_implicit_gemm(
         fmt, path, C.c_void_p(a_codes.data_ptr()), C.c_void_p(w_codes.data_ptr()), Nb, Cc, H, W, O, KH, KW,
         stride, pad, pad_mode, None if acc_out is None else _dev(acc_out, torch.int32),

@@ -155,6 +155,7 @@ int rtn_ternarize_pack(const float* x, rtn_layout layout, int64_t d0, int64_t d1
     } else {
         a.N = d0;
         a.HW = d2 * d3;
+        if (fmt == RTN_CODE_I8 && a.Kpad > 2048) return RTN_ERR_UNSUPPORTED;
         const int64_t tiles = (a.HW + 63) / 64;
         if (tiles * a.N > kMaxDim) return RTN_ERR_SHAPE;
         e = fmt == RTN_CODE_I8 ? rtn::launch_pack_nchw_i8(a, st) : rtn::launch_pack_nchw_planes(a, st);
@@ -219,6 +220,20 @@ size_t rtn_conv2d_workspace_bytes(int64_t O, int KH, int KW, int pad)
     return (size_t)O * (size_t)(p1 * p1 * p1 * p1) * sizeof(double);
 }
 
+int rtn_conv2d_prepare_constants(int64_t C, int64_t O, int KH, int KW, int pad, const rtn_epilogue* ep,
+                                 void* workspace, size_t workspace_bytes, void* stream)
+{
+    rtn::ConvArgs c = {};
+    // geometry fields the table depends on: C, O, KH, KW, pad (image size is irrelevant)
+    int rc = make_geom(1, C, KH, KW, O, KH, KW, 1, pad, RTN_PAD_TRUE_ZERO, c.g);
+    if (rc != RTN_OK) return rc;
+    if ((rc = make_epilogue(ep, true, c.ep)) != RTN_OK) return rc;
+    if (!workspace || workspace_bytes < rtn_conv2d_workspace_bytes(O, KH, KW, pad)) return RTN_ERR_WORKSPACE;
+    if (!aligned(workspace, 8)) return RTN_ERR_ALIGN;
+    const hipError_t he = rtn::launch_conv_class_consts(c, (double*)workspace, (hipStream_t)stream);
+    return he == hipSuccess ? RTN_OK : hip_fail(he);
+}
+
 int rtn_ternary_conv2d_implicit_gemm(rtn_code_format fmt, rtn_path path, const void* a_codes,
                                      const void* w_codes, int64_t Nb, int64_t C, int64_t H, int64_t W,
                                      int64_t O, int KH, int KW, int stride, int pad,
@@ -247,10 +262,6 @@ int rtn_ternary_conv2d_implicit_gemm(rtn_code_format fmt, rtn_path path, const v
     c.cst_cls = (const double*)workspace;
     hipStream_t st = (hipStream_t)stream;
     hipError_t he;
-    if (ep) {
-        he = rtn::launch_conv_class_consts(c, (double*)workspace, st);
-        if (he != hipSuccess) return hip_fail(he);
-    }
     he = rtn::launch_conv_mfma(c, st);
     return he == hipSuccess ? RTN_OK : hip_fail(he);
 }

@@ -110,45 +110,122 @@ __global__ __launch_bounds__(256) void k_pack_rows_planes(PackArgs a)
 }
 
 // ---- NCHW layout, int8 codes, channel-innermost output -------------------
-// Block = one image n and 64 consecutive pixels; lane <-> pixel, so every load
-// (fixed channel, 64 pixels) is a coalesced 256-byte read.  Wave w owns the
-// 16-channel groups g = w, w+4, ...; a lane packs its 16 codes of a group into
-// one 16-byte store at [n][p][g*16].  Channel sums are combined through LDS.
+// A block owns 64 consecutive pixels of the flattened (image, pixel) index, so
+// its output -- 64 rows of Cpad bytes -- is one contiguous run of the
+// [N][H][W][Cpad] tensor, whatever H*W is.  lane <-> pixel: every load (fixed
+// channel, 64 pixels) is a coalesced 256-byte read.  Wave w owns the 16-channel
+// groups g = w, w+4, ...; a lane packs its 16 codes of a group into 16 bytes
+// and parks them in an LDS image of the output run, which the block then
+// streams out with consecutive lanes writing consecutive 16-byte chunks (full
+// cache lines).  Channel sums are combined through LDS.
 __global__ __launch_bounds__(256) void k_pack_nchw_i8(PackArgs a)
 {
+    extern __shared__ __attribute__((aligned(16))) uint8_t tile[];  // [64][Cpad]
     __shared__ int part[4][64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int64_t tiles = (a.HW + 63) >> 6;
-    const int64_t n = blockIdx.x / tiles;
-    const int64_t p = ((int64_t)blockIdx.x - n * tiles) * 64 + lane;
-    const bool pin = p < a.HW;
+    const int64_t total = a.N * a.HW;
+    const int64_t q0 = (int64_t)blockIdx.x * 64, q = q0 + lane;
+    const bool pin = q < total;
+    const int64_t n = pin ? q / a.HW : 0;
+    const int64_t p = pin ? q - n * a.HW : 0;
     const float lo = thr(a.lo, n), hi = thr(a.hi, n);
-    const float* xn = a.x + n * a.K * a.HW;
-    int8_t* out = (int8_t*)a.codes + (n * a.HW + p) * a.Kpad;
+    const float* xn = a.x + n * a.K * a.HW + p;
     const int groups = (int)(a.Kpad >> 4);
     int sum = 0;
     for (int g = wave; g < groups; g += 4) {
-        uint32_t q[4] = {0, 0, 0, 0};
+        uint32_t w4[4] = {0, 0, 0, 0};
         float v[16];
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
             const int64_t c = (int64_t)g * 16 + j;
-            v[j] = (pin && c < a.K) ? xn[c * a.HW + p] : 0.0f;
+            v[j] = (pin && c < a.K) ? xn[c * a.HW] : 0.0f;
         }
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
             const int64_t c = (int64_t)g * 16 + j;
             const int t = (pin && c < a.K) ? tern(v[j], lo, hi) : 0;
             sum += t;
-            q[j >> 2] |= (uint32_t)(t & 0xff) << (8 * (j & 3));
+            w4[j >> 2] |= (uint32_t)(t & 0xff) << (8 * (j & 3));
         }
-        if (pin) *(uint4*)(out + g * 16) = make_uint4(q[0], q[1], q[2], q[3]);
+        *(uint4*)(tile + (size_t)lane * a.Kpad + g * 16) = make_uint4(w4[0], w4[1], w4[2], w4[3]);
+    }
+    part[wave][lane] = sum;
+    __syncthreads();
+    if (a.sum_t && wave == 0 && pin) a.sum_t[q] = part[0][lane] + part[1][lane] + part[2][lane] + part[3][lane];
+    const int64_t valid = total - q0 < 64 ? total - q0 : 64;
+    const int chunks = (int)(valid * groups);
+    uint8_t* out = (uint8_t*)a.codes + q0 * a.Kpad;
+    for (int e = threadIdx.x; e < chunks; e += 256) *(uint4*)(out + (size_t)e * 16) = *(const uint4*)(tile + (size_t)e * 16);
+}
+
+// ---- NCHW layout, int8 codes, 16-byte loads ---------------------------------
+// Variant for H*W % 4 == 0 and a 16-byte aligned input: a block owns 256
+// consecutive pixels; lane l holds pixels 4l..4l+3 and reads them with one
+// 16-byte load per channel (a wave reads 1 KiB per channel).  Channels go in
+// chunks of 64: wave w takes channels 16w..16w+15 of the chunk, so a lane ends
+// up with, for each of its 4 pixels, the 16 code bytes that are contiguous in
+// the channel-innermost output.  They are parked in a 256 x 64-byte LDS image
+// (16-byte slots XOR-swizzled by lane to spread banks) and streamed out with
+// 4 consecutive lanes writing the 64 contiguous bytes of a pixel.
+__global__ __launch_bounds__(256) void k_pack_nchw_i8_v4(PackArgs a)
+{
+    __shared__ __attribute__((aligned(16))) uint8_t tile[256 * 64];
+    __shared__ int part[4][256];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int64_t total = a.N * a.HW;
+    const int64_t q0 = (int64_t)blockIdx.x * 256, q = q0 + 4 * lane;
+    const bool pin = q < total;  // total % 4 == 0: all four pixels or none
+    const int64_t n = pin ? q / a.HW : 0;
+    const int64_t p = pin ? q - n * a.HW : 0;
+    const float lo = thr(a.lo, n), hi = thr(a.hi, n);
+    const float* xn = a.x + n * a.K * a.HW + p;
+    const int nchunk = (int)(a.Kpad >> 6);
+    const int64_t valid = total - q0 < 256 ? total - q0 : 256;
+    uint8_t* out = (uint8_t*)a.codes + q0 * a.Kpad;
+    int sum[4] = {0, 0, 0, 0};
+    for (int cb = 0; cb < nchunk; ++cb) {
+        float4 v[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int64_t c = (int64_t)cb * 64 + wave * 16 + j;
+            v[j] = (pin && c < a.K) ? *(const float4*)(xn + c * a.HW) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+        uint32_t w4[4][4];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int k = 0; k < 4; ++k) w4[i][k] = 0;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const int64_t c = (int64_t)cb * 64 + wave * 16 + j;
+            const bool ok = pin && c < a.K;
+            const float e[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int t = ok ? tern(e[i], lo, hi) : 0;
+                sum[i] += t;
+                w4[i][j >> 2] |= (uint32_t)(t & 0xff) << (8 * (j & 3));
+            }
+        }
+        if (cb > 0) __syncthreads();  // previous chunk fully streamed out
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+            *(uint4*)(tile + (4 * lane + i) * 64 + ((wave ^ (lane & 3)) << 4)) =
+                make_uint4(w4[i][0], w4[i][1], w4[i][2], w4[i][3]);
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int e = tid + 256 * k, px = e >> 2, pp = e & 3;
+            const int logical = pp ^ ((px >> 2) & 3);
+            if (px < valid)
+                *(uint4*)(out + (size_t)px * a.Kpad + cb * 64 + logical * 16) = *(const uint4*)(tile + e * 16);
+        }
     }
     if (a.sum_t) {
-        part[wave][lane] = sum;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) part[wave][4 * lane + i] = sum[i];
         __syncthreads();
-        if (wave == 0 && pin)
-            a.sum_t[n * a.HW + p] = part[0][lane] + part[1][lane] + part[2][lane] + part[3][lane];
+        if (tid < valid) a.sum_t[q0 + tid] = part[0][tid] + part[1][tid] + part[2][tid] + part[3][tid];
     }
 }
 
@@ -224,8 +301,22 @@ hipError_t launch_pack_rows_planes(const PackArgs& a, hipStream_t st)
 
 hipError_t launch_pack_nchw_i8(const PackArgs& a, hipStream_t st)
 {
-    const dim3 grid((unsigned)(((a.HW + 63) / 64) * a.N)), block(256);
-    hipLaunchKernelGGL(k_pack_nchw_i8, grid, block, 0, st, a);
+    const size_t smem = (size_t)64 * a.Kpad;  // LDS image of the block's output run
+    if (smem > 128 * 1024) return hipErrorInvalidValue;
+    static bool attr_done = false;
+    if (!attr_done) {
+        hipError_t e = hipFuncSetAttribute((const void*)k_pack_nchw_i8,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
+        if (e != hipSuccess) return e;
+        attr_done = true;
+    }
+    if (a.HW % 4 == 0 && ((uintptr_t)a.x) % 16 == 0) {
+        const dim3 grid4((unsigned)((a.N * a.HW + 255) / 256));
+        hipLaunchKernelGGL(k_pack_nchw_i8_v4, grid4, dim3(256), 0, st, a);
+        return hipGetLastError();
+    }
+    const dim3 grid((unsigned)((a.N * a.HW + 63) / 64)), block(256);
+    hipLaunchKernelGGL(k_pack_nchw_i8, grid, block, smem, st, a);
     return hipGetLastError();
 }
 

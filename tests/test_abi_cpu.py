@@ -151,3 +151,14 @@ def test_binding_refuses_missing_library(monkeypatch, tmp_path):
     monkeypatch.setattr(B, "LIB_PATH", str(tmp_path / "nope.so"))
     with pytest.raises(RuntimeError):
         B.lib()
+
+
+def test_prepare_constants_rejects(L):
+    e = _ep()
+    call = L.rtn_conv2d_prepare_constants
+    assert call(64, 64, 3, 3, 1, None, FAKE, 1 << 20, None) == B.RTN_ERR_NULL
+    assert call(64, 64, 3, 3, 1, C.byref(e), None, 1 << 20, None) == B.RTN_ERR_WORKSPACE
+    assert call(64, 64, 3, 3, 1, C.byref(e), FAKE, 64 * 16 * 8 - 1, None) == B.RTN_ERR_WORKSPACE
+    assert call(64, 64, 3, 3, 3, C.byref(e), FAKE, 1 << 20, None) == B.RTN_ERR_UNSUPPORTED   # pad >= kernel
+    assert call(0, 64, 3, 3, 1, C.byref(e), FAKE, 1 << 20, None) == B.RTN_ERR_SHAPE
+    assert call(64, 64, 3, 3, 1, C.byref(e), ODD, 1 << 20, None) == B.RTN_ERR_ALIGN
