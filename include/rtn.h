@@ -113,8 +113,9 @@ int rtn_last_hip_error(void);
 /* Tuning and testing aid for the matrix-core kernels.  The output tile a
  * 256-thread block owns is BP x BQ (BP along M for the GEMM and along O for the
  * conv; BQ along N resp. along output pixels).  Index: 0 = 64x64, 1 = 128x128,
- * 2 = 256x256, 3 = 64x256, 4 = 128x256, 5 = 256x128; -1 (default) lets the
- * library choose from the problem shape.  Every configuration computes the same
+ * 2 = 256x256, 3 = 64x256, 4 = 128x256, 5 = 256x128, 6 = 64x128, 7 = 64x256
+ * with a two-stage operand ring; -1 (default) lets the library choose from the
+ * problem shape.  Every configuration computes the same
  * result.  The setting is process-wide and not thread-safe.
  * Returns RTN_ERR_UNSUPPORTED for an index outside -1 .. rtn_num_tile_configs()-1. */
 int rtn_num_tile_configs(void);

@@ -80,6 +80,8 @@ int make_geom(int64_t Nb, int64_t C, int64_t H, int64_t W, int64_t O, int KH, in
     g.Nb = (int)Nb, g.C = (int)C, g.Cpad = (int)Cpad, g.H = (int)H, g.W = (int)W, g.O = (int)O;
     g.KH = KH, g.KW = KW, g.stride = stride, g.pad = pad, g.OH = (int)OH, g.OW = (int)OW;
     g.code_zero_pad = pad_mode == RTN_PAD_CODE_ZERO;
+    g.div_ohw = rtn::make_fastdiv((uint32_t)(OH * OW));
+    g.div_ow = rtn::make_fastdiv((uint32_t)OW);
     return RTN_OK;
 }
 

@@ -38,9 +38,34 @@ struct EpiArgs {
     const float* bn_shift;
 };
 
+// Division of a 31-bit dividend by a fixed divisor as multiply-high + shift
+// (round-up magic number, exact for 0 <= n < 2^31); m == 0 encodes divisor 1.
+struct FastDiv {
+    uint32_t m, sh;
+};
+inline FastDiv make_fastdiv(uint32_t d)
+{
+    FastDiv f = {0, 0};
+    if (d <= 1) return f;
+    uint32_t L = 0;
+    while ((1ull << L) < d) ++L;
+    f.m = (uint32_t)(((1ull << (31 + L)) + d - 1) / d);
+    f.sh = L - 1;
+    return f;
+}
+__host__ __device__ inline uint32_t fastdiv(uint32_t n, FastDiv f)
+{
+#if defined(__HIP_DEVICE_COMPILE__)
+    return f.m ? (__umulhi(n, f.m) >> f.sh) : n;
+#else
+    return f.m ? (uint32_t)(((uint64_t)n * f.m) >> 32) >> f.sh : n;
+#endif
+}
+
 struct ConvGeom {
     int Nb, C, Cpad, H, W, O, KH, KW, stride, pad, OH, OW;
     int code_zero_pad;  // 1: RTN_PAD_CODE_ZERO
+    FastDiv div_ohw, div_ow;  // by OH*OW and by OW
 };
 
 struct GemmArgs {

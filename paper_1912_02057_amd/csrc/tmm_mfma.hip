@@ -47,6 +47,8 @@ struct TmmParams {
     int64_t ldP, ldQ;  // row pitch in bytes (dense operands)
     int nk;            // number of 64-byte K-steps
     int tilesP;        // number of tiles along P
+    int ntiles;        // tilesP * tilesQ
+    FastDiv div_tilesP;
     int Klogical;      // K of the epilogue's constant term (GEMM)
     ConvGeom g;        // conv only
     int32_t* acc;
@@ -108,7 +110,13 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);  // wave-uniform, lives in an SGPR
     const int wp = wave / WGQ, wq = wave % WGQ;
-    const int tileP = blockIdx.x % prm.tilesP, tileQ = blockIdx.x / prm.tilesP;
+    // Workgroups are dealt to the 8 XCDs round-robin by blockIdx; give each XCD
+    // (and so each L2) one contiguous run of tiles, P-tile index fastest, so
+    // tiles that share operand rows and conv halo pixels share an L2.
+    const int chunk = (int)(gridDim.x >> 3);  // grid is padded to a multiple of 8
+    const int bid = (int)(blockIdx.x & 7) * chunk + (int)(blockIdx.x >> 3);
+    if (bid >= prm.ntiles) return;
+    const int tileQ = (int)fastdiv((uint32_t)bid, prm.div_tilesP), tileP = bid - tileQ * prm.tilesP;
     const int p0 = tileP * BP, q0 = tileQ * BQ;
     const ConvGeom& g = prm.g;
 
@@ -133,8 +141,8 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
         row = row < prm.RQ ? row : prm.RQ - 1;
         if (CONV) {
             const int ohw = g.OH * g.OW;
-            const int nb = row / ohw, pix = row - nb * ohw;
-            const int oh = pix / g.OW, ow = pix - oh * g.OW;
+            const int nb = (int)fastdiv((uint32_t)row, g.div_ohw), pix = row - nb * ohw;
+            const int oh = (int)fastdiv((uint32_t)pix, g.div_ow), ow = pix - oh * g.OW;
             const int ih0 = oh * g.stride - g.pad, iw0 = ow * g.stride - g.pad;
             int m = 0;
             for (int k = 0; k < g.KH; ++k) m |= ((unsigned)(ih0 + k) < (unsigned)g.H) << k;
@@ -266,8 +274,8 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
         for (int j = 0; j < TQ; ++j) {
             int m = q0 + wq * WQ + j * 32 + (lane & 31);
             m = m < prm.RQ ? m : prm.RQ - 1;
-            const int nb = m / ohw, pix = m - nb * ohw;
-            const int oh = pix / g.OW, ow = pix - oh * g.OW;
+            const int nb = (int)fastdiv((uint32_t)m, g.div_ohw), pix = m - nb * ohw;
+            const int oh = (int)fastdiv((uint32_t)pix, g.div_ow), ow = pix - oh * g.OW;
             const int ih0 = oh * g.stride - g.pad, iw0 = ow * g.stride - g.pad;
             int khl, khh, kwl, kwh;
             tap_range(oh, g.stride, g.pad, g.KH, g.H, khl, khh);
@@ -471,7 +479,7 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
             const int m = q0 + wq * WQ + j * 32 + (lane & 31);
             mok[j] = m < prm.RQ;
             const int mm = mok[j] ? m : 0;
-            const int nb = mm / ohw, pix = mm - nb * ohw;
+            const int nb = (int)fastdiv((uint32_t)mm, g.div_ohw), pix = mm - nb * ohw;
             obase[j] = (int64_t)nb * g.O * ohw + pix;
             Sa[j] = (double)(pixinfo[j] >> 8);
             ctab[j] = tab + (4 + (pixinfo[j] & 255)) * BP;
@@ -571,8 +579,11 @@ hipError_t launch_cfg(TmmParams& prm, hipStream_t st)
     prm.tilesP = (prm.RP + BP - 1) / BP;
     const int64_t tilesQ = ((int64_t)prm.RQ + BQ - 1) / BQ;
     const int64_t blocks = (int64_t)prm.tilesP * tilesQ;
-    if (blocks <= 0 || blocks > 0x7fffffff) return hipErrorInvalidValue;
-    hipLaunchKernelGGL(kern, dim3((unsigned)blocks), dim3(256), (size_t)smem, st, prm);
+    if (blocks <= 0 || blocks > 0x7fffff00) return hipErrorInvalidValue;
+    prm.ntiles = (int)blocks;
+    prm.div_tilesP = make_fastdiv((uint32_t)prm.tilesP);
+    const unsigned grid = (unsigned)((blocks + 7) / 8 * 8);
+    hipLaunchKernelGGL(kern, dim3(grid), dim3(256), (size_t)smem, st, prm);
     return hipGetLastError();
 }
 
@@ -582,8 +593,8 @@ inline int64_t nblocks(int64_t rp, int64_t rq, int bp, int bq)
 }
 
 // Tile configurations, indexed as rtn_set_tile_config() documents.
-constexpr int kNumTileConfigs = 6;
-const int kTileBP[kNumTileConfigs] = {64, 128, 256, 64, 128, 256};
+constexpr int kNumTileConfigs = 8;
+const int kTileBP[kNumTileConfigs] = {64, 128, 256, 64, 128, 256, 64, 64};
 int g_forced_tile = -1;
 
 template <bool CONV>
@@ -599,6 +610,8 @@ hipError_t launch_index(int cfg, TmmParams& prm, hipStream_t st)
         case 3: return launch_cfg<64, 256, 1, 4, 3, 3, CONV>(prm, st);
         case 4: return launch_cfg<128, 256, 2, 2, 3, 2, CONV>(prm, st);
         case 5: return launch_cfg<256, 128, 2, 2, 3, 2, CONV>(prm, st);
+        case 6: return launch_cfg<64, 128, 1, 4, 3, 4, CONV>(prm, st);
+        case 7: return launch_cfg<64, 256, 1, 4, 2, 3, CONV>(prm, st);
         default: return hipErrorInvalidValue;
     }
 }
@@ -608,7 +621,7 @@ hipError_t launch_index(int cfg, TmmParams& prm, hipStream_t st)
 // rows run along registers (GEMM: M, conv: O), Q along lanes (GEMM: N, conv: pixels).
 int pick_tile(int64_t rp, int64_t rq)
 {
-    if (rp <= 64) return nblocks(rp, rq, 64, 256) >= 512 ? 3 : 0;
+    if (rp <= 64) return nblocks(rp, rq, 64, 256) >= 512 ? 7 : 0;
     if (rp <= 128) return nblocks(rp, rq, 128, 256) >= 512 ? 4 : (rq > 64 ? 1 : 0);
     if (rq <= 64) return 0;
     if (nblocks(rp, rq, 256, 256) >= 256) return 2;
