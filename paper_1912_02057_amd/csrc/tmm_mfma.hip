@@ -48,7 +48,8 @@ struct TmmParams {
     int nk;            // number of 64-byte K-steps
     int tilesP;        // number of tiles along P
     int ntiles;        // tilesP * tilesQ
-    FastDiv div_tilesP;
+    int band_tiles;    // 8 * tilesQ
+    FastDiv div_band;
     int Klogical;      // K of the epilogue's constant term (GEMM)
     ConvGeom g;        // conv only
     int32_t* acc;
@@ -65,6 +66,14 @@ __device__ __forceinline__ int swz(int row) { return ((row >> 1) & 3) ^ ((row >>
 __device__ __forceinline__ void dma16(const void* gptr, unsigned lds_off)
 {
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(lds_off), "v"(gptr) : "memory");
+}
+
+// Same, with the address split into a wave-uniform 64-bit base (SGPR pair) and
+// a per-lane unsigned 32-bit byte offset: nothing to add per lane per K-step.
+__device__ __forceinline__ void dma16_base(const void* sbase, unsigned voff, unsigned lds_off)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_off), "v"(voff), "s"(sbase)
+                 : "memory");
 }
 
 template <int N>
@@ -116,7 +125,14 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
     const int chunk = (int)(gridDim.x >> 3);  // grid is padded to a multiple of 8
     const int bid = (int)(blockIdx.x & 7) * chunk + (int)(blockIdx.x >> 3);
     if (bid >= prm.ntiles) return;
-    const int tileQ = (int)fastdiv((uint32_t)bid, prm.div_tilesP), tileP = bid - tileQ * prm.tilesP;
+    // Within that run, tiles are visited in bands of up to 8 P-tiles, P fastest,
+    // so the 32 co-resident tiles of an XCD form an 8 x 4 patch of the output
+    // (12 operand row-blocks per K-step instead of 18 for a 16 x 2 strip).
+    const int band = (int)fastdiv((uint32_t)bid, prm.div_band);  // band = 8 * tilesQ tiles
+    const int inband = bid - band * prm.band_tiles;
+    const int bandw = prm.tilesP - band * 8 < 8 ? prm.tilesP - band * 8 : 8;
+    const int tileQ = bandw == 8 ? (inband >> 3) : inband / bandw;
+    const int tileP = band * 8 + inband - tileQ * bandw;
     const int p0 = tileP * BP, q0 = tileQ * BQ;
     const ConvGeom& g = prm.g;
 
@@ -126,19 +142,28 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
     // chunk (l & 3) of that row.
     const int lrow = lane >> 2;
     const int lchunk = (lane & 3) ^ swz(lrow);
-    const int8_t* gP[LP];
+    // Dense operands: block-uniform base + per-lane offset (at most 256 rows of
+    // at most 2^22 bytes).  The conv's Q operand needs a pointer per lane, since
+    // an out-of-image tap is redirected to the zero page.
+    const int8_t* baseP = prm.P + (int64_t)p0 * prm.ldP;
+    const int8_t* baseQ = CONV ? prm.Q : prm.Q + (int64_t)q0 * prm.ldQ;
+    unsigned offP[LP];
 #pragma unroll
     for (int j = 0; j < LP; ++j) {
         int row = p0 + 16 * (wave + 4 * j) + lrow;
         row = row < prm.RP ? row : prm.RP - 1;  // tail rows: any valid data, never stored
-        gP[j] = prm.P + (int64_t)row * prm.ldP + lchunk * 16;
+        offP[j] = (unsigned)(row - p0) * (unsigned)prm.ldP + lchunk * 16;
     }
     const int8_t* gQ[LQ];
+    unsigned offQ[LQ];
     int vmask[LQ];  // conv: bit kh = row tap valid, bit (8 + kw) = column tap valid
 #pragma unroll
     for (int j = 0; j < LQ; ++j) {
         int row = q0 + 16 * (wave + 4 * j) + lrow;
         row = row < prm.RQ ? row : prm.RQ - 1;
+        gQ[j] = nullptr;
+        offQ[j] = 0;
+        vmask[j] = 0;
         if (CONV) {
             const int ohw = g.OH * g.OW;
             const int nb = (int)fastdiv((uint32_t)row, g.div_ohw), pix = row - nb * ohw;
@@ -150,8 +175,7 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
             vmask[j] = m;
             gQ[j] = prm.Q + (((int64_t)nb * g.H + ih0) * g.W + iw0) * g.Cpad + lchunk * 16;
         } else {
-            vmask[j] = 0;
-            gQ[j] = prm.Q + (int64_t)row * prm.ldQ + lchunk * 16;
+            offQ[j] = (unsigned)(row - q0) * (unsigned)prm.ldQ + lchunk * 16;
         }
     }
     // K position of the step being issued: byte offset into a dense row, or for
@@ -184,15 +208,16 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
     // the idx-th of the DPS direct loads of the step set up by issue_begin()
     auto issue_one = [&](int idx) {
         if (idx < LP) {
-            dma16(gP[idx] + is_koffP, is_sbase + (wave + 4 * idx) * 1024);
+            dma16_base(baseP + is_koffP, offP[idx], is_sbase + (wave + 4 * idx) * 1024);
         } else {
             const int j = idx - LP;
-            const int8_t* src = gQ[j] + is_koffQ;
+            const unsigned dst = is_sbase + BP * 64 + (wave + 4 * j) * 1024;
             if (CONV) {
                 const bool ok = ((vmask[j] >> is_kh) & (vmask[j] >> (8 + is_kw)) & 1) != 0;
-                src = ok ? src : zero_page;
+                dma16(ok ? gQ[j] + is_koffQ : zero_page, dst);
+            } else {
+                dma16_base(baseQ + is_koffQ, offQ[j], dst);
             }
-            dma16(src, is_sbase + BP * 64 + (wave + 4 * j) * 1024);
         }
     };
     auto issue = [&](int kt) {
@@ -219,12 +244,18 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
             fragQ[t][ks] = BP * 64 + row * 64 + (((ks * 2 + (lane >> 5)) ^ swz(row)) << 4);
     }
     v4i fa[2][TP], fb[2][TQ];
-    auto load_frags = [&](int kt, int ks) {
+    constexpr int NF = TP + TQ;  // fragments per k-slice
+    // idx-th fragment of slice ks of step kt: P fragments first, then Q
+    auto load_frag = [&](int kt, int ks, int idx) {
         const int8_t* st = smem + (kt % NS) * STAGE;
+        if (idx < TP)
+            fa[ks][idx] = *(const v4i*)(st + fragP[idx][ks]);
+        else
+            fb[ks][idx - TP] = *(const v4i*)(st + fragQ[idx - TP][ks]);
+    };
+    auto load_frags = [&](int kt, int ks) {
 #pragma unroll
-        for (int t = 0; t < TP; ++t) fa[ks][t] = *(const v4i*)(st + fragP[t][ks]);
-#pragma unroll
-        for (int t = 0; t < TQ; ++t) fb[ks][t] = *(const v4i*)(st + fragQ[t][ks]);
+        for (int i = 0; i < NF; ++i) load_frag(kt, ks, i);
     };
 
     v16i acc[TP][TQ];
@@ -234,25 +265,34 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
         for (int j = 0; j < TQ; ++j)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[i][j][r] = 0;
-    auto mma = [&](int ks) {
-#pragma unroll
-        for (int i = 0; i < TP; ++i)
-#pragma unroll
-            for (int j = 0; j < TQ; ++j)
-                acc[i][j] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[ks][i], fb[ks][j], acc[i][j], 0, 0, 0);
-    };
-    // The MFMAs of a k-slice with the DPS direct loads of step kt spread evenly
-    // between them, so that load issue hides behind matrix-core time.
-    auto mma_issue = [&](int ks, int kt) {
-        issue_begin(kt);
+    // One k-slice of MFMAs in a fixed issue order: after the n-th MFMA come its
+    // share of the next slice's fragment reads (slice fks of step fkt) and, if
+    // ISSUE, of the direct loads of step ikt; a scheduling fence after each
+    // group keeps the compiler from sinking the reads back to their first use,
+    // so LDS and load-issue latency hide behind matrix-core time.
+    auto slice = [&](auto with_frags, auto with_issue, int ks, int fkt, int fks, int ikt) {
+        constexpr bool FRAGS = decltype(with_frags)::value, ISSUE = decltype(with_issue)::value;
+        if (ISSUE) issue_begin(ikt);
 #pragma unroll
         for (int n = 0; n < NM; ++n) {
             acc[n / TQ][n % TQ] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[ks][n / TQ], fb[ks][n % TQ],
                                                                         acc[n / TQ][n % TQ], 0, 0, 0);
+            if (FRAGS) {
+                // front-loaded: one read per MFMA when there are enough MFMAs,
+                // so the last read is long done at the end of the slice
+                constexpr int PER = (NF + NM - 1) / NM;
 #pragma unroll
-            for (int d = n * DPS / NM; d < (n + 1) * DPS / NM; ++d) issue_one(d);
+                for (int f = n * PER; f < (n + 1) * PER && f < NF; ++f) load_frag(fkt, fks, f);
+            }
+            if (ISSUE) {
+#pragma unroll
+                for (int d = n * DPS / NM; d < (n + 1) * DPS / NM; ++d) issue_one(d);
+            }
+            __builtin_amdgcn_sched_barrier(0);
         }
     };
+    const std::true_type yes{};
+    const std::false_type no{};
 
     // ---- prologue: start the first NS steps, then per-lane epilogue terms -----
     const int nk = prm.nk;
@@ -314,27 +354,22 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
     // (all but the NS-2 younger load groups done) and, after the barrier, for
     // every wave; the freed stage is refilled with step kt+NS.
     for (; kt + NS < nk; ++kt) {
-        load_frags(kt, 1);
-        mma(0);
+        slice(yes, no, 0, kt, 1, 0);
         wait_lgkm0();
         wait_vm<(NS - 2) * DPS>();
         block_barrier();
-        load_frags(kt + 1, 0);
-        mma_issue(1, kt + NS);
+        slice(yes, yes, 1, kt + 1, 0, kt + NS);
     }
     // Drain: nothing left to issue.
     for (; kt + 1 < nk; ++kt) {
-        load_frags(kt, 1);
-        mma(0);
+        slice(yes, no, 0, kt, 1, 0);
         wait_lgkm0();
         wait_vm<0>();
         block_barrier();
-        load_frags(kt + 1, 0);
-        mma(1);
+        slice(yes, no, 1, kt + 1, 0, 0);
     }
-    load_frags(kt, 1);
-    mma(0);
-    mma(1);
+    slice(yes, no, 0, kt, 1, 0);
+    slice(no, no, 1, 0, 0, 0);
 
     // ---- epilogue ---------------------------------------------------------------
     // acc[i][j][r] is D at P-row  wp*WP + i*32 + 8*(r/4) + 4*(lane/32) + r%4
@@ -581,7 +616,9 @@ hipError_t launch_cfg(TmmParams& prm, hipStream_t st)
     const int64_t blocks = (int64_t)prm.tilesP * tilesQ;
     if (blocks <= 0 || blocks > 0x7fffff00) return hipErrorInvalidValue;
     prm.ntiles = (int)blocks;
-    prm.div_tilesP = make_fastdiv((uint32_t)prm.tilesP);
+    if (tilesQ * 8 > 0x7fffffff) return hipErrorInvalidValue;
+    prm.band_tiles = (int)(8 * tilesQ);
+    prm.div_band = make_fastdiv((uint32_t)prm.band_tiles);
     const unsigned grid = (unsigned)((blocks + 7) / 8 * 8);
     hipLaunchKernelGGL(kern, dim3(grid), dim3(256), (size_t)smem, st, prm);
     return hipGetLastError();
