@@ -114,8 +114,9 @@ int rtn_last_hip_error(void);
  * 256-thread block owns is BP x BQ (BP along M for the GEMM and along O for the
  * conv; BQ along N resp. along output pixels).  Index: 0 = 64x64, 1 = 128x128,
  * 2 = 256x256, 3 = 64x256, 4 = 128x256, 5 = 256x128, 6 = 64x128, 7 = 64x256
- * with a two-stage operand ring; -1 (default) lets the library choose from the
- * problem shape.  Every configuration computes the same
+ * with a two-stage operand ring; 8 .. 13 repeat 128x128, 64x256, 64x128, 64x64,
+ * 128x128 and 128x256 with other ring depths and register budgets; -1 (default)
+ * lets the library choose from the problem shape.  Every configuration computes the same
  * result.  The setting is process-wide and not thread-safe.
  * Returns RTN_ERR_UNSUPPORTED for an index outside -1 .. rtn_num_tile_configs()-1. */
 int rtn_num_tile_configs(void);

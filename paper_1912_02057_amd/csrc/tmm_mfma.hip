@@ -381,7 +381,7 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
     const bool has_bn = ep.bn_scale != nullptr;
     // ReLU and BN are applied unconditionally with neutral parameters when off:
     // max(v, -inf) = v and 1*v + 0 = v exactly, so the element code has no selects.
-    const double relu_floor = ep.relu ? 0.0 : -__builtin_inf();
+    const double relu_floor = __builtin_canonicalize(ep.relu ? 0.0 : -__builtin_inf());
     double* tab = (double*)smem;
     const bool full_tile = p0 + BP <= prm.RP && q0 + BQ <= prm.RQ;
     // The element loops exist in 6 straight-line variants (interior / ragged
@@ -422,28 +422,33 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
         }
         __syncthreads();
         const int64_t N = prm.RQ;
-        int ncol[TQ];
-        bool nok[TQ];
-        double aw[TQ], bw[TQ], bs[TQ], bh[TQ], sw[TQ];
-#pragma unroll
-        for (int j = 0; j < TQ; ++j) {
-            ncol[j] = q0 + wq * WQ + j * 32 + (lane & 31);
-            nok[j] = ncol[j] < prm.RQ;
-            aw[j] = bw[j] = bh[j] = sw[j] = 0.0;
-            bs[j] = 1.0;
-            if (prm.y && nok[j]) {
-                aw[j] = pval(ep.alpha_w, ncol[j]);
-                bw[j] = pval(ep.beta_w, ncol[j]);
-                sw[j] = (double)ep.sum_tw[ncol[j]];
-                if (has_bn) {
-                    bs[j] = ep.bn_scale[ncol[j]];
-                    bh[j] = ep.bn_shift ? (double)ep.bn_shift[ncol[j]] : 0.0;
-                }
-            }
-        }
         dispatch([&](auto full, auto want_acc, auto want_y) {
             constexpr bool FULL = decltype(full)::value, ACC = decltype(want_acc)::value,
                            Y = decltype(want_y)::value;
+            // per lane: its TQ output columns, their factors and base pointers.  Set up
+            // inside each variant so that a variant holds only what it uses.
+            bool nok[TQ];
+            double aw[TQ], bw[TQ], bs[TQ], bh[TQ], sw[TQ];
+            int32_t* accp[TQ];
+            float* yp[TQ];
+#pragma unroll
+            for (int j = 0; j < TQ; ++j) {
+                const int ncol = q0 + wq * WQ + j * 32 + (lane & 31);
+                nok[j] = FULL || ncol < prm.RQ;
+                aw[j] = bw[j] = bh[j] = sw[j] = 0.0;
+                bs[j] = 1.0;
+                if (Y && nok[j]) {
+                    aw[j] = pval(ep.alpha_w, ncol);
+                    bw[j] = pval(ep.beta_w, ncol);
+                    sw[j] = (double)ep.sum_tw[ncol];
+                    if (has_bn) {
+                        bs[j] = ep.bn_scale[ncol];
+                        bh[j] = ep.bn_shift ? (double)ep.bn_shift[ncol] : 0.0;
+                    }
+                }
+                accp[j] = ACC ? prm.acc + (nok[j] ? ncol : 0) : nullptr;
+                yp[j] = Y ? prm.y + (nok[j] ? ncol : 0) : nullptr;
+            }
 #pragma unroll
             for (int i = 0; i < TP; ++i)
 #pragma unroll
@@ -462,12 +467,11 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
                     for (int j = 0; j < TQ; ++j) {
                         if (FULL || (mok && nok[j])) {
                             const int D = acc[i][j][r];
-                            const int64_t idx = rowoff + ncol[j];
-                            if (ACC) prm.acc[idx] = D;
+                            if (ACC) accp[j][rowoff] = D;
                             if (Y) {
                                 double v = aw[j] * (aa * (double)D + ba * sw[j]) + bw[j] * r2;
                                 v = __builtin_fmax(v, relu_floor);
-                                prm.y[idx] = (float)(bs[j] * v + bh[j]);
+                                yp[j][rowoff] = (float)(bs[j] * v + bh[j]);
                             }
                         }
                     }
@@ -505,23 +509,27 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
             }
         }
         __syncthreads();
-        bool mok[TQ];
-        double Sa[TQ];
-        const double* ctab[TQ];
-        int64_t obase[TQ];
-#pragma unroll
-        for (int j = 0; j < TQ; ++j) {
-            const int m = q0 + wq * WQ + j * 32 + (lane & 31);
-            mok[j] = m < prm.RQ;
-            const int mm = mok[j] ? m : 0;
-            const int nb = (int)fastdiv((uint32_t)mm, g.div_ohw), pix = mm - nb * ohw;
-            obase[j] = (int64_t)nb * g.O * ohw + pix;
-            Sa[j] = (double)(pixinfo[j] >> 8);
-            ctab[j] = tab + (4 + (pixinfo[j] & 255)) * BP;
-        }
         dispatch([&](auto full, auto want_acc, auto want_y) {
             constexpr bool FULL = decltype(full)::value, ACC = decltype(want_acc)::value,
                            Y = decltype(want_y)::value;
+            // per lane: its TQ output pixels -> Sa, class constants, output base pointers
+            bool mok[TQ];
+            double Sa[TQ];
+            const double* ctab[TQ];
+            int32_t* accp[TQ];
+            float* yp[TQ];
+#pragma unroll
+            for (int j = 0; j < TQ; ++j) {
+                const int m = q0 + wq * WQ + j * 32 + (lane & 31);
+                mok[j] = FULL || m < prm.RQ;
+                const int mm = mok[j] ? m : 0;
+                const int nb = (int)fastdiv((uint32_t)mm, g.div_ohw), pix = mm - nb * ohw;
+                const int64_t obase = (int64_t)nb * g.O * ohw + pix;
+                accp[j] = ACC ? prm.acc + obase : nullptr;
+                yp[j] = Y ? prm.y + obase : nullptr;
+                Sa[j] = (double)(pixinfo[j] >> 8);
+                ctab[j] = tab + (4 + (pixinfo[j] & 255)) * BP;
+            }
 #pragma unroll
             for (int i = 0; i < TP; ++i)
 #pragma unroll
@@ -543,12 +551,11 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
                     for (int j = 0; j < TQ; ++j) {
                         if (FULL || (ook && mok[j])) {
                             const int D = acc[i][j][r];
-                            const int64_t idx = obase[j] + rowoff;
-                            if (ACC) prm.acc[idx] = D;
+                            if (ACC) accp[j][rowoff] = D;
                             if (Y) {
                                 double v = g1 * (double)D + (c2 * Sa[j] + cc[j]);
                                 v = __builtin_fmax(v, relu_floor);
-                                prm.y[idx] = (float)(bs * v + bh);
+                                yp[j][rowoff] = (float)(bs * v + bh);
                             }
                         }
                     }
@@ -630,8 +637,8 @@ inline int64_t nblocks(int64_t rp, int64_t rq, int bp, int bq)
 }
 
 // Tile configurations, indexed as rtn_set_tile_config() documents.
-constexpr int kNumTileConfigs = 8;
-const int kTileBP[kNumTileConfigs] = {64, 128, 256, 64, 128, 256, 64, 64};
+constexpr int kNumTileConfigs = 14;
+const int kTileBP[kNumTileConfigs] = {64, 128, 256, 64, 128, 256, 64, 64, 128, 64, 64, 64, 128, 128};
 int g_forced_tile = -1;
 
 template <bool CONV>
@@ -649,6 +656,12 @@ hipError_t launch_index(int cfg, TmmParams& prm, hipStream_t st)
         case 5: return launch_cfg<256, 128, 2, 2, 3, 2, CONV>(prm, st);
         case 6: return launch_cfg<64, 128, 1, 4, 3, 4, CONV>(prm, st);
         case 7: return launch_cfg<64, 256, 1, 4, 2, 3, CONV>(prm, st);
+        case 8: return launch_cfg<128, 128, 2, 2, 3, 3, CONV>(prm, st);
+        case 9: return launch_cfg<64, 256, 1, 4, 2, 4, CONV>(prm, st);
+        case 10: return launch_cfg<64, 128, 1, 4, 4, 4, CONV>(prm, st);
+        case 11: return launch_cfg<64, 64, 2, 2, 4, 6, CONV>(prm, st);
+        case 12: return launch_cfg<128, 128, 2, 2, 2, 4, CONV>(prm, st);
+        case 13: return launch_cfg<128, 256, 2, 2, 2, 2, CONV>(prm, st);
         default: return hipErrorInvalidValue;
     }
 }
@@ -656,9 +669,19 @@ hipError_t launch_index(int cfg, TmmParams& prm, hipStream_t st)
 // Heuristic: the largest tile that still gives every one of the 256 CUs a
 // block (two for the tiles small enough to share a CU); P is the operand whose
 // rows run along registers (GEMM: M, conv: O), Q along lanes (GEMM: N, conv: pixels).
-int pick_tile(int64_t rp, int64_t rq)
+// The conv rules come from timing the ResNet-18 layer shapes at batch 256: a
+// grid that fits the chip in one round beats a finer one that needs a second,
+// and the short-K layers prefer more resident blocks over a deeper ring.
+int pick_tile(int64_t rp, int64_t rq, bool conv)
 {
     if (rp <= 64) return nblocks(rp, rq, 64, 256) >= 512 ? 7 : 0;
+    if (conv) {
+        const int64_t t256 = nblocks(rp, rq, 128, 256), t128 = nblocks(rp, rq, 128, 128);
+        if (t256 >= 256 && t256 <= 512) return 13;
+        if (t128 >= 1024) return 12;
+        if (t128 >= 256 || rq > 64) return 1;
+        return 0;
+    }
     if (rp <= 128) return nblocks(rp, rq, 128, 256) >= 512 ? 4 : (rq > 64 ? 1 : 0);
     if (rq <= 64) return 0;
     if (nblocks(rp, rq, 256, 256) >= 256) return 2;
@@ -694,7 +717,7 @@ hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t st)
     prm.acc = a.acc;
     prm.y = a.y;
     prm.ep = a.ep;
-    const int cfg = g_forced_tile >= 0 ? g_forced_tile : pick_tile(a.M, a.N);
+    const int cfg = g_forced_tile >= 0 ? g_forced_tile : pick_tile(a.M, a.N, false);
     return launch_index<false>(cfg, prm, st);
 }
 
@@ -715,7 +738,7 @@ hipError_t launch_conv_mfma(const ConvArgs& a, hipStream_t st)
     prm.y = a.y;
     prm.cst_cls = a.cst_cls;
     prm.ep = a.ep;
-    const int cfg = g_forced_tile >= 0 ? g_forced_tile : pick_tile(g.O, prm.RQ);
+    const int cfg = g_forced_tile >= 0 ? g_forced_tile : pick_tile(g.O, prm.RQ, true);
     return launch_index<true>(cfg, prm, st);
 }
 

@@ -238,10 +238,10 @@ def tile_reset():
     B.set_tile_config(-1)
 
 
-@pytest.mark.parametrize("cfg", range(8))
+@pytest.mark.parametrize("cfg", range(14))
 def test_all_tile_configs_gemm_and_conv(cfg, tile_reset):
     _say("tile config %d" % cfg)
-    assert B.num_tile_configs() == 8
+    assert B.num_tile_configs() == 14
     B.set_tile_config(cfg)
     case = wl.gemm_case(300, 530, 320, seed=cfg)          # several tiles + ragged tails in M and N
     ref, got = T.oracle_gemm(case), T.hip_gemm(case)
