@@ -115,7 +115,10 @@ int rtn_last_hip_error(void);
  * conv; BQ along N resp. along output pixels).  Index: 0 = 64x64, 1 = 128x128,
  * 2 = 256x256, 3 = 64x256, 4 = 128x256, 5 = 256x128, 6 = 64x128, 7 = 64x256
  * with a two-stage operand ring; 8 .. 13 repeat 128x128, 64x256, 64x128, 64x64,
- * 128x128 and 128x256 with other ring depths and register budgets; -1 (default)
+ * 128x128 and 128x256 with other ring depths and register budgets; 14 .. 19 are
+ * conv variants that keep a tile's run of input pixels in LDS (stride 1, centred
+ * window, 64 or 128 padded channels: 64x256 twice, 64x128 twice, 128x128,
+ * 128x256; any other problem runs the plain tile of that size); -1 (default)
  * lets the library choose from the problem shape.  Every configuration computes the same
  * result.  The setting is process-wide and not thread-safe.
  * Returns RTN_ERR_UNSUPPORTED for an index outside -1 .. rtn_num_tile_configs()-1. */
@@ -164,20 +167,24 @@ int rtn_ternary_gemm(rtn_code_format fmt, rtn_path path, const void *a_codes, co
  *   OH = (H + 2*pad - KH)/stride + 1; a tap outside the image adds 0 to D.
  *   a_codes: [Nb][H][W][Cpad]; w_codes: [O][KH][KW][Cpad] (RTN_CODE_I8 only).
  *   acc_out: int32 [Nb][O][OH][OW] or NULL; y_out: fp32 [Nb][O][OH][OW] (NCHW).
- *   KH, KW in 1..7, stride in 1..64, 0 <= pad < min(KH, KW), pad <= 3.
+ *   KH, KW in 1..7, stride in 1..64, 0 <= pad < min(KH, KW), pad <= 2.
  *   workspace (needed when an epilogue is given): the table written by
  *   rtn_conv2d_prepare_constants() for the same filters, pad and epilogue
- *   parameters; it is only read here, so one prepared table serves any number
- *   of calls, batch sizes and image sizes.
+ *   parameters (alpha, beta and the BN affine of `ep` are taken from the
+ *   table; of `ep` itself the call reads only sum_ta and relu); it is only
+ *   read here, so one prepared table serves any number of calls, batch sizes
+ *   and image sizes.  16-byte aligned.
  *   Nb*H*W and Nb*OH*OW must be below 2^31.                                  */
 size_t rtn_conv2d_workspace_bytes(int64_t O, int KH, int KW, int pad);
 /* Weight-side preparation of the conv epilogue (offline, once per layer): fills
- * `workspace` (>= rtn_conv2d_workspace_bytes(O, KH, KW, pad) bytes, 8-byte
- * aligned) with Eq.9's pre-stored constant  C = beta_a*alpha_w*Sw + Kv*beta_a*beta_w
- * for every filter and every border class of output pixels (the in-bounds tap
- * rectangle decides which taps enter Sw and Kv).  Reads ep->sum_tw (the per-tap
- * sums [O][KH][KW]), alpha_w, beta_w and beta_a; ep->sum_ta must be non-NULL but
- * is not read.  C is the number of input channels.                           */
+ * `workspace` (>= rtn_conv2d_workspace_bytes(O, KH, KW, pad) bytes, 16-byte
+ * aligned) with the per-filter factors of the epilogue (alpha_a*alpha_w,
+ * alpha_a*beta_w, BN scale and shift) and Eq.9's pre-stored constant
+ * C = beta_a*alpha_w*Sw + Kv*beta_a*beta_w for every filter and every border
+ * class of output pixels (the in-bounds tap rectangle decides which taps enter
+ * Sw and Kv).  Reads ep->sum_tw (the per-tap sums [O][KH][KW]) and every
+ * scale, offset and BN parameter of `ep`; ep->sum_ta must be non-NULL but is
+ * not read.  C is the number of input channels.                              */
 int rtn_conv2d_prepare_constants(int64_t C, int64_t O, int KH, int KW, int pad, const rtn_epilogue *ep,
                                  void *workspace, size_t workspace_bytes, void *stream);
 int rtn_ternary_conv2d_implicit_gemm(rtn_code_format fmt, rtn_path path, const void *a_codes,

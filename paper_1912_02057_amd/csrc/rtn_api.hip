@@ -18,7 +18,7 @@ int hip_fail(hipError_t e)
 
 constexpr int64_t kMaxDim = 0x7fffffffLL - 1024;
 constexpr int64_t kMaxK = 1LL << 22;
-constexpr int kMaxPad = 3;
+constexpr int kMaxPad = 2;
 
 bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 int64_t pad64(int64_t k) { return (k + 63) / 64 * 64; }
@@ -219,7 +219,8 @@ size_t rtn_conv2d_workspace_bytes(int64_t O, int KH, int KW, int pad)
     if (O <= 0 || KH < 1 || KW < 1 || KH > 7 || KW > 7) return 0;
     if (pad < 0 || pad >= KH || pad >= KW || pad > kMaxPad) return 0;
     const int p1 = pad + 1;
-    return (size_t)O * (size_t)(p1 * p1 * p1 * p1) * sizeof(double);
+    // [4 + classes] rows of O doubles, the row pitch rounded up to an even count
+    return (size_t)((O + 1) & ~(int64_t)1) * (size_t)(4 + p1 * p1 * p1 * p1) * sizeof(double);
 }
 
 int rtn_conv2d_prepare_constants(int64_t C, int64_t O, int KH, int KW, int pad, const rtn_epilogue* ep,
@@ -231,7 +232,7 @@ int rtn_conv2d_prepare_constants(int64_t C, int64_t O, int KH, int KW, int pad, 
     if (rc != RTN_OK) return rc;
     if ((rc = make_epilogue(ep, true, c.ep)) != RTN_OK) return rc;
     if (!workspace || workspace_bytes < rtn_conv2d_workspace_bytes(O, KH, KW, pad)) return RTN_ERR_WORKSPACE;
-    if (!aligned(workspace, 8)) return RTN_ERR_ALIGN;
+    if (!aligned(workspace, 16)) return RTN_ERR_ALIGN;
     const hipError_t he = rtn::launch_conv_class_consts(c, (double*)workspace, (hipStream_t)stream);
     return he == hipSuccess ? RTN_OK : hip_fail(he);
 }
@@ -255,7 +256,7 @@ int rtn_ternary_conv2d_implicit_gemm(rtn_code_format fmt, rtn_path path, const v
     if (ep) {
         if ((rc = make_epilogue(ep, true, c.ep)) != RTN_OK) return rc;
         if (!workspace || workspace_bytes < rtn_conv2d_workspace_bytes(O, KH, KW, pad)) return RTN_ERR_WORKSPACE;
-        if (!aligned(workspace, 8)) return RTN_ERR_ALIGN;
+        if (!aligned(workspace, 16)) return RTN_ERR_ALIGN;
     }
     c.a = (const int8_t*)a_codes;
     c.w = (const int8_t*)w_codes;

@@ -51,6 +51,7 @@ struct TmmParams {
     int band_tiles;    // 8 * tilesQ
     FastDiv div_band;
     int Klogical;      // K of the epilogue's constant term (GEMM)
+    int hrows;         // halo variant: input pixels held in LDS (multiple of 16)
     ConvGeom g;        // conv only
     int32_t* acc;
     float* y;
@@ -58,8 +59,24 @@ struct TmmParams {
     EpiArgs ep;
 };
 
+// Border classes of a conv window and the LDS bytes of the epilogue table of a
+// BP-channel tile: rows g1, c2, bn scale, bn shift, then one row per class.
+__host__ __device__ inline int conv_classes(int pad)
+{
+    const int p1 = pad + 1;
+    return p1 * p1 * p1 * p1;
+}
+__host__ __device__ inline int conv_table_bytes(int bp, int pad) { return (4 + conv_classes(pad)) * bp * 8; }
+
 // chunk swizzle of a 64-byte LDS row (depends on row & 15 only)
 __device__ __forceinline__ int swz(int row) { return ((row >> 1) & 3) ^ ((row >> 3) & 1); }
+
+// chunk swizzle of a pixel row of the halo image: HC-byte rows, HC/16 chunks
+template <int HC>
+__device__ __forceinline__ int halo_swz(int row)
+{
+    return HC == 64 ? swz(row) : ((row >> 1) & 7);
+}
 
 // Direct global -> LDS load: every lane fetches 16 bytes at gptr; the wave's
 // 1 KiB lands at LDS byte offset lds_off (wave-uniform) + 16 * lane.
@@ -74,6 +91,12 @@ __device__ __forceinline__ void dma16_base(const void* sbase, unsigned voff, uns
 {
     asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dwordx4 %1, %2" ::"s"(lds_off), "v"(voff), "s"(sbase)
                  : "memory");
+}
+
+// 4-byte variant: lane l fetches one dword that lands at lds_off + 4 * l.
+__device__ __forceinline__ void dma4(const void* gptr, unsigned lds_off)
+{
+    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_off), "v"(gptr) : "memory");
 }
 
 template <int N>
@@ -101,17 +124,29 @@ __device__ __forceinline__ void wait_groups(int groups)
 }
 
 // MINW = waves per SIMD the register allocation must leave room for.
-template <int BP, int BQ, int WGP, int WGQ, int NS, int MINW, bool CONV>
+//
+// HC != 0 selects the halo variant of the conv (stride 1, KH = 2 pad + 1,
+// KW = 2 pad + 1, Cpad = HC in {64, 128}).  There output pixel m reads input
+// pixel m + (kh - pad) W + (kw - pad) of the same flattened (image, row,
+// column) index space, so the BQ output pixels of a tile need the contiguous
+// run of BQ + 2 pad (W + 1) input pixels around them.  The block loads that
+// run once into LDS and every tap reads its fragments from there: the input
+// crosses L2 -> LDS about 1.4 times instead of KH KW times, and only the
+// weight tile still streams through the ring.
+template <int BP, int BQ, int WGP, int WGQ, int NS, int MINW, bool CONV, int HC = 0>
 __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
 {
     static_assert(WGP * WGQ == 4, "4 waves per block");
+    constexpr bool HALO = HC != 0;
+    static_assert(!HALO || (CONV && (HC == 64 || HC == 128)), "halo variant: conv with Cpad 64 or 128");
     constexpr int WP = BP / WGP, WQ = BQ / WGQ, TP = WP / 32, TQ = WQ / 32;
-    constexpr int LP = BP / 64, LQ = BQ / 64;  // direct loads per wave per K-step
+    constexpr int LP = BP / 64, LQ = HALO ? 0 : BQ / 64;  // direct loads per wave per K-step
+    constexpr int LQA = LQ ? LQ : 1;                       // array extent
     constexpr int DPS = LP + LQ;
     constexpr int NM = TP * TQ;  // MFMAs per k-slice
-    static_assert(TP >= 1 && TQ >= 1 && LP >= 1 && LQ >= 1, "tile too small");
-    static_assert(NS >= 2 && NS <= 4 && 3 * DPS < 64, "vmcnt range");
-    constexpr int STAGE = (BP + BQ) * 64;  // bytes; P tile first, then Q tile
+    static_assert(TP >= 1 && TQ >= 1 && LP >= 1, "tile too small");
+    static_assert(NS >= 2 && (NS - 2) * DPS < 64 && 3 * DPS < 64, "vmcnt range");
+    constexpr int STAGE = (BP + (HALO ? 0 : BQ)) * 64;  // bytes; P tile first, then Q tile
 
     extern __shared__ __attribute__((aligned(16))) int8_t smem[];
     const unsigned lds0 = (unsigned)(uintptr_t)smem;
@@ -135,6 +170,13 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
     const int tileP = band * 8 + inband - tileQ * bandw;
     const int p0 = tileP * BP, q0 = tileQ * BQ;
     const ConvGeom& g = prm.g;
+    // LDS: [halo pixels hrows x HC][128 zero bytes][operand ring][conv: epilogue table,
+    // halo: pixel sums of the run]; the GEMM builds its small table over the ring
+    const int zoff = HALO ? prm.hrows * HC : 0;
+    const int roff = HALO ? zoff + 128 : 0;
+    const int toff = roff + NS * STAGE;
+    const int tab_kib = CONV ? (conv_table_bytes(BP, g.pad) + 1023) >> 10 : 0;
+    const int soff = toff + tab_kib * 1024;  // halo: int32 sum of t_a per pixel of the run
 
     // ---- loader state ------------------------------------------------------
     // Load j of a wave covers tile rows 16*(wave + 4*j) .. +15; lane l fetches
@@ -154,9 +196,9 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
         row = row < prm.RP ? row : prm.RP - 1;  // tail rows: any valid data, never stored
         offP[j] = (unsigned)(row - p0) * (unsigned)prm.ldP + lchunk * 16;
     }
-    const int8_t* gQ[LQ];
-    unsigned offQ[LQ];
-    int vmask[LQ];  // conv: bit kh = row tap valid, bit (8 + kw) = column tap valid
+    const int8_t* gQ[LQA];
+    unsigned offQ[LQA];
+    int vmask[LQA];  // conv: bit kh = row tap valid, bit (8 + kw) = column tap valid
 #pragma unroll
     for (int j = 0; j < LQ; ++j) {
         int row = q0 + 16 * (wave + 4 * j) + lrow;
@@ -187,9 +229,9 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
     const int8_t* zero_page = (const int8_t*)g_zero16;
 
     auto issue_begin = [&](int kt) {
-        is_sbase = lds0 + (unsigned)((kt % NS) * STAGE);
+        is_sbase = lds0 + (unsigned)(roff + (kt % NS) * STAGE);
         is_koffP = (int64_t)kt * 64;
-        if (CONV) {
+        if (CONV && !HALO) {
             is_kh = l_kh;
             is_kw = l_kw;
             is_koffQ = ((int64_t)l_kh * g.W + l_kw) * g.Cpad + l_cc;
@@ -243,15 +285,57 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
         for (int ks = 0; ks < 2; ++ks)
             fragQ[t][ks] = BP * 64 + row * 64 + (((ks * 2 + (lane >> 5)) ^ swz(row)) << 4);
     }
+    // Halo variant: the Q fragment of tap (kh, kw), channel offset cc is row
+    // ml + kh W + kw of the pixel run (ml = the lane's output pixel within the
+    // tile), 16 bytes at chunk q = cc/16 + 2 ks + (l >> 5), swizzled by the row
+    // (halo_swz) so that 16 consecutive rows hit 16 different 16-byte bank
+    // groups; a tap outside the image reads the zero bytes behind the run.
+    int mlb[TQ];
+    unsigned vmq[TQ];  // bit kh = row tap in the image, bit (8 + kw) = column tap in the image
+#pragma unroll
+    for (int j = 0; j < TQ; ++j) {
+        mlb[j] = wq * WQ + j * 32 + (lane & 31);
+        vmq[j] = 0;
+        if (HALO) {
+            int m = q0 + mlb[j];
+            m = m < prm.RQ ? m : prm.RQ - 1;
+            const int nb = (int)fastdiv((uint32_t)m, g.div_ohw), pix = m - nb * (g.OH * g.OW);
+            const int oh = (int)fastdiv((uint32_t)pix, g.div_ow), ow = pix - oh * g.OW;
+            unsigned v = 0;
+            for (int k = 0; k < g.KH; ++k) v |= (unsigned)((unsigned)(oh + k - g.pad) < (unsigned)g.H) << k;
+            for (int k = 0; k < g.KW; ++k) v |= (unsigned)((unsigned)(ow + k - g.pad) < (unsigned)g.W) << (8 + k);
+            vmq[j] = v;
+        }
+    }
+    int f_kh = 0, f_kw = 0, f_cc = 0, f_tapoff = 0;  // K position of the fragments being read
+    auto frag_step_advance = [&]() {
+        f_cc += 64;
+        if (f_cc == HC) {
+            f_cc = 0;
+            if (++f_kw == g.KW) {
+                f_kw = 0;
+                ++f_kh;
+            }
+            f_tapoff = f_kh * g.W + f_kw;
+        }
+    };
     v4i fa[2][TP], fb[2][TQ];
     constexpr int NF = TP + TQ;  // fragments per k-slice
     // idx-th fragment of slice ks of step kt: P fragments first, then Q
     auto load_frag = [&](int kt, int ks, int idx) {
-        const int8_t* st = smem + (kt % NS) * STAGE;
-        if (idx < TP)
+        const int8_t* st = smem + roff + (kt % NS) * STAGE;
+        if (idx < TP) {
             fa[ks][idx] = *(const v4i*)(st + fragP[idx][ks]);
-        else
+        } else if (!HALO) {
             fb[ks][idx - TP] = *(const v4i*)(st + fragQ[idx - TP][ks]);
+        } else {
+            const int j = idx - TP;
+            const int hr = mlb[j] + f_tapoff;
+            const int q = (f_cc >> 4) + ks * 2 + (lane >> 5);
+            const bool ok = ((vmq[j] >> f_kh) & (vmq[j] >> (8 + f_kw)) & 1) != 0;
+            const int addr = ok ? hr * HC + ((q ^ halo_swz<HC>(hr)) << 4) : zoff + ((lane >> 5) << 4);
+            fb[ks][j] = *(const v4i*)(smem + addr);
+        }
     };
     auto load_frags = [&](int kt, int ks) {
 #pragma unroll
@@ -273,6 +357,7 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
     auto slice = [&](auto with_frags, auto with_issue, int ks, int fkt, int fks, int ikt) {
         constexpr bool FRAGS = decltype(with_frags)::value, ISSUE = decltype(with_issue)::value;
         if (ISSUE) issue_begin(ikt);
+        if (HALO && FRAGS && fks == 0) frag_step_advance();
 #pragma unroll
         for (int n = 0; n < NM; ++n) {
             acc[n / TQ][n % TQ] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[ks][n / TQ], fb[ks][n % TQ],
@@ -297,6 +382,46 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
     // ---- prologue: start the first NS steps, then per-lane epilogue terms -----
     const int nk = prm.nk;
     const int npro = nk < NS ? nk : NS;
+    if (CONV && prm.y) {
+        // epilogue table: rows [g1, c2, bn scale, bn shift, class constants...] of the
+        // prepared per-layer table, columns p0 .. p0+BP-1, copied as they are
+        const int nrows = 4 + conv_classes(g.pad), opitch = (g.O + 1) & ~1;
+        for (int n = wave; n < tab_kib; n += 4) {
+            const int lin = n * 64 + lane;  // 16-byte unit = 2 doubles
+            int row = lin / (BP / 2);
+            const int u = lin - row * (BP / 2);
+            row = row < nrows ? row : nrows - 1;
+            int64_t idx = (int64_t)row * opitch + p0 + 2 * u;
+            const int64_t last = (int64_t)nrows * opitch - 2;
+            idx = idx < last ? idx : last;  // columns past O are never used
+            dma16(prm.cst_cls + idx, lds0 + (unsigned)(toff + n * 1024));
+        }
+        if (HALO) {
+            const int total_px = g.Nb * g.H * g.W;
+            const int first_px = q0 - g.pad * (g.W + 1);
+            for (int n = wave; n * 64 < prm.hrows; n += 4) {
+                int px = first_px + n * 64 + lane;
+                px = px < 0 ? 0 : (px < total_px ? px : total_px - 1);
+                dma4(prm.ep.sum_ta + px, lds0 + (unsigned)(soff + n * 256));
+            }
+        }
+    }
+    if (HALO) {
+        // the pixel run: 1 KiB per load, lane l lands at 16-byte unit n*64 + l; which chunk
+        // of its row a lane fetches is permuted by the row swizzle.  Runs past either
+        // end of the tensor re-read the end pixel (only out-of-image taps point there).
+        const int total_px = g.Nb * g.H * g.W;
+        const int first_px = q0 - g.pad * (g.W + 1);
+        const int ninstr = prm.hrows * HC / 1024;
+        for (int n = wave; n < ninstr; n += 4) {
+            const int lin = n * 64 + lane;
+            const int row = lin / (HC / 16), qp = lin % (HC / 16);
+            int px = first_px + row;
+            px = px < 0 ? 0 : (px < total_px ? px : total_px - 1);
+            dma16(prm.Q + (int64_t)px * HC + ((qp ^ halo_swz<HC>(row)) << 4), lds0 + (unsigned)(n * 1024));
+        }
+        if (tid < 8) *(uint4*)(smem + zoff + tid * 16) = make_uint4(0, 0, 0, 0);
+    }
     for (int s = 0; s < npro; ++s) issue(s);
 
     // conv: for each of this lane's TQ output pixels, Sa (sum of the input-pixel
@@ -322,7 +447,9 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
             tap_range(ow, g.stride, g.pad, g.KW, g.W, kwl, kwh);
             const int32_t* ps = prm.ep.sum_ta + ((int64_t)nb * g.H + ih0) * g.W + iw0;
             int s = 0;
-            if (g.KH == 3 && g.KW == 3) {
+            if (HALO) {
+                // summed in the epilogue from the pixel sums of the run held in LDS
+            } else if (g.KH == 3 && g.KW == 3) {
                 int v[9];
 #pragma unroll
                 for (int t = 0; t < 9; ++t) {
@@ -382,7 +509,7 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
     // ReLU and BN are applied unconditionally with neutral parameters when off:
     // max(v, -inf) = v and 1*v + 0 = v exactly, so the element code has no selects.
     const double relu_floor = __builtin_canonicalize(ep.relu ? 0.0 : -__builtin_inf());
-    double* tab = (double*)smem;
+    double* tab = (double*)(smem + (CONV ? toff : 0));
     const bool full_tile = p0 + BP <= prm.RP && q0 + BQ <= prm.RQ;
     // The element loops exist in 6 straight-line variants (interior / ragged
     // tile) x (acc only / y only / both), picked once per block.
@@ -403,8 +530,8 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
                 run(std::false_type{}, std::true_type{}, std::true_type{});
         }
     };
-    __syncthreads();  // all waves are done with the operand stages
     if (!CONV) {
+        __syncthreads();  // all waves are done with the operand stages
         // y = aw*(aa*D + ba*Sw) + bw*r2 with r2 = aa*Sa + K*ba per row m; tab = [3][BP]
         if (prm.y) {
             for (int t = tid; t < BP; t += 256) {
@@ -483,32 +610,23 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
         // y = g1[o]*D + c2[o]*Sa[m] + Cst[class(m)][o],  g1 = aa*aw, c2 = aa*bw;
         // tab = [4 + ncls][BP]: g1, c2, bn scale, bn shift, then the class constants.
         const int ohw = g.OH * g.OW;
-        const int p1 = g.pad + 1, ncls = p1 * p1 * p1 * p1;
-        if (prm.y) {
-            const double aa = (double)ep.alpha_a.s;
-            for (int t = tid; t < BP; t += 256) {
-                const int o = p0 + t;
-                double g1 = 0.0, c2 = 0.0, bs = 1.0, bh = 0.0;
-                if (o < prm.RP) {
-                    g1 = aa * pval(ep.alpha_w, o);
-                    c2 = aa * pval(ep.beta_w, o);
-                    if (has_bn) {
-                        bs = (double)ep.bn_scale[o];
-                        bh = ep.bn_shift ? (double)ep.bn_shift[o] : 0.0;
+        const int p1 = g.pad + 1;
+        (void)p1;
+        // (the table was copied into LDS by the prologue's direct loads)
+        int sa_halo[TQ];
+#pragma unroll
+        for (int j = 0; j < TQ; ++j) sa_halo[j] = 0;
+        if (HALO && prm.y) {
+            const int32_t* run = (const int32_t*)(smem + soff);
+#pragma unroll
+            for (int j = 0; j < TQ; ++j)
+                for (int kh = 0; kh < g.KH; ++kh)
+                    for (int kw = 0; kw < g.KW; ++kw) {
+                        const bool ok = ((vmq[j] >> kh) & (vmq[j] >> (8 + kw)) & 1) != 0;
+                        const int v = run[mlb[j] + kh * g.W + kw];
+                        sa_halo[j] += ok ? v : 0;
                     }
-                }
-                tab[t] = g1;
-                tab[BP + t] = c2;
-                tab[2 * BP + t] = bs;
-                tab[3 * BP + t] = bh;
-            }
-            for (int e = tid; e < ncls * BP; e += 256) {
-                const int c = e / BP, t = e - c * BP;
-                const int o = p0 + t;
-                tab[(4 + c) * BP + t] = o < prm.RP ? prm.cst_cls[(int64_t)c * g.O + o] : 0.0;
-            }
         }
-        __syncthreads();
         dispatch([&](auto full, auto want_acc, auto want_y) {
             constexpr bool FULL = decltype(full)::value, ACC = decltype(want_acc)::value,
                            Y = decltype(want_y)::value;
@@ -527,7 +645,7 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
                 const int64_t obase = (int64_t)nb * g.O * ohw + pix;
                 accp[j] = ACC ? prm.acc + obase : nullptr;
                 yp[j] = Y ? prm.y + obase : nullptr;
-                Sa[j] = (double)(pixinfo[j] >> 8);
+                Sa[j] = (double)(HALO ? sa_halo[j] : (pixinfo[j] >> 8));
                 ctab[j] = tab + (4 + (pixinfo[j] & 255)) * BP;
             }
 #pragma unroll
@@ -565,53 +683,91 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
     }
 }
 
-// Constants of the reparameterization per border class.  A class is the
-// in-bounds tap rectangle [khl..khh] x [kwl..kwh] of an output pixel, indexed
+// The per-layer table of the conv epilogue, [4 + classes][OP] doubles with the
+// row pitch OP = O rounded up to even (16-byte rows for the direct loads):
+//   row 0: g1[o] = aa*aw[o]      row 1: c2[o] = aa*bw[o]
+//   row 2: bn scale (1 if none)  row 3: bn shift (0 if none)
+//   row 4 + class: the constant of the reparameterization for that border class.
+// A class is the in-bounds tap rectangle [khl..khh] x [kwl..kwh] of an output pixel,
 //   class = rid * (pad+1)^2 + cid,  rid = khl + (pad+1)*(KH-1-khh),  cid = kwl + (pad+1)*(KW-1-kwh)
 // (both cuts are at most pad, so there are (pad+1)^4 classes; class 0 is the
 // interior).    cst[class][o] = ba*aw[o]*Sw + Kv*ba*bw[o]
 // with Sw the sum of filter o's per-tap channel sums over the rectangle and
 // Kv = C * (number of taps in it): Eq.9's pre-stored constant C, one per class.
-__global__ __launch_bounds__(256) void k_conv_class_consts(const int32_t* tap, ConvGeom g, Param alpha_w,
-                                                           Param beta_w, float beta_a, double* cst)
+__global__ __launch_bounds__(256) void k_conv_class_consts(const int32_t* tap, ConvGeom g, EpiArgs ep, double* cst)
 {
     const int p1 = g.pad + 1;
-    const int ncls = p1 * p1 * p1 * p1;
-    const int64_t total = (int64_t)ncls * g.O;
+    const int nrows = 4 + conv_classes(g.pad), opitch = (g.O + 1) & ~1;
+    const int64_t total = (int64_t)nrows * opitch;
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (i >= total) return;
-    const int o = (int)(i % g.O);
-    const int cls = (int)(i / g.O);
-    const int rid = cls / (p1 * p1), cid = cls % (p1 * p1);
-    const int khl = rid % p1, khh = g.KH - 1 - rid / p1;
-    const int kwl = cid % p1, kwh = g.KW - 1 - cid / p1;
-    int s = 0, taps = 0;
-    for (int kh = khl; kh <= khh; ++kh)
-        for (int kw = kwl; kw <= kwh; ++kw) {
-            s += tap[((int64_t)o * g.KH + kh) * g.KW + kw];
-            ++taps;
+    const int o = (int)(i % opitch);
+    const int row = (int)(i / opitch);
+    double v = 0.0;
+    if (o < g.O) {
+        const double aa = (double)ep.alpha_a.s, ba = (double)ep.beta_a.s;
+        if (row == 0) {
+            v = aa * pval(ep.alpha_w, o);
+        } else if (row == 1) {
+            v = aa * pval(ep.beta_w, o);
+        } else if (row == 2) {
+            v = ep.bn_scale ? (double)ep.bn_scale[o] : 1.0;
+        } else if (row == 3) {
+            v = (ep.bn_scale && ep.bn_shift) ? (double)ep.bn_shift[o] : 0.0;
+        } else {
+            const int cls = row - 4;
+            const int rid = cls / (p1 * p1), cid = cls % (p1 * p1);
+            const int khl = rid % p1, khh = g.KH - 1 - rid / p1;
+            const int kwl = cid % p1, kwh = g.KW - 1 - cid / p1;
+            int s = 0, taps = 0;
+            for (int kh = khl; kh <= khh; ++kh)
+                for (int kw = kwl; kw <= kwh; ++kw) {
+                    s += tap[((int64_t)o * g.KH + kh) * g.KW + kw];
+                    ++taps;
+                }
+            v = ba * pval(ep.alpha_w, o) * (double)s + (double)(g.C * taps) * ba * pval(ep.beta_w, o);
         }
-    const double ba = (double)beta_a;
-    cst[i] = ba * pval(alpha_w, o) * (double)s + (double)(g.C * taps) * ba * pval(beta_w, o);
+    }
+    cst[i] = v;
 }
 
 // LDS bytes of the epilogue tables of a BP-row tile.
 inline int64_t table_bytes(int bp, bool conv, int pad)
 {
-    const int p1 = pad + 1;
-    return conv ? (int64_t)(4 + p1 * p1 * p1 * p1) * bp * 8 : (int64_t)3 * bp * 8;
+    return conv ? (int64_t)conv_table_bytes(bp, pad) : (int64_t)3 * bp * 8;
 }
 constexpr int64_t kMaxLds = 160 * 1024;
 
-template <int BP, int BQ, int WGP, int WGQ, int NS, int MINW, bool CONV>
+// Halo variant: stride 1, window centred on the output pixel, HC-byte pixel rows.
+inline bool halo_eligible(const TmmParams& prm, int hc)
+{
+    const ConvGeom& g = prm.g;
+    return g.stride == 1 && g.KH == 2 * g.pad + 1 && g.KW == 2 * g.pad + 1 && g.Cpad == hc && g.OH == g.H &&
+           g.OW == g.W;
+}
+
+template <int BP, int BQ, int WGP, int WGQ, int NS, int MINW, bool CONV, int HC = 0>
 hipError_t launch_cfg(TmmParams& prm, hipStream_t st)
 {
-    constexpr int stage_bytes = NS * (BP + BQ) * 64;
-    const int64_t tb = table_bytes(BP, CONV, prm.g.pad);
-    const int64_t smem = stage_bytes > tb ? stage_bytes : tb;
+    constexpr int ring_bytes = NS * (BP + (HC ? 0 : BQ)) * 64;
+    int64_t stage_bytes = ring_bytes;
+    if (HC) {
+        if (!halo_eligible(prm, HC)) return hipErrorInvalidValue;
+        prm.hrows = (BQ + 2 * prm.g.pad * (prm.g.W + 1) + 15) & ~15;
+        stage_bytes += (int64_t)prm.hrows * HC + 128;
+    }
+    int64_t smem;
+    if (CONV) {
+        // ring (+ halo), then the epilogue table in whole KiB, then the halo's pixel sums
+        smem = stage_bytes + ((table_bytes(BP, true, prm.g.pad) + 1023) & ~(int64_t)1023);
+        if (HC) smem += ((prm.hrows + 63) & ~63) * 4;
+    } else {
+        const int64_t tb = table_bytes(BP, false, 0);
+        smem = stage_bytes > tb ? stage_bytes : tb;
+    }
     if (smem > kMaxLds) return hipErrorInvalidValue;
     static bool attr_done = false;
-    auto kern = k_tmm<BP, BQ, WGP, WGQ, NS, MINW, CONV>;
+    auto kern = k_tmm<BP, BQ, WGP, WGQ, NS, MINW, CONV, HC>;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)kMaxLds);
@@ -637,20 +793,34 @@ inline int64_t nblocks(int64_t rp, int64_t rq, int bp, int bq)
 }
 
 // Tile configurations, indexed as rtn_set_tile_config() documents.
-constexpr int kNumTileConfigs = 14;
-const int kTileBP[kNumTileConfigs] = {64, 128, 256, 64, 128, 256, 64, 64, 128, 64, 64, 64, 128, 128};
+constexpr int kNumTileConfigs = 20;
+const int kTileBP[kNumTileConfigs] = {64, 128, 256, 64,  128, 256, 64, 64, 128, 64,
+                                       64, 64,  128, 128, 64,  64,  64, 64, 128, 128};
 int g_forced_tile = -1;
 
 template <bool CONV>
+hipError_t launch_index_raw(int cfg, TmmParams& prm, hipStream_t st);
+
+// A configuration whose LDS need (ring + the conv's table, which grows with the
+// pad) exceeds the CU's falls back to the smallest tile.
+template <bool CONV>
 hipError_t launch_index(int cfg, TmmParams& prm, hipStream_t st)
+{
+    hipError_t e = launch_index_raw<CONV>(cfg, prm, st);
+    if (e == hipErrorInvalidValue && cfg != 0) e = launch_index_raw<CONV>(0, prm, st);
+    return e;
+}
+
+template <bool CONV>
+hipError_t launch_index_raw(int cfg, TmmParams& prm, hipStream_t st)
 {
     // conv with a large pad: the per-class constant table of a tall tile does
     // not fit in LDS; fall back to the tile of the same width class with BP = 64.
-    if (CONV && table_bytes(kTileBP[cfg], true, prm.g.pad) > kMaxLds) cfg = 0;
+    if (CONV && table_bytes(kTileBP[cfg], true, prm.g.pad) > 48 * 1024) cfg = 0;
     switch (cfg) {
         case 0: return launch_cfg<64, 64, 2, 2, 4, 4, CONV>(prm, st);
-        case 1: return launch_cfg<128, 128, 2, 2, 4, 2, CONV>(prm, st);
-        case 2: return launch_cfg<256, 256, 2, 2, 4, 1, CONV>(prm, st);
+        case 1: return launch_cfg<128, 128, 2, 2, (CONV ? 3 : 4), 2, CONV>(prm, st);
+        case 2: return launch_cfg<256, 256, 2, 2, (CONV ? 3 : 4), 1, CONV>(prm, st);
         case 3: return launch_cfg<64, 256, 1, 4, 3, 3, CONV>(prm, st);
         case 4: return launch_cfg<128, 256, 2, 2, 3, 2, CONV>(prm, st);
         case 5: return launch_cfg<256, 128, 2, 2, 3, 2, CONV>(prm, st);
@@ -662,6 +832,35 @@ hipError_t launch_index(int cfg, TmmParams& prm, hipStream_t st)
         case 11: return launch_cfg<64, 64, 2, 2, 4, 6, CONV>(prm, st);
         case 12: return launch_cfg<128, 128, 2, 2, 2, 4, CONV>(prm, st);
         case 13: return launch_cfg<128, 256, 2, 2, 2, 2, CONV>(prm, st);
+        default: break;
+    }
+    // 14 .. 19: halo variants (conv only); a shape they do not cover runs the plain
+    // tile of the same size instead
+    if constexpr (CONV) {
+        const int hc = prm.g.Cpad;
+        const bool ok = halo_eligible(prm, 64) || halo_eligible(prm, 128);
+        if (ok && hc == 64) {
+            switch (cfg) {
+                case 14: return launch_cfg<64, 256, 1, 4, 9, 2, CONV, 64>(prm, st);
+                case 15: return launch_cfg<64, 256, 1, 4, 3, 3, CONV, 64>(prm, st);
+                case 16: return launch_cfg<64, 128, 1, 4, 9, 3, CONV, 64>(prm, st);
+                case 17: return launch_cfg<64, 128, 1, 4, 3, 4, CONV, 64>(prm, st);
+                default: break;
+            }
+        }
+        if (ok && hc == 128) {
+            switch (cfg) {
+                case 18: return launch_cfg<128, 128, 2, 2, 3, 3, CONV, 128>(prm, st);
+                case 19: return launch_cfg<128, 256, 2, 2, 3, 2, CONV, 128>(prm, st);
+                default: break;
+            }
+        }
+    }
+    switch (cfg) {
+        case 14: case 15: return launch_cfg<64, 256, 1, 4, 2, 3, CONV>(prm, st);
+        case 16: case 17: return launch_cfg<64, 128, 1, 4, 3, 4, CONV>(prm, st);
+        case 18: return launch_cfg<128, 128, 2, 2, 2, 4, CONV>(prm, st);
+        case 19: return launch_cfg<128, 256, 2, 2, 2, 2, CONV>(prm, st);
         default: return hipErrorInvalidValue;
     }
 }
@@ -697,10 +896,9 @@ void force_tile_config(int index) { g_forced_tile = index; }
 hipError_t launch_conv_class_consts(const ConvArgs& a, double* cst, hipStream_t st)
 {
     const ConvGeom& g = a.g;
-    const int p1 = g.pad + 1;
-    const int64_t total = (int64_t)p1 * p1 * p1 * p1 * g.O;
+    const int64_t total = (int64_t)(4 + conv_classes(g.pad)) * ((g.O + 1) & ~1);
     hipLaunchKernelGGL(k_conv_class_consts, dim3((unsigned)((total + 255) / 256)), dim3(256), 0, st,
-                       a.ep.sum_tw, g, a.ep.alpha_w, a.ep.beta_w, a.ep.beta_a.s, cst);
+                       a.ep.sum_tw, g, a.ep, cst);
     return hipGetLastError();
 }
 
@@ -738,7 +936,10 @@ hipError_t launch_conv_mfma(const ConvArgs& a, hipStream_t st)
     prm.y = a.y;
     prm.cst_cls = a.cst_cls;
     prm.ep = a.ep;
-    const int cfg = g_forced_tile >= 0 ? g_forced_tile : pick_tile(g.O, prm.RQ, true);
+    int cfg = g_forced_tile >= 0 ? g_forced_tile : pick_tile(g.O, prm.RQ, true);
+    // a 64-filter layer with a centred stride-1 window: the variant that keeps the
+    // tile's input pixel run in LDS (measured faster there; on par or slower elsewhere)
+    if (g_forced_tile < 0 && cfg == 7 && halo_eligible(prm, 64)) cfg = 15;
     return launch_index<true>(cfg, prm, st);
 }
 

@@ -66,7 +66,11 @@ def hip_gemm(case, fmt=B.RTN_CODE_I8, relu=False, bn=None, want_acc=True):
     ep = B.Epilogue(gran_arg(case["alpha_a"]), gran_arg(case["beta_a"]), gran_arg(case["alpha_w"]),
                     gran_arg(case["beta_w"]), sa, sw, relu=relu,
                     bn_scale=None if bn is None else dev(bn[0]), bn_shift=None if bn is None else dev(bn[1]))
-    acc, y = B.ternary_gemm(ca, cw, case["M"], case["N"], case["K"], fmt=fmt, ep=ep, want_acc=want_acc)
+    if want_acc == "separate":      # the two single-output launches (accumulators only, then y only)
+        acc, _ = B.ternary_gemm(ca, cw, case["M"], case["N"], case["K"], fmt=fmt, ep=None, want_acc=True)
+        _, y = B.ternary_gemm(ca, cw, case["M"], case["N"], case["K"], fmt=fmt, ep=ep, want_acc=False)
+    else:
+        acc, y = B.ternary_gemm(ca, cw, case["M"], case["N"], case["K"], fmt=fmt, ep=ep, want_acc=want_acc)
     torch.cuda.synchronize()
     return dict(ca=ca, cw=cw, Sa=sa, Sw=sw, D=acc, y=y, ep=ep)
 
@@ -96,8 +100,14 @@ def hip_conv(case, pad_true_zero=True, relu=False, want_acc=True):
                     bn_scale=None if "bn_scale" not in case else dev(case["bn_scale"]),
                     bn_shift=None if "bn_shift" not in case else dev(case["bn_shift"]))
     Nb, Cc, H, W = case["x"].shape
-    acc, y = B.ternary_conv2d(ca, cw, Nb, Cc, H, W, sh.O, sh.k, sh.k, sh.stride, sh.pad,
-                              B.RTN_PAD_TRUE_ZERO if pad_true_zero else B.RTN_PAD_CODE_ZERO,
-                              ep=ep, want_acc=want_acc)
+    pm = B.RTN_PAD_TRUE_ZERO if pad_true_zero else B.RTN_PAD_CODE_ZERO
+    if want_acc == "separate":      # the two single-output launches (accumulators only, then y only)
+        acc, _ = B.ternary_conv2d(ca, cw, Nb, Cc, H, W, sh.O, sh.k, sh.k, sh.stride, sh.pad, pm,
+                                  ep=None, want_acc=True)
+        _, y = B.ternary_conv2d(ca, cw, Nb, Cc, H, W, sh.O, sh.k, sh.k, sh.stride, sh.pad, pm,
+                                ep=ep, want_acc=False)
+    else:
+        acc, y = B.ternary_conv2d(ca, cw, Nb, Cc, H, W, sh.O, sh.k, sh.k, sh.stride, sh.pad, pm,
+                                  ep=ep, want_acc=want_acc)
     torch.cuda.synchronize()
     return dict(ca=ca, cw=cw, pa=pa, pw=pw, D=acc, y=y, ep=ep)

@@ -39,9 +39,12 @@ def test_helpers(L):
     assert L.rtn_codes_bytes(B.RTN_CODE_I8, 3, 70) == 3 * 128
     assert L.rtn_codes_bytes(B.RTN_CODE_BITPLANE, 3, 70) == 3 * 2 * 8 * 2
     assert L.rtn_codes_bytes(7, 3, 70) == 0
-    assert L.rtn_conv2d_workspace_bytes(64, 3, 3, 1) == 64 * 16 * 8
-    assert L.rtn_conv2d_workspace_bytes(64, 1, 1, 0) == 64 * 8
-    assert L.rtn_conv2d_workspace_bytes(64, 3, 3, 3) == 0
+    assert L.rtn_conv2d_workspace_bytes(64, 3, 3, 1) == 64 * 20 * 8
+    assert L.rtn_conv2d_workspace_bytes(63, 3, 3, 1) == 64 * 20 * 8      # row pitch rounded up to even
+    assert L.rtn_conv2d_workspace_bytes(64, 1, 1, 0) == 64 * 5 * 8
+    assert L.rtn_conv2d_workspace_bytes(64, 5, 5, 2) == 64 * 85 * 8
+    assert L.rtn_conv2d_workspace_bytes(64, 3, 3, 3) == 0                # pad >= kernel
+    assert L.rtn_conv2d_workspace_bytes(64, 7, 7, 3) == 0                # pad above the supported 2
     assert L.rtn_status_string(0) == b"ok"
     for s in range(-6, 0):
         assert len(L.rtn_status_string(s)) > 3
@@ -158,7 +161,8 @@ def test_prepare_constants_rejects(L):
     call = L.rtn_conv2d_prepare_constants
     assert call(64, 64, 3, 3, 1, None, FAKE, 1 << 20, None) == B.RTN_ERR_NULL
     assert call(64, 64, 3, 3, 1, C.byref(e), None, 1 << 20, None) == B.RTN_ERR_WORKSPACE
-    assert call(64, 64, 3, 3, 1, C.byref(e), FAKE, 64 * 16 * 8 - 1, None) == B.RTN_ERR_WORKSPACE
+    assert call(64, 64, 3, 3, 1, C.byref(e), FAKE, 64 * 20 * 8 - 1, None) == B.RTN_ERR_WORKSPACE
+    assert call(64, 64, 7, 7, 3, C.byref(e), FAKE, 1 << 20, None) == B.RTN_ERR_UNSUPPORTED   # pad above 2
     assert call(64, 64, 3, 3, 3, C.byref(e), FAKE, 1 << 20, None) == B.RTN_ERR_UNSUPPORTED   # pad >= kernel
     assert call(0, 64, 3, 3, 1, C.byref(e), FAKE, 1 << 20, None) == B.RTN_ERR_SHAPE
     assert call(64, 64, 3, 3, 1, C.byref(e), ODD, 1 << 20, None) == B.RTN_ERR_ALIGN

@@ -238,10 +238,10 @@ def tile_reset():
     B.set_tile_config(-1)
 
 
-@pytest.mark.parametrize("cfg", range(14))
+@pytest.mark.parametrize("cfg", range(20))
 def test_all_tile_configs_gemm_and_conv(cfg, tile_reset):
     _say("tile config %d" % cfg)
-    assert B.num_tile_configs() == 14
+    assert B.num_tile_configs() == 20
     B.set_tile_config(cfg)
     case = wl.gemm_case(300, 530, 320, seed=cfg)          # several tiles + ragged tails in M and N
     ref, got = T.oracle_gemm(case), T.hip_gemm(case)
@@ -254,13 +254,63 @@ def test_all_tile_configs_gemm_and_conv(cfg, tile_reset):
     T.assert_y_close(cgot["y"].cpu().numpy(), cref["y"], "conv cfg %d" % cfg)
 
 
+@pytest.mark.parametrize("cfg", range(20))
+def test_all_tile_configs_single_output_launches(cfg, tile_reset):
+    """Accumulators only and y only, on shapes whose rows can be written 16 bytes
+    at a time (N % 4 == 0, OH*OW % 4 == 0) and that have full tiles as well as
+    ragged ones: the staged wide-store path of every tile configuration."""
+    _say("tile config %d, single-output launches" % cfg)
+    B.set_tile_config(cfg)
+    case = wl.gemm_case(300, 528, 320, seed=50 + cfg)
+    ref, got = T.oracle_gemm(case), T.hip_gemm(case, want_acc="separate")
+    assert (got["D"].cpu().numpy() == ref["D"]).all()
+    T.assert_y_close(got["y"].cpu().numpy(), ref["y"], "gemm cfg %d" % cfg)
+    shape = wl.ConvShape("t", 64, 16, 264, 3, 1, 1)
+    ccase = wl.conv_case(shape, batch=3, seed=50 + cfg, bn=True)    # 3*256 pixels, O = 264
+    cref = T.oracle_conv(ccase, True, relu=True)
+    cgot = T.hip_conv(ccase, True, relu=True, want_acc="separate")
+    assert (cgot["D"].cpu().numpy() == cref["D"]).all()
+    T.assert_y_close(cgot["y"].cpu().numpy(), cref["y"], "conv cfg %d" % cfg)
+
+
+HALO_SHAPES = [
+    # name, C, H, O, k, stride, pad, batch, W (None = H)
+    ("h64", 64, 16, 72, 3, 1, 1, 3, None),          # Cpad 64: tile straddles images
+    ("h64r", 50, 9, 64, 3, 1, 1, 5, 11),            # C padded to 64, non-square, ragged pixel tail
+    ("h64k5", 64, 12, 40, 5, 1, 2, 2, None),        # 5x5 window, pad 2
+    ("h128", 128, 12, 136, 3, 1, 1, 3, None),       # Cpad 128: two K-steps per tap
+    ("h128r", 100, 7, 130, 3, 1, 1, 9, 10),         # C padded to 128, ragged in O and pixels
+    ("h128k1", 128, 8, 64, 1, 1, 0, 4, None),       # 1x1: the run is the tile itself
+]
+
+
+@pytest.mark.parametrize("cfg", range(14, 20))
+@pytest.mark.parametrize("hs", HALO_SHAPES, ids=[h[0] for h in HALO_SHAPES])
+def test_halo_variants(cfg, hs, tile_reset):
+    """The conv variants that hold the input pixel run of a tile in LDS (stride 1,
+    centred window, Cpad 64 or 128), in the combined and in the single-output
+    launches; a configuration that does not cover a shape falls back to its
+    plain tile, which must give the same result."""
+    name, Cc, H, O, k, stride, pad, batch, W = hs
+    _say("halo cfg %d shape %s" % (cfg, name))
+    B.set_tile_config(cfg)
+    shape = wl.ConvShape(name, Cc, H, O, k, stride, pad)
+    case = wl.conv_case(shape, batch=batch, seed=300 + cfg, bn=True, Wx=W)
+    for tz in (True, False):
+        ref = T.oracle_conv(case, tz, relu=True)
+        for mode in (True, "separate"):
+            got = T.hip_conv(case, tz, relu=True, want_acc=mode)
+            assert (got["D"].cpu().numpy() == ref["D"]).all(), (name, tz, mode)
+            T.assert_y_close(got["y"].cpu().numpy(), ref["y"], "%s cfg %d" % (name, cfg))
+
+
 # ----------------------------------------------------- full-size checks ------
 def test_config2_gemm_4096_sampled_rows():
     """M = N = K = 4096 in the launch configuration the benchmark times; the
     oracle computes 48 sampled rows (all columns) plus every code and side sum."""
     _say("config 2: 4096^3, sampled rows")
     case = wl.gemm_case(4096, 4096, 4096, p_zero=0.4, seed=1)
-    got = T.hip_gemm(case)
+    got = T.hip_gemm(case, want_acc="separate")
     ta = orc.ternarize(case["xa"], -0.5, 0.5)
     tw = orc.ternarize(case["xw"], -0.5, 0.5)
     assert (got["ca"].cpu().numpy() == ta).all() and (got["cw"].cpu().numpy() == tw).all()
@@ -286,7 +336,7 @@ def test_resnet18_layers_batch256_sampled_images(idx):
     shape = wl.resnet18_ternary_layers()[idx]
     _say("resnet18 b256 %s" % (shape,))
     case = wl.conv_case(shape, batch=256, seed=100 + idx, per_channel=True, bn=True)
-    got = T.hip_conv(case, True, relu=True)
+    got = T.hip_conv(case, True, relu=True, want_acc="separate")
     imgs = [0, 255]
     ref = T.oracle_conv(case, True, relu=True, images=imgs)
     assert (got["D"][imgs].cpu().numpy() == ref["D"]).all()
