@@ -159,35 +159,42 @@ __global__ __launch_bounds__(256) void k_pack_nchw_i8(PackArgs a)
 }
 
 // ---- NCHW layout, int8 codes, 16-byte loads ---------------------------------
-// Variant for H*W % 4 == 0 and a 16-byte aligned input: a block owns 256
-// consecutive pixels; lane l holds pixels 4l..4l+3 and reads them with one
-// 16-byte load per channel (a wave reads 1 KiB per channel).  Channels go in
-// chunks of 64: wave w takes channels 16w..16w+15 of the chunk, so a lane ends
-// up with, for each of its 4 pixels, the 16 code bytes that are contiguous in
-// the channel-innermost output.  They are parked in a 256 x 64-byte LDS image
-// (16-byte slots XOR-swizzled by lane to spread banks) and streamed out with
-// 4 consecutive lanes writing the 64 contiguous bytes of a pixel.
+// Variant for H*W % 4 == 0 and a 16-byte aligned input.  A block owns
+// PB = 4*LPR consecutive pixels; LPR lanes read one channel's run of them with
+// one 16-byte load each (lane l: pixels 4q..4q+3, q = l % LPR), and the
+// SUBS = 64/LPR lane groups of a wave read channels 16 apart.  Channels go in
+// groups of 64*SUBS: wave w, lane group s take channels 16*(w*SUBS+s) .. +15 of
+// the group, so a lane ends up with, for each of its 4 pixels, 16 code bytes
+// that are contiguous in the channel-innermost output.  They are parked in a
+// PB x (64*SUBS)-byte LDS image (always 16 KiB; 16-byte slots XOR-swizzled by
+// the pixel quad to spread banks) and streamed out with consecutive lanes
+// writing consecutive 16-byte pieces of a pixel's 64*SUBS contiguous bytes.
+// LPR = 64 gives the widest pixel runs; the smaller ones trade them for more
+// blocks (a tensor with few pixels and many channels) and fewer passes.
+template <int LPR>
 __global__ __launch_bounds__(256) void k_pack_nchw_i8_v4(PackArgs a)
 {
-    __shared__ __attribute__((aligned(16))) uint8_t tile[256 * 64];
-    __shared__ int part[4][256];
+    constexpr int SUBS = 64 / LPR, PB = 4 * LPR, RB = 64 * SUBS, NSLOT = RB / 16;
+    __shared__ __attribute__((aligned(16))) uint8_t tile[PB * RB];
+    __shared__ int part[4 * SUBS][PB];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int quad = lane % LPR, cblk = wave * SUBS + lane / LPR;
     const int64_t total = a.N * a.HW;
-    const int64_t q0 = (int64_t)blockIdx.x * 256, q = q0 + 4 * lane;
+    const int64_t q0 = (int64_t)blockIdx.x * PB, q = q0 + 4 * quad;
     const bool pin = q < total;  // total % 4 == 0: all four pixels or none
     const int64_t n = pin ? q / a.HW : 0;
     const int64_t p = pin ? q - n * a.HW : 0;
     const float lo = thr(a.lo, n), hi = thr(a.hi, n);
     const float* xn = a.x + n * a.K * a.HW + p;
-    const int nchunk = (int)(a.Kpad >> 6);
-    const int64_t valid = total - q0 < 256 ? total - q0 : 256;
+    const int ngroup = (int)((a.Kpad + RB - 1) / RB);
+    const int64_t valid = total - q0 < PB ? total - q0 : PB;
     uint8_t* out = (uint8_t*)a.codes + q0 * a.Kpad;
     int sum[4] = {0, 0, 0, 0};
-    for (int cb = 0; cb < nchunk; ++cb) {
+    for (int cg = 0; cg < ngroup; ++cg) {
         float4 v[16];
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
-            const int64_t c = (int64_t)cb * 64 + wave * 16 + j;
+            const int64_t c = (int64_t)cg * RB + cblk * 16 + j;
             v[j] = (pin && c < a.K) ? *(const float4*)(xn + c * a.HW) : make_float4(0.f, 0.f, 0.f, 0.f);
         }
         uint32_t w4[4][4];
@@ -197,7 +204,7 @@ __global__ __launch_bounds__(256) void k_pack_nchw_i8_v4(PackArgs a)
             for (int k = 0; k < 4; ++k) w4[i][k] = 0;
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
-            const int64_t c = (int64_t)cb * 64 + wave * 16 + j;
+            const int64_t c = (int64_t)cg * RB + cblk * 16 + j;
             const bool ok = pin && c < a.K;
             const float e[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
 #pragma unroll
@@ -207,25 +214,102 @@ __global__ __launch_bounds__(256) void k_pack_nchw_i8_v4(PackArgs a)
                 w4[i][j >> 2] |= (uint32_t)(t & 0xff) << (8 * (j & 3));
             }
         }
-        if (cb > 0) __syncthreads();  // previous chunk fully streamed out
+        if (cg > 0) __syncthreads();  // previous group fully streamed out
 #pragma unroll
         for (int i = 0; i < 4; ++i)
-            *(uint4*)(tile + (4 * lane + i) * 64 + ((wave ^ (lane & 3)) << 4)) =
+            *(uint4*)(tile + (4 * quad + i) * RB + ((cblk ^ (quad & (NSLOT - 1))) << 4)) =
                 make_uint4(w4[i][0], w4[i][1], w4[i][2], w4[i][3]);
         __syncthreads();
 #pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int e = tid + 256 * k, px = e >> 2, pp = e & 3;
-            const int logical = pp ^ ((px >> 2) & 3);
-            if (px < valid)
-                *(uint4*)(out + (size_t)px * a.Kpad + cb * 64 + logical * 16) = *(const uint4*)(tile + e * 16);
+        for (int k = 0; k < PB * NSLOT / 256; ++k) {
+            const int e = tid + 256 * k, px = e / NSLOT, pp = e % NSLOT;
+            const int logical = pp ^ ((px >> 2) & (NSLOT - 1));
+            const int64_t cbyte = (int64_t)cg * RB + logical * 16;  // the last group may overhang Kpad
+            if (px < valid && cbyte < a.Kpad)
+                *(uint4*)(out + (size_t)px * a.Kpad + cbyte) = *(const uint4*)(tile + e * 16);
         }
     }
     if (a.sum_t) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) part[wave][4 * lane + i] = sum[i];
+        for (int i = 0; i < 4; ++i) part[cblk][4 * quad + i] = sum[i];
         __syncthreads();
-        if (tid < valid) a.sum_t[q0 + tid] = part[0][tid] + part[1][tid] + part[2][tid] + part[3][tid];
+        if (tid < valid && tid < PB) {
+            int s = 0;
+#pragma unroll
+            for (int b = 0; b < 4 * SUBS; ++b) s += part[b][tid];
+            a.sum_t[q0 + tid] = s;
+        }
+    }
+}
+
+// ---- NCHW layout, int8 codes, small images whose H*W is not a multiple of 4 ---
+// One 1024-thread block per image.  The image's C*H*W floats are one contiguous,
+// 16-byte aligned run (C*H*W % 4 == 0), read with 16-byte loads regardless of
+// where the channel rows start; element e is channel e / HW, pixel e % HW.  Codes
+// are dropped byte by byte into an LDS image [HW][Cpad + 4] (the 4 pad bytes put
+// consecutive pixels of a channel on consecutive banks), which is then streamed
+// out in 16-byte pieces, every piece adding its 16 codes to its pixel's sum.
+__global__ __launch_bounds__(1024) void k_pack_nchw_i8_flat(PackArgs a, FastDiv div_hw)
+{
+    extern __shared__ __attribute__((aligned(16))) uint8_t img[];  // [HW][Cpad + 4], then int psum[HW]
+    const int tid = threadIdx.x;
+    const int64_t n = blockIdx.x;
+    const int HW = (int)a.HW, K = (int)a.K, Kpad = (int)a.Kpad, pitch = Kpad + 4;
+    int* psum = (int*)(img + (size_t)HW * pitch);
+    const float lo = thr(a.lo, n), hi = thr(a.hi, n);
+    const float* xn = a.x + n * a.K * a.HW;
+    for (int p = tid; p < HW; p += 1024) psum[p] = 0;
+    // channels K .. Kpad-1 of every pixel are zero codes
+    const int padc = Kpad - K;
+    for (int e = tid; e < HW * padc; e += 1024) {
+        const int p = e / padc;
+        img[p * pitch + K + (e - p * padc)] = 0;
+    }
+    const int nvec = K * HW / 4;
+    for (int v0 = tid; v0 < nvec; v0 += 4 * 1024) {
+        float4 v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int vi = v0 + u * 1024;
+            v[u] = vi < nvec ? *(const float4*)(xn + 4 * (int64_t)vi) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int vi = v0 + u * 1024;
+            if (vi < nvec) {
+                int c = (int)fastdiv((uint32_t)(4 * vi), div_hw), p = 4 * vi - c * HW;
+                const float e[4] = {v[u].x, v[u].y, v[u].z, v[u].w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    img[p * pitch + c] = (uint8_t)(tern(e[i], lo, hi) & 0xff);
+                    if (++p == HW) {
+                        p = 0;
+                        ++c;
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();
+    const int np = Kpad / 16;
+    uint8_t* out = (uint8_t*)a.codes + n * a.HW * a.Kpad;
+    for (int e = tid; e < HW * np; e += 1024) {
+        const int p = e / np, piece = e - p * np;
+        const uint32_t* src = (const uint32_t*)(img + p * pitch + piece * 16);
+        const uint4 w = make_uint4(src[0], src[1], src[2], src[3]);
+        *(uint4*)(out + (size_t)p * Kpad + piece * 16) = w;
+        if (a.sum_t) {
+            int s = 0;
+            s = __builtin_amdgcn_sdot4((int)w.x, 0x01010101, s, false);
+            s = __builtin_amdgcn_sdot4((int)w.y, 0x01010101, s, false);
+            s = __builtin_amdgcn_sdot4((int)w.z, 0x01010101, s, false);
+            s = __builtin_amdgcn_sdot4((int)w.w, 0x01010101, s, false);
+            atomicAdd(&psum[p], s);
+        }
+    }
+    if (a.sum_t) {
+        __syncthreads();
+        for (int p = tid; p < HW; p += 1024) a.sum_t[n * a.HW + p] = psum[p];
     }
 }
 
@@ -311,8 +395,24 @@ hipError_t launch_pack_nchw_i8(const PackArgs& a, hipStream_t st)
         attr_done = true;
     }
     if (a.HW % 4 == 0 && ((uintptr_t)a.x) % 16 == 0) {
-        const dim3 grid4((unsigned)((a.N * a.HW + 255) / 256));
-        hipLaunchKernelGGL(k_pack_nchw_i8_v4, grid4, dim3(256), 0, st, a);
+        // widest pixel runs that still give every CU several blocks and one pass over
+        // the channels where the row is long enough
+        const int64_t px = a.N * a.HW;
+        if (a.Kpad >= 256 && px < 2048 * 256) {
+            hipLaunchKernelGGL(k_pack_nchw_i8_v4<16>, dim3((unsigned)((px + 63) / 64)), dim3(256), 0, st, a);
+        } else if (a.Kpad >= 128 && px < 4096 * 256) {
+            hipLaunchKernelGGL(k_pack_nchw_i8_v4<32>, dim3((unsigned)((px + 127) / 128)), dim3(256), 0, st, a);
+        } else {
+            hipLaunchKernelGGL(k_pack_nchw_i8_v4<64>, dim3((unsigned)((px + 255) / 256)), dim3(256), 0, st, a);
+        }
+        return hipGetLastError();
+    }
+    // small images with H*W % 4 != 0: one block per image over the flat C*H*W run
+    const size_t flat_smem = (size_t)a.HW * (a.Kpad + 4) + (size_t)a.HW * 4;
+    if ((a.K * a.HW) % 4 == 0 && ((uintptr_t)a.x) % 16 == 0 && flat_smem <= 64 * 1024 && a.HW >= 4 &&
+        a.K * a.HW < ((int64_t)1 << 30) && a.N <= 0x7fffffff) {
+        hipLaunchKernelGGL(k_pack_nchw_i8_flat, dim3((unsigned)a.N), dim3(1024), flat_smem, st, a,
+                           make_fastdiv((uint32_t)a.HW));
         return hipGetLastError();
     }
     const dim3 grid((unsigned)((a.N * a.HW + 63) / 64)), block(256);

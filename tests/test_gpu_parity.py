@@ -62,7 +62,12 @@ def test_pack_rows_unaligned_base():
 
 
 @pytest.mark.parametrize("shape", [(2, 5, 7, 9), (3, 64, 8, 8), (2, 130, 5, 5), (1, 64, 56, 56),
-                                   (8, 70, 3, 3), (4, 256, 1, 1)])
+                                   (8, 70, 3, 3), (4, 256, 1, 1),
+                                   # 16-byte-load kernels: 128- and 256-byte output runs, channel
+                                   # groups overhanging the padded row, ragged last pixel block
+                                   (2, 130, 6, 6), (5, 128, 10, 10), (3, 300, 4, 4), (2, 512, 14, 14),
+                                   # one-block-per-image kernel: H*W % 4 != 0, C*H*W % 4 == 0
+                                   (4, 64, 7, 7), (3, 512, 7, 7), (2, 100, 3, 5)])
 @pytest.mark.parametrize("per_lead", [False, True])
 def test_pack_nchw(shape, per_lead):
     _say("pack_nchw %s per_lead=%s" % (shape, per_lead))
