@@ -348,3 +348,64 @@ def test_resnet18_layers_batch256_sampled_images(idx):
     T.assert_y_close(got["y"][imgs].cpu().numpy(), ref["y"], shape.name)
     # properties that hold at any size: |D| <= K, D has the parity pattern of an integer sum
     assert int(got["D"].abs().max()) <= shape.K
+
+
+# ------------------------------------ config 3: the conv stack at batch 64 ------
+@pytest.mark.parametrize("idx", range(19))
+def test_resnet18_layers_batch64_sampled_images(idx):
+    """The 19 ternary ResNet-18 layer shapes at batch 64, each standalone, per-filter
+    thresholds and scales, one activation threshold per tensor; single-output launches
+    as the benchmark issues them.  The oracle recomputes two whole images."""
+    shape = wl.resnet18_ternary_layers()[idx]
+    _say("resnet18 b64 %s" % (shape,))
+    case = wl.conv_case(shape, batch=64, seed=400 + idx, per_channel=True)
+    got = T.hip_conv(case, True, want_acc="separate")
+    imgs = [3, 63]
+    ref = T.oracle_conv(case, True, images=imgs)
+    assert (got["ca"][imgs].cpu().numpy() == orc.nchw_to_nhwc_i8(ref["ta"], got["ca"].shape[-1])).all()
+    assert (got["D"][imgs].cpu().numpy() == ref["D"]).all()
+    T.assert_y_close(got["y"][imgs].cpu().numpy(), ref["y"], shape.name)
+    assert int(got["D"].abs().max()) <= shape.K
+
+
+# ------------------------------------ config 5: the large GEMM sweep -------------
+SWEEP = [(M, NK, p0) for M in (8192, 16384) for NK in (4096, 8192) for p0 in (0.2, 0.5, 0.8)]
+
+
+def _sweep_check(M, NK, p0, fmt, seed):
+    case = wl.gemm_case(M, NK, NK, p_zero=p0, seed=seed)
+    got = T.hip_gemm(case, fmt=fmt, want_acc="separate")
+    rows = np.sort(np.random.default_rng(seed).choice(M, 12, replace=False)).astype(np.int64)
+    rows[0], rows[-1] = 0, M - 1
+    ta = orc.ternarize(case["xa"][rows], -0.5, 0.5)
+    tw = orc.ternarize(case["xw"], -0.5, 0.5)
+    Sa, Sw = orc.row_sums(ta), orc.row_sums(tw)
+    assert (got["Sa"].cpu().numpy()[rows] == Sa).all() and (got["Sw"].cpu().numpy() == Sw).all()
+    if fmt == B.RTN_CODE_I8:
+        assert (got["ca"][torch.as_tensor(rows)].cpu().numpy() == ta).all()
+        assert (got["cw"].cpu().numpy() == tw).all()
+    D = orc.gemm_acc_rows(ta, tw, np.arange(rows.size, dtype=np.int64))
+    assert (got["D"].cpu().numpy()[rows] == D).all()
+    y = orc.gemm_epilogue(D, NK, Sa, Sw, case["alpha_a"][rows], case["beta_a"][rows],
+                          case["alpha_w"], case["beta_w"])
+    T.assert_y_close(got["y"].cpu().numpy()[rows], y, "sweep %d %d %.1f" % (M, NK, p0))
+    # the draw fixes E[D] = 0 and Var[D] = K (1 - p0)^2
+    Dall = got["D"][:: max(1, M // 512)].double()
+    assert abs(float(Dall.mean())) < 0.2
+    assert abs(float(Dall.var()) / (NK * (1 - p0) ** 2) - 1) < 0.02
+
+
+@pytest.mark.parametrize("M,NK,p0", SWEEP)
+def test_config5_gemm_sweep_mfma(M, NK, p0):
+    """Large ternary GEMMs at three sparsities on the matrix-core path: 12 sampled
+    rows (all columns) against the oracle, all side sums, all weight codes."""
+    _say("sweep mfma M=%d N=K=%d P(0)=%.1f" % (M, NK, p0))
+    _sweep_check(M, NK, p0, B.RTN_CODE_I8, seed=int(1000 * p0) + M // 1024 + NK // 512)
+
+
+@pytest.mark.parametrize("M,NK,p0", [(8192, 4096, 0.2), (8192, 4096, 0.5), (8192, 4096, 0.8), (16384, 8192, 0.5)])
+def test_config5_gemm_sweep_popcount(M, NK, p0):
+    """The same sweep on the bit-plane popcount path (Eq.8): every sparsity at the
+    smallest size, and the largest size once."""
+    _say("sweep popc M=%d N=K=%d P(0)=%.1f" % (M, NK, p0))
+    _sweep_check(M, NK, p0, B.RTN_CODE_BITPLANE, seed=int(1000 * p0) + 7)
