@@ -171,9 +171,10 @@ int rtn_ternary_gemm(rtn_code_format fmt, rtn_path path, const void *a_codes, co
  *   workspace (needed when an epilogue is given): the table written by
  *   rtn_conv2d_prepare_constants() for the same filters, pad and epilogue
  *   parameters (alpha, beta and the BN affine of `ep` are taken from the
- *   table; of `ep` itself the call reads only sum_ta and relu); it is only
- *   read here, so one prepared table serves any number of calls, batch sizes
- *   and image sizes.  16-byte aligned.
+ *   table; of `ep` itself the call reads only relu -- the sum of t_a over a
+ *   pixel's window is formed from the codes inside the kernel, ep->sum_ta must
+ *   be non-NULL but is not read); it is only read here, so one prepared table
+ *   serves any number of calls, batch sizes and image sizes.  16-byte aligned.
  *   Nb*H*W and Nb*OH*OW must be below 2^31.                                  */
 size_t rtn_conv2d_workspace_bytes(int64_t O, int KH, int KW, int pad);
 /* Weight-side preparation of the conv epilogue (offline, once per layer): fills

@@ -104,12 +104,6 @@ __device__ __forceinline__ const int8_t* uniform_ptr(const int8_t* p)
     return (const int8_t*)(uintptr_t)(((uint64_t)hi << 32) | lo);
 }
 
-// 4-byte variant: lane l fetches one dword that lands at lds_off + 4 * l.
-__device__ __forceinline__ void dma4(const void* gptr, unsigned lds_off)
-{
-    asm volatile("s_mov_b32 m0, %0\n\tglobal_load_lds_dword %1, off" ::"s"(lds_off), "v"(gptr) : "memory");
-}
-
 template <int N>
 __device__ __forceinline__ void wait_vm()
 {
@@ -187,13 +181,12 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
     // conv layers, because a new block's loads no longer queue behind other blocks'
     // stores as often).
     __builtin_amdgcn_s_setprio(3);
-    // LDS: [halo pixels hrows x HC][128 zero bytes][operand ring][conv: epilogue table,
-    // halo: pixel sums of the run]; the GEMM builds its small table over the ring
+    // LDS: [halo pixels hrows x HC][128 zero bytes][operand ring][conv: epilogue table];
+    // the GEMM builds its small table over the ring
     const int zoff = HALO ? prm.hrows * HC : 0;
     const int roff = HALO ? zoff + 128 : 0;
     const int toff = roff + NS * STAGE;
     const int tab_kib = CONV ? (conv_table_bytes(BP, g.pad) + 1023) >> 10 : 0;
-    const int soff = toff + tab_kib * 1024;  // halo: int32 sum of t_a per pixel of the run
 
     // ---- loader state ------------------------------------------------------
     // Load j of a wave covers tile rows 16*(wave + 4*j) .. +15; lane l fetches
@@ -359,6 +352,14 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
         for (int i = 0; i < NF; ++i) load_frag(kt, ks, i);
     };
 
+    // conv: Sa of an output pixel -- the sum of t_a over its in-bounds taps -- is the
+    // sum of all code bytes of its row of the patch matrix (out-of-image taps are zero
+    // bytes), i.e. of the Q fragments this lane multiplies anyway: 4 byte-sum dot
+    // products per fragment, added up beside the MFMAs.  A lane holds half of a
+    // row's bytes (the other k-chunks sit in lane ^ 32); the halves meet in the epilogue.
+    int sa_part[TQ];
+#pragma unroll
+    for (int j = 0; j < TQ; ++j) sa_part[j] = 0;
     v16i acc[TP][TQ];
 #pragma unroll
     for (int i = 0; i < TP; ++i)
@@ -392,6 +393,12 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
             }
             __builtin_amdgcn_sched_barrier(0);
         }
+        if (CONV) {
+#pragma unroll
+            for (int j = 0; j < TQ; ++j)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) sa_part[j] = __builtin_amdgcn_sdot4(fb[ks][j][e], 0x01010101, sa_part[j], false);
+        }
     };
     const std::true_type yes{};
     const std::false_type no{};
@@ -413,15 +420,6 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
             idx = idx < last ? idx : last;  // columns past O are never used
             dma16(prm.cst_cls + idx, lds0 + (unsigned)(toff + n * 1024));
         }
-        if (HALO) {
-            const int total_px = g.Nb * g.H * g.W;
-            const int first_px = q0 - g.pad * (g.W + 1);
-            for (int n = wave; n * 64 < prm.hrows; n += 4) {
-                int px = first_px + n * 64 + lane;
-                px = px < 0 ? 0 : (px < total_px ? px : total_px - 1);
-                dma4(prm.ep.sum_ta + px, lds0 + (unsigned)(soff + n * 256));
-            }
-        }
     }
     if (HALO) {
         // the pixel run: 1 KiB per load, lane l lands at 16-byte unit n*64 + l; which chunk
@@ -441,16 +439,13 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
     }
     for (int s = 0; s < npro; ++s) issue(s);
 
-    // conv: for each of this lane's TQ output pixels, Sa (sum of the input-pixel
-    // channel sums over the in-bounds taps) and the border class, packed as
-    // (Sa << 8) | class.  Computed here so that the pixel-sum loads overlap the
-    // latency of the first operand loads.
+    // conv: the border class of each of this lane's TQ output pixels,
     //   class = rid * (pad+1)^2 + cid,  rid = khl + (pad+1)*(KH-1-khh), cid likewise;
     //   class 0 is the interior (all taps in bounds).
-    int pixinfo[TQ];
+    int pixcls[TQ];
 #pragma unroll
-    for (int j = 0; j < TQ; ++j) pixinfo[j] = 0;
-    if (CONV && prm.y) {
+    for (int j = 0; j < TQ; ++j) pixcls[j] = 0;
+    if (CONV && prm.y && !g.code_zero_pad) {
         const int ohw = g.OH * g.OW, p1 = g.pad + 1;
 #pragma unroll
         for (int j = 0; j < TQ; ++j) {
@@ -458,35 +453,12 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
             m = m < prm.RQ ? m : prm.RQ - 1;
             const int nb = (int)fastdiv((uint32_t)m, g.div_ohw), pix = m - nb * ohw;
             const int oh = (int)fastdiv((uint32_t)pix, g.div_ow), ow = pix - oh * g.OW;
-            const int ih0 = oh * g.stride - g.pad, iw0 = ow * g.stride - g.pad;
             int khl, khh, kwl, kwh;
             tap_range(oh, g.stride, g.pad, g.KH, g.H, khl, khh);
             tap_range(ow, g.stride, g.pad, g.KW, g.W, kwl, kwh);
-            const int32_t* ps = prm.ep.sum_ta + ((int64_t)nb * g.H + ih0) * g.W + iw0;
-            int s = 0;
-            if (HALO) {
-                // summed in the epilogue from the pixel sums of the run held in LDS
-            } else if (g.KH == 3 && g.KW == 3) {
-                int v[9];
-#pragma unroll
-                for (int t = 0; t < 9; ++t) {
-                    const int kh = t / 3, kw = t % 3;
-                    const bool ok = kh >= khl && kh <= khh && kw >= kwl && kw <= kwh;
-                    v[t] = ok ? ps[kh * g.W + kw] : 0;
-                }
-#pragma unroll
-                for (int t = 0; t < 9; ++t) s += v[t];
-            } else {
-                for (int kh = khl; kh <= khh; ++kh)
-                    for (int kw = kwl; kw <= kwh; ++kw) s += ps[kh * g.W + kw];
-            }
-            int cls = 0;
-            if (!g.code_zero_pad)
-                cls = (khl + p1 * (g.KH - 1 - khh)) * p1 * p1 + (kwl + p1 * (g.KW - 1 - kwh));
-            pixinfo[j] = s * 256 + cls;
+            pixcls[j] = (khl + p1 * (g.KH - 1 - khh)) * p1 * p1 + (kwl + p1 * (g.KW - 1 - kwh));
         }
     }
-
     __builtin_amdgcn_s_setprio(2);
     // ---- main loop ------------------------------------------------------------
     // Steps kt .. kt+NS-1 are in flight or resident while step kt is multiplied.
@@ -633,20 +605,9 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
         const int p1 = g.pad + 1;
         (void)p1;
         // (the table was copied into LDS by the prologue's direct loads)
-        int sa_halo[TQ];
+        int sa_full[TQ];
 #pragma unroll
-        for (int j = 0; j < TQ; ++j) sa_halo[j] = 0;
-        if (HALO && prm.y) {
-            const int32_t* run = (const int32_t*)(smem + soff);
-#pragma unroll
-            for (int j = 0; j < TQ; ++j)
-                for (int kh = 0; kh < g.KH; ++kh)
-                    for (int kw = 0; kw < g.KW; ++kw) {
-                        const bool ok = ((vmq[j] >> kh) & (vmq[j] >> (8 + kw)) & 1) != 0;
-                        const int v = run[mlb[j] + kh * g.W + kw];
-                        sa_halo[j] += ok ? v : 0;
-                    }
-        }
+        for (int j = 0; j < TQ; ++j) sa_full[j] = sa_part[j] + __shfl_xor(sa_part[j], 32, 64);
         dispatch([&](auto full, auto want_acc, auto want_y) {
             constexpr bool FULL = decltype(full)::value, ACC = decltype(want_acc)::value,
                            Y = decltype(want_y)::value;
@@ -665,8 +626,8 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
                 const int64_t obase = (int64_t)nb * g.O * ohw + pix;
                 accp[j] = ACC ? prm.acc + obase : nullptr;
                 yp[j] = Y ? prm.y + obase : nullptr;
-                Sa[j] = (double)(HALO ? sa_halo[j] : (pixinfo[j] >> 8));
-                ctab[j] = tab + (4 + (pixinfo[j] & 255)) * BP;
+                Sa[j] = (double)sa_full[j];
+                ctab[j] = tab + (4 + pixcls[j]) * BP;
             }
 #pragma unroll
             for (int i = 0; i < TP; ++i)
@@ -778,9 +739,8 @@ hipError_t launch_cfg(TmmParams& prm, hipStream_t st)
     }
     int64_t smem;
     if (CONV) {
-        // ring (+ halo), then the epilogue table in whole KiB, then the halo's pixel sums
+        // ring (+ halo), then the epilogue table in whole KiB
         smem = stage_bytes + ((table_bytes(BP, true, prm.g.pad) + 1023) & ~(int64_t)1023);
-        if (HC) smem += ((prm.hrows + 63) & ~63) * 4;
     } else {
         const int64_t tb = table_bytes(BP, false, 0);
         smem = stage_bytes > tb ? stage_bytes : tb;
