@@ -34,7 +34,7 @@ def main():
                     choices=["resnet18_ternary_convs", "gemm4096"])
     ap.add_argument("--tile", type=int, default=-1, help="force an MFMA tile configuration (tuning)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--cpu-images", type=int, default=64,
+    ap.add_argument("--cpu-images", type=int, default=128,
                     help="images per layer the oracle is timed on (cpu_baseline sample)")
     args = ap.parse_args()
     if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:

@@ -490,12 +490,19 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
 
     __builtin_amdgcn_s_setprio(0);
     // ---- epilogue ---------------------------------------------------------------
-    // Outputs are written with the non-temporal hint: they are not read again here,
+    // The conv's outputs are written with the non-temporal hint: they are not read again here,
     // and a plain store leaves its dirty lines to be written back while the *next*
     // kernel runs (measured: a 205 MB read kernel takes 57 us right after 205 MB of
     // plain stores, 32 us after the same stores marked non-temporal; over the
     // ResNet-18 stack the hint shortens the step by 6 %, the small layers included).
-    auto put = [&](auto value, auto* ptr) { __builtin_nontemporal_store(value, ptr); };
+    // The GEMM keeps plain stores: its 256 tiles finish together, and the cache
+    // absorbs that burst faster than HBM takes it.
+    auto put = [&](auto value, auto* ptr) {
+        if (CONV)
+            __builtin_nontemporal_store(value, ptr);
+        else
+            *ptr = value;
+    };
     const EpiArgs& ep = prm.ep;
     const bool has_bn = ep.bn_scale != nullptr;
     // ReLU and BN are applied unconditionally with neutral parameters when off:
