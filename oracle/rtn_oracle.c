@@ -356,6 +356,31 @@ void orc_conv_epilogue(const int32_t *D, const int32_t *Sa, const int32_t *Sw, c
             }
 }
 
+/* ------------------------------------------------------------------ O7 --
+ * The activation handed to the next ternary layer.  RTN's layer order is
+ * conv -> ReLU -> BN -> ternarize (Section "Reparameterized Ternarization":
+ * BN follows ReLU so that negative values exist again), so the next layer's
+ * fixed ternary input is Q applied to the fp32 output z of the epilogue above:
+ *   t[nb][o][p] = (z > hi[o]) - (z < lo[o])        (Eq.1; strict, on fp32 z)
+ * with one (lo, hi) per layer (per_channel = 0) or per output channel
+ * (per_channel = 1).  The per-channel form is what Eq.3 needs when the BN
+ * affine k*z + b is not applied but folded into the thresholds,
+ * hi = (0.5-b)/k, lo = -(0.5+b)/k.  z: [Nb][O][HW] fp32, t: same shape.     */
+void orc_ternarize_nchw(const float *z, int64_t Nb, int64_t O, int64_t HW,
+                        const float *lo, const float *hi, int per_channel, int8_t *t)
+{
+#pragma omp parallel for
+    for (int64_t nb = 0; nb < Nb; ++nb)
+        for (int64_t o = 0; o < O; ++o) {
+            float l = per_channel ? lo[o] : lo[0];
+            float h = per_channel ? hi[o] : hi[0];
+            for (int64_t p = 0; p < HW; ++p) {
+                float v = z[(nb * O + o) * HW + p];
+                t[(nb * O + o) * HW + p] = (int8_t)((v > h) - (v < l));
+            }
+        }
+}
+
 /* Conv form of O6: direct conv of the reparameterized values in double.
  * pad_true_zero = 1 pads the value tensor (aa*t+ba) with 0.0;
  * pad_true_zero = 0 pads the code tensor with 0, i.e. the value with ba.     */

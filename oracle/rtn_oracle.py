@@ -294,3 +294,27 @@ def conv_direct(ta, tw, stride, pad, alpha_a, beta_a, alpha_w, beta_w=None, pad_
                           _f32(float(alpha_a)), _f32(float(beta_a)), _p(aw), _p(bw), C.c_int(sw_),
                           _p(y))
     return y
+
+
+def ternarize_nchw(z, lo, hi):
+    """O7.  z: float32 [Nb,O,OH,OW]; lo/hi scalars or one per channel -> int8 codes, same shape."""
+    z = _c(z, np.float32)
+    Nb, O = z.shape[0], z.shape[1]
+    HW = z.size // (Nb * O)
+    lo = np.atleast_1d(np.asarray(lo, dtype=np.float32))
+    hi = np.atleast_1d(np.asarray(hi, dtype=np.float32))
+    per_ch = int(lo.size > 1 or hi.size > 1)
+    if per_ch:
+        assert lo.size == O and hi.size == O
+    t = np.empty(z.shape, dtype=np.int8)
+    lib().orc_ternarize_nchw(_p(z), _i64(Nb), _i64(O), _i64(HW), _p(lo), _p(hi), C.c_int(per_ch), _p(t))
+    return t
+
+
+def conv_next_codes(D, Sa, Sw, Kv, alpha_a, beta_a, alpha_w, beta_w, relu, bn_scale, bn_shift,
+                    lo, hi, Cpad):
+    """O5 then O7 then the channel-innermost code layout of O2: the next ternary
+    layer's input codes [Nb,OH,OW,Cpad] (int8, padding channels 0), and z itself."""
+    z = conv_epilogue(D, Sa, Sw, Kv, alpha_a, beta_a, alpha_w, beta_w, relu, bn_scale, bn_shift)
+    t = ternarize_nchw(z, lo, hi)
+    return nchw_to_nhwc_i8(t, Cpad), z

@@ -299,3 +299,117 @@ def test_conv_epilogue_equals_direct_float_conv(true_zero):
                                   bw.astype(np.float64)[:, None, None, None])
             lib = torch.nn.functional.conv2d(va, vw, stride=s, padding=p).numpy()
             assert np.allclose(direct, lib, rtol=1e-12, atol=1e-12)
+
+
+# ------------------------------------------------------------------ O7 ----
+def test_ternarize_nchw_hand_listed_and_channel_axis():
+    # 1 image, 2 channels, 3 pixels; channel 0 thresholds (-0.2, 0.2), channel 1 (-0.5, 0.5)
+    z = np.array([[[0.3, -0.3, 0.2], [0.3, -0.3, 0.6]]], dtype=np.float32).reshape(1, 2, 1, 3)
+    t = orc.ternarize_nchw(z, np.array([-0.2, -0.5], np.float32), np.array([0.2, 0.5], np.float32))
+    assert t.reshape(2, 3).tolist() == [[1, -1, 0], [0, 0, 1]]      # 0.2 == hi is a tie -> 0
+    t1 = orc.ternarize_nchw(z, -0.25, 0.25)
+    assert t1.reshape(2, 3).tolist() == [[1, -1, 0], [1, -1, 1]]
+    nan = np.full((1, 1, 1, 2), np.nan, np.float32)
+    assert (orc.ternarize_nchw(nan, -0.5, 0.5) == 0).all()
+
+
+def test_ternarize_nchw_eq3_fold_of_bn_is_exact_for_dyadic_k_b():
+    # Eq.3 with BN's (k, b) folded into per-channel thresholds on z itself.  k a power
+    # of two and b a multiple of 1/8: k*z+b and both thresholds are exact in fp32, so
+    # the two routes must agree on every element, ties included.
+    rng = np.random.default_rng(21)
+    Nb, O, H, W = 3, 6, 5, 4
+    z = (rng.integers(-64, 65, size=(Nb, O, H, W)) / 16.0).astype(np.float32)   # many exact ties
+    k = np.array([0.5, 1.0, 2.0, 4.0, 0.25, 1.0], np.float32)
+    b = np.array([0.125, -0.25, 0.0, 0.375, -0.125, 0.5], np.float32)
+    hi, lo = (0.5 - b) / k, -(0.5 + b) / k
+    folded = orc.ternarize_nchw(z, lo, hi)
+    affine = (k[None, :, None, None] * z + b[None, :, None, None]).astype(np.float32)
+    want = np.where(np.abs(affine) > 0.5, np.sign(affine), 0).astype(np.int8)     # Eq.1 on k*z+b
+    assert (folded == want).all()
+    assert {-1, 0, 1} <= set(np.unique(folded))
+
+
+def _next_codes_setup(seed, C, H, W, O, k, s, p, Nb=2):
+    rng = np.random.default_rng(seed)
+    ta, tw = _rand_t(rng, (Nb, C, H, W)), _rand_t(rng, (O, C, k, k))
+    aw = rng.uniform(0.5, 1.5, O).astype(np.float32)
+    bw = rng.uniform(-0.2, 0.2, O).astype(np.float32)
+    aa, ba = np.float32(1.1), np.float32(0.17)
+    bs = rng.uniform(0.5, 1.5, O).astype(np.float32)
+    bh = rng.normal(0.0, 0.6, O).astype(np.float32)
+    return ta, tw, aa, ba, aw, bw, bs, bh
+
+
+def test_conv_next_codes_brute_force_python_loops():
+    # direct float dot product of the reparameterized values over in-bounds taps
+    # (true-zero padding), ReLU, BN affine, Eq.1 -- all in pure Python floats
+    C, H, W, O, k, s, p = 3, 5, 4, 5, 3, 1, 1
+    ta, tw, aa, ba, aw, bw, bs, bh = _next_codes_setup(22, C, H, W, O, k, s, p)
+    delta = np.float32(0.45)
+    D = orc.conv_acc(ta, tw, s, p)
+    Sa, Sw, Kv = orc.conv_sums(ta, tw, s, p, True)
+    codes, z = orc.conv_next_codes(D, Sa, Sw, Kv, aa, ba, aw, bw, True, bs, bh, -delta, delta, 64)
+    Nb, OH, OW = ta.shape[0], D.shape[2], D.shape[3]
+    assert codes.shape == (Nb, OH, OW, 64) and codes.dtype == np.int8
+    assert (codes[..., O:] == 0).all()
+    near = 0
+    for nb, o, oh, ow in itertools.product(range(Nb), range(O), range(OH), range(OW)):
+        v = 0.0
+        for c, kh, kw in itertools.product(range(C), range(k), range(k)):
+            ih, iw = oh * s - p + kh, ow * s - p + kw
+            if 0 <= ih < H and 0 <= iw < W:
+                v += (float(aa) * int(ta[nb, c, ih, iw]) + float(ba)) * \
+                     (float(aw[o]) * int(tw[o, c, kh, kw]) + float(bw[o]))
+        v = float(bs[o]) * max(v, 0.0) + float(bh[o])
+        if abs(abs(v) - float(delta)) < 1e-5:      # decision within rounding of the threshold
+            near += 1
+            continue
+        want = (v > float(delta)) - (v < -float(delta))
+        assert codes[nb, oh, ow, o] == want, (nb, o, oh, ow, v)
+    assert near < 5
+    assert {-1, 0, 1} <= set(np.unique(codes[..., :O]))
+
+
+def test_conv_next_codes_eq10_integer_threshold_form_exact_rationals():
+    # Eq.10 (beta_w = 0, alpha, gamma > 0, ReLU, no BN, no padding so C is one constant
+    # per filter):  z = alpha * max(0, gamma*D + T), T = beta * (1 (x) W^t), hence with a
+    # threshold Delta > 0 the next code is +1 iff D > (Delta/alpha - T)/gamma and never -1:
+    # an integer comparison, evaluated here in exact rational arithmetic.
+    from fractions import Fraction as F
+    C, H, W, O, k, s, p = 4, 6, 6, 7, 3, 1, 0
+    ta, tw, gamma, beta, alpha, *_ = _next_codes_setup(23, C, H, W, O, k, s, p)
+    delta = np.float32(1.3)
+    D = orc.conv_acc(ta, tw, s, p)
+    Sa, Sw, Kv = orc.conv_sums(ta, tw, s, p, True)
+    codes, _ = orc.conv_next_codes(D, Sa, Sw, Kv, gamma, beta, alpha, None, True, None, None,
+                                   -delta, delta, 64)
+    assert (codes >= 0).all()
+    ones = 0
+    for o in range(O):
+        T = F(float(beta)) * int(tw[o].astype(np.int64).sum())
+        bound = (F(float(delta)) / F(float(alpha[o])) - T) / F(float(gamma))
+        want = (D[:, o].astype(np.int64) > np.floor(float(bound))).astype(np.int8) \
+            if bound.denominator != 1 else (D[:, o] > int(bound)).astype(np.int8)
+        got = codes[..., o]
+        assert (got == want).all(), o
+        ones += int(got.sum())
+    assert 0 < ones < codes[..., :O].size
+
+
+def test_conv_next_codes_layout_is_pack_of_nchw():
+    # [Nb,OH,OW,Cpad] position (n,h,w,c) holds the code of z[n,c,h,w]; Cpad > O is zero
+    C, H, W, O, k, s, p = 4, 7, 5, 6, 3, 2, 1
+    ta, tw, aa, ba, aw, bw, bs, bh = _next_codes_setup(24, C, H, W, O, k, s, p)
+    D = orc.conv_acc(ta, tw, s, p)
+    Sa, Sw, Kv = orc.conv_sums(ta, tw, s, p, True)
+    lo = -np.abs(bh) * 0.5 - 0.1
+    hi = np.abs(bh) * 0.5 + 0.2
+    codes, z = orc.conv_next_codes(D, Sa, Sw, Kv, aa, ba, aw, bw, False, bs, bh, lo, hi, 128)
+    want = np.zeros(codes.shape, np.int8)
+    for o in range(O):
+        want[..., o] = (z[:, o] > hi[o]).astype(np.int8) - (z[:, o] < lo[o]).astype(np.int8)
+    assert (codes == want).all()
+    # the same z through the row ternarizer (channels moved to the row axis)
+    t_rows = orc.ternarize(np.ascontiguousarray(z.transpose(1, 0, 2, 3)), lo, hi).transpose(1, 0, 2, 3)
+    assert (codes[..., :O] == t_rows.transpose(0, 2, 3, 1)).all()
