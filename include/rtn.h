@@ -172,8 +172,8 @@ int rtn_ternary_gemm(rtn_code_format fmt, rtn_path path, const void *a_codes, co
  *   rtn_conv2d_prepare_constants() for the same filters, pad and epilogue
  *   parameters (alpha, beta and the BN affine of `ep` are taken from the
  *   table; of `ep` itself the call reads only relu -- the sum of t_a over a
- *   pixel's window is formed from the codes inside the kernel, ep->sum_ta must
- *   be non-NULL but is not read); it is only read here, so one prepared table
+ *   pixel's window is formed from the codes inside the kernel, so ep->sum_ta
+ *   may be NULL here); it is only read here, so one prepared table
  *   serves any number of calls, batch sizes and image sizes.  16-byte aligned.
  *   Nb*H*W and Nb*OH*OW must be below 2^31.                                  */
 size_t rtn_conv2d_workspace_bytes(int64_t O, int KH, int KW, int pad);
@@ -184,8 +184,8 @@ size_t rtn_conv2d_workspace_bytes(int64_t O, int KH, int KW, int pad);
  * C = beta_a*alpha_w*Sw + Kv*beta_a*beta_w for every filter and every border
  * class of output pixels (the in-bounds tap rectangle decides which taps enter
  * Sw and Kv).  Reads ep->sum_tw (the per-tap sums [O][KH][KW]) and every
- * scale, offset and BN parameter of `ep`; ep->sum_ta must be non-NULL but is
- * not read.  C is the number of input channels.                              */
+ * scale, offset and BN parameter of `ep`; ep->sum_ta may be NULL.  C is the
+ * number of input channels.                                                  */
 int rtn_conv2d_prepare_constants(int64_t C, int64_t O, int KH, int KW, int pad, const rtn_epilogue *ep,
                                  void *workspace, size_t workspace_bytes, void *stream);
 int rtn_ternary_conv2d_implicit_gemm(rtn_code_format fmt, rtn_path path, const void *a_codes,
@@ -194,6 +194,31 @@ int rtn_ternary_conv2d_implicit_gemm(rtn_code_format fmt, rtn_path path, const v
                                      rtn_pad_mode pad_mode, int32_t *acc_out,
                                      const rtn_epilogue *ep, float *y_out, void *workspace,
                                      size_t workspace_bytes, void *stream);
+
+/* The same convolution with a ternarizing epilogue: the activation of Eq.9 is
+ * handed to the next ternary layer as codes, never as fp32.  RTN's layer order
+ * is conv -> ReLU -> BN -> ternarize, so with z the fp32 value the epilogue of
+ * rtn_ternary_conv2d_implicit_gemm would have stored for output channel o,
+ *   t = (z > thr_hi[o]) - (z < thr_lo[o])            (Eq.1, strict, NaN -> 0)
+ * is written channel-innermost as the next layer's input:
+ *   codes_out: int8 [Nb][OH][OW][rtn_padded_k(O)], 16-byte aligned; the padding
+ *   channels O .. rtn_padded_k(O)-1 are written as code 0.
+ * Thresholds: RTN_SCALAR (host pointers, lo <= hi) or RTN_VECTOR (device, one
+ * pair per output channel).  The per-channel form is Eq.3: a BN affine k*z + b
+ * with k > 0 need not be applied (leave ep->bn_scale NULL) when the caller
+ * passes hi = (0.5-b)/k, lo = -(0.5+b)/k; with ReLU and a positive scale the
+ * comparison is Eq.10's thresholded ReLU on the integer sum.  Pixel sums of
+ * the written codes are not produced: the conv entry points form them from the
+ * codes.  ep, workspace and every other argument as for
+ * rtn_ternary_conv2d_implicit_gemm (ep->sum_ta may be NULL); Nb*OH*OW*
+ * rtn_padded_k(O) must be below 2^40.                                        */
+int rtn_ternary_conv2d_ternarize(rtn_code_format fmt, rtn_path path, const void *a_codes,
+                                 const void *w_codes, int64_t Nb, int64_t C, int64_t H, int64_t W,
+                                 int64_t O, int KH, int KW, int stride, int pad,
+                                 rtn_pad_mode pad_mode, const rtn_epilogue *ep,
+                                 const float *thr_lo, const float *thr_hi, rtn_gran thr_gran,
+                                 void *codes_out, void *workspace, size_t workspace_bytes,
+                                 void *stream);
 
 /* Stand-alone epilogue on stored accumulators (Eq.9 generalised, see
  * rtn_epilogue).  GEMM form: acc, y_out are [M][N] row-major.               */

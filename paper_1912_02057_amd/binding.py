@@ -24,7 +24,8 @@ RTN_PATH_AUTO, RTN_PATH_MFMA_I8, RTN_PATH_POPC = 0, 1, 2
 EXPORTS = ["rtn_status_string", "rtn_last_hip_error", "rtn_num_tile_configs", "rtn_set_tile_config", "rtn_padded_k", "rtn_codes_bytes",
            "rtn_ternarize_pack", "rtn_ternary_gemm", "rtn_conv2d_workspace_bytes",
            "rtn_conv2d_prepare_constants",
-           "rtn_ternary_conv2d_implicit_gemm", "rtn_epilogue_reparam", "rtn_epilogue_reparam_conv2d"]
+           "rtn_ternary_conv2d_implicit_gemm", "rtn_ternary_conv2d_ternarize", "rtn_epilogue_reparam",
+           "rtn_epilogue_reparam_conv2d"]
 
 
 class RtnEpilogue(C.Structure):
@@ -73,6 +74,9 @@ def lib():
         L.rtn_ternary_conv2d_implicit_gemm.restype = ci
         L.rtn_ternary_conv2d_implicit_gemm.argtypes = [ci, ci, vp, vp, i64, i64, i64, i64, i64, ci, ci,
                                                        ci, ci, ci, vp, vp, vp, vp, C.c_size_t, vp]
+        L.rtn_ternary_conv2d_ternarize.restype = ci
+        L.rtn_ternary_conv2d_ternarize.argtypes = [ci, ci, vp, vp, i64, i64, i64, i64, i64, ci, ci, ci, ci,
+                                                   ci, vp, vp, vp, ci, vp, vp, C.c_size_t, vp]
         L.rtn_epilogue_reparam.restype = ci
         L.rtn_epilogue_reparam.argtypes = [vp, i64, i64, i64, vp, vp, vp]
         L.rtn_epilogue_reparam_conv2d.restype = ci
@@ -161,7 +165,8 @@ class Epilogue:
         assert self._d.gran is None or self._c.gran == self._d.gran
         self._tensors = (alpha_a, beta_a, alpha_w, beta_w, sum_ta, sum_tw, bn_scale, bn_shift)
         self.s = RtnEpilogue(self._a.ptr, self._b.ptr, self._a.gran, self._c.ptr, self._d.ptr,
-                             self._c.gran, _dev(sum_ta, torch.int32), _dev(sum_tw, torch.int32),
+                             self._c.gran, None if sum_ta is None else _dev(sum_ta, torch.int32),
+                             _dev(sum_tw, torch.int32),
                              int(bool(relu)),
                              None if bn_scale is None else _dev(bn_scale, torch.float32),
                              None if bn_shift is None else _dev(bn_shift, torch.float32))
@@ -225,6 +230,26 @@ def ternary_conv2d(a_codes, w_codes, Nb, Cc, H, W, O, KH, KW, stride, pad, pad_m
         0 if workspace is None else workspace.numel() * workspace.element_size(), _stream())
     _check(rc, "rtn_ternary_conv2d_implicit_gemm")
     return acc_out, y_out
+
+
+def ternary_conv2d_ternarize(a_codes, w_codes, Nb, Cc, H, W, O, KH, KW, stride, pad, ep, lo, hi,
+                             pad_mode=RTN_PAD_TRUE_ZERO, codes_out=None, workspace=None,
+                             fmt=RTN_CODE_I8, path=RTN_PATH_AUTO):
+    """The conv with the ternarizing epilogue.  lo/hi: python floats or cuda float32
+    vectors (one per output channel).  Returns int8 codes [Nb,OH,OW,padded_k(O)]."""
+    OH, OW = conv_out_hw(H, W, KH, KW, stride, pad)
+    if codes_out is None:
+        codes_out = torch.empty((Nb, OH, OW, padded_k(O)), dtype=torch.int8, device=a_codes.device)
+    if workspace is None:
+        workspace = conv2d_prepare_constants(Cc, O, KH, KW, pad, ep)
+    glo, ghi = _Gran(lo), _Gran(hi)
+    assert glo.gran == ghi.gran
+    rc = lib().rtn_ternary_conv2d_ternarize(
+        fmt, path, C.c_void_p(a_codes.data_ptr()), C.c_void_p(w_codes.data_ptr()), Nb, Cc, H, W, O, KH, KW,
+        stride, pad, pad_mode, ep.ref(), glo.ptr, ghi.ptr, glo.gran, _dev(codes_out, torch.int8),
+        C.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(), _stream())
+    _check(rc, "rtn_ternary_conv2d_ternarize")
+    return codes_out
 
 
 def epilogue_reparam(acc, K, ep, y_out=None):

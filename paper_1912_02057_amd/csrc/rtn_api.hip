@@ -40,8 +40,10 @@ int make_param(const float* p, rtn_gran gran, bool nullable, rtn::Param& out)
     return RTN_OK;
 }
 
-// Validates an rtn_epilogue for the GEMM (conv = false) or conv form.
-int make_epilogue(const rtn_epilogue* ep, bool conv, rtn::EpiArgs& out)
+// Validates an rtn_epilogue for the GEMM (conv = false) or conv form.  The
+// matrix-core conv forms the activation sums from the codes and the table builder
+// reads only weight-side sums, so those callers pass need_sum_ta = false.
+int make_epilogue(const rtn_epilogue* ep, bool conv, rtn::EpiArgs& out, bool need_sum_ta = true)
 {
     if (!ep) return RTN_ERR_NULL;
     if (ep->gran_a != RTN_SCALAR && ep->gran_a != RTN_VECTOR) return RTN_ERR_UNSUPPORTED;
@@ -52,7 +54,7 @@ int make_epilogue(const rtn_epilogue* ep, bool conv, rtn::EpiArgs& out)
     if ((rc = make_param(ep->beta_a, ep->gran_a, false, out.beta_a)) != RTN_OK) return rc;
     if ((rc = make_param(ep->alpha_w, ep->gran_w, false, out.alpha_w)) != RTN_OK) return rc;
     if ((rc = make_param(ep->beta_w, ep->gran_w, true, out.beta_w)) != RTN_OK) return rc;
-    if (!ep->sum_ta || !ep->sum_tw) return RTN_ERR_NULL;
+    if ((need_sum_ta && !ep->sum_ta) || !ep->sum_tw) return RTN_ERR_NULL;
     if (!aligned(ep->sum_ta, 4) || !aligned(ep->sum_tw, 4)) return RTN_ERR_ALIGN;
     if (ep->bn_shift && !ep->bn_scale) return RTN_ERR_NULL;
     if (!aligned(ep->bn_scale, 4) || !aligned(ep->bn_shift, 4)) return RTN_ERR_ALIGN;
@@ -230,7 +232,7 @@ int rtn_conv2d_prepare_constants(int64_t C, int64_t O, int KH, int KW, int pad, 
     // geometry fields the table depends on: C, O, KH, KW, pad (image size is irrelevant)
     int rc = make_geom(1, C, KH, KW, O, KH, KW, 1, pad, RTN_PAD_TRUE_ZERO, c.g);
     if (rc != RTN_OK) return rc;
-    if ((rc = make_epilogue(ep, true, c.ep)) != RTN_OK) return rc;
+    if ((rc = make_epilogue(ep, true, c.ep, false)) != RTN_OK) return rc;
     if (!workspace || workspace_bytes < rtn_conv2d_workspace_bytes(O, KH, KW, pad)) return RTN_ERR_WORKSPACE;
     if (!aligned(workspace, 16)) return RTN_ERR_ALIGN;
     const hipError_t he = rtn::launch_conv_class_consts(c, (double*)workspace, (hipStream_t)stream);
@@ -254,7 +256,7 @@ int rtn_ternary_conv2d_implicit_gemm(rtn_code_format fmt, rtn_path path, const v
     if (!aligned(a_codes, 16) || !aligned(w_codes, 16) || !aligned(acc_out, 4) || !aligned(y_out, 4))
         return RTN_ERR_ALIGN;
     if (ep) {
-        if ((rc = make_epilogue(ep, true, c.ep)) != RTN_OK) return rc;
+        if ((rc = make_epilogue(ep, true, c.ep, false)) != RTN_OK) return rc;
         if (!workspace || workspace_bytes < rtn_conv2d_workspace_bytes(O, KH, KW, pad)) return RTN_ERR_WORKSPACE;
         if (!aligned(workspace, 16)) return RTN_ERR_ALIGN;
     }
@@ -266,6 +268,37 @@ int rtn_ternary_conv2d_implicit_gemm(rtn_code_format fmt, rtn_path path, const v
     hipStream_t st = (hipStream_t)stream;
     hipError_t he;
     he = rtn::launch_conv_mfma(c, st);
+    return he == hipSuccess ? RTN_OK : hip_fail(he);
+}
+
+int rtn_ternary_conv2d_ternarize(rtn_code_format fmt, rtn_path path, const void* a_codes,
+                                 const void* w_codes, int64_t Nb, int64_t C, int64_t H, int64_t W, int64_t O,
+                                 int KH, int KW, int stride, int pad, rtn_pad_mode pad_mode,
+                                 const rtn_epilogue* ep, const float* thr_lo, const float* thr_hi,
+                                 rtn_gran thr_gran, void* codes_out, void* workspace, size_t workspace_bytes,
+                                 void* stream)
+{
+    if (!a_codes || !w_codes || !codes_out || !ep || !thr_lo || !thr_hi) return RTN_ERR_NULL;
+    if (fmt != RTN_CODE_I8) return RTN_ERR_UNSUPPORTED;
+    if (path != RTN_PATH_AUTO && path != RTN_PATH_MFMA_I8) return RTN_ERR_UNSUPPORTED;
+    rtn::ConvArgs c = {};
+    int rc = make_geom(Nb, C, H, W, O, KH, KW, stride, pad, pad_mode, c.g);
+    if (rc != RTN_OK) return rc;
+    if (!aligned(a_codes, 16) || !aligned(w_codes, 16) || !aligned(codes_out, 16)) return RTN_ERR_ALIGN;
+    if ((rc = make_epilogue(ep, true, c.ep, false)) != RTN_OK) return rc;
+    if ((rc = make_param(thr_lo, thr_gran, false, c.thr_lo)) != RTN_OK) return rc;
+    if ((rc = make_param(thr_hi, thr_gran, false, c.thr_hi)) != RTN_OK) return rc;
+    if (thr_gran == RTN_SCALAR && !(c.thr_lo.s <= c.thr_hi.s)) return RTN_ERR_SHAPE;
+    if (!workspace || workspace_bytes < rtn_conv2d_workspace_bytes(O, KH, KW, pad)) return RTN_ERR_WORKSPACE;
+    if (!aligned(workspace, 16)) return RTN_ERR_ALIGN;
+    const int64_t ldc = pad64(O);
+    if (ldc > kMaxDim || (double)c.g.Nb * c.g.OH * c.g.OW * (double)ldc >= 1099511627776.0) return RTN_ERR_SHAPE;
+    c.a = (const int8_t*)a_codes;
+    c.w = (const int8_t*)w_codes;
+    c.cst_cls = (const double*)workspace;
+    c.codes = (int8_t*)codes_out;
+    c.ldc = (int)ldc;
+    const hipError_t he = rtn::launch_conv_mfma(c, (hipStream_t)stream);
     return he == hipSuccess ? RTN_OK : hip_fail(he);
 }
 

@@ -83,8 +83,13 @@ struct ConvArgs {
     ConvGeom g;
     int32_t* acc;          // nullable, [Nb][O][OH][OW]
     float* y;              // nullable
-    const double* cst_cls; // workspace: [KH*KH*KW*KW][O] per-border-class constants (when y)
+    const double* cst_cls; // workspace: the prepared per-layer epilogue table (when y or codes)
     EpiArgs ep;
+    // ternarizing epilogue (acc and y NULL): codes [Nb*OH*OW][ldc] int8, thresholds
+    // scalar or per output channel
+    int8_t* codes;
+    int ldc;
+    Param thr_lo, thr_hi;
 };
 
 hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t st);

@@ -57,6 +57,11 @@ struct TmmParams {
     float* y;
     const double* cst_cls;  // conv: [class][O] constants (see k_conv_class_consts)
     EpiArgs ep;
+    // conv, ternarizing epilogue: the output is the next layer's code tensor
+    // [pixel][ldc] (int8, channel-innermost) instead of acc / y
+    int8_t* codes;
+    int ldc;
+    Param thr_lo, thr_hi;  // vector: per output channel
 };
 
 // Border classes of a conv window and the LDS bytes of the epilogue table of a
@@ -138,9 +143,14 @@ __device__ __forceinline__ void wait_groups(int groups)
 // run once into LDS and every tap reads its fragments from there: the input
 // crosses L2 -> LDS about 1.4 times instead of KH KW times, and only the
 // weight tile still streams through the ring.
-template <int BP, int BQ, int WGP, int WGQ, int NS, int MINW, bool CONV, int HC = 0>
+//
+// TERN selects the conv whose epilogue ternarizes its own output (codes for the
+// next layer instead of acc / y); it is a kernel of its own so that its epilogue
+// does not enter the register budget of the others.
+template <int BP, int BQ, int WGP, int WGQ, int NS, int MINW, bool CONV, bool TERN = false, int HC = 0>
 __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
 {
+    static_assert(!TERN || CONV, "the ternarizing epilogue belongs to the conv");
     static_assert(WGP * WGQ == 4, "4 waves per block");
     constexpr bool HALO = HC != 0;
     static_assert(!HALO || (CONV && (HC == 64 || HC == 128)), "halo variant: conv with Cpad 64 or 128");
@@ -181,12 +191,13 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
     // conv layers, because a new block's loads no longer queue behind other blocks'
     // stores as often).
     __builtin_amdgcn_s_setprio(3);
-    // LDS: [halo pixels hrows x HC][128 zero bytes][operand ring][conv: epilogue table];
-    // the GEMM builds its small table over the ring
+    // LDS: [halo pixels hrows x HC][128 zero bytes][operand ring][conv: epilogue table]
+    // [ternarizing conv: BP threshold pairs]; the GEMM builds its small table over the ring
     const int zoff = HALO ? prm.hrows * HC : 0;
     const int roff = HALO ? zoff + 128 : 0;
     const int toff = roff + NS * STAGE;
     const int tab_kib = CONV ? (conv_table_bytes(BP, g.pad) + 1023) >> 10 : 0;
+    const bool want_ep = TERN || prm.y != nullptr;
 
     // ---- loader state ------------------------------------------------------
     // Load j of a wave covers tile rows 16*(wave + 4*j) .. +15; lane l fetches
@@ -406,7 +417,15 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
     // ---- prologue: start the first NS steps, then per-lane epilogue terms -----
     const int nk = prm.nk;
     const int npro = nk < NS ? nk : NS;
-    if (CONV && prm.y) {
+    if (TERN) {
+        // thresholds of this tile's channels, (lo, hi) pairs behind the table
+        // (visible to every wave after the first barrier of the main loop)
+        if (tid < BP) {
+            const int o = p0 + tid < prm.RP ? p0 + tid : prm.RP - 1;
+            ((float2*)(smem + toff + tab_kib * 1024))[tid] = make_float2((float)pval(prm.thr_lo, o), (float)pval(prm.thr_hi, o));
+        }
+    }
+    if (CONV && want_ep) {
         // epilogue table: rows [g1, c2, bn scale, bn shift, class constants...] of the
         // prepared per-layer table, columns p0 .. p0+BP-1, copied as they are
         const int nrows = 4 + conv_classes(g.pad), opitch = (g.O + 1) & ~1;
@@ -445,7 +464,7 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
     int pixcls[TQ];
 #pragma unroll
     for (int j = 0; j < TQ; ++j) pixcls[j] = 0;
-    if (CONV && prm.y && !g.code_zero_pad) {
+    if (CONV && want_ep && !g.code_zero_pad) {
         const int ohw = g.OH * g.OW, p1 = g.pad + 1;
 #pragma unroll
         for (int j = 0; j < TQ; ++j) {
@@ -615,6 +634,54 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
         int sa_full[TQ];
 #pragma unroll
         for (int j = 0; j < TQ; ++j) sa_full[j] = sa_part[j] + __shfl_xor(sa_part[j], 32, 64);
+        if constexpr (TERN) {
+            // Ternarizing epilogue (Eq.1 / Eq.3 applied to the activation of Eq.9): the
+            // fp32 value z is formed exactly as below, compared with the channel's
+            // thresholds, and only the code leaves the chip.  A lane's accumulator
+            // registers 4 r4 .. 4 r4 + 3 are 4 consecutive channels of one pixel: one
+            // dword of the channel-innermost code tensor.  Channels O .. ldc-1 get code 0.
+            const float2* thr = (const float2*)(smem + toff + tab_kib * 1024);
+            auto run_codes = [&](auto full) {
+                constexpr bool FULL = decltype(full)::value;
+#pragma unroll
+                for (int j = 0; j < TQ; ++j) {
+                    const int m = q0 + wq * WQ + j * 32 + (lane & 31);
+                    const bool mok = FULL || m < prm.RQ;
+                    int8_t* cp = prm.codes + (int64_t)(mok ? m : 0) * prm.ldc;
+                    const double Sa = (double)sa_full[j];
+                    const double* ctab = tab + (4 + pixcls[j]) * BP;
+#pragma unroll
+                    for (int i = 0; i < TP; ++i)
+#pragma unroll
+                        for (int r4 = 0; r4 < 4; ++r4) {
+                            const int t0 = wp * WP + i * 32 + 8 * r4 + 4 * (lane >> 5);
+                            const int o0 = p0 + t0;
+                            unsigned word = 0;
+#pragma unroll
+                            for (int b = 0; b < 4; ++b) {
+                                const int t = t0 + b;
+                                const bool ook = FULL || o0 + b < prm.RP;
+                                const double g1 = tab[t], c2 = tab[BP + t], bs = tab[2 * BP + t], bh = tab[3 * BP + t];
+                                const float2 th = thr[t];
+                                const int D = acc[i][j][4 * r4 + b];
+                                double v = g1 * (double)D + (c2 * Sa + ctab[t]);
+                                v = __builtin_fmax(v, relu_floor);
+                                const float z = (float)(bs * v + bh);
+                                int code = (int)(z > th.y) - (int)(z < th.x);
+                                if (!FULL && !ook) code = 0;
+                                word |= (unsigned)(code & 0xff) << (8 * b);
+                            }
+                            if (FULL || (mok && o0 < prm.ldc)) *(unsigned*)(cp + o0) = word;
+                            __builtin_amdgcn_sched_barrier(0);
+                        }
+                }
+            };
+            if (full_tile)
+                run_codes(std::true_type{});
+            else
+                run_codes(std::false_type{});
+            return;
+        }
         dispatch([&](auto full, auto want_acc, auto want_y) {
             constexpr bool FULL = decltype(full)::value, ACC = decltype(want_acc)::value,
                            Y = decltype(want_y)::value;
@@ -734,7 +801,7 @@ inline bool halo_eligible(const TmmParams& prm, int hc)
            g.OW == g.W;
 }
 
-template <int BP, int BQ, int WGP, int WGQ, int NS, int MINW, bool CONV, int HC = 0>
+template <int BP, int BQ, int WGP, int WGQ, int NS, int MINW, bool CONV, bool TERN = false, int HC = 0>
 hipError_t launch_cfg(TmmParams& prm, hipStream_t st)
 {
     constexpr int ring_bytes = NS * (BP + (HC ? 0 : BQ)) * 64;
@@ -748,13 +815,14 @@ hipError_t launch_cfg(TmmParams& prm, hipStream_t st)
     if (CONV) {
         // ring (+ halo), then the epilogue table in whole KiB
         smem = stage_bytes + ((table_bytes(BP, true, prm.g.pad) + 1023) & ~(int64_t)1023);
+        if (TERN) smem += BP * 8;  // threshold pairs of the ternarizing epilogue
     } else {
         const int64_t tb = table_bytes(BP, false, 0);
         smem = stage_bytes > tb ? stage_bytes : tb;
     }
     if (smem > kMaxLds) return hipErrorInvalidValue;
     static bool attr_done = false;
-    auto kern = k_tmm<BP, BQ, WGP, WGQ, NS, MINW, CONV, HC>;
+    auto kern = k_tmm<BP, BQ, WGP, WGQ, NS, MINW, CONV, TERN, HC>;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)kMaxLds);
@@ -785,40 +853,40 @@ const int kTileBP[kNumTileConfigs] = {64, 128, 256, 64,  128, 256, 64, 64, 128, 
                                        64, 64,  128, 128, 64,  64,  64, 64, 128, 128};
 int g_forced_tile = -1;
 
-template <bool CONV>
+template <bool CONV, bool TERN = false>
 hipError_t launch_index_raw(int cfg, TmmParams& prm, hipStream_t st);
 
 // A configuration whose LDS need (ring + the conv's table, which grows with the
 // pad) exceeds the CU's falls back to the smallest tile.
-template <bool CONV>
+template <bool CONV, bool TERN = false>
 hipError_t launch_index(int cfg, TmmParams& prm, hipStream_t st)
 {
-    hipError_t e = launch_index_raw<CONV>(cfg, prm, st);
-    if (e == hipErrorInvalidValue && cfg != 0) e = launch_index_raw<CONV>(0, prm, st);
+    hipError_t e = launch_index_raw<CONV, TERN>(cfg, prm, st);
+    if (e == hipErrorInvalidValue && cfg != 0) e = launch_index_raw<CONV, TERN>(0, prm, st);
     return e;
 }
 
-template <bool CONV>
+template <bool CONV, bool TERN>
 hipError_t launch_index_raw(int cfg, TmmParams& prm, hipStream_t st)
 {
     // conv with a large pad: the per-class constant table of a tall tile does
     // not fit in LDS; fall back to the tile of the same width class with BP = 64.
     if (CONV && table_bytes(kTileBP[cfg], true, prm.g.pad) > 48 * 1024) cfg = 0;
     switch (cfg) {
-        case 0: return launch_cfg<64, 64, 2, 2, 4, 4, CONV>(prm, st);
-        case 1: return launch_cfg<128, 128, 2, 2, (CONV ? 3 : 4), 2, CONV>(prm, st);
-        case 2: return launch_cfg<256, 256, 2, 2, (CONV ? 3 : 4), 1, CONV>(prm, st);
-        case 3: return launch_cfg<64, 256, 1, 4, 3, 3, CONV>(prm, st);
-        case 4: return launch_cfg<128, 256, 2, 2, 3, 2, CONV>(prm, st);
-        case 5: return launch_cfg<256, 128, 2, 2, 3, 2, CONV>(prm, st);
-        case 6: return launch_cfg<64, 128, 1, 4, 3, 4, CONV>(prm, st);
-        case 7: return launch_cfg<64, 256, 1, 4, 2, 3, CONV>(prm, st);
-        case 8: return launch_cfg<128, 128, 2, 2, 3, 3, CONV>(prm, st);
-        case 9: return launch_cfg<64, 256, 1, 4, 2, 4, CONV>(prm, st);
-        case 10: return launch_cfg<64, 128, 1, 4, 4, 4, CONV>(prm, st);
-        case 11: return launch_cfg<64, 64, 2, 2, 4, 6, CONV>(prm, st);
-        case 12: return launch_cfg<128, 128, 2, 2, 2, 4, CONV>(prm, st);
-        case 13: return launch_cfg<128, 256, 2, 2, 2, 2, CONV>(prm, st);
+        case 0: return launch_cfg<64, 64, 2, 2, 4, 4, CONV, TERN>(prm, st);
+        case 1: return launch_cfg<128, 128, 2, 2, (CONV ? 3 : 4), 2, CONV, TERN>(prm, st);
+        case 2: return launch_cfg<256, 256, 2, 2, (CONV ? 3 : 4), 1, CONV, TERN>(prm, st);
+        case 3: return launch_cfg<64, 256, 1, 4, 3, 3, CONV, TERN>(prm, st);
+        case 4: return launch_cfg<128, 256, 2, 2, 3, 2, CONV, TERN>(prm, st);
+        case 5: return launch_cfg<256, 128, 2, 2, 3, 2, CONV, TERN>(prm, st);
+        case 6: return launch_cfg<64, 128, 1, 4, 3, 4, CONV, TERN>(prm, st);
+        case 7: return launch_cfg<64, 256, 1, 4, 2, 3, CONV, TERN>(prm, st);
+        case 8: return launch_cfg<128, 128, 2, 2, 3, 3, CONV, TERN>(prm, st);
+        case 9: return launch_cfg<64, 256, 1, 4, 2, 4, CONV, TERN>(prm, st);
+        case 10: return launch_cfg<64, 128, 1, 4, 4, 4, CONV, TERN>(prm, st);
+        case 11: return launch_cfg<64, 64, 2, 2, 4, 6, CONV, TERN>(prm, st);
+        case 12: return launch_cfg<128, 128, 2, 2, 2, 4, CONV, TERN>(prm, st);
+        case 13: return launch_cfg<128, 256, 2, 2, 2, 2, CONV, TERN>(prm, st);
         default: break;
     }
     // 14 .. 19: halo variants (conv only); a shape they do not cover runs the plain
@@ -828,26 +896,26 @@ hipError_t launch_index_raw(int cfg, TmmParams& prm, hipStream_t st)
         const bool ok = halo_eligible(prm, 64) || halo_eligible(prm, 128);
         if (ok && hc == 64) {
             switch (cfg) {
-                case 14: return launch_cfg<64, 256, 1, 4, 9, 2, CONV, 64>(prm, st);
-                case 15: return launch_cfg<64, 256, 1, 4, 3, 3, CONV, 64>(prm, st);
-                case 16: return launch_cfg<64, 128, 1, 4, 9, 3, CONV, 64>(prm, st);
-                case 17: return launch_cfg<64, 128, 1, 4, 3, 4, CONV, 64>(prm, st);
+                case 14: return launch_cfg<64, 256, 1, 4, 9, 2, CONV, TERN, 64>(prm, st);
+                case 15: return launch_cfg<64, 256, 1, 4, 3, 3, CONV, TERN, 64>(prm, st);
+                case 16: return launch_cfg<64, 128, 1, 4, 9, 3, CONV, TERN, 64>(prm, st);
+                case 17: return launch_cfg<64, 128, 1, 4, 3, 4, CONV, TERN, 64>(prm, st);
                 default: break;
             }
         }
         if (ok && hc == 128) {
             switch (cfg) {
-                case 18: return launch_cfg<128, 128, 2, 2, 3, 3, CONV, 128>(prm, st);
-                case 19: return launch_cfg<128, 256, 2, 2, 3, 2, CONV, 128>(prm, st);
+                case 18: return launch_cfg<128, 128, 2, 2, 3, 3, CONV, TERN, 128>(prm, st);
+                case 19: return launch_cfg<128, 256, 2, 2, 3, 2, CONV, TERN, 128>(prm, st);
                 default: break;
             }
         }
     }
     switch (cfg) {
-        case 14: case 15: return launch_cfg<64, 256, 1, 4, 2, 3, CONV>(prm, st);
-        case 16: case 17: return launch_cfg<64, 128, 1, 4, 3, 4, CONV>(prm, st);
-        case 18: return launch_cfg<128, 128, 2, 2, 2, 4, CONV>(prm, st);
-        case 19: return launch_cfg<128, 256, 2, 2, 2, 2, CONV>(prm, st);
+        case 14: case 15: return launch_cfg<64, 256, 1, 4, 2, 3, CONV, TERN>(prm, st);
+        case 16: case 17: return launch_cfg<64, 128, 1, 4, 3, 4, CONV, TERN>(prm, st);
+        case 18: return launch_cfg<128, 128, 2, 2, 2, 4, CONV, TERN>(prm, st);
+        case 19: return launch_cfg<128, 256, 2, 2, 2, 2, CONV, TERN>(prm, st);
         default: return hipErrorInvalidValue;
     }
 }
@@ -923,11 +991,15 @@ hipError_t launch_conv_mfma(const ConvArgs& a, hipStream_t st)
     prm.y = a.y;
     prm.cst_cls = a.cst_cls;
     prm.ep = a.ep;
+    prm.codes = a.codes;
+    prm.ldc = a.ldc;
+    prm.thr_lo = a.thr_lo;
+    prm.thr_hi = a.thr_hi;
     int cfg = g_forced_tile >= 0 ? g_forced_tile : pick_tile(g.O, prm.RQ, true);
     // a 64-filter layer with a centred stride-1 window: the variant that keeps the
     // tile's input pixel run in LDS (measured faster there; on par or slower elsewhere)
     if (g_forced_tile < 0 && cfg == 7 && halo_eligible(prm, 64)) cfg = 15;
-    return launch_index<true>(cfg, prm, st);
+    return a.codes ? launch_index<true, true>(cfg, prm, st) : launch_index<true>(cfg, prm, st);
 }
 
 }  // namespace rtn

@@ -111,3 +111,55 @@ def hip_conv(case, pad_true_zero=True, relu=False, want_acc=True):
                                   ep=ep, want_acc=want_acc)
     torch.cuda.synchronize()
     return dict(ca=ca, cw=cw, pa=pa, pw=pw, D=acc, y=y, ep=ep)
+
+
+def oracle_next_codes(ref, lo, hi):
+    """Oracle codes [Nb,OH,OW,Opad] of the next layer from an oracle_conv() result."""
+    O = ref["y"].shape[1]
+    return orc.nchw_to_nhwc_i8(orc.ternarize_nchw(ref["y"], lo, hi), (O + 63) // 64 * 64)
+
+
+def hip_conv_ternarize(case, lo, hi, pad_true_zero=True, relu=False):
+    """pack -> conv with the ternarizing epilogue; returns the int8 code tensor (device)."""
+    sh = case["shape"]
+    da, dw = case["delta_a"], case["delta_w"]
+    x, w = dev(case["x"]), dev(case["w"])
+    ca, _ = B.ternarize_pack(x, thr_arg(-da), thr_arg(da), want_sum=False)
+    cw, pw = B.ternarize_pack(w, thr_arg(-np.asarray(dw)), thr_arg(dw))
+    ep = B.Epilogue(gran_arg(case["alpha_a"]), gran_arg(case["beta_a"]), gran_arg(case["alpha_w"]),
+                    gran_arg(case["beta_w"]), None, pw, relu=relu,
+                    bn_scale=None if "bn_scale" not in case else dev(case["bn_scale"]),
+                    bn_shift=None if "bn_shift" not in case else dev(case["bn_shift"]))
+    Nb, Cc, H, W = case["x"].shape
+    pm = B.RTN_PAD_TRUE_ZERO if pad_true_zero else B.RTN_PAD_CODE_ZERO
+    # poison the output so that unwritten bytes (padding channels included) show
+    OH, OW = B.conv_out_hw(H, W, sh.k, sh.k, sh.stride, sh.pad)
+    out = torch.full((Nb, OH, OW, B.padded_k(sh.O)), 77, dtype=torch.int8, device=DEV)
+    codes = B.ternary_conv2d_ternarize(ca, cw, Nb, Cc, H, W, sh.O, sh.k, sh.k, sh.stride, sh.pad, ep,
+                                       thr_arg(lo), thr_arg(hi), pad_mode=pm, codes_out=out)
+    torch.cuda.synchronize()
+    return codes
+
+
+def assert_codes_match(codes, want, z, lo, hi, what=""):
+    """Codes decided by a floating-point comparison: both sides compare the fp32 value
+    z with the fp32 thresholds.  The two sides may round z differently in its last
+    bit (fp64 evaluation order), which can move a code only where z sits within a few
+    fp32 ulps of a threshold; everywhere else the codes must be identical, and such
+    elements must be rare.  z: oracle fp32 [Nb,O,OH,OW]; codes/want: [Nb,OH,OW,Opad]."""
+    codes = np.asarray(codes)
+    assert codes.shape == want.shape and codes.dtype == np.int8, (codes.shape, want.shape, codes.dtype)
+    O = z.shape[1]
+    assert (codes[..., O:] == 0).all(), what + ": padding channels must be code 0"
+    bad = codes != want
+    if not bad.any():
+        return 0
+    zz = z.transpose(0, 2, 3, 1).astype(np.float64)
+    lo_b = np.broadcast_to(np.asarray(lo, np.float64), (O,))
+    hi_b = np.broadcast_to(np.asarray(hi, np.float64), (O,))
+    tol = 4e-7 * np.maximum(1.0, np.abs(zz))
+    near = (np.abs(zz - lo_b) <= tol) | (np.abs(zz - hi_b) <= tol)
+    badv = bad[..., :O]
+    assert not (badv & ~near).any(), "%s: %d codes differ away from a threshold" % (what, int((badv & ~near).sum()))
+    assert int(badv.sum()) <= 2 + zz.size // 1000000, "%s: %d codes differ at a threshold" % (what, int(badv.sum()))
+    return int(badv.sum())

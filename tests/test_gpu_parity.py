@@ -309,6 +309,108 @@ def test_halo_variants(cfg, hs, tile_reset):
             T.assert_y_close(got["y"].cpu().numpy(), ref["y"], "%s cfg %d" % (name, cfg))
 
 
+# ---------------------- conv with the ternarizing epilogue (next layer's codes) ----
+def _thresholds(kind, case, O, seed):
+    """scalar: one Delta for the layer; vector: Eq.3's BN-folded pair per channel."""
+    if kind == "scalar":
+        return np.float32(-0.4), np.float32(0.6)
+    rng = np.random.default_rng(seed)
+    k = rng.uniform(0.5, 1.5, O)
+    b = rng.normal(0.0, 0.3, O)
+    return (-(0.5 + b) / k).astype(np.float32), ((0.5 - b) / k).astype(np.float32)
+
+
+@pytest.mark.parametrize("shape", CONV_SHAPES, ids=lambda s: s.name)
+@pytest.mark.parametrize("kind", ["scalar", "vector"])
+def test_conv_ternarize_vs_oracle(shape, kind):
+    _say("conv+ternarize %s thresholds=%s" % (shape, kind))
+    true_zero = kind == "scalar"
+    relu = kind == "vector"
+    case = wl.conv_case(shape, batch=3, seed=40 + len(shape.name), per_channel=True, bn=(kind == "scalar"))
+    lo, hi = _thresholds(kind, case, shape.O, 5)
+    ref = T.oracle_conv(case, true_zero, relu=relu)
+    want = T.oracle_next_codes(ref, lo, hi)
+    got = T.hip_conv_ternarize(case, lo, hi, true_zero, relu=relu).cpu().numpy()
+    T.assert_codes_match(got, want, ref["y"], lo, hi, shape.name)
+    assert {0, 1} <= set(np.unique(want))          # the case decides something
+
+
+@pytest.mark.parametrize("cfg", range(20))
+def test_all_tile_configs_conv_ternarize(cfg, tile_reset):
+    _say("tile config %d, ternarizing epilogue" % cfg)
+    B.set_tile_config(cfg)
+    for shape, batch in [(wl.ConvShape("t", 64, 13, 200, 3, 2, 1), 7),       # ragged in O and pixels
+                         (wl.ConvShape("u", 64, 16, 256, 3, 1, 1), 3)]:      # full tiles only
+        case = wl.conv_case(shape, batch=batch, seed=90 + cfg, bn=True)
+        lo, hi = _thresholds("vector", case, shape.O, cfg)
+        ref = T.oracle_conv(case, True, relu=True)
+        want = T.oracle_next_codes(ref, lo, hi)
+        got = T.hip_conv_ternarize(case, lo, hi, True, relu=True).cpu().numpy()
+        T.assert_codes_match(got, want, ref["y"], lo, hi, "cfg %d %s" % (cfg, shape.name))
+        assert {-1, 0, 1} <= set(np.unique(want))
+
+
+@pytest.mark.parametrize("cfg", range(14, 20))
+@pytest.mark.parametrize("hs", HALO_SHAPES, ids=[h[0] for h in HALO_SHAPES])
+def test_halo_variants_conv_ternarize(cfg, hs, tile_reset):
+    name, Cc, H, O, k, stride, pad, batch, W = hs
+    _say("halo cfg %d shape %s, ternarizing epilogue" % (cfg, name))
+    B.set_tile_config(cfg)
+    shape = wl.ConvShape(name, Cc, H, O, k, stride, pad)
+    case = wl.conv_case(shape, batch=batch, seed=400 + cfg, bn=True, Wx=W)
+    lo, hi = _thresholds("scalar", case, O, 0)
+    ref = T.oracle_conv(case, True, relu=True)
+    got = T.hip_conv_ternarize(case, lo, hi, True, relu=True).cpu().numpy()
+    T.assert_codes_match(got, T.oracle_next_codes(ref, lo, hi), ref["y"], lo, hi, "%s cfg %d" % (name, cfg))
+
+
+def test_conv_ternarize_equals_pack_of_conv_output():
+    """The fused epilogue against the library's own two-step route (fp32 y, then
+    rtn_ternarize_pack): the same codes, and Eq.3's fold -- BN applied and one
+    threshold pair of +-0.5, against no BN and per-channel thresholds -- agrees away
+    from ties."""
+    _say("conv+ternarize vs pack(conv)")
+    shape = wl.ConvShape("f", 64, 14, 128, 3, 1, 1)
+    case = wl.conv_case(shape, batch=4, seed=61, bn=True)
+    case["bn_scale"] = np.abs(case["bn_scale"]) + np.float32(0.25)          # k > 0
+    fused = T.hip_conv_ternarize(case, np.float32(-0.5), np.float32(0.5), True, relu=True)
+    two = T.hip_conv(case, True, relu=True, want_acc=False)
+    packed, _ = B.ternarize_pack(two["y"], -0.5, 0.5, want_sum=False)
+    torch.cuda.synchronize()
+    assert torch.equal(fused, packed)
+    k, b = case["bn_scale"].astype(np.float64), case["bn_shift"].astype(np.float64)
+    lo, hi = (-(0.5 + b) / k).astype(np.float32), ((0.5 - b) / k).astype(np.float32)
+    nobn = {kk: v for kk, v in case.items() if kk not in ("bn_scale", "bn_shift")}
+    folded = T.hip_conv_ternarize(nobn, lo, hi, True, relu=True)
+    diff = (folded != fused)
+    z = two["y"].permute(0, 2, 3, 1)                        # bn(relu(.)) as stored
+    near = (z.abs() - 0.5).abs() < 1e-5
+    assert not bool((diff & ~near).any())
+    assert int(diff.sum()) < 20
+
+
+CONV1_OF_BLOCK = [0, 2, 4, 7, 9, 12, 14, 17]
+
+
+@pytest.mark.parametrize("idx", CONV1_OF_BLOCK)
+def test_resnet18_conv1_layers_batch256_ternarize_sampled_images(idx):
+    """The first conv of each ResNet-18 block at batch 256 (the shapes whose output
+    feeds another ternary conv), ternarizing epilogue, launch configuration as the
+    benchmark's fused workload; the oracle recomputes two whole images."""
+    shape = wl.resnet18_ternary_layers()[idx]
+    _say("resnet18 b256 conv+ternarize %s" % (shape,))
+    case = wl.conv_case(shape, batch=256, seed=500 + idx, per_channel=True, bn=True)
+    lo, hi = np.float32(-0.5), np.float32(0.5)
+    got = T.hip_conv_ternarize(case, lo, hi, True, relu=True)
+    imgs = [0, 255]
+    ref = T.oracle_conv(case, True, relu=True, images=imgs)
+    T.assert_codes_match(got[imgs].cpu().numpy(), T.oracle_next_codes(ref, lo, hi), ref["y"], lo, hi, shape.name)
+    # properties at any size: only codes, zero padding channels, a plausible mix
+    assert int(got.abs().max()) == 1
+    frac = got.float().abs().mean().item()
+    assert 0.02 < frac < 0.98
+
+
 # ----------------------------------------------------- full-size checks ------
 def test_config2_gemm_4096_sampled_rows():
     """M = N = K = 4096 in the launch configuration the benchmark times; the
