@@ -882,10 +882,10 @@ hipError_t launch_index_raw(int cfg, TmmParams& prm, hipStream_t st)
         case 6: return launch_cfg<64, 128, 1, 4, 3, 4, CONV, TERN>(prm, st);
         case 7: return launch_cfg<64, 256, 1, 4, 2, 3, CONV, TERN>(prm, st);
         case 8: return launch_cfg<128, 128, 2, 2, 3, 3, CONV, TERN>(prm, st);
-        case 9: return launch_cfg<64, 256, 1, 4, 2, 4, CONV, TERN>(prm, st);
+        case 9: return launch_cfg<64, 256, 1, 4, 2, (TERN ? 3 : 4), CONV, TERN>(prm, st);
         case 10: return launch_cfg<64, 128, 1, 4, 4, 4, CONV, TERN>(prm, st);
         case 11: return launch_cfg<64, 64, 2, 2, 4, 6, CONV, TERN>(prm, st);
-        case 12: return launch_cfg<128, 128, 2, 2, 2, 4, CONV, TERN>(prm, st);
+        case 12: return launch_cfg<128, 128, 2, 2, 2, (TERN ? 3 : 4), CONV, TERN>(prm, st);
         case 13: return launch_cfg<128, 256, 2, 2, 2, 2, CONV, TERN>(prm, st);
         default: break;
     }
@@ -914,7 +914,7 @@ hipError_t launch_index_raw(int cfg, TmmParams& prm, hipStream_t st)
     switch (cfg) {
         case 14: case 15: return launch_cfg<64, 256, 1, 4, 2, 3, CONV, TERN>(prm, st);
         case 16: case 17: return launch_cfg<64, 128, 1, 4, 3, 4, CONV, TERN>(prm, st);
-        case 18: return launch_cfg<128, 128, 2, 2, 2, 4, CONV, TERN>(prm, st);
+        case 18: return launch_cfg<128, 128, 2, 2, 2, (TERN ? 3 : 4), CONV, TERN>(prm, st);
         case 19: return launch_cfg<128, 256, 2, 2, 2, 2, CONV, TERN>(prm, st);
         default: return hipErrorInvalidValue;
     }
