@@ -591,3 +591,67 @@ def test_config4_chained_blocks_small_batch():
         T.assert_y_close(xh_next.cpu().numpy(), xo_next, "block %d out" % bi)
         xo, xh = xo_next, xh_next
     assert xo.shape == (2, 512, 7, 7)
+
+
+def test_config4_chained_blocks_ternarizing_epilogue():
+    """The chained stack of test_config4_chained_blocks_small_batch with the first conv
+    of every block handing its output to the second as codes (ternarizing epilogue),
+    and the block input packed once for conv1 and the downsample conv.  The oracle
+    runs the two-step definition (fp32 activation, then Eq.1); codes entering every
+    conv and the block outputs must agree."""
+    _say("config 4: chained blocks with the ternarizing epilogue, batch 2")
+    P = _chain_params(2, 700)
+    rng = np.random.default_rng(77)
+    x0 = rng.standard_normal((2, 64, 56, 56)).astype(np.float32)
+    lo, hi = -DELTA_CHAIN, DELTA_CHAIN
+
+    def weights(p):
+        cw, pw = B.ternarize_pack(T.dev(p["w"]), T.thr_arg(-np.asarray(p["dw"])), T.thr_arg(p["dw"]))
+        ep = B.Epilogue(T.gran_arg(p["aa"]), T.gran_arg(p["ba"]), T.gran_arg(p["aw"]), T.gran_arg(p["bw"]),
+                        None, pw, relu=p["relu"], bn_scale=T.dev(p["bs"]), bn_shift=T.dev(p["bh"]))
+        return cw, ep
+
+    def oracle_layer(ta, p, relu):
+        sh = p["sh"]
+        tw = orc.ternarize(p["w"], -np.asarray(p["dw"]), p["dw"])
+        D = orc.conv_acc(ta, tw, sh.stride, sh.pad)
+        Sa, Sw, Kv = orc.conv_sums(ta, tw, sh.stride, sh.pad, True)
+        return orc.conv_epilogue(D, Sa, Sw, Kv, p["aa"], p["ba"], p["aw"], p["bw"], relu=relu,
+                                 bn_scale=p["bs"], bn_shift=p["bh"])
+
+    xo, xh = x0, T.dev(x0)
+    for bi, (i1, i2, ids) in enumerate(_chain_topology()):
+        p1, p2 = dict(P[i1], relu=True), dict(P[i2], relu=False)
+        sh1, sh2 = p1["sh"], p2["sh"]
+        # oracle: T(x) -> conv1 -> relu -> bn -> T -> conv2 -> bn ; shortcut ; add ; relu
+        ta1 = orc.ternarize(xo, lo, hi)
+        y1 = oracle_layer(ta1, p1, True)
+        ta2 = orc.ternarize_nchw(y1, lo, hi)
+        y2 = oracle_layer(ta2, p2, False)
+        sc = xo if ids is None else oracle_layer(ta1, P[ids], False)
+        xo_next = np.maximum(y2 + sc, np.float32(0)).astype(np.float32)
+        # HIP: one pack, conv1 with the ternarizing epilogue, conv2 (and downsample) to fp32
+        Nb, Cc, H, W = xh.shape
+        ca1, _ = B.ternarize_pack(xh, float(lo), float(hi), want_sum=False)
+        cw1, ep1 = weights(p1)
+        ca2 = B.ternary_conv2d_ternarize(ca1, cw1, Nb, Cc, H, W, sh1.O, sh1.k, sh1.k, sh1.stride, sh1.pad,
+                                         ep1, float(lo), float(hi))
+        cw2, ep2 = weights(p2)
+        _, h2 = B.ternary_conv2d(ca2, cw2, Nb, sh2.C, sh2.H, sh2.H, sh2.O, sh2.k, sh2.k, sh2.stride, sh2.pad,
+                                 ep=ep2)
+        if ids is None:
+            sh_ = xh
+        else:
+            pd = dict(P[ids], relu=False)
+            cwd, epd = weights(pd)
+            s3 = pd["sh"]
+            _, sh_ = B.ternary_conv2d(ca1, cwd, Nb, Cc, H, W, s3.O, s3.k, s3.k, s3.stride, s3.pad, ep=epd)
+        xh_next = torch.clamp_min(h2 + sh_, 0.0)
+        torch.cuda.synchronize()
+        assert (ca1.cpu().numpy() == orc.nchw_to_nhwc_i8(ta1, ca1.shape[-1])).all(), "block %d conv1 codes" % bi
+        T.assert_codes_match(ca2.cpu().numpy(), orc.nchw_to_nhwc_i8(ta2, ca2.shape[-1]), y1, lo, hi,
+                             "block %d conv2 codes" % bi)
+        assert (ca2.cpu().numpy() == orc.nchw_to_nhwc_i8(ta2, ca2.shape[-1])).all(), "block %d conv2 codes" % bi
+        T.assert_y_close(xh_next.cpu().numpy(), xo_next, "block %d out" % bi)
+        xo, xh = xo_next, xh_next
+    assert xo.shape == (2, 512, 7, 7)
