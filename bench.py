@@ -21,7 +21,7 @@ sys.path.insert(0, ROOT)
 INT8_PEAK_TOPS = 5000.0   # MI355X dense int8 MFMA, TOP/s (2 ops per MAC)
 HBM_PEAK_GBS = 8000.0
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this file's default run (see profiles/)
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 130.7e6
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 129.8e6
 
 
 def main():
