@@ -209,14 +209,24 @@ int rtn_ternary_conv2d_implicit_gemm(rtn_code_format fmt, rtn_path path, const v
  * passes hi = (0.5-b)/k, lo = -(0.5+b)/k; with ReLU and a positive scale the
  * comparison is Eq.10's thresholded ReLU on the integer sum.  Pixel sums of
  * the written codes are not produced: the conv entry points form them from the
- * codes.  ep, workspace and every other argument as for
+ * codes.
+ * Block-tail form (the last conv of a residual block, whose output meets the
+ * shortcut before the next block ternarizes it): with `residual` (fp32
+ * [Nb][O][OH][OW], nullable) and `relu_out`,
+ *   s = z + residual   (one fp32 add on the rounded z, as a separate add kernel
+ *                       would compute it),     s = max(s, 0) if relu_out,
+ * and s takes the place of z in the comparison.  y_out (fp32 [Nb][O][OH][OW],
+ * nullable) receives the value that was ternarized (z, or s), for the next
+ * block's shortcut.  residual and y_out may be the same buffer.
+ * ep, workspace and every other argument as for
  * rtn_ternary_conv2d_implicit_gemm (ep->sum_ta may be NULL); Nb*OH*OW*
  * rtn_padded_k(O) must be below 2^40.                                        */
 int rtn_ternary_conv2d_ternarize(rtn_code_format fmt, rtn_path path, const void *a_codes,
                                  const void *w_codes, int64_t Nb, int64_t C, int64_t H, int64_t W,
                                  int64_t O, int KH, int KW, int stride, int pad,
                                  rtn_pad_mode pad_mode, const rtn_epilogue *ep,
-                                 const float *thr_lo, const float *thr_hi, rtn_gran thr_gran,
+                                 const float *residual, int relu_out, const float *thr_lo,
+                                 const float *thr_hi, rtn_gran thr_gran, float *y_out,
                                  void *codes_out, void *workspace, size_t workspace_bytes,
                                  void *stream);
 

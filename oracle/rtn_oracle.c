@@ -381,6 +381,21 @@ void orc_ternarize_nchw(const float *z, int64_t Nb, int64_t O, int64_t HW,
         }
 }
 
+/* ------------------------------------------------------------------ O8 --
+ * Tail of a residual block: the last conv's activation z meets the shortcut
+ * r before the next block ternarizes the sum.  The adds of the network are
+ * plain fp32 tensor operations, so  s = z + r  is ONE fp32 addition of the two
+ * stored fp32 values (no wider intermediate), followed by max(s, 0) if relu.  */
+void orc_add_relu(const float *z, const float *r, int64_t n, int relu, float *s)
+{
+#pragma omp parallel for
+    for (int64_t i = 0; i < n; ++i) {
+        volatile float v = z[i] + r[i]; /* volatile: force the fp32 rounding of the sum */
+        float w = v;
+        s[i] = (relu && w < 0.0f) ? 0.0f : w;
+    }
+}
+
 /* Conv form of O6: direct conv of the reparameterized values in double.
  * pad_true_zero = 1 pads the value tensor (aa*t+ba) with 0.0;
  * pad_true_zero = 0 pads the code tensor with 0, i.e. the value with ba.     */

@@ -318,3 +318,12 @@ def conv_next_codes(D, Sa, Sw, Kv, alpha_a, beta_a, alpha_w, beta_w, relu, bn_sc
     z = conv_epilogue(D, Sa, Sw, Kv, alpha_a, beta_a, alpha_w, beta_w, relu, bn_scale, bn_shift)
     t = ternarize_nchw(z, lo, hi)
     return nchw_to_nhwc_i8(t, Cpad), z
+
+
+def add_relu(z, r, relu=True):
+    """O8.  One fp32 add of two fp32 tensors of the same shape, then ReLU if asked."""
+    z, r = _c(z, np.float32), _c(r, np.float32)
+    assert z.shape == r.shape
+    out = np.empty(z.shape, dtype=np.float32)
+    lib().orc_add_relu(_p(z), _p(r), _i64(z.size), C.c_int(int(relu)), _p(out))
+    return out

@@ -76,7 +76,7 @@ def lib():
                                                        ci, ci, ci, vp, vp, vp, vp, C.c_size_t, vp]
         L.rtn_ternary_conv2d_ternarize.restype = ci
         L.rtn_ternary_conv2d_ternarize.argtypes = [ci, ci, vp, vp, i64, i64, i64, i64, i64, ci, ci, ci, ci,
-                                                   ci, vp, vp, vp, ci, vp, vp, C.c_size_t, vp]
+                                                   ci, vp, vp, ci, vp, vp, ci, vp, vp, vp, C.c_size_t, vp]
         L.rtn_epilogue_reparam.restype = ci
         L.rtn_epilogue_reparam.argtypes = [vp, i64, i64, i64, vp, vp, vp]
         L.rtn_epilogue_reparam_conv2d.restype = ci
@@ -234,9 +234,11 @@ def ternary_conv2d(a_codes, w_codes, Nb, Cc, H, W, O, KH, KW, stride, pad, pad_m
 
 def ternary_conv2d_ternarize(a_codes, w_codes, Nb, Cc, H, W, O, KH, KW, stride, pad, ep, lo, hi,
                              pad_mode=RTN_PAD_TRUE_ZERO, codes_out=None, workspace=None,
+                             residual=None, relu_out=False, y_out=None,
                              fmt=RTN_CODE_I8, path=RTN_PATH_AUTO):
     """The conv with the ternarizing epilogue.  lo/hi: python floats or cuda float32
-    vectors (one per output channel).  Returns int8 codes [Nb,OH,OW,padded_k(O)]."""
+    vectors (one per output channel).  residual / relu_out / y_out: the block-tail
+    form (fp32 NCHW tensors).  Returns int8 codes [Nb,OH,OW,padded_k(O)]."""
     OH, OW = conv_out_hw(H, W, KH, KW, stride, pad)
     if codes_out is None:
         codes_out = torch.empty((Nb, OH, OW, padded_k(O)), dtype=torch.int8, device=a_codes.device)
@@ -246,7 +248,9 @@ def ternary_conv2d_ternarize(a_codes, w_codes, Nb, Cc, H, W, O, KH, KW, stride, 
     assert glo.gran == ghi.gran
     rc = lib().rtn_ternary_conv2d_ternarize(
         fmt, path, C.c_void_p(a_codes.data_ptr()), C.c_void_p(w_codes.data_ptr()), Nb, Cc, H, W, O, KH, KW,
-        stride, pad, pad_mode, ep.ref(), glo.ptr, ghi.ptr, glo.gran, _dev(codes_out, torch.int8),
+        stride, pad, pad_mode, ep.ref(), None if residual is None else _dev(residual, torch.float32),
+        int(bool(relu_out)), glo.ptr, ghi.ptr, glo.gran,
+        None if y_out is None else _dev(y_out, torch.float32), _dev(codes_out, torch.int8),
         C.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(), _stream())
     _check(rc, "rtn_ternary_conv2d_ternarize")
     return codes_out

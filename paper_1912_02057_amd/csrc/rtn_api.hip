@@ -274,9 +274,9 @@ int rtn_ternary_conv2d_implicit_gemm(rtn_code_format fmt, rtn_path path, const v
 int rtn_ternary_conv2d_ternarize(rtn_code_format fmt, rtn_path path, const void* a_codes,
                                  const void* w_codes, int64_t Nb, int64_t C, int64_t H, int64_t W, int64_t O,
                                  int KH, int KW, int stride, int pad, rtn_pad_mode pad_mode,
-                                 const rtn_epilogue* ep, const float* thr_lo, const float* thr_hi,
-                                 rtn_gran thr_gran, void* codes_out, void* workspace, size_t workspace_bytes,
-                                 void* stream)
+                                 const rtn_epilogue* ep, const float* residual, int relu_out,
+                                 const float* thr_lo, const float* thr_hi, rtn_gran thr_gran, float* y_out,
+                                 void* codes_out, void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!a_codes || !w_codes || !codes_out || !ep || !thr_lo || !thr_hi) return RTN_ERR_NULL;
     if (fmt != RTN_CODE_I8) return RTN_ERR_UNSUPPORTED;
@@ -285,6 +285,7 @@ int rtn_ternary_conv2d_ternarize(rtn_code_format fmt, rtn_path path, const void*
     int rc = make_geom(Nb, C, H, W, O, KH, KW, stride, pad, pad_mode, c.g);
     if (rc != RTN_OK) return rc;
     if (!aligned(a_codes, 16) || !aligned(w_codes, 16) || !aligned(codes_out, 16)) return RTN_ERR_ALIGN;
+    if (!aligned(residual, 4) || !aligned(y_out, 4)) return RTN_ERR_ALIGN;
     if ((rc = make_epilogue(ep, true, c.ep, false)) != RTN_OK) return rc;
     if ((rc = make_param(thr_lo, thr_gran, false, c.thr_lo)) != RTN_OK) return rc;
     if ((rc = make_param(thr_hi, thr_gran, false, c.thr_hi)) != RTN_OK) return rc;
@@ -298,6 +299,9 @@ int rtn_ternary_conv2d_ternarize(rtn_code_format fmt, rtn_path path, const void*
     c.cst_cls = (const double*)workspace;
     c.codes = (int8_t*)codes_out;
     c.ldc = (int)ldc;
+    c.res = residual;
+    c.relu_out = relu_out != 0;
+    c.y = y_out;
     const hipError_t he = rtn::launch_conv_mfma(c, (hipStream_t)stream);
     return he == hipSuccess ? RTN_OK : hip_fail(he);
 }

@@ -90,6 +90,8 @@ struct ConvArgs {
     int8_t* codes;
     int ldc;
     Param thr_lo, thr_hi;
+    const float* res;  // nullable: fp32 NCHW added to the activation before it is ternarized
+    int relu_out;      // ReLU after that add; with codes, `y` (nullable) receives the ternarized fp32 value
 };
 
 hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t st);

@@ -62,6 +62,10 @@ struct TmmParams {
     int8_t* codes;
     int ldc;
     Param thr_lo, thr_hi;  // vector: per output channel
+    // ... optionally after a residual add (res, fp32 NCHW, nullable) and a second
+    // ReLU; the fp32 value that is ternarized is also stored when y is given
+    const float* res;
+    int relu_out;
 };
 
 // Border classes of a conv window and the LDS bytes of the epilogue table of a
@@ -144,10 +148,11 @@ __device__ __forceinline__ void wait_groups(int groups)
 // crosses L2 -> LDS about 1.4 times instead of KH KW times, and only the
 // weight tile still streams through the ring.
 //
-// TERN selects the conv whose epilogue ternarizes its own output (codes for the
-// next layer instead of acc / y); it is a kernel of its own so that its epilogue
-// does not enter the register budget of the others.
-template <int BP, int BQ, int WGP, int WGQ, int NS, int MINW, bool CONV, bool TERN = false, int HC = 0>
+// TERN != 0 selects the conv whose epilogue ternarizes its own output (codes for
+// the next layer instead of acc / y); 2 is the block-tail form of it (residual
+// add, second ReLU, fp32 copy of the result).  Each is a kernel of its own so
+// that its epilogue does not enter the register budget of the others.
+template <int BP, int BQ, int WGP, int WGQ, int NS, int MINW, bool CONV, int TERN = 0, int HC = 0>
 __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
 {
     static_assert(!TERN || CONV, "the ternarizing epilogue belongs to the conv");
@@ -641,8 +646,11 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
             // registers 4 r4 .. 4 r4 + 3 are 4 consecutive channels of one pixel: one
             // dword of the channel-innermost code tensor.  Channels O .. ldc-1 get code 0.
             const float2* thr = (const float2*)(smem + toff + tab_kib * 1024);
-            auto run_codes = [&](auto full) {
-                constexpr bool FULL = decltype(full)::value;
+            // STREAM: the block-tail form -- z + residual (fp32 add, as a separate add
+            // kernel would do it), a second ReLU, and the fp32 result stored as well.
+            const float relu_out_floor = __builtin_canonicalizef(prm.relu_out ? 0.0f : -__builtin_inff());
+            auto run_codes = [&](auto full, auto stream) {
+                constexpr bool FULL = decltype(full)::value, STREAM = decltype(stream)::value;
 #pragma unroll
                 for (int j = 0; j < TQ; ++j) {
                     const int m = q0 + wq * WQ + j * 32 + (lane & 31);
@@ -650,8 +658,25 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
                     int8_t* cp = prm.codes + (int64_t)(mok ? m : 0) * prm.ldc;
                     const double Sa = (double)sa_full[j];
                     const double* ctab = tab + (4 + pixcls[j]) * BP;
+                    int64_t obase = 0;
+                    if (STREAM) {
+                        const int mm = mok ? m : 0;
+                        const int nb = (int)fastdiv((uint32_t)mm, g.div_ohw), pix = mm - nb * ohw;
+                        obase = (int64_t)nb * g.O * ohw + pix;
+                    }
 #pragma unroll
-                    for (int i = 0; i < TP; ++i)
+                    for (int i = 0; i < TP; ++i) {
+                        // residual values of this lane's 16 channels, fetched ahead of their use
+                        float rv[16];
+                        if (STREAM) {
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) {
+                                const int o = p0 + wp * WP + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                                rv[r] = 0.0f;
+                                if (prm.res && (FULL || (mok && o < prm.RP)))
+                                    rv[r] = __builtin_nontemporal_load(prm.res + obase + (int64_t)o * ohw);
+                            }
+                        }
 #pragma unroll
                         for (int r4 = 0; r4 < 4; ++r4) {
                             const int t0 = wp * WP + i * 32 + 8 * r4 + 4 * (lane >> 5);
@@ -666,7 +691,12 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
                                 const int D = acc[i][j][4 * r4 + b];
                                 double v = g1 * (double)D + (c2 * Sa + ctab[t]);
                                 v = __builtin_fmax(v, relu_floor);
-                                const float z = (float)(bs * v + bh);
+                                float z = (float)(bs * v + bh);
+                                if (STREAM) {
+                                    z = __builtin_fmaxf(z + rv[4 * r4 + b], relu_out_floor);
+                                    if (prm.y && (FULL || (mok && ook)))
+                                        __builtin_nontemporal_store(z, prm.y + obase + (int64_t)(o0 + b) * ohw);
+                                }
                                 int code = (int)(z > th.y) - (int)(z < th.x);
                                 if (!FULL && !ook) code = 0;
                                 word |= (unsigned)(code & 0xff) << (8 * b);
@@ -674,12 +704,13 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
                             if (FULL || (mok && o0 < prm.ldc)) *(unsigned*)(cp + o0) = word;
                             __builtin_amdgcn_sched_barrier(0);
                         }
+                    }
                 }
             };
             if (full_tile)
-                run_codes(std::true_type{});
+                run_codes(std::true_type{}, std::integral_constant<bool, TERN == 2>{});
             else
-                run_codes(std::false_type{});
+                run_codes(std::false_type{}, std::integral_constant<bool, TERN == 2>{});
             return;
         }
         dispatch([&](auto full, auto want_acc, auto want_y) {
@@ -801,7 +832,7 @@ inline bool halo_eligible(const TmmParams& prm, int hc)
            g.OW == g.W;
 }
 
-template <int BP, int BQ, int WGP, int WGQ, int NS, int MINW, bool CONV, bool TERN = false, int HC = 0>
+template <int BP, int BQ, int WGP, int WGQ, int NS, int MINW, bool CONV, int TERN = 0, int HC = 0>
 hipError_t launch_cfg(TmmParams& prm, hipStream_t st)
 {
     constexpr int ring_bytes = NS * (BP + (HC ? 0 : BQ)) * 64;
@@ -853,12 +884,12 @@ const int kTileBP[kNumTileConfigs] = {64, 128, 256, 64,  128, 256, 64, 64, 128, 
                                        64, 64,  128, 128, 64,  64,  64, 64, 128, 128};
 int g_forced_tile = -1;
 
-template <bool CONV, bool TERN = false>
+template <bool CONV, int TERN = 0>
 hipError_t launch_index_raw(int cfg, TmmParams& prm, hipStream_t st);
 
 // A configuration whose LDS need (ring + the conv's table, which grows with the
 // pad) exceeds the CU's falls back to the smallest tile.
-template <bool CONV, bool TERN = false>
+template <bool CONV, int TERN = 0>
 hipError_t launch_index(int cfg, TmmParams& prm, hipStream_t st)
 {
     hipError_t e = launch_index_raw<CONV, TERN>(cfg, prm, st);
@@ -866,26 +897,29 @@ hipError_t launch_index(int cfg, TmmParams& prm, hipStream_t st)
     return e;
 }
 
-template <bool CONV, bool TERN>
+template <bool CONV, int TERN>
 hipError_t launch_index_raw(int cfg, TmmParams& prm, hipStream_t st)
 {
     // conv with a large pad: the per-class constant table of a tall tile does
     // not fit in LDS; fall back to the tile of the same width class with BP = 64.
     if (CONV && table_bytes(kTileBP[cfg], true, prm.g.pad) > 48 * 1024) cfg = 0;
+    // waves per SIMD the 64-accumulator tiles are compiled for: the ternarizing epilogue
+    // needs a few registers more than the plain one, its block-tail form about 50 more
+    constexpr int W3 = TERN == 2 ? 2 : 3, W4 = TERN == 2 ? 2 : (TERN == 1 ? 3 : 4);
     switch (cfg) {
         case 0: return launch_cfg<64, 64, 2, 2, 4, 4, CONV, TERN>(prm, st);
         case 1: return launch_cfg<128, 128, 2, 2, (CONV ? 3 : 4), 2, CONV, TERN>(prm, st);
         case 2: return launch_cfg<256, 256, 2, 2, (CONV ? 3 : 4), 1, CONV, TERN>(prm, st);
-        case 3: return launch_cfg<64, 256, 1, 4, 3, 3, CONV, TERN>(prm, st);
+        case 3: return launch_cfg<64, 256, 1, 4, 3, W3, CONV, TERN>(prm, st);
         case 4: return launch_cfg<128, 256, 2, 2, 3, 2, CONV, TERN>(prm, st);
         case 5: return launch_cfg<256, 128, 2, 2, 3, 2, CONV, TERN>(prm, st);
         case 6: return launch_cfg<64, 128, 1, 4, 3, 4, CONV, TERN>(prm, st);
-        case 7: return launch_cfg<64, 256, 1, 4, 2, 3, CONV, TERN>(prm, st);
-        case 8: return launch_cfg<128, 128, 2, 2, 3, 3, CONV, TERN>(prm, st);
-        case 9: return launch_cfg<64, 256, 1, 4, 2, (TERN ? 3 : 4), CONV, TERN>(prm, st);
+        case 7: return launch_cfg<64, 256, 1, 4, 2, W3, CONV, TERN>(prm, st);
+        case 8: return launch_cfg<128, 128, 2, 2, 3, W3, CONV, TERN>(prm, st);
+        case 9: return launch_cfg<64, 256, 1, 4, 2, W4, CONV, TERN>(prm, st);
         case 10: return launch_cfg<64, 128, 1, 4, 4, 4, CONV, TERN>(prm, st);
         case 11: return launch_cfg<64, 64, 2, 2, 4, 6, CONV, TERN>(prm, st);
-        case 12: return launch_cfg<128, 128, 2, 2, 2, (TERN ? 3 : 4), CONV, TERN>(prm, st);
+        case 12: return launch_cfg<128, 128, 2, 2, 2, W4, CONV, TERN>(prm, st);
         case 13: return launch_cfg<128, 256, 2, 2, 2, 2, CONV, TERN>(prm, st);
         default: break;
     }
@@ -897,7 +931,7 @@ hipError_t launch_index_raw(int cfg, TmmParams& prm, hipStream_t st)
         if (ok && hc == 64) {
             switch (cfg) {
                 case 14: return launch_cfg<64, 256, 1, 4, 9, 2, CONV, TERN, 64>(prm, st);
-                case 15: return launch_cfg<64, 256, 1, 4, 3, 3, CONV, TERN, 64>(prm, st);
+                case 15: return launch_cfg<64, 256, 1, 4, 3, W3, CONV, TERN, 64>(prm, st);
                 case 16: return launch_cfg<64, 128, 1, 4, 9, 3, CONV, TERN, 64>(prm, st);
                 case 17: return launch_cfg<64, 128, 1, 4, 3, 4, CONV, TERN, 64>(prm, st);
                 default: break;
@@ -905,16 +939,16 @@ hipError_t launch_index_raw(int cfg, TmmParams& prm, hipStream_t st)
         }
         if (ok && hc == 128) {
             switch (cfg) {
-                case 18: return launch_cfg<128, 128, 2, 2, 3, 3, CONV, TERN, 128>(prm, st);
+                case 18: return launch_cfg<128, 128, 2, 2, 3, W3, CONV, TERN, 128>(prm, st);
                 case 19: return launch_cfg<128, 256, 2, 2, 3, 2, CONV, TERN, 128>(prm, st);
                 default: break;
             }
         }
     }
     switch (cfg) {
-        case 14: case 15: return launch_cfg<64, 256, 1, 4, 2, 3, CONV, TERN>(prm, st);
+        case 14: case 15: return launch_cfg<64, 256, 1, 4, 2, W3, CONV, TERN>(prm, st);
         case 16: case 17: return launch_cfg<64, 128, 1, 4, 3, 4, CONV, TERN>(prm, st);
-        case 18: return launch_cfg<128, 128, 2, 2, 2, (TERN ? 3 : 4), CONV, TERN>(prm, st);
+        case 18: return launch_cfg<128, 128, 2, 2, 2, W4, CONV, TERN>(prm, st);
         case 19: return launch_cfg<128, 256, 2, 2, 2, 2, CONV, TERN>(prm, st);
         default: return hipErrorInvalidValue;
     }
@@ -995,11 +1029,15 @@ hipError_t launch_conv_mfma(const ConvArgs& a, hipStream_t st)
     prm.ldc = a.ldc;
     prm.thr_lo = a.thr_lo;
     prm.thr_hi = a.thr_hi;
+    prm.res = a.res;
+    prm.relu_out = a.relu_out;
     int cfg = g_forced_tile >= 0 ? g_forced_tile : pick_tile(g.O, prm.RQ, true);
     // a 64-filter layer with a centred stride-1 window: the variant that keeps the
     // tile's input pixel run in LDS (measured faster there; on par or slower elsewhere)
     if (g_forced_tile < 0 && cfg == 7 && halo_eligible(prm, 64)) cfg = 15;
-    return a.codes ? launch_index<true, true>(cfg, prm, st) : launch_index<true>(cfg, prm, st);
+    if (!a.codes) return launch_index<true>(cfg, prm, st);
+    const bool tail = a.res != nullptr || a.y != nullptr || a.relu_out;
+    return tail ? launch_index<true, 2>(cfg, prm, st) : launch_index<true, 1>(cfg, prm, st);
 }
 
 }  // namespace rtn

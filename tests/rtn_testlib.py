@@ -119,8 +119,10 @@ def oracle_next_codes(ref, lo, hi):
     return orc.nchw_to_nhwc_i8(orc.ternarize_nchw(ref["y"], lo, hi), (O + 63) // 64 * 64)
 
 
-def hip_conv_ternarize(case, lo, hi, pad_true_zero=True, relu=False):
-    """pack -> conv with the ternarizing epilogue; returns the int8 code tensor (device)."""
+def hip_conv_ternarize(case, lo, hi, pad_true_zero=True, relu=False, residual=None, relu_out=False,
+                       want_y=False):
+    """pack -> conv with the ternarizing epilogue; returns the int8 code tensor (device),
+    or (codes, y) with want_y (the block-tail form's fp32 output)."""
     sh = case["shape"]
     da, dw = case["delta_a"], case["delta_w"]
     x, w = dev(case["x"]), dev(case["w"])
@@ -135,10 +137,13 @@ def hip_conv_ternarize(case, lo, hi, pad_true_zero=True, relu=False):
     # poison the output so that unwritten bytes (padding channels included) show
     OH, OW = B.conv_out_hw(H, W, sh.k, sh.k, sh.stride, sh.pad)
     out = torch.full((Nb, OH, OW, B.padded_k(sh.O)), 77, dtype=torch.int8, device=DEV)
+    y = torch.full((Nb, sh.O, OH, OW), float("nan"), dtype=torch.float32, device=DEV) if want_y else None
     codes = B.ternary_conv2d_ternarize(ca, cw, Nb, Cc, H, W, sh.O, sh.k, sh.k, sh.stride, sh.pad, ep,
-                                       thr_arg(lo), thr_arg(hi), pad_mode=pm, codes_out=out)
+                                       thr_arg(lo), thr_arg(hi), pad_mode=pm, codes_out=out,
+                                       residual=None if residual is None else dev(residual),
+                                       relu_out=relu_out, y_out=y)
     torch.cuda.synchronize()
-    return codes
+    return (codes, y) if want_y else codes
 
 
 def assert_codes_match(codes, want, z, lo, hi, what=""):

@@ -173,7 +173,7 @@ def test_conv_ternarize_rejects(L):
     e = _ep()
     lo, hi = _f(-0.5), _f(0.5)
     ok = [B.RTN_CODE_I8, B.RTN_PATH_AUTO, FAKE, FAKE, 1, 64, 8, 8, 64, 3, 3, 1, 1, B.RTN_PAD_TRUE_ZERO,
-          C.byref(e), lo, hi, B.RTN_SCALAR, FAKE, FAKE, 1 << 20, None]
+          C.byref(e), None, 0, lo, hi, B.RTN_SCALAR, None, FAKE, FAKE, 1 << 20, None]
 
     def with_(**kw):
         a = list(ok)
@@ -182,17 +182,19 @@ def test_conv_ternarize_rejects(L):
         return call(*a)
     assert with_(_2=None) == B.RTN_ERR_NULL
     assert with_(_14=None) == B.RTN_ERR_NULL                    # the epilogue is not optional here
-    assert with_(_15=None) == B.RTN_ERR_NULL                    # thresholds
-    assert with_(_18=None) == B.RTN_ERR_NULL                    # codes_out
-    assert with_(_18=ODD) == B.RTN_ERR_ALIGN
+    assert with_(_17=None) == B.RTN_ERR_NULL                    # thresholds
+    assert with_(_21=None) == B.RTN_ERR_NULL                    # codes_out
+    assert with_(_21=ODD) == B.RTN_ERR_ALIGN
+    assert with_(_15=ODD) == B.RTN_ERR_ALIGN                    # residual
+    assert with_(_20=ODD) == B.RTN_ERR_ALIGN                    # y_out
     assert with_(_0=B.RTN_CODE_BITPLANE) == B.RTN_ERR_UNSUPPORTED
     assert with_(_1=B.RTN_PATH_POPC) == B.RTN_ERR_UNSUPPORTED
     assert with_(_12=3) == B.RTN_ERR_UNSUPPORTED                # pad >= kernel
-    assert with_(_17=7) == B.RTN_ERR_UNSUPPORTED                # threshold granularity
-    assert with_(_15=_f(0.5), _16=_f(-0.5)) == B.RTN_ERR_SHAPE  # lo > hi
+    assert with_(_19=7) == B.RTN_ERR_UNSUPPORTED                # threshold granularity
+    assert with_(_17=_f(0.5), _18=_f(-0.5)) == B.RTN_ERR_SHAPE  # lo > hi
     assert with_(_4=0) == B.RTN_ERR_SHAPE
-    assert with_(_19=None) == B.RTN_ERR_WORKSPACE
-    assert with_(_20=16) == B.RTN_ERR_WORKSPACE
-    assert with_(_19=ODD) == B.RTN_ERR_ALIGN
+    assert with_(_22=None) == B.RTN_ERR_WORKSPACE
+    assert with_(_23=16) == B.RTN_ERR_WORKSPACE
+    assert with_(_22=ODD) == B.RTN_ERR_ALIGN
     e2 = _ep(sums=False)
     assert with_(_14=C.byref(e2)) == B.RTN_ERR_NULL             # weight tap sums are required

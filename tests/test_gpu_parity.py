@@ -389,6 +389,79 @@ def test_conv_ternarize_equals_pack_of_conv_output():
     assert int(diff.sum()) < 20
 
 
+def _block_tail_check(case, shape, true_zero, lo, hi, use_res, relu_out, want_y, what):
+    """conv -> (BN) -> + residual -> ReLU -> ternarize, fused, against the oracle's steps."""
+    ref = T.oracle_conv(case, true_zero, relu=False)
+    rng = np.random.default_rng(len(what))
+    res = rng.standard_normal(ref["y"].shape).astype(np.float32) if use_res else None
+    s = ref["y"]
+    if use_res:
+        s = orc.add_relu(s, res, relu_out)
+    elif relu_out:
+        s = orc.add_relu(s, np.zeros_like(s), True)
+    want = orc.nchw_to_nhwc_i8(orc.ternarize_nchw(s, lo, hi), (shape.O + 63) // 64 * 64)
+    got = T.hip_conv_ternarize(case, lo, hi, true_zero, relu=False, residual=res, relu_out=relu_out,
+                               want_y=want_y)
+    codes, y = got if want_y else (got, None)
+    T.assert_codes_match(codes.cpu().numpy(), want, s, lo, hi, what)
+    if want_y:
+        # the stored fp32 value: the oracle's z within the fp32 tolerance, then the same fp32 add
+        yh = y.cpu().numpy()
+        assert not np.isnan(yh).any(), what + ": unwritten outputs"
+        floor = 1e-9 * max(1.0, float(np.abs(ref["y"]).max()))
+        tol = 1e-5 * np.abs(ref["y"]) + floor + 1e-6 * (np.abs(res) if use_res else 0.0)
+        assert (np.abs(yh.astype(np.float64) - s) <= tol).all(), what
+
+
+@pytest.mark.parametrize("shape", CONV_SHAPES, ids=lambda s: s.name)
+@pytest.mark.parametrize("mode", ["res_relu_y", "res_only", "y_only", "relu_only"])
+def test_conv_block_tail_vs_oracle(shape, mode):
+    _say("conv block tail %s %s" % (shape, mode))
+    case = wl.conv_case(shape, batch=3, seed=70 + len(shape.name), per_channel=True, bn=True)
+    lo, hi = _thresholds("vector" if mode == "res_only" else "scalar", case, shape.O, 9)
+    _block_tail_check(case, shape, mode != "y_only", lo, hi,
+                      use_res=mode in ("res_relu_y", "res_only"),
+                      relu_out=mode in ("res_relu_y", "relu_only"),
+                      want_y=mode in ("res_relu_y", "y_only"), what="%s %s" % (shape.name, mode))
+
+
+@pytest.mark.parametrize("cfg", range(20))
+def test_all_tile_configs_conv_block_tail(cfg, tile_reset):
+    _say("tile config %d, block-tail epilogue" % cfg)
+    B.set_tile_config(cfg)
+    for shape, batch in [(wl.ConvShape("t", 64, 13, 200, 3, 2, 1), 7),       # ragged in O and pixels
+                         (wl.ConvShape("u", 64, 16, 256, 3, 1, 1), 3),       # full tiles only
+                         (wl.ConvShape("v", 128, 12, 136, 3, 1, 1), 3)]:     # Cpad 128 (halo-eligible)
+        case = wl.conv_case(shape, batch=batch, seed=190 + cfg, bn=True)
+        lo, hi = _thresholds("scalar", case, shape.O, cfg)
+        _block_tail_check(case, shape, True, lo, hi, True, True, True, "cfg %d %s" % (cfg, shape.name))
+
+
+CONV2_OF_BLOCK = [1, 3, 5, 8, 10, 13, 15, 18]
+
+
+@pytest.mark.parametrize("idx", CONV2_OF_BLOCK)
+def test_resnet18_conv2_layers_batch256_block_tail_sampled_images(idx):
+    """The last conv of each ResNet-18 block at batch 256 with the block-tail epilogue
+    (residual add, ReLU, fp32 output and the next block's codes), in the launch
+    configuration of the benchmark's trunk forward; the oracle recomputes two images."""
+    shape = wl.resnet18_ternary_layers()[idx]
+    _say("resnet18 b256 block tail %s" % (shape,))
+    case = wl.conv_case(shape, batch=256, seed=600 + idx, per_channel=True, bn=True)
+    lo, hi = np.float32(-0.5), np.float32(0.5)
+    rng = np.random.default_rng(idx)
+    res = rng.standard_normal((256, shape.O, shape.OH, shape.OH)).astype(np.float32)
+    codes, y = T.hip_conv_ternarize(case, lo, hi, True, relu=False, residual=res, relu_out=True, want_y=True)
+    imgs = [0, 255]
+    ref = T.oracle_conv(case, True, relu=False, images=imgs)
+    s = orc.add_relu(ref["y"], res[imgs], True)
+    want = orc.nchw_to_nhwc_i8(orc.ternarize_nchw(s, lo, hi), (shape.O + 63) // 64 * 64)
+    T.assert_codes_match(codes[imgs].cpu().numpy(), want, s, lo, hi, shape.name)
+    T.assert_y_close(y[imgs].cpu().numpy(), s, shape.name + " block output")
+    assert not bool(torch.isnan(y).any())
+    assert float(y.min()) >= 0.0 and int(codes.abs().max()) == 1
+
+
 CONV1_OF_BLOCK = [0, 2, 4, 7, 9, 12, 14, 17]
 
 

@@ -413,3 +413,20 @@ def test_conv_next_codes_layout_is_pack_of_nchw():
     # the same z through the row ternarizer (channels moved to the row axis)
     t_rows = orc.ternarize(np.ascontiguousarray(z.transpose(1, 0, 2, 3)), lo, hi).transpose(1, 0, 2, 3)
     assert (codes[..., :O] == t_rows.transpose(0, 2, 3, 1)).all()
+
+
+# ------------------------------------------------------------------ O8 ----
+def test_add_relu_is_one_fp32_add_then_max():
+    z = np.array([1.0, -2.0, 0.1, 16777216.0, -0.0, 3.0], np.float32)
+    r = np.array([0.5, 1.0, 0.2, 1.0, 0.0, -3.0], np.float32)
+    s = orc.add_relu(z, r, relu=True)
+    # 16777216 + 1 is not representable in fp32: the sum must show fp32 rounding
+    assert s.tolist() == [1.5, 0.0, float(np.float32(0.1) + np.float32(0.2)), 16777216.0, 0.0, 0.0]
+    s2 = orc.add_relu(z, r, relu=False)
+    assert s2.tolist()[1] == -1.0
+    rng = np.random.default_rng(31)
+    a = rng.standard_normal(10000).astype(np.float32) * 100
+    b = rng.standard_normal(10000).astype(np.float32)
+    assert (orc.add_relu(a, b, True) == np.maximum(a + b, np.float32(0))).all()      # numpy's fp32 add
+    wide = (a.astype(np.float64) + b.astype(np.float64))
+    assert (orc.add_relu(a, b, False) == wide.astype(np.float32)).all()               # = correctly rounded sum
