@@ -80,7 +80,14 @@ def main():
                             garg(case["beta_w"]), pa, pw, relu=True,
                             bn_scale=to_dev(case["bn_scale"]), bn_shift=to_dev(case["bn_shift"]))
             B.conv2d_prepare_constants(sh.C, sh.O, sh.k, sh.k, sh.pad, ep, ws)   # S0, offline
+            # block tails: conv -> BN -> (+ shortcut) -> ReLU, i.e. no ReLU before the BN affine
+            ep_tail = B.Epilogue(garg(case["alpha_a"]), garg(case["beta_a"]), garg(case["alpha_w"]),
+                                 garg(case["beta_w"]), pa, pw, relu=False,
+                                 bn_scale=to_dev(case["bn_scale"]), bn_shift=to_dev(case["bn_shift"]))
+            ws_tail = torch.empty_like(ws)
+            B.conv2d_prepare_constants(sh.C, sh.O, sh.k, sh.k, sh.pad, ep_tail, ws_tail)
             layers.append(dict(sh=sh, x=x, cw=cw, pw=pw, ca=ca, pa=pa, y=y, ws=ws, ep=ep,
+                               ep_tail=ep_tail, ws_tail=ws_tail,
                                da=float(case["delta_a"]), case=case if i < 0 else None))
             del case
         L = B.lib()
@@ -120,6 +127,35 @@ def main():
                 conv(l2)
                 if ids is not None:
                     conv(layers[ids], ca=l1["ca"])
+
+        # The trunk as one chained forward: the input is packed once; conv1 of a block emits
+        # conv2's codes; conv2's block-tail epilogue adds the shortcut (the block input, or
+        # the downsample conv's output), applies the ReLU and writes both the fp32 block
+        # output (the next shortcut) and the next block's codes.  1 pack + 19 convs.
+        last_codes = torch.empty((args.batch, 7, 7, 512), dtype=torch.int8, device=dev)
+
+        def trunk_forward():
+            pack(layers[0])
+            cur_x, cur_codes = layers[0]["x"], layers[0]["ca"]
+            for bi, (i1, i2, ids) in enumerate(blocks):
+                l1, l2 = layers[i1], layers[i2]
+                sh, sh2 = l1["sh"], l2["sh"]
+                B.ternary_conv2d_ternarize(cur_codes, l1["cw"], args.batch, sh.C, sh.H, sh.H, sh.O, sh.k, sh.k,
+                                           sh.stride, sh.pad, l1["ep"], -l2["da"], l2["da"],
+                                           codes_out=l2["ca"], workspace=l1["ws"])
+                if ids is not None:
+                    conv(layers[ids], ca=cur_codes)
+                    res = layers[ids]["y"]
+                else:
+                    res = cur_x
+                nxt = layers[blocks[bi + 1][0]] if bi + 1 < len(blocks) else None
+                nxt_codes = nxt["ca"] if nxt is not None else last_codes
+                nda = nxt["da"] if nxt is not None else 0.5
+                B.ternary_conv2d_ternarize(l2["ca"], l2["cw"], args.batch, sh2.C, sh2.H, sh2.H, sh2.O, sh2.k,
+                                           sh2.k, sh2.stride, sh2.pad, l2["ep_tail"], -nda, nda,
+                                           codes_out=nxt_codes, workspace=l2["ws_tail"], residual=res,
+                                           relu_out=True, y_out=l2["y"])
+                cur_x, cur_codes = l2["y"], nxt_codes
 
         stream = C.c_void_p(torch.cuda.current_stream().cuda_stream)
 
@@ -196,11 +232,25 @@ def main():
             step_blocks()
         torch.cuda.synchronize()
         ms_blocks = (time.perf_counter() - tb0) * 1e3 / args.steps
+        for _ in range(args.warmup):
+            trunk_forward()
+        torch.cuda.synchronize()
+        tb0 = time.perf_counter()
+        for _ in range(args.steps):
+            trunk_forward()
+        torch.cuda.synchronize()
+        ms_trunk = (time.perf_counter() - tb0) * 1e3 / args.steps
         blocks_info = {
             "what": "the same 19 convs as 8 residual blocks: conv1 of a block emits the next conv's codes "
                     "(rtn_ternary_conv2d_ternarize), one pack per block input; 8 packs + 19 convs per step",
             "ms_per_step": round(ms_blocks, 4),
-            "tmacs": round(macs_step / (ms_blocks * 1e-3) / 1e12, 3)}
+            "tmacs": round(macs_step / (ms_blocks * 1e-3) / 1e12, 3),
+            "trunk_forward": {
+                "what": "the 8 blocks chained as one forward pass: 1 pack, conv1 emits codes, conv2's block-tail "
+                        "epilogue adds the shortcut, applies ReLU and writes the fp32 block output and the next "
+                        "block's codes; 1 pack + 19 convs per step, residual adds included",
+                "ms_per_step": round(ms_trunk, 4),
+                "tmacs": round(macs_step / (ms_trunk * 1e-3) / 1e12, 3)}}
 
     # ---- per-kernel durations with HIP events on the launch stream ---------
     reps = max(3, min(args.steps, 10))

@@ -463,6 +463,31 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
     }
     for (int s = 0; s < npro; ++s) issue(s);
 
+    // Block-tail form: the residual values this lane will add, fetched now so that their
+    // HBM latency passes behind the K loop (tiles whose accumulators leave the registers
+    // for it; the larger tiles fetch them in the epilogue, 16 at a time).
+    constexpr bool RES_EARLY = TERN == 2 && TP * TQ <= 4;
+    float rv_all[RES_EARLY ? TQ : 1][RES_EARLY ? TP : 1][16];
+    if constexpr (RES_EARLY) {
+        const int ohw = g.OH * g.OW;
+#pragma unroll
+        for (int j = 0; j < TQ; ++j) {
+            const int m = q0 + wq * WQ + j * 32 + (lane & 31);
+            const bool mok = m < prm.RQ;
+            const int mm = mok ? m : 0;
+            const int nb = (int)fastdiv((uint32_t)mm, g.div_ohw), pix = mm - nb * ohw;
+            const float* rp = prm.res + ((int64_t)nb * g.O * ohw + pix);
+#pragma unroll
+            for (int i = 0; i < TP; ++i)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const int o = p0 + wp * WP + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                    rv_all[j][i][r] = 0.0f;
+                    if (prm.res && mok && o < prm.RP) rv_all[j][i][r] = __builtin_nontemporal_load(rp + (int64_t)o * ohw);
+                }
+        }
+    }
+
     // conv: the border class of each of this lane's TQ output pixels,
     //   class = rid * (pad+1)^2 + cid,  rid = khl + (pad+1)*(KH-1-khh), cid likewise;
     //   class 0 is the interior (all taps in bounds).
@@ -668,7 +693,10 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
                     for (int i = 0; i < TP; ++i) {
                         // residual values of this lane's 16 channels, fetched ahead of their use
                         float rv[16];
-                        if (STREAM) {
+                        if constexpr (RES_EARLY) {
+#pragma unroll
+                            for (int r = 0; r < 16; ++r) rv[r] = rv_all[j][i][r];
+                        } else if (STREAM) {
 #pragma unroll
                             for (int r = 0; r < 16; ++r) {
                                 const int o = p0 + wp * WP + i * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
@@ -1037,6 +1065,9 @@ hipError_t launch_conv_mfma(const ConvArgs& a, hipStream_t st)
     if (g_forced_tile < 0 && cfg == 7 && halo_eligible(prm, 64)) cfg = 15;
     if (!a.codes) return launch_index<true>(cfg, prm, st);
     const bool tail = a.res != nullptr || a.y != nullptr || a.relu_out;
+    // the block-tail epilogue prefetches its residual values only for the tiles with
+    // 64 accumulators per lane: prefer 128x128 over 128x256 there
+    if (tail && g_forced_tile < 0 && cfg == 13) cfg = 12;
     return tail ? launch_index<true, 2>(cfg, prm, st) : launch_index<true, 1>(cfg, prm, st);
 }
 

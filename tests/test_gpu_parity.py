@@ -728,3 +728,73 @@ def test_config4_chained_blocks_ternarizing_epilogue():
         T.assert_y_close(xh_next.cpu().numpy(), xo_next, "block %d out" % bi)
         xo, xh = xo_next, xh_next
     assert xo.shape == (2, 512, 7, 7)
+
+
+def test_config4_trunk_forward_fully_fused():
+    """The chained stack with every hand-over fused: one pack of the trunk input, then
+    per block conv1 with the ternarizing epilogue and conv2 with the block-tail epilogue
+    (shortcut add, ReLU, fp32 output for the next shortcut, codes for the next block);
+    the downsample conv reads the same codes as conv1.  20 launches for 19 convs.
+    The oracle runs the step-by-step definition."""
+    _say("config 4: trunk forward, fully fused, batch 2")
+    P = _chain_params(2, 700)
+    rng = np.random.default_rng(78)
+    x0 = rng.standard_normal((2, 64, 56, 56)).astype(np.float32)
+    lo, hi = -DELTA_CHAIN, DELTA_CHAIN
+
+    def weights(p, relu):
+        cw, pw = B.ternarize_pack(T.dev(p["w"]), T.thr_arg(-np.asarray(p["dw"])), T.thr_arg(p["dw"]))
+        ep = B.Epilogue(T.gran_arg(p["aa"]), T.gran_arg(p["ba"]), T.gran_arg(p["aw"]), T.gran_arg(p["bw"]),
+                        None, pw, relu=relu, bn_scale=T.dev(p["bs"]), bn_shift=T.dev(p["bh"]))
+        return cw, ep
+
+    def oracle_layer(ta, p, relu):
+        sh = p["sh"]
+        tw = orc.ternarize(p["w"], -np.asarray(p["dw"]), p["dw"])
+        D = orc.conv_acc(ta, tw, sh.stride, sh.pad)
+        Sa, Sw, Kv = orc.conv_sums(ta, tw, sh.stride, sh.pad, True)
+        return orc.conv_epilogue(D, Sa, Sw, Kv, p["aa"], p["ba"], p["aw"], p["bw"], relu=relu,
+                                 bn_scale=p["bs"], bn_shift=p["bh"])
+
+    xo = x0
+    ta_o = orc.ternarize(xo, lo, hi)
+    xh = T.dev(x0)
+    ca, _ = B.ternarize_pack(xh, float(lo), float(hi), want_sum=False)
+    torch.cuda.synchronize()
+    assert (ca.cpu().numpy() == orc.nchw_to_nhwc_i8(ta_o, ca.shape[-1])).all()
+    for bi, (i1, i2, ids) in enumerate(_chain_topology()):
+        p1, p2 = P[i1], P[i2]
+        sh1, sh2 = p1["sh"], p2["sh"]
+        # oracle
+        y1 = oracle_layer(ta_o, p1, True)
+        ta2 = orc.ternarize_nchw(y1, lo, hi)
+        y2 = oracle_layer(ta2, p2, False)
+        sc = xo if ids is None else oracle_layer(ta_o, P[ids], False)
+        xo = orc.add_relu(y2, sc, True)
+        ta_o = orc.ternarize_nchw(xo, lo, hi)
+        # HIP
+        Nb, Cc, H, W = xh.shape
+        cw1, ep1 = weights(p1, True)
+        ca2 = B.ternary_conv2d_ternarize(ca, cw1, Nb, Cc, H, W, sh1.O, sh1.k, sh1.k, sh1.stride, sh1.pad,
+                                         ep1, float(lo), float(hi))
+        if ids is None:
+            res = xh
+        else:
+            s3 = P[ids]["sh"]
+            cwd, epd = weights(P[ids], False)
+            _, res = B.ternary_conv2d(ca, cwd, Nb, Cc, H, W, s3.O, s3.k, s3.k, s3.stride, s3.pad, ep=epd)
+        cw2, ep2 = weights(p2, False)
+        out = torch.empty((Nb, sh2.O, sh2.OH, sh2.OH), dtype=torch.float32, device=T.DEV)
+        ca = B.ternary_conv2d_ternarize(ca2, cw2, Nb, sh2.C, sh2.H, sh2.H, sh2.O, sh2.k, sh2.k, sh2.stride,
+                                        sh2.pad, ep2, float(lo), float(hi), residual=res, relu_out=True,
+                                        y_out=out)
+        torch.cuda.synchronize()
+        T.assert_codes_match(ca2.cpu().numpy(), orc.nchw_to_nhwc_i8(ta2, ca2.shape[-1]), y1, lo, hi,
+                             "block %d conv2 input codes" % bi)
+        T.assert_y_close(out.cpu().numpy(), xo, "block %d output" % bi)
+        T.assert_codes_match(ca.cpu().numpy(), orc.nchw_to_nhwc_i8(ta_o, ca.shape[-1]), xo, lo, hi,
+                             "block %d output codes" % bi)
+        # the chain stays comparable only while the codes agree exactly
+        assert (ca.cpu().numpy() == orc.nchw_to_nhwc_i8(ta_o, ca.shape[-1])).all(), "block %d" % bi
+        xh = out
+    assert xo.shape == (2, 512, 7, 7)
