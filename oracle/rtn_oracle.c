@@ -396,6 +396,27 @@ void orc_add_relu(const float *z, const float *r, int64_t n, int relu, float *s)
     }
 }
 
+/* ------------------------------------------------------------------ O9 --
+ * Weight-only ternary layer (the 2-bit-weight / 32-bit-activation rows of the
+ * ImageNet table): the weights are alpha * W^t as everywhere else (Section
+ * "Weight Ternarization": scale only, no offset), the activations stay fp32:
+ *   y[m][n] = alpha_w[n] * sum_k x[m][k] * t_w[n][k]
+ * summed in double in index order, then the same tail as O5 (ReLU, BN affine),
+ * rounded once to fp32.  aw: one scalar (stride_w = 0) or one per column.   */
+void orc_wgemm(const float *x, const int8_t *tw, int64_t M, int64_t N, int64_t K,
+               const float *aw, int stride_w, int relu,
+               const float *bn_scale, const float *bn_shift, float *y)
+{
+#pragma omp parallel for
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            double s = 0.0;
+            for (int64_t k = 0; k < K; ++k) s += (double)x[m * K + k] * (double)tw[n * K + k];
+            double v = (double)aw[n * stride_w] * s;
+            y[m * N + n] = (float)apply_tail(v, relu, bn_scale, bn_shift, n);
+        }
+}
+
 /* Conv form of O6: direct conv of the reparameterized values in double.
  * pad_true_zero = 1 pads the value tensor (aa*t+ba) with 0.0;
  * pad_true_zero = 0 pads the code tensor with 0, i.e. the value with ba.     */

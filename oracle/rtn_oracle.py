@@ -327,3 +327,17 @@ def add_relu(z, r, relu=True):
     out = np.empty(z.shape, dtype=np.float32)
     lib().orc_add_relu(_p(z), _p(r), _i64(z.size), C.c_int(int(relu)), _p(out))
     return out
+
+
+def wgemm(x, tw, alpha_w, relu=False, bn_scale=None, bn_shift=None):
+    """O9.  x: float32 [M,K]; tw: int8 [N,K]; alpha_w scalar or [N] -> float32 [M,N]."""
+    x, tw = _c(x, np.float32), _c(tw, np.int8)
+    M, K = x.shape
+    N, K2 = tw.shape
+    assert K == K2
+    aw, sw_ = _gran(alpha_w, N)
+    bs, bh = _c(bn_scale, np.float32), _c(bn_shift, np.float32)
+    y = np.empty((M, N), dtype=np.float32)
+    lib().orc_wgemm(_p(x), _p(tw), _i64(M), _i64(N), _i64(K), _p(aw), C.c_int(sw_), C.c_int(int(relu)),
+                    _p(bs), _p(bh), _p(y))
+    return y

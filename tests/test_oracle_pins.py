@@ -430,3 +430,39 @@ def test_add_relu_is_one_fp32_add_then_max():
     assert (orc.add_relu(a, b, True) == np.maximum(a + b, np.float32(0))).all()      # numpy's fp32 add
     wide = (a.astype(np.float64) + b.astype(np.float64))
     assert (orc.add_relu(a, b, False) == wide.astype(np.float32)).all()               # = correctly rounded sum
+
+
+# ------------------------------------------------------------------ O9 ----
+def test_wgemm_vs_numpy_float64_matmul_and_brute_force():
+    rng = np.random.default_rng(41)
+    M, N, K = 9, 7, 53
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    tw = _rand_t(rng, (N, K))
+    aw = rng.uniform(0.5, 1.5, N).astype(np.float32)
+    y = orc.wgemm(x, tw, aw)
+    ref = (x.astype(np.float64) @ tw.astype(np.float64).T) * aw.astype(np.float64)[None, :]   # library routine
+    assert np.abs(y - ref).max() <= 1e-6 * np.abs(ref).max()
+    # pure-Python loops on a corner, exact rational arithmetic
+    from fractions import Fraction as F
+    for m, n in [(0, 0), (M - 1, N - 1), (3, 5)]:
+        s = sum(F(float(x[m, k])) * int(tw[n, k]) for k in range(K)) * F(float(aw[n]))
+        assert abs(float(s) - float(y[m, n])) <= 6e-8 * abs(float(s)) + 1e-30
+    # scalar alpha, ReLU then BN affine (the order of O5)
+    bs, bh = rng.uniform(0.5, 1.5, N).astype(np.float32), rng.normal(0, 0.1, N).astype(np.float32)
+    y2 = orc.wgemm(x, tw, 0.75, relu=True, bn_scale=bs, bn_shift=bh)
+    ref2 = bs.astype(np.float64) * np.maximum(0.75 * (x.astype(np.float64) @ tw.T.astype(np.float64)), 0) + bh
+    assert np.abs(y2 - ref2).max() <= 1e-6 * np.abs(ref2).max()
+
+
+def test_wgemm_special_cases():
+    rng = np.random.default_rng(42)
+    x = rng.standard_normal((5, 16)).astype(np.float32)
+    eye = np.eye(16, dtype=np.int8)
+    assert (orc.wgemm(x, eye, 1.0) == x).all()                        # identity weights return x
+    assert (orc.wgemm(x, -eye, 2.0) == -2.0 * x).all()                # sign and scale
+    assert (orc.wgemm(x, np.zeros((3, 16), np.int8), 1.0) == 0).all()
+    ones = np.ones((1, 16), np.int8)
+    assert np.allclose(orc.wgemm(x, ones, 1.0)[:, 0], x.astype(np.float64).sum(1), rtol=1e-6, atol=1e-6)
+    # ternary activations in fp32 reduce it to the integer contraction of O3
+    ta, tw = _rand_t(rng, (6, 40)), _rand_t(rng, (4, 40))
+    assert (orc.wgemm(ta.astype(np.float32), tw, 1.0) == orc.gemm_acc(ta, tw).astype(np.float32)).all()
