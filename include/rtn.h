@@ -230,6 +230,27 @@ int rtn_ternary_conv2d_ternarize(rtn_code_format fmt, rtn_path path, const void 
                                  void *codes_out, void *workspace, size_t workspace_bytes,
                                  void *stream);
 
+/* Weight-only ternary layer (the 2-bit-weight / 32-bit-activation rows of the
+ * paper's ImageNet table): ternary weights alpha_w * t_w as everywhere else
+ * (Section "Weight Ternarization": a scale, no offset), activations left in fp32:
+ *   y[m][n] = alpha_w[n] * sum_k x[m][k] * t_w[n][k];  then ReLU if relu; then
+ *   bn_scale[n]*y + bn_shift[n] if bn_scale (both nullable, DEVICE vectors).
+ *   x: fp32 [M][K] row-major; w_codes: RTN_CODE_I8 [N][rtn_padded_k(K)] as written
+ *   by rtn_ternarize_pack; alpha_w: RTN_SCALAR (host) or RTN_VECTOR over N (device);
+ *   y_out: fp32 [M][N].
+ * On the matrix cores each fp32 activation is split exactly into three bf16 terms
+ * (x = hi + mid + lo); the products with -1, 0, +1 are exact and are accumulated in
+ * fp32, so the result differs from the exactly rounded one only by the fp32
+ * accumulation of 3K terms: |y - y_exact| <= 3K * 2^-24 * alpha_w * sum_k |x[m][k]| in
+ * the worst case, about sqrt(3K) * 2^-24 of that sum typically.  x must be finite.
+ * workspace: rtn_weight_gemm_workspace_bytes(M, N, K) bytes, 16-byte aligned (holds
+ * the split activations and the weights as bf16; overwritten by every call).    */
+size_t rtn_weight_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K);
+int rtn_ternary_weight_gemm(const float *x, const void *w_codes, int64_t M, int64_t N, int64_t K,
+                            const float *alpha_w, rtn_gran gran_w, int relu, const float *bn_scale,
+                            const float *bn_shift, float *y_out, void *workspace,
+                            size_t workspace_bytes, void *stream);
+
 /* Stand-alone epilogue on stored accumulators (Eq.9 generalised, see
  * rtn_epilogue).  GEMM form: acc, y_out are [M][N] row-major.               */
 int rtn_epilogue_reparam(const int32_t *acc, int64_t M, int64_t N, int64_t K,

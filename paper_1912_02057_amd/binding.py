@@ -24,7 +24,8 @@ RTN_PATH_AUTO, RTN_PATH_MFMA_I8, RTN_PATH_POPC = 0, 1, 2
 EXPORTS = ["rtn_status_string", "rtn_last_hip_error", "rtn_num_tile_configs", "rtn_set_tile_config", "rtn_padded_k", "rtn_codes_bytes",
            "rtn_ternarize_pack", "rtn_ternary_gemm", "rtn_conv2d_workspace_bytes",
            "rtn_conv2d_prepare_constants",
-           "rtn_ternary_conv2d_implicit_gemm", "rtn_ternary_conv2d_ternarize", "rtn_epilogue_reparam",
+           "rtn_ternary_conv2d_implicit_gemm", "rtn_ternary_conv2d_ternarize",
+           "rtn_weight_gemm_workspace_bytes", "rtn_ternary_weight_gemm", "rtn_epilogue_reparam",
            "rtn_epilogue_reparam_conv2d"]
 
 
@@ -77,6 +78,10 @@ def lib():
         L.rtn_ternary_conv2d_ternarize.restype = ci
         L.rtn_ternary_conv2d_ternarize.argtypes = [ci, ci, vp, vp, i64, i64, i64, i64, i64, ci, ci, ci, ci,
                                                    ci, vp, vp, ci, vp, vp, ci, vp, vp, vp, C.c_size_t, vp]
+        L.rtn_weight_gemm_workspace_bytes.restype = C.c_size_t
+        L.rtn_weight_gemm_workspace_bytes.argtypes = [i64, i64, i64]
+        L.rtn_ternary_weight_gemm.restype = ci
+        L.rtn_ternary_weight_gemm.argtypes = [vp, vp, i64, i64, i64, vp, ci, ci, vp, vp, vp, vp, C.c_size_t, vp]
         L.rtn_epilogue_reparam.restype = ci
         L.rtn_epilogue_reparam.argtypes = [vp, i64, i64, i64, vp, vp, vp]
         L.rtn_epilogue_reparam_conv2d.restype = ci
@@ -254,6 +259,25 @@ def ternary_conv2d_ternarize(a_codes, w_codes, Nb, Cc, H, W, O, KH, KW, stride, 
         C.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(), _stream())
     _check(rc, "rtn_ternary_conv2d_ternarize")
     return codes_out
+
+
+def ternary_weight_gemm(x, w_codes, M, N, K, alpha_w, relu=False, bn_scale=None, bn_shift=None, y_out=None,
+                        workspace=None):
+    """Weight-only ternary GEMM: x cuda float32 [M,K], w_codes int8 [N,Kpad]; alpha_w python
+    float or cuda float32 [N].  Returns y float32 [M,N]."""
+    if y_out is None:
+        y_out = torch.empty((M, N), dtype=torch.float32, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(lib().rtn_weight_gemm_workspace_bytes(M, N, K), dtype=torch.uint8,
+                                device=x.device)
+    ga = _Gran(alpha_w)
+    rc = lib().rtn_ternary_weight_gemm(
+        _dev(x, torch.float32), C.c_void_p(w_codes.data_ptr()), M, N, K, ga.ptr, ga.gran, int(bool(relu)),
+        None if bn_scale is None else _dev(bn_scale, torch.float32),
+        None if bn_shift is None else _dev(bn_shift, torch.float32), _dev(y_out, torch.float32),
+        C.c_void_p(workspace.data_ptr()), workspace.numel(), _stream())
+    _check(rc, "rtn_ternary_weight_gemm")
+    return y_out
 
 
 def epilogue_reparam(acc, K, ep, y_out=None):

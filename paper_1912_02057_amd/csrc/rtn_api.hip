@@ -306,6 +306,44 @@ int rtn_ternary_conv2d_ternarize(rtn_code_format fmt, rtn_path path, const void*
     return he == hipSuccess ? RTN_OK : hip_fail(he);
 }
 
+size_t rtn_weight_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
+{
+    if (M <= 0 || N <= 0 || K <= 0 || M > kMaxDim || N > kMaxDim || K > kMaxK) return 0;
+    return (size_t)(3 * M + N) * (size_t)pad64(K) * 2u;
+}
+
+int rtn_ternary_weight_gemm(const float* x, const void* w_codes, int64_t M, int64_t N, int64_t K,
+                            const float* alpha_w, rtn_gran gran_w, int relu, const float* bn_scale,
+                            const float* bn_shift, float* y_out, void* workspace, size_t workspace_bytes,
+                            void* stream)
+{
+    if (!x || !w_codes || !alpha_w || !y_out) return RTN_ERR_NULL;
+    if (bn_shift && !bn_scale) return RTN_ERR_NULL;
+    if (M <= 0 || N <= 0 || K <= 0 || M > kMaxDim || N > kMaxDim || K > kMaxK) return RTN_ERR_SHAPE;
+    // the three bf16 terms of a row sit side by side: 6 * Kpad bytes per row must stay below 2^31
+    if (3 * pad64(K) * 2 * 256 > kMaxDim || M * pad64(K) > (int64_t)1 << 40) return RTN_ERR_SHAPE;
+    if (!aligned(x, 4) || !aligned(w_codes, 16) || !aligned(y_out, 4) || !aligned(bn_scale, 4) ||
+        !aligned(bn_shift, 4))
+        return RTN_ERR_ALIGN;
+    rtn::WGemmArgs a = {};
+    int rc;
+    if (gran_w != RTN_SCALAR && gran_w != RTN_VECTOR) return RTN_ERR_UNSUPPORTED;
+    if ((rc = make_param(alpha_w, gran_w, false, a.ep.alpha_w)) != RTN_OK) return rc;
+    if (!workspace || workspace_bytes < rtn_weight_gemm_workspace_bytes(M, N, K)) return RTN_ERR_WORKSPACE;
+    if (!aligned(workspace, 16)) return RTN_ERR_ALIGN;
+    a.ep.alpha_a.s = 1.0f;
+    a.ep.relu = relu != 0;
+    a.ep.bn_scale = bn_scale;
+    a.ep.bn_shift = bn_shift;
+    a.x = x;
+    a.w = (const int8_t*)w_codes;
+    a.M = M, a.N = N, a.K = K, a.Kpad = pad64(K);
+    a.y = y_out;
+    a.workspace = workspace;
+    const hipError_t he = rtn::launch_wgemm(a, (hipStream_t)stream);
+    return he == hipSuccess ? RTN_OK : hip_fail(he);
+}
+
 int rtn_epilogue_reparam(const int32_t* acc, int64_t M, int64_t N, int64_t K, const rtn_epilogue* ep,
                          float* y_out, void* stream)
 {

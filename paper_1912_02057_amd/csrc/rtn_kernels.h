@@ -95,6 +95,17 @@ struct ConvArgs {
 };
 
 hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t st);
+
+// Weight-only ternary GEMM: y[m][n] = alpha_w[n] * sum_k x[m][k] * t_w[n][k] (+ tail of ep).
+struct WGemmArgs {
+    const float* x;    // [M][K] fp32
+    const int8_t* w;   // [N][Kpad] int8 codes
+    int64_t M, N, K, Kpad;
+    float* y;          // [M][N]
+    void* workspace;   // (3 M + N) * Kpad bf16
+    EpiArgs ep;        // alpha_a = 1, beta_a = 0, beta_w = 0; alpha_w, relu, bn as given
+};
+hipError_t launch_wgemm(const WGemmArgs& a, hipStream_t st);
 hipError_t launch_conv_mfma(const ConvArgs& a, hipStream_t st);
 // Tile configuration override for tuning and tests (-1 = heuristic).
 int tile_config_count();

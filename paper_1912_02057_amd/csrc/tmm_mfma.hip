@@ -36,6 +36,8 @@ namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v16i __attribute__((ext_vector_type(16)));
+typedef float v16f __attribute__((ext_vector_type(16)));
+typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
 // 16 zero bytes every out-of-image tap reads from.
 __device__ __attribute__((aligned(16))) int g_zero16[4] = {0, 0, 0, 0};
@@ -66,6 +68,9 @@ struct TmmParams {
     // ReLU; the fp32 value that is ternarized is also stored when y is given
     const float* res;
     int relu_out;
+    // bf16 operands (DT = 1): the Q rows are qwrap bytes long and are walked again
+    // from the start each time the K offset passes their end
+    unsigned qwrap;
 };
 
 // Border classes of a conv window and the LDS bytes of the epilogue table of a
@@ -152,9 +157,15 @@ __device__ __forceinline__ void wait_groups(int groups)
 // the next layer instead of acc / y); 2 is the block-tail form of it (residual
 // add, second ReLU, fp32 copy of the result).  Each is a kernel of its own so
 // that its epilogue does not enter the register budget of the others.
-template <int BP, int BQ, int WGP, int WGQ, int NS, int MINW, bool CONV, int TERN = 0, int HC = 0>
+//
+// DT = 1 multiplies bf16 operands into fp32 accumulators (v_mfma_f32_32x32x16_bf16; a
+// lane's 16 operand bytes are 8 bf16 of the same row, so tiles, ring and fragment
+// addressing are those of the int8 form): the weight-only ternary GEMM, whose
+// activations are fp32 values split into three bf16 terms laid side by side along K.
+template <int BP, int BQ, int WGP, int WGQ, int NS, int MINW, bool CONV, int TERN = 0, int HC = 0, int DT = 0>
 __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
 {
+    static_assert(DT == 0 || (!CONV && TERN == 0), "bf16 operands: GEMM only");
     static_assert(!TERN || CONV, "the ternarizing epilogue belongs to the conv");
     static_assert(WGP * WGQ == 4, "4 waves per block");
     constexpr bool HALO = HC != 0;
@@ -271,6 +282,7 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
             }
         } else {
             is_koffQ = is_koffP;
+            if (DT == 1) is_koffQ = (int64_t)((unsigned)is_koffP % prm.qwrap);
         }
     };
     // the idx-th of the DPS direct loads of the step set up by issue_begin()
@@ -376,7 +388,8 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
     int sa_part[TQ];
 #pragma unroll
     for (int j = 0; j < TQ; ++j) sa_part[j] = 0;
-    v16i acc[TP][TQ];
+    using AccV = std::conditional_t<DT == 1, v16f, v16i>;
+    AccV acc[TP][TQ];
 #pragma unroll
     for (int i = 0; i < TP; ++i)
 #pragma unroll
@@ -394,8 +407,13 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
         if (HALO && FRAGS && fks == 0) frag_step_advance();
 #pragma unroll
         for (int n = 0; n < NM; ++n) {
-            acc[n / TQ][n % TQ] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[ks][n / TQ], fb[ks][n % TQ],
-                                                                        acc[n / TQ][n % TQ], 0, 0, 0);
+            if constexpr (DT == 1)
+                acc[n / TQ][n % TQ] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
+                    __builtin_bit_cast(v8bf, fa[ks][n / TQ]), __builtin_bit_cast(v8bf, fb[ks][n % TQ]),
+                    acc[n / TQ][n % TQ], 0, 0, 0);
+            else
+                acc[n / TQ][n % TQ] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[ks][n / TQ], fb[ks][n % TQ],
+                                                                            acc[n / TQ][n % TQ], 0, 0, 0);
             if (FRAGS) {
                 // front-loaded: one read per MFMA when there are enough MFMAs,
                 // so the last read is long done at the end of the slice
@@ -588,7 +606,7 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
                 if (m < prm.RP) {
                     aa = pval(ep.alpha_a, m);
                     ba = pval(ep.beta_a, m);
-                    r2 = aa * (double)ep.sum_ta[m] + (double)prm.Klogical * ba;
+                    if (DT == 0) r2 = aa * (double)ep.sum_ta[m] + (double)prm.Klogical * ba;
                 }
                 tab[t] = aa;
                 tab[BP + t] = ba;
@@ -615,7 +633,7 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
                 if (Y && nok[j]) {
                     aw[j] = pval(ep.alpha_w, ncol);
                     bw[j] = pval(ep.beta_w, ncol);
-                    sw[j] = (double)ep.sum_tw[ncol];
+                    if (DT == 0) sw[j] = (double)ep.sum_tw[ncol];
                     if (has_bn) {
                         bs[j] = ep.bn_scale[ncol];
                         bh[j] = ep.bn_shift ? (double)ep.bn_shift[ncol] : 0.0;
@@ -641,8 +659,8 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
 #pragma unroll
                     for (int j = 0; j < TQ; ++j) {
                         if (FULL || (mok && nok[j])) {
-                            const int D = acc[i][j][r];
-                            if (ACC) put(D, accp[j] + rowoff);
+                            const auto D = acc[i][j][r];
+                            if (ACC) put((int)D, accp[j] + rowoff);
                             if (Y) {
                                 double v = aw[j] * (aa * (double)D + ba * sw[j]) + bw[j] * r2;
                                 v = __builtin_fmax(v, relu_floor);
@@ -860,7 +878,7 @@ inline bool halo_eligible(const TmmParams& prm, int hc)
            g.OW == g.W;
 }
 
-template <int BP, int BQ, int WGP, int WGQ, int NS, int MINW, bool CONV, int TERN = 0, int HC = 0>
+template <int BP, int BQ, int WGP, int WGQ, int NS, int MINW, bool CONV, int TERN = 0, int HC = 0, int DT = 0>
 hipError_t launch_cfg(TmmParams& prm, hipStream_t st)
 {
     constexpr int ring_bytes = NS * (BP + (HC ? 0 : BQ)) * 64;
@@ -881,7 +899,7 @@ hipError_t launch_cfg(TmmParams& prm, hipStream_t st)
     }
     if (smem > kMaxLds) return hipErrorInvalidValue;
     static bool attr_done = false;
-    auto kern = k_tmm<BP, BQ, WGP, WGQ, NS, MINW, CONV, TERN, HC>;
+    auto kern = k_tmm<BP, BQ, WGP, WGQ, NS, MINW, CONV, TERN, HC, DT>;
     if (!attr_done) {
         hipError_t e = hipFuncSetAttribute((const void*)kern, hipFuncAttributeMaxDynamicSharedMemorySize,
                                            (int)kMaxLds);
@@ -1034,6 +1052,77 @@ hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t st)
     prm.ep = a.ep;
     const int cfg = g_forced_tile >= 0 ? g_forced_tile : pick_tile(a.M, a.N, false);
     return launch_index<false>(cfg, prm, st);
+}
+
+// ---- weight-only ternary GEMM: fp32 activations x (alpha * t_w) ----------------
+// bf16 round-to-nearest-even of an fp32 value, as bits
+__device__ __forceinline__ unsigned bf16_rn(float v)
+{
+    const unsigned u = __float_as_uint(v);
+    return (u + 0x7fffu + ((u >> 16) & 1u)) >> 16;
+}
+
+// x = hi + mid + lo with three bf16 terms: each residual is exact in fp32 and at most
+// half an ulp of the term before it, so 8 + 8 + 8 significand bits cover fp32's 24.
+// out: [M][3 * Kpad] bf16, the three terms of a row side by side, zero beyond K.
+__global__ __launch_bounds__(256) void k_split_bf16x3(const float* x, int64_t M, int K, int Kpad, uint16_t* out)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= M * Kpad) return;
+    const int64_t m = i / Kpad;
+    const int k = (int)(i - m * Kpad);
+    unsigned h = 0, md = 0, lo = 0;
+    if (k < K) {
+        const float v = x[m * K + k];
+        h = bf16_rn(v);
+        const float r1 = v - __uint_as_float(h << 16);
+        md = bf16_rn(r1);
+        const float r2 = r1 - __uint_as_float(md << 16);
+        lo = bf16_rn(r2);
+    }
+    uint16_t* row = out + m * 3 * (int64_t)Kpad;
+    row[k] = (uint16_t)h;
+    row[Kpad + k] = (uint16_t)md;
+    row[2 * Kpad + k] = (uint16_t)lo;
+}
+
+// int8 codes [N][Kpad] -> the same values as bf16 (-1, 0, +1 are exact)
+__global__ __launch_bounds__(256) void k_codes_to_bf16(const int8_t* codes, int64_t n, uint16_t* out)
+{
+    const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (i >= n) return;
+    const int t = codes[i];
+    out[i] = t > 0 ? 0x3f80 : (t < 0 ? 0xbf80 : 0);
+}
+
+hipError_t launch_wgemm(const WGemmArgs& a, hipStream_t st)
+{
+    uint16_t* a3 = (uint16_t*)a.workspace;
+    uint16_t* wb = a3 + (size_t)a.M * 3 * a.Kpad;
+    const int64_t na = a.M * a.Kpad, nw = a.N * a.Kpad;
+    hipLaunchKernelGGL(k_split_bf16x3, dim3((unsigned)((na + 255) / 256)), dim3(256), 0, st, a.x, a.M, (int)a.K,
+                       (int)a.Kpad, a3);
+    hipLaunchKernelGGL(k_codes_to_bf16, dim3((unsigned)((nw + 255) / 256)), dim3(256), 0, st, a.w, nw, wb);
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    TmmParams prm = {};
+    prm.P = (const int8_t*)a3;
+    prm.Q = (const int8_t*)wb;
+    prm.RP = (int)a.M;
+    prm.RQ = (int)a.N;
+    prm.ldP = 3 * a.Kpad * 2;
+    prm.ldQ = a.Kpad * 2;
+    prm.qwrap = (unsigned)(a.Kpad * 2);
+    prm.nk = (int)(prm.ldP / 64);
+    prm.Klogical = (int)a.K;
+    prm.y = a.y;
+    prm.ep = a.ep;
+    const int cfg = g_forced_tile >= 0 ? g_forced_tile : pick_tile(a.M, a.N, false);
+    switch (kTileBP[cfg] >= 256 ? 2 : (kTileBP[cfg] >= 128 ? 1 : 0)) {
+        case 2: return launch_cfg<256, 256, 2, 2, 4, 1, false, 0, 0, 1>(prm, st);
+        case 1: return launch_cfg<128, 128, 2, 2, 4, 2, false, 0, 0, 1>(prm, st);
+        default: return launch_cfg<64, 64, 2, 2, 4, 4, false, 0, 0, 1>(prm, st);
+    }
 }
 
 hipError_t launch_conv_mfma(const ConvArgs& a, hipStream_t st)

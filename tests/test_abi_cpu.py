@@ -198,3 +198,29 @@ def test_conv_ternarize_rejects(L):
     assert with_(_22=ODD) == B.RTN_ERR_ALIGN
     e2 = _ep(sums=False)
     assert with_(_14=C.byref(e2)) == B.RTN_ERR_NULL             # weight tap sums are required
+
+
+def test_weight_gemm_rejects(L):
+    call = L.rtn_ternary_weight_gemm
+    a1 = _f(1.0)
+    ok = [FAKE, FAKE, 8, 8, 64, a1, B.RTN_SCALAR, 0, None, None, FAKE, FAKE, 1 << 20, None]
+
+    def with_(**kw):
+        a = list(ok)
+        for i, v in kw.items():
+            a[int(i[1:])] = v
+        return call(*a)
+    assert L.rtn_weight_gemm_workspace_bytes(8, 8, 64) == (3 * 8 + 8) * 64 * 2
+    assert L.rtn_weight_gemm_workspace_bytes(8, 8, 65) == (3 * 8 + 8) * 128 * 2
+    assert L.rtn_weight_gemm_workspace_bytes(0, 8, 64) == 0
+    assert with_(_0=None) == B.RTN_ERR_NULL
+    assert with_(_5=None) == B.RTN_ERR_NULL                     # alpha_w
+    assert with_(_10=None) == B.RTN_ERR_NULL                    # y_out
+    assert with_(_9=FAKE) == B.RTN_ERR_NULL                     # bn_shift without bn_scale
+    assert with_(_2=0) == B.RTN_ERR_SHAPE
+    assert with_(_4=(1 << 22) + 1) == B.RTN_ERR_SHAPE
+    assert with_(_1=ODD) == B.RTN_ERR_ALIGN
+    assert with_(_6=5) == B.RTN_ERR_UNSUPPORTED
+    assert with_(_11=None) == B.RTN_ERR_WORKSPACE
+    assert with_(_12=100) == B.RTN_ERR_WORKSPACE
+    assert with_(_11=ODD) == B.RTN_ERR_ALIGN

@@ -798,3 +798,77 @@ def test_config4_trunk_forward_fully_fused():
         assert (ca.cpu().numpy() == orc.nchw_to_nhwc_i8(ta_o, ca.shape[-1])).all(), "block %d" % bi
         xh = out
     assert xo.shape == (2, 512, 7, 7)
+
+
+# ------------------------- weight-only ternary GEMM (fp32 activations) ----------
+def _wgemm_check(M, N, K, seed, vector_alpha=True, relu=False, bn=False, rows=None, what=""):
+    """HIP weight-only GEMM against the oracle.  The kernel sums 3K exact bf16 products
+    in fp32 (order fixed by the matrix core), the oracle in double: the difference is
+    fp32 accumulation error, bounded by 3K * 2^-24 * alpha * sum|x| in the worst case.
+    Asserted here: the random-walk size of it, (4 sqrt(3K) + 8) * 2^-24 * alpha * sum|x|,
+    plus one fp32 rounding of y."""
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((M, K)).astype(np.float32)
+    x[0, 0] = 0.0
+    if M > 1 and K > 1:
+        x[1, 1] = np.float32(1e-20)           # tiny and huge magnitudes in one row
+        x[1, 0] = np.float32(3e4)
+    w = (rng.standard_normal((N, K)) * 0.05).astype(np.float32)
+    dw = wl.twn_threshold(w, axis=0)
+    aw = rng.uniform(0.5, 1.5, N).astype(np.float32) if vector_alpha else np.float32(0.8)
+    bs = rng.uniform(0.5, 1.5, N).astype(np.float32) if bn else None
+    bh = rng.normal(0, 0.1, N).astype(np.float32) if bn else None
+    tw = orc.ternarize(w, -dw, dw)
+    cw, _ = B.ternarize_pack(T.dev(w), T.thr_arg(-dw), T.thr_arg(dw), want_sum=False)
+    y = B.ternary_weight_gemm(T.dev(x), cw, M, N, K, T.thr_arg(aw), relu=relu,
+                              bn_scale=None if bs is None else T.dev(bs),
+                              bn_shift=None if bh is None else T.dev(bh))
+    torch.cuda.synchronize()
+    y = y.cpu().numpy()
+    sel = np.arange(M) if rows is None else rows
+    ref = orc.wgemm(x[sel], tw, aw, relu=relu, bn_scale=bs, bn_shift=bh).astype(np.float64)
+    scale = np.abs(x[sel].astype(np.float64)).sum(1)[:, None] * np.abs(np.asarray(aw, np.float64))[None, ...]
+    if bn:
+        scale = scale * np.abs(bs.astype(np.float64))[None, :]
+    tol = (4.0 * np.sqrt(3.0 * K) + 8.0) * 2.0 ** -24 * scale + 1.2e-7 * np.abs(ref) + 1e-30
+    err = np.abs(y[sel].astype(np.float64) - ref)
+    assert (err <= tol).all(), "%s: worst err/tol %.3g" % (what, float((err / tol).max()))
+    return float((err / tol).max())
+
+
+WGEMM_SHAPES = [(1, 1, 1), (37, 19, 131), (64, 64, 64), (65, 33, 64), (300, 200, 576), (129, 257, 1000),
+                (512, 384, 2304)]
+
+
+@pytest.mark.parametrize("M,N,K", WGEMM_SHAPES)
+def test_weight_gemm_vs_oracle(M, N, K):
+    _say("weight-only gemm %dx%dx%d" % (M, N, K))
+    _wgemm_check(M, N, K, seed=M + N + K, vector_alpha=True, what="wgemm")
+    _wgemm_check(M, N, K, seed=M + N + K + 1, vector_alpha=False, relu=True, bn=True, what="wgemm relu bn")
+
+
+@pytest.mark.parametrize("cfg", [0, 1, 2])
+def test_weight_gemm_tile_configs(cfg, tile_reset):
+    _say("weight-only gemm, tile config %d" % cfg)
+    B.set_tile_config(cfg)
+    _wgemm_check(300, 530, 320, seed=cfg, what="wgemm cfg %d" % cfg)
+
+
+def test_weight_gemm_exact_on_ternary_activations():
+    """Activations that are themselves -1/0/+1 (exact in bf16, zero middle and low terms):
+    the result must equal the integer contraction exactly."""
+    _say("weight-only gemm on ternary activations")
+    case = wl.gemm_case(200, 136, 448, seed=9)
+    ref = T.oracle_gemm(case)
+    cw, _ = B.ternarize_pack(T.dev(case["xw"]), -0.5, 0.5, want_sum=False)
+    y = B.ternary_weight_gemm(T.dev(case["xa"]), cw, 200, 136, 448, 1.0)
+    torch.cuda.synchronize()
+    assert (y.cpu().numpy() == ref["D"].astype(np.float32)).all()
+
+
+def test_weight_gemm_4096_sampled_rows():
+    _say("weight-only gemm 4096^3, sampled rows")
+    rows = np.sort(np.random.default_rng(1).choice(4096, 24, replace=False))
+    rows[0], rows[-1] = 0, 4095
+    worst = _wgemm_check(4096, 4096, 4096, seed=5, rows=rows, what="wgemm 4096")
+    assert worst < 1.0
