@@ -19,6 +19,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 INT8_PEAK_TOPS = 5000.0   # MI355X dense int8 MFMA, TOP/s (2 ops per MAC)
+BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
 HBM_PEAK_GBS = 8000.0
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this file's default run (see profiles/)
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 129.8e6
@@ -31,7 +32,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--batch", type=int, default=256)
     ap.add_argument("--workload", default="resnet18_ternary_convs",
-                    choices=["resnet18_ternary_convs", "gemm4096"])
+                    choices=["resnet18_ternary_convs", "gemm4096", "wgemm4096"])
     ap.add_argument("--tile", type=int, default=-1, help="force an MFMA tile configuration (tuning)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-images", type=int, default=128,
@@ -173,6 +174,30 @@ def main():
         macs_step = sum(l["sh"].macs(args.batch) for l in layers)
         workload = "ResNet-18 ternary conv stack (19 layers), batch %d, fp32 NCHW in/out" % args.batch
         nlaunch = len(layers)
+    elif args.workload == "wgemm4096":
+        # weight-only ternary GEMM: fp32 activations N(0,1), ternary weights, per-column alpha
+        rng = np.random.Generator(np.random.PCG64(3))
+        wx = rng.standard_normal((4096, 4096), dtype=np.float32)
+        ww = rng.standard_normal((4096, 4096), dtype=np.float32) * np.float32(0.02)
+        wdw = wl.twn_threshold(ww, axis=0)
+        waw = rng.uniform(0.5, 1.5, 4096).astype(np.float32)
+        xd, awd = to_dev(wx), to_dev(waw)
+        cw, _ = B.ternarize_pack(to_dev(ww), garg(-wdw), garg(wdw), want_sum=False)        # S0, offline
+        y = torch.empty((4096, 4096), dtype=torch.float32, device=dev)
+        wsp = torch.empty(B.lib().rtn_weight_gemm_workspace_bytes(4096, 4096, 4096), dtype=torch.uint8, device=dev)
+
+        def step(timers=None):
+            if timers is not None:
+                timers[0][0].record()
+                timers[0][1].record()
+            B.ternary_weight_gemm(xd, cw, 4096, 4096, 4096, awd, y_out=y, workspace=wsp)
+            if timers is not None:
+                timers[0][2].record()
+
+        macs_step = 4096 ** 3
+        workload = "weight-only ternary GEMM M=N=K=4096 (fp32 activations, ternary weights), fp32 out"
+        nlaunch = 1
+        layers = [dict(sh=None)]
     else:
         case = wl.gemm_case(4096, 4096, 4096, 0.4, seed=1)
         xa, xw = to_dev(case["xa"]), to_dev(case["xw"])
@@ -310,6 +335,16 @@ def main():
                         launches_per_step=nlaunch, avg_launch_us=round(conv_total_s / nlaunch * 1e6, 1),
                         bytes_per_launch=round(alg_bytes_launch, 0),
                         mfma_tops=round(achieved_tops, 1), mfma_frac=round(achieved_tops / INT8_PEAK_TOPS, 4))
+    elif args.workload == "wgemm4096":
+        # the call = split kernel + weight conversion + matrix-core GEMM; the GEMM executes three
+        # bf16 products per ternary MAC (the three terms of the exact fp32 split)
+        bf16_tflops = 3 * achieved_tops
+        roofline = dict(bound="mfma", kernel="activation split + k_tmm (bf16 MFMA, fp32 accumulate)",
+                        achieved=round(bf16_tflops, 1), peak=BF16_PEAK_TFLOPS, unit="TFLOP/s",
+                        frac=round(bf16_tflops / BF16_PEAK_TFLOPS, 4), traffic=None,
+                        launches_per_step=nlaunch, avg_launch_us=round(conv_total_s / nlaunch * 1e6, 1),
+                        flops_per_launch=6 * macs_step / nlaunch,
+                        effective_fp32_tflops=round(achieved_tops, 1), fp32_vector_peak_tflops=157.3)
     else:
         roofline = dict(bound="mfma", kernel="k_tmm (int8 MFMA GEMM + fused epilogue)",
                         achieved=round(achieved_tops, 1), peak=INT8_PEAK_TOPS, unit="TOP/s",
@@ -336,6 +371,14 @@ def main():
                 t_cpu += time.perf_counter() - c0
                 macs_cpu += sh.macs(n_img)
             sample = "all 19 layers, %d images each (of %d)" % (n_img, args.batch)
+        elif args.workload == "wgemm4096":
+            rows = np.arange(0, 4096, 4096 // 64, dtype=np.int64)
+            c0 = time.perf_counter()
+            tw = orc.ternarize(ww, -wdw, wdw)
+            orc.wgemm(wx[rows], tw, waw)
+            t_cpu = time.perf_counter() - c0
+            macs_cpu = rows.size * 4096 * 4096
+            sample = "64 of 4096 output rows, all columns"
         else:
             rows = np.arange(0, 4096, 4096 // 64, dtype=np.int64)
             c0 = time.perf_counter()
@@ -353,10 +396,12 @@ def main():
     value = macs_step / (ms_per_step * 1e-3) / 1e12
     out = {
         "metric": "effective ternary MAC/s (dense MAC count, S1+S2+S3+S4 per layer), ResNet-18 ternary layers"
-        if args.workload == "resnet18_ternary_convs" else "effective ternary MAC/s, ternary GEMM",
+        if args.workload == "resnet18_ternary_convs" else
+        ("effective MAC/s, weight-only ternary GEMM" if args.workload == "wgemm4096"
+         else "effective ternary MAC/s, ternary GEMM"),
         "value": round(value, 3), "unit": "TMAC/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "i8", "data": "synthetic",
+        "vs_baseline": None, "dtype": "bf16x3" if args.workload == "wgemm4096" else "i8", "data": "synthetic",
         "config": {"workload": workload, "batch": args.batch, "tile": args.tile},
         "tops": round(2 * value, 1), "pct_int8_mfma_peak": round(100 * 2 * value / INT8_PEAK_TOPS, 2),
         "contraction_only": {"tmacs": round(macs_step / conv_total_s / 1e12, 3),

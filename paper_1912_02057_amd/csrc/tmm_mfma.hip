@@ -1067,39 +1067,63 @@ __device__ __forceinline__ unsigned bf16_rn(float v)
 // out: [M][3 * Kpad] bf16, the three terms of a row side by side, zero beyond K.
 __global__ __launch_bounds__(256) void k_split_bf16x3(const float* x, int64_t M, int K, int Kpad, uint16_t* out)
 {
+    // one thread: 8 consecutive k of one row -> three 16-byte stores
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= M * Kpad) return;
-    const int64_t m = i / Kpad;
-    const int k = (int)(i - m * Kpad);
-    unsigned h = 0, md = 0, lo = 0;
-    if (k < K) {
-        const float v = x[m * K + k];
-        h = bf16_rn(v);
-        const float r1 = v - __uint_as_float(h << 16);
-        md = bf16_rn(r1);
-        const float r2 = r1 - __uint_as_float(md << 16);
-        lo = bf16_rn(r2);
+    const int per_row = Kpad / 8;
+    if (i >= M * per_row) return;
+    const int64_t m = i / per_row;
+    const int k0 = (int)(i - m * per_row) * 8;
+    float v[8];
+    const float* src = x + m * K + k0;
+    if (k0 + 8 <= K && (K & 3) == 0 && ((uintptr_t)x & 15) == 0) {
+        const float4 a = *(const float4*)src, b = *(const float4*)(src + 4);
+        v[0] = a.x, v[1] = a.y, v[2] = a.z, v[3] = a.w, v[4] = b.x, v[5] = b.y, v[6] = b.z, v[7] = b.w;
+    } else {
+#pragma unroll
+        for (int e = 0; e < 8; ++e) v[e] = k0 + e < K ? src[e] : 0.0f;
     }
-    uint16_t* row = out + m * 3 * (int64_t)Kpad;
-    row[k] = (uint16_t)h;
-    row[Kpad + k] = (uint16_t)md;
-    row[2 * Kpad + k] = (uint16_t)lo;
+    unsigned h[8], md[8], lo[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        h[e] = bf16_rn(v[e]);
+        const float r1 = v[e] - __uint_as_float(h[e] << 16);
+        md[e] = bf16_rn(r1);
+        const float r2 = r1 - __uint_as_float(md[e] << 16);
+        lo[e] = bf16_rn(r2);
+    }
+    auto pack8 = [](const unsigned* t) {
+        return make_uint4(t[0] | (t[1] << 16), t[2] | (t[3] << 16), t[4] | (t[5] << 16), t[6] | (t[7] << 16));
+    };
+    uint16_t* row = out + m * 3 * (int64_t)Kpad + k0;
+    *(uint4*)row = pack8(h);
+    *(uint4*)(row + Kpad) = pack8(md);
+    *(uint4*)(row + 2 * Kpad) = pack8(lo);
 }
 
-// int8 codes [N][Kpad] -> the same values as bf16 (-1, 0, +1 are exact)
-__global__ __launch_bounds__(256) void k_codes_to_bf16(const int8_t* codes, int64_t n, uint16_t* out)
+// int8 codes [N][Kpad] -> the same values as bf16 (-1, 0, +1 are exact); 16 codes per thread
+__global__ __launch_bounds__(256) void k_codes_to_bf16(const int8_t* codes, int64_t n16, uint16_t* out)
 {
     const int64_t i = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (i >= n) return;
-    const int t = codes[i];
-    out[i] = t > 0 ? 0x3f80 : (t < 0 ? 0xbf80 : 0);
+    if (i >= n16) return;
+    const uint4 c = *(const uint4*)(codes + i * 16);
+    const unsigned w[4] = {c.x, c.y, c.z, c.w};
+    unsigned o[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const int t0 = (int8_t)(w[e >> 1] >> (16 * (e & 1))), t1 = (int8_t)(w[e >> 1] >> (16 * (e & 1) + 8));
+        const unsigned b0 = t0 > 0 ? 0x3f80u : (t0 < 0 ? 0xbf80u : 0u), b1 = t1 > 0 ? 0x3f80u : (t1 < 0 ? 0xbf80u : 0u);
+        o[e] = b0 | (b1 << 16);
+    }
+    uint4* dst = (uint4*)(out + i * 16);
+    dst[0] = make_uint4(o[0], o[1], o[2], o[3]);
+    dst[1] = make_uint4(o[4], o[5], o[6], o[7]);
 }
 
 hipError_t launch_wgemm(const WGemmArgs& a, hipStream_t st)
 {
     uint16_t* a3 = (uint16_t*)a.workspace;
     uint16_t* wb = a3 + (size_t)a.M * 3 * a.Kpad;
-    const int64_t na = a.M * a.Kpad, nw = a.N * a.Kpad;
+    const int64_t na = a.M * a.Kpad / 8, nw = a.N * a.Kpad / 16;
     hipLaunchKernelGGL(k_split_bf16x3, dim3((unsigned)((na + 255) / 256)), dim3(256), 0, st, a.x, a.M, (int)a.K,
                        (int)a.Kpad, a3);
     hipLaunchKernelGGL(k_codes_to_bf16, dim3((unsigned)((nw + 255) / 256)), dim3(256), 0, st, a.w, nw, wb);
