@@ -417,6 +417,34 @@ void orc_wgemm(const float *x, const int8_t *tw, int64_t M, int64_t N, int64_t K
         }
 }
 
+/* Conv form of O9: fp32 activations x [Nb][C][H][W], ternary weights
+ * alpha_w[o] * t_w [O][C][KH][KW], cross-correlation with zero padding (a padded
+ * tap adds nothing), summed in double in (c, kh, kw) order, same tail.       */
+void orc_wconv(const float *x, const int8_t *tw, int64_t Nb, int64_t C, int64_t H, int64_t W,
+               int64_t O, int64_t KH, int64_t KW, int64_t stride, int64_t pad,
+               const float *aw, int stride_w, int relu,
+               const float *bn_scale, const float *bn_shift, float *y)
+{
+    int64_t OH = (H + 2 * pad - KH) / stride + 1, OW = (W + 2 * pad - KW) / stride + 1;
+#pragma omp parallel for collapse(2)
+    for (int64_t nb = 0; nb < Nb; ++nb)
+        for (int64_t o = 0; o < O; ++o)
+            for (int64_t oh = 0; oh < OH; ++oh)
+                for (int64_t ow = 0; ow < OW; ++ow) {
+                    double s = 0.0;
+                    for (int64_t c = 0; c < C; ++c)
+                        for (int64_t kh = 0; kh < KH; ++kh)
+                            for (int64_t kw = 0; kw < KW; ++kw) {
+                                int64_t ih = oh * stride - pad + kh, iw = ow * stride - pad + kw;
+                                if (ih < 0 || ih >= H || iw < 0 || iw >= W) continue;
+                                s += (double)x[((nb * C + c) * H + ih) * W + iw] *
+                                     (double)tw[((o * C + c) * KH + kh) * KW + kw];
+                            }
+                    double v = (double)aw[o * stride_w] * s;
+                    y[((nb * O + o) * OH + oh) * OW + ow] = (float)apply_tail(v, relu, bn_scale, bn_shift, o);
+                }
+}
+
 /* Conv form of O6: direct conv of the reparameterized values in double.
  * pad_true_zero = 1 pads the value tensor (aa*t+ba) with 0.0;
  * pad_true_zero = 0 pads the code tensor with 0, i.e. the value with ba.     */

@@ -341,3 +341,16 @@ def wgemm(x, tw, alpha_w, relu=False, bn_scale=None, bn_shift=None):
     lib().orc_wgemm(_p(x), _p(tw), _i64(M), _i64(N), _i64(K), _p(aw), C.c_int(sw_), C.c_int(int(relu)),
                     _p(bs), _p(bh), _p(y))
     return y
+
+
+def wconv(x, tw, stride, pad, alpha_w, relu=False, bn_scale=None, bn_shift=None):
+    """Conv form of O9.  x: float32 [Nb,C,H,W]; tw: int8 [O,C,KH,KW] -> float32 [Nb,O,OH,OW]."""
+    x, tw = _c(x, np.float32), _c(tw, np.int8)
+    Nb, Cc, H, W, O, KH, KW = _geom(x, tw)
+    OH, OW = conv_out_shape(H, W, KH, KW, stride, pad)
+    aw, sw_ = _gran(alpha_w, O)
+    bs, bh = _c(bn_scale, np.float32), _c(bn_shift, np.float32)
+    y = np.empty((Nb, O, OH, OW), dtype=np.float32)
+    lib().orc_wconv(_p(x), _p(tw), _i64(Nb), _i64(Cc), _i64(H), _i64(W), _i64(O), _i64(KH), _i64(KW),
+                    _i64(stride), _i64(pad), _p(aw), C.c_int(sw_), C.c_int(int(relu)), _p(bs), _p(bh), _p(y))
+    return y

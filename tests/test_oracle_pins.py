@@ -466,3 +466,25 @@ def test_wgemm_special_cases():
     # ternary activations in fp32 reduce it to the integer contraction of O3
     ta, tw = _rand_t(rng, (6, 40)), _rand_t(rng, (4, 40))
     assert (orc.wgemm(ta.astype(np.float32), tw, 1.0) == orc.gemm_acc(ta, tw).astype(np.float32)).all()
+
+
+def test_wconv_vs_torch_float64_conv_and_integer_conv():
+    rng = np.random.default_rng(43)
+    for (C, H, W, O, k, s, p) in [(5, 9, 7, 4, 3, 1, 1), (6, 10, 10, 3, 3, 2, 1), (4, 8, 8, 5, 1, 2, 0),
+                                  (3, 6, 5, 2, 5, 1, 2)]:
+        x = rng.standard_normal((2, C, H, W)).astype(np.float32)
+        tw = _rand_t(rng, (O, C, k, k))
+        aw = rng.uniform(0.5, 1.5, O).astype(np.float32)
+        y = orc.wconv(x, tw, s, p, aw)
+        lib = torch.nn.functional.conv2d(torch.from_numpy(x.astype(np.float64)),
+                                         torch.from_numpy(tw.astype(np.float64)), stride=s, padding=p).numpy()
+        ref = lib * aw.astype(np.float64)[None, :, None, None]
+        assert y.shape == ref.shape
+        assert np.abs(y - ref).max() <= 1e-6 * np.abs(ref).max()
+        # ternary activations stored as fp32: the integer contraction of O3, exactly
+        ta = _rand_t(rng, (2, C, H, W))
+        assert (orc.wconv(ta.astype(np.float32), tw, s, p, 1.0) == orc.conv_acc(ta, tw, s, p).astype(np.float32)).all()
+    # tail order: ReLU, then the BN affine
+    bs, bh = np.full(O, 2.0, np.float32), np.full(O, -1.0, np.float32)
+    y2 = orc.wconv(x, tw, s, p, aw, relu=True, bn_scale=bs, bn_shift=bh)
+    assert np.abs(y2 - (2.0 * np.maximum(ref, 0) - 1.0)).max() <= 1e-5 * np.abs(ref).max()
