@@ -251,6 +251,23 @@ int rtn_ternary_weight_gemm(const float *x, const void *w_codes, int64_t M, int6
                             const float *bn_shift, float *y_out, void *workspace,
                             size_t workspace_bytes, void *stream);
 
+/* conv form of the weight-only ternary layer: x fp32 [Nb][C][H][W], w_codes
+ * RTN_CODE_I8 [O][KH][KW][rtn_padded_k(C)] as written by rtn_ternarize_pack with
+ * RTN_NCHW, zero padding (a padded tap adds nothing), geometry limits as for
+ * rtn_ternary_conv2d_implicit_gemm:
+ *   y[n][o][oh][ow] = alpha_w[o] * sum over in-bounds (c, kh, kw) of x * t_w,
+ * then ReLU / BN affine as above; y_out fp32 [Nb][O][OH][OW].  Same exact split of
+ * the activations and the same error bound with K = C*KH*KW.  workspace:
+ * rtn_weight_conv2d_workspace_bytes(...) bytes, 16-byte aligned, overwritten by
+ * every call.                                                                  */
+size_t rtn_weight_conv2d_workspace_bytes(int64_t Nb, int64_t C, int64_t H, int64_t W, int64_t O, int KH,
+                                         int KW, int pad);
+int rtn_ternary_weight_conv2d(const float *x, const void *w_codes, int64_t Nb, int64_t C, int64_t H,
+                              int64_t W, int64_t O, int KH, int KW, int stride, int pad,
+                              const float *alpha_w, rtn_gran gran_w, int relu, const float *bn_scale,
+                              const float *bn_shift, float *y_out, void *workspace,
+                              size_t workspace_bytes, void *stream);
+
 /* Stand-alone epilogue on stored accumulators (Eq.9 generalised, see
  * rtn_epilogue).  GEMM form: acc, y_out are [M][N] row-major.               */
 int rtn_epilogue_reparam(const int32_t *acc, int64_t M, int64_t N, int64_t K,

@@ -25,7 +25,8 @@ EXPORTS = ["rtn_status_string", "rtn_last_hip_error", "rtn_num_tile_configs", "r
            "rtn_ternarize_pack", "rtn_ternary_gemm", "rtn_conv2d_workspace_bytes",
            "rtn_conv2d_prepare_constants",
            "rtn_ternary_conv2d_implicit_gemm", "rtn_ternary_conv2d_ternarize",
-           "rtn_weight_gemm_workspace_bytes", "rtn_ternary_weight_gemm", "rtn_epilogue_reparam",
+           "rtn_weight_gemm_workspace_bytes", "rtn_ternary_weight_gemm",
+           "rtn_weight_conv2d_workspace_bytes", "rtn_ternary_weight_conv2d", "rtn_epilogue_reparam",
            "rtn_epilogue_reparam_conv2d"]
 
 
@@ -82,6 +83,11 @@ def lib():
         L.rtn_weight_gemm_workspace_bytes.argtypes = [i64, i64, i64]
         L.rtn_ternary_weight_gemm.restype = ci
         L.rtn_ternary_weight_gemm.argtypes = [vp, vp, i64, i64, i64, vp, ci, ci, vp, vp, vp, vp, C.c_size_t, vp]
+        L.rtn_weight_conv2d_workspace_bytes.restype = C.c_size_t
+        L.rtn_weight_conv2d_workspace_bytes.argtypes = [i64, i64, i64, i64, i64, ci, ci, ci]
+        L.rtn_ternary_weight_conv2d.restype = ci
+        L.rtn_ternary_weight_conv2d.argtypes = [vp, vp, i64, i64, i64, i64, i64, ci, ci, ci, ci, vp, ci, ci, vp,
+                                                vp, vp, vp, C.c_size_t, vp]
         L.rtn_epilogue_reparam.restype = ci
         L.rtn_epilogue_reparam.argtypes = [vp, i64, i64, i64, vp, vp, vp]
         L.rtn_epilogue_reparam_conv2d.restype = ci
@@ -277,6 +283,27 @@ def ternary_weight_gemm(x, w_codes, M, N, K, alpha_w, relu=False, bn_scale=None,
         None if bn_shift is None else _dev(bn_shift, torch.float32), _dev(y_out, torch.float32),
         C.c_void_p(workspace.data_ptr()), workspace.numel(), _stream())
     _check(rc, "rtn_ternary_weight_gemm")
+    return y_out
+
+
+def ternary_weight_conv2d(x, w_codes, O, KH, KW, stride, pad, alpha_w, relu=False, bn_scale=None,
+                          bn_shift=None, y_out=None, workspace=None):
+    """conv form of the weight-only ternary layer: x cuda float32 [Nb,C,H,W], w_codes int8
+    [O,KH,KW,Cpad].  Returns y float32 [Nb,O,OH,OW]."""
+    Nb, Cc, H, W = x.shape
+    OH, OW = conv_out_hw(H, W, KH, KW, stride, pad)
+    if y_out is None:
+        y_out = torch.empty((Nb, O, OH, OW), dtype=torch.float32, device=x.device)
+    if workspace is None:
+        workspace = torch.empty(lib().rtn_weight_conv2d_workspace_bytes(Nb, Cc, H, W, O, KH, KW, pad),
+                                dtype=torch.uint8, device=x.device)
+    ga = _Gran(alpha_w)
+    rc = lib().rtn_ternary_weight_conv2d(
+        _dev(x, torch.float32), C.c_void_p(w_codes.data_ptr()), Nb, Cc, H, W, O, KH, KW, stride, pad, ga.ptr,
+        ga.gran, int(bool(relu)), None if bn_scale is None else _dev(bn_scale, torch.float32),
+        None if bn_shift is None else _dev(bn_shift, torch.float32), _dev(y_out, torch.float32),
+        C.c_void_p(workspace.data_ptr()), workspace.numel(), _stream())
+    _check(rc, "rtn_ternary_weight_conv2d")
     return y_out
 
 

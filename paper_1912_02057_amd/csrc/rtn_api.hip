@@ -344,6 +344,50 @@ int rtn_ternary_weight_gemm(const float* x, const void* w_codes, int64_t M, int6
     return he == hipSuccess ? RTN_OK : hip_fail(he);
 }
 
+size_t rtn_weight_conv2d_workspace_bytes(int64_t Nb, int64_t C, int64_t H, int64_t W, int64_t O, int KH, int KW,
+                                         int pad)
+{
+    rtn::ConvGeom g = {};
+    if (make_geom(Nb, C, H > KH ? H : KH, W > KW ? W : KW, O, KH, KW, 1, pad, RTN_PAD_TRUE_ZERO, g) != RTN_OK) return 0;
+    if (H <= 0 || W <= 0) return 0;
+    const size_t cp = (size_t)pad64(C);
+    return (size_t)3 * (size_t)Nb * (size_t)H * (size_t)W * cp * 2u + (size_t)O * KH * KW * cp * 2u + 16u +
+           rtn_conv2d_workspace_bytes(O, KH, KW, pad);
+}
+
+int rtn_ternary_weight_conv2d(const float* x, const void* w_codes, int64_t Nb, int64_t C, int64_t H, int64_t W,
+                              int64_t O, int KH, int KW, int stride, int pad, const float* alpha_w,
+                              rtn_gran gran_w, int relu, const float* bn_scale, const float* bn_shift,
+                              float* y_out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!x || !w_codes || !alpha_w || !y_out) return RTN_ERR_NULL;
+    if (bn_shift && !bn_scale) return RTN_ERR_NULL;
+    rtn::WConvArgs a = {};
+    int rc = make_geom(Nb, C, H, W, O, KH, KW, stride, pad, RTN_PAD_TRUE_ZERO, a.g);
+    if (rc != RTN_OK) return rc;
+    // three planes of K bytes each are walked by 32-bit offsets
+    if (3 * (int64_t)a.g.Cpad * 2 * KH * KW > kMaxK || Nb * H * W * (int64_t)a.g.Cpad > (int64_t)1 << 36)
+        return RTN_ERR_SHAPE;
+    if (!aligned(x, 4) || !aligned(w_codes, 16) || !aligned(y_out, 4) || !aligned(bn_scale, 4) ||
+        !aligned(bn_shift, 4))
+        return RTN_ERR_ALIGN;
+    if (gran_w != RTN_SCALAR && gran_w != RTN_VECTOR) return RTN_ERR_UNSUPPORTED;
+    if ((rc = make_param(alpha_w, gran_w, false, a.ep.alpha_w)) != RTN_OK) return rc;
+    if (!workspace || workspace_bytes < rtn_weight_conv2d_workspace_bytes(Nb, C, H, W, O, KH, KW, pad))
+        return RTN_ERR_WORKSPACE;
+    if (!aligned(workspace, 16)) return RTN_ERR_ALIGN;
+    a.ep.alpha_a.s = 1.0f;
+    a.ep.relu = relu != 0;
+    a.ep.bn_scale = bn_scale;
+    a.ep.bn_shift = bn_shift;
+    a.x = x;
+    a.w = (const int8_t*)w_codes;
+    a.y = y_out;
+    a.workspace = workspace;
+    const hipError_t he = rtn::launch_wconv(a, (hipStream_t)stream);
+    return he == hipSuccess ? RTN_OK : hip_fail(he);
+}
+
 int rtn_epilogue_reparam(const int32_t* acc, int64_t M, int64_t N, int64_t K, const rtn_epilogue* ep,
                          float* y_out, void* stream)
 {

@@ -106,6 +106,18 @@ struct WGemmArgs {
     EpiArgs ep;        // alpha_a = 1, beta_a = 0, beta_w = 0; alpha_w, relu, bn as given
 };
 hipError_t launch_wgemm(const WGemmArgs& a, hipStream_t st);
+
+// conv form: x fp32 NCHW, w int8 [O][KH][KW][Cpad] (g.Cpad in elements), y fp32 NCHW;
+// workspace: 3 activation planes + weights as bf16, then the epilogue table
+struct WConvArgs {
+    const float* x;
+    const int8_t* w;
+    ConvGeom g;
+    float* y;
+    void* workspace;
+    EpiArgs ep;
+};
+hipError_t launch_wconv(const WConvArgs& a, hipStream_t st);
 hipError_t launch_conv_mfma(const ConvArgs& a, hipStream_t st);
 // Tile configuration override for tuning and tests (-1 = heuristic).
 int tile_config_count();

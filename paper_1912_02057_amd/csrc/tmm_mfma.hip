@@ -68,9 +68,11 @@ struct TmmParams {
     // ReLU; the fp32 value that is ternarized is also stored when y is given
     const float* res;
     int relu_out;
-    // bf16 operands (DT = 1): the Q rows are qwrap bytes long and are walked again
-    // from the start each time the K offset passes their end
-    unsigned qwrap;
+    // bf16 operands (DT = 1): the weight rows (GEMM: Q, conv: P) are wwrap bytes long and
+    // are walked again from the start each time the K offset passes their end; the
+    // conv's three activation planes lie qplane bytes apart
+    unsigned wwrap;
+    int64_t qplane;
 };
 
 // Border classes of a conv window and the LDS bytes of the epilogue table of a
@@ -165,7 +167,7 @@ __device__ __forceinline__ void wait_groups(int groups)
 template <int BP, int BQ, int WGP, int WGQ, int NS, int MINW, bool CONV, int TERN = 0, int HC = 0, int DT = 0>
 __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
 {
-    static_assert(DT == 0 || (!CONV && TERN == 0), "bf16 operands: GEMM only");
+    static_assert(DT == 0 || (TERN == 0 && HC == 0), "bf16 operands: plain GEMM and plain conv only");
     static_assert(!TERN || CONV, "the ternarizing epilogue belongs to the conv");
     static_assert(WGP * WGQ == 4, "4 waves per block");
     constexpr bool HALO = HC != 0;
@@ -265,24 +267,30 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
     int is_kh = 0, is_kw = 0;
     const int8_t* zero_page = (const int8_t*)g_zero16;
 
+    int64_t l_plane = 0;  // DT = 1 conv: byte offset of the activation plane being walked
     auto issue_begin = [&](int kt) {
         is_sbase = lds0 + (unsigned)(roff + (kt % NS) * STAGE);
         is_koffP = (int64_t)kt * 64;
+        if (CONV && DT == 1) is_koffP = (int64_t)((unsigned)is_koffP % prm.wwrap);
         if (CONV && !HALO) {
             is_kh = l_kh;
             is_kw = l_kw;
-            is_koffQ = ((int64_t)l_kh * g.W + l_kw) * g.Cpad + l_cc;
+            is_koffQ = ((int64_t)l_kh * g.W + l_kw) * g.Cpad + l_cc + l_plane;
             l_cc += 64;
             if (l_cc == g.Cpad) {
                 l_cc = 0;
                 if (++l_kw == g.KW) {
                     l_kw = 0;
                     ++l_kh;
+                    if (DT == 1 && l_kh == g.KH) {
+                        l_kh = 0;
+                        l_plane += prm.qplane;
+                    }
                 }
             }
         } else {
             is_koffQ = is_koffP;
-            if (DT == 1) is_koffQ = (int64_t)((unsigned)is_koffP % prm.qwrap);
+            if (DT == 1) is_koffQ = (int64_t)((unsigned)is_koffP % prm.wwrap);
         }
     };
     // the idx-th of the DPS direct loads of the step set up by issue_begin()
@@ -427,7 +435,7 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
             }
             __builtin_amdgcn_sched_barrier(0);
         }
-        if (CONV) {
+        if (CONV && DT == 0) {
 #pragma unroll
             for (int j = 0; j < TQ; ++j)
 #pragma unroll
@@ -800,8 +808,8 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
 #pragma unroll
                     for (int j = 0; j < TQ; ++j) {
                         if (FULL || (ook && mok[j])) {
-                            const int D = acc[i][j][r];
-                            if (ACC) put(D, accp[j] + rowoff);
+                            const auto D = acc[i][j][r];
+                            if (ACC) put((int)D, accp[j] + rowoff);
                             if (Y) {
                                 double v = g1 * (double)D + (c2 * Sa[j] + cc[j]);
                                 v = __builtin_fmax(v, relu_floor);
@@ -854,7 +862,7 @@ __global__ __launch_bounds__(256) void k_conv_class_consts(const int32_t* tap, C
             int s = 0, taps = 0;
             for (int kh = khl; kh <= khh; ++kh)
                 for (int kw = kwl; kw <= kwh; ++kw) {
-                    s += tap[((int64_t)o * g.KH + kh) * g.KW + kw];
+                    s += tap ? tap[((int64_t)o * g.KH + kh) * g.KW + kw] : 0;
                     ++taps;
                 }
             v = ba * pval(ep.alpha_w, o) * (double)s + (double)(g.C * taps) * ba * pval(ep.beta_w, o);
@@ -1119,6 +1127,79 @@ __global__ __launch_bounds__(256) void k_codes_to_bf16(const int8_t* codes, int6
     dst[1] = make_uint4(o[4], o[5], o[6], o[7]);
 }
 
+// The same split for an NCHW activation tensor, written channel-innermost as the conv
+// reads it: out[plane][pixel][Cpad] bf16, plane 0 = hi, 1 = mid, 2 = lo, planes
+// `plane_elems` apart, channels C .. Cpad-1 zero.  One thread: one pixel, 8 channels
+// (lanes run along pixels, so the fp32 reads of a channel are contiguous).
+__global__ __launch_bounds__(256) void k_split_nchw_bf16x3(const float* x, int64_t Nb, int C, int Cpad, int HW,
+                                                           int64_t plane_elems, uint16_t* out)
+{
+    const int64_t npix = Nb * HW;
+    const int64_t pix = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    const int c0 = (int)blockIdx.y * 8;
+    if (pix >= npix) return;
+    const int64_t nb = pix / HW;
+    const int p = (int)(pix - nb * HW);
+    unsigned h[8], md[8], lo[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+        const float v = c0 + e < C ? x[(nb * C + c0 + e) * HW + p] : 0.0f;
+        h[e] = bf16_rn(v);
+        const float r1 = v - __uint_as_float(h[e] << 16);
+        md[e] = bf16_rn(r1);
+        const float r2 = r1 - __uint_as_float(md[e] << 16);
+        lo[e] = bf16_rn(r2);
+    }
+    auto pack8 = [](const unsigned* t) {
+        return make_uint4(t[0] | (t[1] << 16), t[2] | (t[3] << 16), t[4] | (t[5] << 16), t[6] | (t[7] << 16));
+    };
+    uint16_t* row = out + pix * Cpad + c0;
+    *(uint4*)row = pack8(h);
+    *(uint4*)(row + plane_elems) = pack8(md);
+    *(uint4*)(row + 2 * plane_elems) = pack8(lo);
+}
+
+hipError_t launch_wconv(const WConvArgs& a, hipStream_t st)
+{
+    const ConvGeom& g0 = a.g;  // Cpad in elements here
+    const int64_t npix = (int64_t)g0.Nb * g0.H * g0.W;
+    const int64_t plane = npix * g0.Cpad;
+    uint16_t* a3 = (uint16_t*)a.workspace;
+    uint16_t* wb = a3 + 3 * plane;
+    const int64_t wn = (int64_t)g0.O * g0.KH * g0.KW * g0.Cpad;
+    double* tab = (double*)(((uintptr_t)(wb + wn) + 15) & ~(uintptr_t)15);
+    hipLaunchKernelGGL(k_split_nchw_bf16x3, dim3((unsigned)((npix + 255) / 256), (unsigned)(g0.Cpad / 8)), dim3(256), 0,
+                       st, a.x, (int64_t)g0.Nb, g0.C, g0.Cpad, g0.H * g0.W, plane, a3);
+    hipLaunchKernelGGL(k_codes_to_bf16, dim3((unsigned)((wn / 16 + 255) / 256)), dim3(256), 0, st, a.w, wn / 16, wb);
+    ConvArgs c = {};
+    c.g = g0;
+    c.ep = a.ep;
+    hipError_t e = launch_conv_class_consts(c, tab, st);  // g1 = alpha_w, BN rows; the class constants are 0
+    if (e != hipSuccess) return e;
+    TmmParams prm = {};
+    prm.g = g0;
+    prm.g.Cpad = g0.Cpad * 2;  // bytes per pixel row: the kernel's K bookkeeping is in bytes
+    prm.P = (const int8_t*)wb;
+    prm.Q = (const int8_t*)a3;
+    prm.RP = g0.O;
+    prm.RQ = (int)((int64_t)g0.Nb * g0.OH * g0.OW);
+    prm.ldP = (int64_t)g0.KH * g0.KW * g0.Cpad * 2;
+    prm.wwrap = (unsigned)prm.ldP;
+    prm.qplane = plane * 2;
+    prm.nk = (int)(3 * prm.ldP / 64);
+    prm.Klogical = g0.C * g0.KH * g0.KW;
+    prm.y = a.y;
+    prm.cst_cls = tab;
+    prm.ep = a.ep;
+    const int cfg = g_forced_tile >= 0 ? g_forced_tile : pick_tile(g0.O, prm.RQ, true);
+    const int bp = kTileBP[cfg];
+    if (cfg == 13 || cfg == 4 || cfg == 19) return launch_cfg<128, 256, 2, 2, 2, 2, true, 0, 0, 1>(prm, st);
+    if (bp >= 128) return launch_cfg<128, 128, 2, 2, 3, 2, true, 0, 0, 1>(prm, st);
+    if (cfg == 3 || cfg == 7 || cfg == 9 || cfg == 14 || cfg == 15)
+        return launch_cfg<64, 256, 1, 4, 2, 3, true, 0, 0, 1>(prm, st);
+    return launch_cfg<64, 64, 2, 2, 4, 4, true, 0, 0, 1>(prm, st);
+}
+
 hipError_t launch_wgemm(const WGemmArgs& a, hipStream_t st)
 {
     uint16_t* a3 = (uint16_t*)a.workspace;
@@ -1136,7 +1217,7 @@ hipError_t launch_wgemm(const WGemmArgs& a, hipStream_t st)
     prm.RQ = (int)a.N;
     prm.ldP = 3 * a.Kpad * 2;
     prm.ldQ = a.Kpad * 2;
-    prm.qwrap = (unsigned)(a.Kpad * 2);
+    prm.wwrap = (unsigned)(a.Kpad * 2);
     prm.nk = (int)(prm.ldP / 64);
     prm.Klogical = (int)a.K;
     prm.y = a.y;

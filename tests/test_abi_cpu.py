@@ -224,3 +224,30 @@ def test_weight_gemm_rejects(L):
     assert with_(_11=None) == B.RTN_ERR_WORKSPACE
     assert with_(_12=100) == B.RTN_ERR_WORKSPACE
     assert with_(_11=ODD) == B.RTN_ERR_ALIGN
+
+
+def test_weight_conv_rejects(L):
+    call = L.rtn_ternary_weight_conv2d
+    a1 = _f(1.0)
+    ok = [FAKE, FAKE, 1, 64, 8, 8, 64, 3, 3, 1, 1, a1, B.RTN_SCALAR, 0, None, None, FAKE, FAKE, 1 << 24, None]
+
+    def with_(**kw):
+        a = list(ok)
+        for i, v in kw.items():
+            a[int(i[1:])] = v
+        return call(*a)
+    wsb = L.rtn_weight_conv2d_workspace_bytes
+    assert wsb(1, 64, 8, 8, 64, 3, 3, 1) == 3 * 64 * 64 * 2 + 64 * 9 * 64 * 2 + 16 + 64 * 20 * 8
+    assert wsb(1, 64, 8, 8, 64, 3, 3, 3) == 0
+    assert with_(_0=None) == B.RTN_ERR_NULL
+    assert with_(_11=None) == B.RTN_ERR_NULL                    # alpha_w
+    assert with_(_16=None) == B.RTN_ERR_NULL                    # y_out
+    assert with_(_15=FAKE) == B.RTN_ERR_NULL                    # bn_shift without bn_scale
+    assert with_(_7=8) == B.RTN_ERR_UNSUPPORTED                 # kernel size
+    assert with_(_10=3) == B.RTN_ERR_UNSUPPORTED                # pad >= kernel
+    assert with_(_2=0) == B.RTN_ERR_SHAPE
+    assert with_(_1=ODD) == B.RTN_ERR_ALIGN
+    assert with_(_12=5) == B.RTN_ERR_UNSUPPORTED
+    assert with_(_17=None) == B.RTN_ERR_WORKSPACE
+    assert with_(_18=100) == B.RTN_ERR_WORKSPACE
+    assert with_(_17=ODD) == B.RTN_ERR_ALIGN

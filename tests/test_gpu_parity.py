@@ -872,3 +872,72 @@ def test_weight_gemm_4096_sampled_rows():
     rows[0], rows[-1] = 0, 4095
     worst = _wgemm_check(4096, 4096, 4096, seed=5, rows=rows, what="wgemm 4096")
     assert worst < 1.0
+
+
+def _wconv_check(shape, batch, seed, relu=False, bn=False, Wx=None, images=None, what=""):
+    """conv form of the weight-only layer against the oracle; tolerance as for the GEMM
+    form, with the sum of |x| taken over each output's window (a conv of |x| with ones)."""
+    rng = np.random.default_rng(seed)
+    H, W = shape.H, (shape.H if Wx is None else Wx)
+    x = rng.standard_normal((batch, shape.C, H, W)).astype(np.float32)
+    w = (rng.standard_normal((shape.O, shape.C, shape.k, shape.k)) * 0.05).astype(np.float32)
+    dw = wl.twn_threshold(w, axis=0)
+    aw = rng.uniform(0.5, 1.5, shape.O).astype(np.float32)
+    bs = rng.uniform(0.5, 1.5, shape.O).astype(np.float32) if bn else None
+    bh = rng.normal(0, 0.1, shape.O).astype(np.float32) if bn else None
+    tw = orc.ternarize(w, -dw, dw)
+    cw, _ = B.ternarize_pack(T.dev(w), T.thr_arg(-dw), T.thr_arg(dw), want_sum=False)
+    y = B.ternary_weight_conv2d(T.dev(x), cw, shape.O, shape.k, shape.k, shape.stride, shape.pad, T.dev(aw),
+                                relu=relu, bn_scale=None if bs is None else T.dev(bs),
+                                bn_shift=None if bh is None else T.dev(bh))
+    torch.cuda.synchronize()
+    y = y.cpu().numpy()
+    sel = list(range(batch)) if images is None else images
+    ref = orc.wconv(x[sel], tw, shape.stride, shape.pad, aw, relu=relu, bn_scale=bs, bn_shift=bh).astype(np.float64)
+    absum = torch.nn.functional.conv2d(torch.from_numpy(np.abs(x[sel]).astype(np.float64)),
+                                       torch.ones(1, shape.C, shape.k, shape.k, dtype=torch.float64),
+                                       stride=shape.stride, padding=shape.pad).numpy()       # [n,1,OH,OW]
+    scale = absum * np.abs(aw.astype(np.float64))[None, :, None, None]
+    if bn:
+        scale = scale * np.abs(bs.astype(np.float64))[None, :, None, None]
+    K = shape.C * shape.k * shape.k
+    tol = (4.0 * np.sqrt(3.0 * K) + 8.0) * 2.0 ** -24 * scale + 1.2e-7 * np.abs(ref) + 1e-30
+    err = np.abs(y[sel].astype(np.float64) - ref)
+    assert y.shape[1:] == ref.shape[1:]
+    assert (err <= tol).all(), "%s: worst err/tol %.3g" % (what, float((err / tol).max()))
+
+
+@pytest.mark.parametrize("shape", CONV_SHAPES, ids=lambda s: s.name)
+def test_weight_conv_vs_oracle(shape):
+    _say("weight-only conv %s" % (shape,))
+    _wconv_check(shape, 3, seed=len(shape.name), what=shape.name)
+    _wconv_check(shape, 2, seed=len(shape.name) + 50, relu=True, bn=True, what=shape.name + " relu bn")
+
+
+@pytest.mark.parametrize("cfg", [0, 1, 7, 13])
+def test_weight_conv_tile_configs(cfg, tile_reset):
+    _say("weight-only conv, tile config %d" % cfg)
+    B.set_tile_config(cfg)
+    _wconv_check(wl.ConvShape("t", 64, 13, 200, 3, 2, 1), 7, seed=cfg, what="wconv cfg %d" % cfg)
+    _wconv_check(wl.ConvShape("u", 128, 12, 136, 3, 1, 1), 3, seed=cfg + 9, Wx=10, what="wconv cfg %d rect" % cfg)
+
+
+def test_weight_conv_exact_on_ternary_activations():
+    _say("weight-only conv on ternary activations")
+    shape = wl.ConvShape("e", 64, 10, 96, 3, 1, 1)
+    rng = np.random.default_rng(3)
+    ta = rng.integers(-1, 2, size=(2, 64, 10, 10)).astype(np.int8)
+    w = (rng.standard_normal((96, 64, 3, 3)) * 0.05).astype(np.float32)
+    dw = wl.twn_threshold(w, axis=0)
+    tw = orc.ternarize(w, -dw, dw)
+    cw, _ = B.ternarize_pack(T.dev(w), T.thr_arg(-dw), T.thr_arg(dw), want_sum=False)
+    y = B.ternary_weight_conv2d(T.dev(ta.astype(np.float32)), cw, 96, 3, 3, 1, 1, 1.0)
+    torch.cuda.synchronize()
+    assert (y.cpu().numpy() == orc.conv_acc(ta, tw, 1, 1).astype(np.float32)).all()
+
+
+@pytest.mark.parametrize("idx", [0, 4, 6, 10, 15])
+def test_weight_conv_resnet18_layers_batch64_sampled_images(idx):
+    shape = wl.resnet18_ternary_layers()[idx]
+    _say("weight-only conv, resnet18 b64 %s" % (shape,))
+    _wconv_check(shape, 64, seed=800 + idx, relu=True, bn=True, images=[0, 63], what=shape.name)
