@@ -32,7 +32,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--batch", type=int, default=256)
     ap.add_argument("--workload", default="resnet18_ternary_convs",
-                    choices=["resnet18_ternary_convs", "gemm4096", "wgemm4096"])
+                    choices=["resnet18_ternary_convs", "gemm4096", "wgemm4096", "resnet18_weight_only_convs"])
     ap.add_argument("--tile", type=int, default=-1, help="force an MFMA tile configuration (tuning)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-images", type=int, default=128,
@@ -174,6 +174,37 @@ def main():
         macs_step = sum(l["sh"].macs(args.batch) for l in layers)
         workload = "ResNet-18 ternary conv stack (19 layers), batch %d, fp32 NCHW in/out" % args.batch
         nlaunch = len(layers)
+    elif args.workload == "resnet18_weight_only_convs":
+        # the same 19 layer shapes with ternary weights and fp32 activations (one call per layer:
+        # activation split, weight copy, epilogue table, bf16 matrix-core conv)
+        wlayers = []
+        for i, sh in enumerate(wl.resnet18_ternary_layers()):
+            case = wl.conv_case(sh, batch=args.batch, seed=100 + i, per_channel=True, bn=True)
+            dw = np.asarray(case["delta_w"])
+            cw, _ = B.ternarize_pack(to_dev(case["w"]), garg(-dw), garg(dw), want_sum=False)    # S0, offline
+            wlayers.append(dict(sh=sh, x=to_dev(case["x"]), cw=cw, aw=to_dev(case["alpha_w"]),
+                                bs=to_dev(case["bn_scale"]), bh=to_dev(case["bn_shift"]),
+                                y=torch.empty((args.batch, sh.O, sh.OH, sh.OH), dtype=torch.float32, device=dev),
+                                ws=torch.empty(B.lib().rtn_weight_conv2d_workspace_bytes(
+                                    args.batch, sh.C, sh.H, sh.H, sh.O, sh.k, sh.k, sh.pad), dtype=torch.uint8,
+                                    device=dev)))
+            del case
+
+        def step(timers=None):
+            for i, l in enumerate(wlayers):
+                sh = l["sh"]
+                if timers is not None:
+                    timers[i][0].record()
+                    timers[i][1].record()
+                B.ternary_weight_conv2d(l["x"], l["cw"], sh.O, sh.k, sh.k, sh.stride, sh.pad, l["aw"], relu=True,
+                                        bn_scale=l["bs"], bn_shift=l["bh"], y_out=l["y"], workspace=l["ws"])
+                if timers is not None:
+                    timers[i][2].record()
+
+        macs_step = sum(l["sh"].macs(args.batch) for l in wlayers)
+        workload = "ResNet-18 conv stack (19 layers), ternary weights x fp32 activations, batch %d" % args.batch
+        nlaunch = len(wlayers)
+        layers = [dict(sh=None)] * nlaunch
     elif args.workload == "wgemm4096":
         # weight-only ternary GEMM: fp32 activations N(0,1), ternary weights, per-column alpha
         rng = np.random.Generator(np.random.PCG64(3))
@@ -335,6 +366,14 @@ def main():
                         launches_per_step=nlaunch, avg_launch_us=round(conv_total_s / nlaunch * 1e6, 1),
                         bytes_per_launch=round(alg_bytes_launch, 0),
                         mfma_tops=round(achieved_tops, 1), mfma_frac=round(achieved_tops / INT8_PEAK_TOPS, 4))
+    elif args.workload == "resnet18_weight_only_convs":
+        bf16_tflops = 3 * achieved_tops
+        roofline = dict(bound="mfma", kernel="activation split + k_tmm (bf16 MFMA implicit-GEMM conv, fp32 accumulate)",
+                        achieved=round(bf16_tflops, 1), peak=BF16_PEAK_TFLOPS, unit="TFLOP/s",
+                        frac=round(bf16_tflops / BF16_PEAK_TFLOPS, 4), traffic=None,
+                        launches_per_step=nlaunch, avg_launch_us=round(conv_total_s / nlaunch * 1e6, 1),
+                        flops_per_launch=6 * macs_step / nlaunch,
+                        effective_fp32_tflops=round(achieved_tops, 1), fp32_vector_peak_tflops=157.3)
     elif args.workload == "wgemm4096":
         # the call = split kernel + weight conversion + matrix-core GEMM; the GEMM executes three
         # bf16 products per ternary MAC (the three terms of the exact fp32 split)
@@ -371,6 +410,17 @@ def main():
                 t_cpu += time.perf_counter() - c0
                 macs_cpu += sh.macs(n_img)
             sample = "all 19 layers, %d images each (of %d)" % (n_img, args.batch)
+        elif args.workload == "resnet18_weight_only_convs":
+            n_img = max(1, args.cpu_images // 8)
+            for i, sh in enumerate(wl.resnet18_ternary_layers()):
+                case = wl.conv_case(sh, batch=n_img, seed=100 + i, per_channel=True, bn=True)
+                c0 = time.perf_counter()
+                tw = orc.ternarize(case["w"], -case["delta_w"], case["delta_w"])
+                orc.wconv(case["x"], tw, sh.stride, sh.pad, case["alpha_w"], relu=True,
+                          bn_scale=case["bn_scale"], bn_shift=case["bn_shift"])
+                t_cpu += time.perf_counter() - c0
+                macs_cpu += sh.macs(n_img)
+            sample = "all 19 layers, %d images each (of %d)" % (n_img, args.batch)
         elif args.workload == "wgemm4096":
             rows = np.arange(0, 4096, 4096 // 64, dtype=np.int64)
             c0 = time.perf_counter()
@@ -398,10 +448,11 @@ def main():
         "metric": "effective ternary MAC/s (dense MAC count, S1+S2+S3+S4 per layer), ResNet-18 ternary layers"
         if args.workload == "resnet18_ternary_convs" else
         ("effective MAC/s, weight-only ternary GEMM" if args.workload == "wgemm4096"
-         else "effective ternary MAC/s, ternary GEMM"),
+         else ("effective MAC/s, weight-only ternary convs of ResNet-18"
+               if args.workload == "resnet18_weight_only_convs" else "effective ternary MAC/s, ternary GEMM")),
         "value": round(value, 3), "unit": "TMAC/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16x3" if args.workload == "wgemm4096" else "i8", "data": "synthetic",
+        "vs_baseline": None, "dtype": "bf16x3" if args.workload in ("wgemm4096", "resnet18_weight_only_convs") else "i8", "data": "synthetic",
         "config": {"workload": workload, "batch": args.batch, "tile": args.tile},
         "tops": round(2 * value, 1), "pct_int8_mfma_peak": round(100 * 2 * value / INT8_PEAK_TOPS, 2),
         "contraction_only": {"tmacs": round(macs_step / conv_total_s / 1e12, 3),

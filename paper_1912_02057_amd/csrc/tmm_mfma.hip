@@ -1129,34 +1129,56 @@ __global__ __launch_bounds__(256) void k_codes_to_bf16(const int8_t* codes, int6
 
 // The same split for an NCHW activation tensor, written channel-innermost as the conv
 // reads it: out[plane][pixel][Cpad] bf16, plane 0 = hi, 1 = mid, 2 = lo, planes
-// `plane_elems` apart, channels C .. Cpad-1 zero.  One thread: one pixel, 8 channels
-// (lanes run along pixels, so the fp32 reads of a channel are contiguous).
+// `plane_elems` apart, channels C .. Cpad-1 zero.  A block transposes 64 pixels x 64
+// channels through LDS: lanes run along pixels for the fp32 reads (256 contiguous
+// bytes per channel) and along channels for the stores (128 contiguous bytes per pixel
+// and plane).  LDS rows are 33 dwords (two bf16 per dword), so both phases are free of
+// bank conflicts.
 __global__ __launch_bounds__(256) void k_split_nchw_bf16x3(const float* x, int64_t Nb, int C, int Cpad, int HW,
                                                            int64_t plane_elems, uint16_t* out)
 {
+    __shared__ unsigned tile[3][64][33];
     const int64_t npix = Nb * HW;
-    const int64_t pix = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    const int c0 = (int)blockIdx.y * 8;
-    if (pix >= npix) return;
-    const int64_t nb = pix / HW;
-    const int p = (int)(pix - nb * HW);
-    unsigned h[8], md[8], lo[8];
+    const int64_t pix0 = (int64_t)blockIdx.x * 64;
+    const int c0 = (int)blockIdx.y * 64;
+    const int tid = threadIdx.x;
+    {
+        const int p = tid & 63, cg = tid >> 6;  // this thread: pixel p, channels c0 + 16 cg .. + 15
+        const int64_t pix = pix0 + p;
+        const bool pok = pix < npix;
+        const int64_t nb = pok ? pix / HW : 0;
+        const int q = pok ? (int)(pix - nb * HW) : 0;
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-        const float v = c0 + e < C ? x[(nb * C + c0 + e) * HW + p] : 0.0f;
-        h[e] = bf16_rn(v);
-        const float r1 = v - __uint_as_float(h[e] << 16);
-        md[e] = bf16_rn(r1);
-        const float r2 = r1 - __uint_as_float(md[e] << 16);
-        lo[e] = bf16_rn(r2);
+        for (int e = 0; e < 16; e += 2) {
+            unsigned w[3] = {0, 0, 0};
+#pragma unroll
+            for (int s = 0; s < 2; ++s) {
+                const int c = c0 + 16 * cg + e + s;
+                const float v = (pok && c < C) ? x[(nb * C + c) * HW + q] : 0.0f;
+                const unsigned h = bf16_rn(v);
+                const float r1 = v - __uint_as_float(h << 16);
+                const unsigned md = bf16_rn(r1);
+                const float r2 = r1 - __uint_as_float(md << 16);
+                const unsigned lo = bf16_rn(r2);
+                w[0] |= h << (16 * s);
+                w[1] |= md << (16 * s);
+                w[2] |= lo << (16 * s);
+            }
+#pragma unroll
+            for (int pl = 0; pl < 3; ++pl) tile[pl][p][8 * cg + e / 2] = w[pl];
+        }
     }
-    auto pack8 = [](const unsigned* t) {
-        return make_uint4(t[0] | (t[1] << 16), t[2] | (t[3] << 16), t[4] | (t[5] << 16), t[6] | (t[7] << 16));
-    };
-    uint16_t* row = out + pix * Cpad + c0;
-    *(uint4*)row = pack8(h);
-    *(uint4*)(row + plane_elems) = pack8(md);
-    *(uint4*)(row + 2 * plane_elems) = pack8(lo);
+    __syncthreads();
+    // 3 planes x 64 pixels x 8 sixteen-byte parts = 1536 stores, 6 per thread
+#pragma unroll
+    for (int i = 0; i < 6; ++i) {
+        const int u = tid + 256 * i;
+        const int pl = u >> 9, p = (u >> 3) & 63, part = u & 7;
+        const int64_t pix = pix0 + p;
+        if (pix >= npix) continue;
+        const unsigned* src = &tile[pl][p][4 * part];
+        *(uint4*)(out + pl * plane_elems + pix * Cpad + c0 + 8 * part) = make_uint4(src[0], src[1], src[2], src[3]);
+    }
 }
 
 hipError_t launch_wconv(const WConvArgs& a, hipStream_t st)
@@ -1168,7 +1190,7 @@ hipError_t launch_wconv(const WConvArgs& a, hipStream_t st)
     uint16_t* wb = a3 + 3 * plane;
     const int64_t wn = (int64_t)g0.O * g0.KH * g0.KW * g0.Cpad;
     double* tab = (double*)(((uintptr_t)(wb + wn) + 15) & ~(uintptr_t)15);
-    hipLaunchKernelGGL(k_split_nchw_bf16x3, dim3((unsigned)((npix + 255) / 256), (unsigned)(g0.Cpad / 8)), dim3(256), 0,
+    hipLaunchKernelGGL(k_split_nchw_bf16x3, dim3((unsigned)((npix + 63) / 64), (unsigned)(g0.Cpad / 64)), dim3(256), 0,
                        st, a.x, (int64_t)g0.Nb, g0.C, g0.Cpad, g0.H * g0.W, plane, a3);
     hipLaunchKernelGGL(k_codes_to_bf16, dim3((unsigned)((wn / 16 + 255) / 256)), dim3(256), 0, st, a.w, wn / 16, wb);
     ConvArgs c = {};
