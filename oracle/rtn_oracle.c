@@ -445,6 +445,32 @@ void orc_wconv(const float *x, const int8_t *tw, int64_t Nb, int64_t C, int64_t 
                 }
 }
 
+/* ----------------------------------------------------------------- O10 --
+ * Backward of the reparameterized ternary activation  Abar^t = gamma*Q(Abar) + beta
+ * (Section "Backward Update in Reparameterized Ternarization").  With g = dL/dAbar^t:
+ *   dL/dgamma = sum_i A^t_i * g_i,   dL/dbeta = sum_i g_i          (Eq.6, layer-wise)
+ *   dL/dAbar_i = gamma * 1[|Abar_i| <= 1] * g_i                     (Eq.7, clipped STE)
+ * A^t = (a > hi) - (a < lo) as in O1.  The sums are taken in double in index
+ * order; gamma*g is one fp32 product.  sums[0] = dgamma, sums[1] = dbeta.      */
+void orc_act_backward(const float *a, const float *g, int64_t n, float lo, float hi, float gamma,
+                      float *da, double *sums)
+{
+    double sg = 0.0, sb = 0.0;
+    for (int64_t i = 0; i < n; ++i) {
+        int t = (a[i] > hi) - (a[i] < lo);
+        sg += (double)t * (double)g[i];
+        sb += (double)g[i];
+        if (da) {
+            volatile float p = gamma * g[i]; /* volatile: one fp32 rounding of the product */
+            float q = p;
+            int inside = (a[i] <= 1.0f) && (a[i] >= -1.0f); /* |a| <= 1; NaN is outside */
+            da[i] = inside ? q : 0.0f;
+        }
+    }
+    sums[0] = sg;
+    sums[1] = sb;
+}
+
 /* Conv form of O6: direct conv of the reparameterized values in double.
  * pad_true_zero = 1 pads the value tensor (aa*t+ba) with 0.0;
  * pad_true_zero = 0 pads the code tensor with 0, i.e. the value with ba.     */

@@ -354,3 +354,14 @@ def wconv(x, tw, stride, pad, alpha_w, relu=False, bn_scale=None, bn_shift=None)
     lib().orc_wconv(_p(x), _p(tw), _i64(Nb), _i64(Cc), _i64(H), _i64(W), _i64(O), _i64(KH), _i64(KW),
                     _i64(stride), _i64(pad), _p(aw), C.c_int(sw_), C.c_int(int(relu)), _p(bs), _p(bh), _p(y))
     return y
+
+
+def act_backward(a, g, lo, hi, gamma, want_da=True):
+    """O10.  a, g: float32, same shape -> (da float32 or None, dgamma float, dbeta float)."""
+    a, g = _c(a, np.float32), _c(g, np.float32)
+    assert a.shape == g.shape
+    da = np.empty(a.shape, dtype=np.float32) if want_da else None
+    sums = np.zeros(2, dtype=np.float64)
+    lib().orc_act_backward(_p(a), _p(g), _i64(a.size), _f32(float(lo)), _f32(float(hi)), _f32(float(gamma)),
+                           _p(da), _p(sums))
+    return da, float(sums[0]), float(sums[1])

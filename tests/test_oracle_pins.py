@@ -488,3 +488,38 @@ def test_wconv_vs_torch_float64_conv_and_integer_conv():
     bs, bh = np.full(O, 2.0, np.float32), np.full(O, -1.0, np.float32)
     y2 = orc.wconv(x, tw, s, p, aw, relu=True, bn_scale=bs, bn_shift=bh)
     assert np.abs(y2 - (2.0 * np.maximum(ref, 0) - 1.0)).max() <= 1e-5 * np.abs(ref).max()
+
+
+# ----------------------------------------------------------------- O10 ----
+def test_act_backward_hand_listed():
+    a = np.array([0.2, 0.7, -0.7, 1.0, -1.0, 1.5, -3.0, 0.5, np.nan], np.float32)
+    g = np.array([1.0, 2.0, 4.0, 8.0, 16.0, 32.0, 64.0, 128.0, 256.0], np.float32)
+    da, dgam, dbeta = orc.act_backward(a, g, -0.5, 0.5, 0.5)
+    # codes at Delta = 0.5:       0    1    -1    1    -1    1    -1    0 (tie)  0 (NaN)
+    assert dgam == 2.0 - 4.0 + 8.0 - 16.0 + 32.0 - 64.0
+    assert dbeta == float(g.astype(np.float64).sum())
+    # |a| <= 1 inclusive (Eq.7); saturated and NaN entries get no gradient
+    assert da.tolist() == [0.5, 1.0, 2.0, 4.0, 8.0, 0.0, 0.0, 64.0, 0.0]
+
+
+def test_act_backward_vs_torch_autograd_of_the_ste_form():
+    # y = gamma * (Q(a) + hardtanh(a) - hardtanh(a).detach()) + beta has forward value gamma*Q(a)+beta and
+    # the clipped straight-through derivative; autograd then yields Eq.6 and Eq.7.
+    rng = np.random.default_rng(51)
+    a = (rng.standard_normal(5000) * 0.9).astype(np.float32)
+    a = a[np.abs(np.abs(a) - 1.0) > 1e-3]            # keep clear of hardtanh's boundary convention
+    g = rng.standard_normal(a.size).astype(np.float32)
+    gamma, beta, delta = 1.37, -0.2, 0.5
+    ta = torch.tensor(a, dtype=torch.float64, requires_grad=True)
+    tg, tb = torch.tensor(gamma, dtype=torch.float64, requires_grad=True), \
+        torch.tensor(beta, dtype=torch.float64, requires_grad=True)
+    q = (ta > delta).double() - (ta < -delta).double()
+    ht = torch.nn.functional.hardtanh(ta)
+    y = tg * (q.detach() + ht - ht.detach()) + tb
+    y.backward(torch.tensor(g, dtype=torch.float64))
+    da, dgam, dbeta = orc.act_backward(a, g, -delta, delta, gamma)
+    assert abs(dgam - float(tg.grad)) <= 1e-9 * max(1.0, abs(float(tg.grad)))
+    assert abs(dbeta - float(tb.grad)) <= 1e-9 * max(1.0, abs(float(tb.grad)))
+    assert np.abs(da - ta.grad.numpy()).max() <= 1e-6 * np.abs(ta.grad.numpy()).max()
+    # gamma * g is ONE fp32 product
+    assert (da[np.abs(a) <= 1] == (np.float32(gamma) * g)[np.abs(a) <= 1]).all()
