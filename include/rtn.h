@@ -268,6 +268,22 @@ int rtn_ternary_weight_conv2d(const float *x, const void *w_codes, int64_t Nb, i
                               const float *bn_shift, float *y_out, void *workspace,
                               size_t workspace_bytes, void *stream);
 
+/* Backward of the reparameterized ternary activation Abar^t = gamma*Q(Abar) + beta
+ * (Section "Backward Update in Reparameterized Ternarization"), for n elements:
+ *   grad_gamma_beta[0] = sum_i t_i * g_i,  grad_gamma_beta[1] = sum_i g_i      (Eq.6)
+ *   grad_in[i] = gamma * g_i if |a_i| <= 1, else 0                            (Eq.7)
+ * with t = (a > thr_hi) - (a < thr_lo) as in rtn_ternarize_pack and g = grad_out.
+ * a, grad_out, grad_in (nullable): DEVICE fp32 [n]; thr_lo, thr_hi, gamma: HOST
+ * floats; grad_gamma_beta: DEVICE double[2], overwritten.  The sums are formed in
+ * double, per 4096-element block and then in block order, so they are reproducible
+ * run to run; gamma*g is one fp32 product.  workspace:
+ * rtn_activation_backward_workspace_bytes(n) bytes, 8-byte aligned.             */
+size_t rtn_activation_backward_workspace_bytes(int64_t n);
+int rtn_activation_backward(const float *a, const float *grad_out, int64_t n, const float *thr_lo,
+                            const float *thr_hi, const float *gamma, float *grad_in,
+                            double *grad_gamma_beta, void *workspace, size_t workspace_bytes,
+                            void *stream);
+
 /* Stand-alone epilogue on stored accumulators (Eq.9 generalised, see
  * rtn_epilogue).  GEMM form: acc, y_out are [M][N] row-major.               */
 int rtn_epilogue_reparam(const int32_t *acc, int64_t M, int64_t N, int64_t K,

@@ -26,7 +26,8 @@ EXPORTS = ["rtn_status_string", "rtn_last_hip_error", "rtn_num_tile_configs", "r
            "rtn_conv2d_prepare_constants",
            "rtn_ternary_conv2d_implicit_gemm", "rtn_ternary_conv2d_ternarize",
            "rtn_weight_gemm_workspace_bytes", "rtn_ternary_weight_gemm",
-           "rtn_weight_conv2d_workspace_bytes", "rtn_ternary_weight_conv2d", "rtn_epilogue_reparam",
+           "rtn_weight_conv2d_workspace_bytes", "rtn_ternary_weight_conv2d",
+           "rtn_activation_backward_workspace_bytes", "rtn_activation_backward", "rtn_epilogue_reparam",
            "rtn_epilogue_reparam_conv2d"]
 
 
@@ -88,6 +89,10 @@ def lib():
         L.rtn_ternary_weight_conv2d.restype = ci
         L.rtn_ternary_weight_conv2d.argtypes = [vp, vp, i64, i64, i64, i64, i64, ci, ci, ci, ci, vp, ci, ci, vp,
                                                 vp, vp, vp, C.c_size_t, vp]
+        L.rtn_activation_backward_workspace_bytes.restype = C.c_size_t
+        L.rtn_activation_backward_workspace_bytes.argtypes = [i64]
+        L.rtn_activation_backward.restype = ci
+        L.rtn_activation_backward.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
         L.rtn_epilogue_reparam.restype = ci
         L.rtn_epilogue_reparam.argtypes = [vp, i64, i64, i64, vp, vp, vp]
         L.rtn_epilogue_reparam_conv2d.restype = ci
@@ -305,6 +310,26 @@ def ternary_weight_conv2d(x, w_codes, O, KH, KW, stride, pad, alpha_w, relu=Fals
         C.c_void_p(workspace.data_ptr()), workspace.numel(), _stream())
     _check(rc, "rtn_ternary_weight_conv2d")
     return y_out
+
+
+def activation_backward(a, grad_out, lo, hi, gamma, want_grad_in=True, grad_in=None, sums=None, workspace=None):
+    """Backward of gamma*Q(a)+beta: returns (grad_in or None, sums) with sums a cuda float64 [2]
+    tensor holding (dL/dgamma, dL/dbeta)."""
+    n = a.numel()
+    if want_grad_in and grad_in is None:
+        grad_in = torch.empty_like(a)
+    if sums is None:
+        sums = torch.empty(2, dtype=torch.float64, device=a.device)
+    if workspace is None:
+        workspace = torch.empty(lib().rtn_activation_backward_workspace_bytes(n), dtype=torch.uint8,
+                                device=a.device)
+    glo, ghi, gg = _Gran(lo), _Gran(hi), _Gran(gamma)
+    rc = lib().rtn_activation_backward(_dev(a, torch.float32), _dev(grad_out, torch.float32), n, glo.ptr, ghi.ptr,
+                                       gg.ptr, None if grad_in is None else _dev(grad_in, torch.float32),
+                                       _dev(sums, torch.float64), C.c_void_p(workspace.data_ptr()),
+                                       workspace.numel(), _stream())
+    _check(rc, "rtn_activation_backward")
+    return grad_in, sums
 
 
 def epilogue_reparam(acc, K, ep, y_out=None):

@@ -388,6 +388,33 @@ int rtn_ternary_weight_conv2d(const float* x, const void* w_codes, int64_t Nb, i
     return he == hipSuccess ? RTN_OK : hip_fail(he);
 }
 
+size_t rtn_activation_backward_workspace_bytes(int64_t n)
+{
+    if (n <= 0 || n > ((int64_t)1 << 40)) return 0;
+    return (size_t)rtn::act_backward_blocks(n) * 2u * sizeof(double);
+}
+
+int rtn_activation_backward(const float* a, const float* grad_out, int64_t n, const float* thr_lo,
+                            const float* thr_hi, const float* gamma, float* grad_in, double* grad_gamma_beta,
+                            void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!a || !grad_out || !thr_lo || !thr_hi || !gamma || !grad_gamma_beta) return RTN_ERR_NULL;
+    if (n <= 0 || n > ((int64_t)1 << 40) || rtn::act_backward_blocks(n) > kMaxDim) return RTN_ERR_SHAPE;
+    if (!(*thr_lo <= *thr_hi)) return RTN_ERR_SHAPE;
+    if (!aligned(a, 4) || !aligned(grad_out, 4) || !aligned(grad_in, 4) || !aligned(grad_gamma_beta, 8))
+        return RTN_ERR_ALIGN;
+    if (!workspace || workspace_bytes < rtn_activation_backward_workspace_bytes(n)) return RTN_ERR_WORKSPACE;
+    if (!aligned(workspace, 8)) return RTN_ERR_ALIGN;
+    rtn::ActBwdArgs p = {};
+    p.a = a, p.g = grad_out, p.n = n;
+    p.lo = *thr_lo, p.hi = *thr_hi, p.gamma = *gamma;
+    p.da = grad_in;
+    p.partials = (double*)workspace;
+    p.sums = grad_gamma_beta;
+    const hipError_t he = rtn::launch_act_backward(p, (hipStream_t)stream);
+    return he == hipSuccess ? RTN_OK : hip_fail(he);
+}
+
 int rtn_epilogue_reparam(const int32_t* acc, int64_t M, int64_t N, int64_t K, const rtn_epilogue* ep,
                          float* y_out, void* stream)
 {

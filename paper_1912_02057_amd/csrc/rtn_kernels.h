@@ -27,6 +27,19 @@ hipError_t launch_pack_rows_planes(const PackArgs& a, hipStream_t st);
 hipError_t launch_pack_nchw_i8(const PackArgs& a, hipStream_t st);
 hipError_t launch_pack_nchw_planes(const PackArgs& a, hipStream_t st);
 
+// Backward of the reparameterized ternary activation.
+struct ActBwdArgs {
+    const float* a;    // pre-ternarization activation
+    const float* g;    // dL/d(gamma*t + beta)
+    int64_t n;
+    float lo, hi, gamma;
+    float* da;         // nullable
+    double* partials;  // workspace: 2 doubles per block
+    double* sums;      // out: {dgamma, dbeta}
+};
+int64_t act_backward_blocks(int64_t n);
+hipError_t launch_act_backward(const ActBwdArgs& p, hipStream_t st);
+
 // Epilogue parameters as the kernels see them.
 struct EpiArgs {
     Param alpha_a, beta_a;  // vector: per GEMM row m (GEMM only)

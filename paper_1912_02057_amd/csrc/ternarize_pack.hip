@@ -427,4 +427,102 @@ hipError_t launch_pack_nchw_planes(const PackArgs& a, hipStream_t st)
     return hipGetLastError();
 }
 
+// ---- backward of the reparameterized ternary activation (Eq.6, Eq.7) -----------
+// One block: 4096 consecutive elements (16 per thread).  Writes dL/dAbar and the
+// block's two partial sums (dgamma, dbeta) in double; a second single-block kernel
+// adds the partials in index order, so the result does not depend on scheduling.
+namespace {
+constexpr int kBwdPerBlock = 4096;
+
+__device__ __forceinline__ double wave_sum(double v)
+{
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_down(v, o, 64);
+    return v;
+}
+
+template <bool VEC>
+__global__ __launch_bounds__(256) void k_act_backward(ActBwdArgs p)
+{
+    __shared__ double red[2][4];
+    const int tid = threadIdx.x;
+    const int64_t base = (int64_t)blockIdx.x * kBwdPerBlock;
+    double sg = 0.0, sb = 0.0;
+    auto one = [&](float a, float g, float& da) {
+        const int t = (int)(a > p.hi) - (int)(a < p.lo);
+        sg += (double)t * (double)g;
+        sb += (double)g;
+        const float prod = __fmul_rn(p.gamma, g);  // one fp32 product, never fused
+        da = (a <= 1.0f && a >= -1.0f) ? prod : 0.0f;
+    };
+    if (VEC) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int64_t e = base + (int64_t)(i * 256 + tid) * 4;
+            if (e + 4 <= p.n) {
+                const float4 a = *(const float4*)(p.a + e), g = *(const float4*)(p.g + e);
+                float4 d;
+                one(a.x, g.x, d.x), one(a.y, g.y, d.y), one(a.z, g.z, d.z), one(a.w, g.w, d.w);
+                if (p.da) *(float4*)(p.da + e) = d;
+            } else {
+                for (int64_t k = e; k < p.n; ++k) {
+                    float d;
+                    one(p.a[k], p.g[k], d);
+                    if (p.da) p.da[k] = d;
+                }
+            }
+        }
+    } else {
+#pragma unroll 4
+        for (int i = 0; i < 16; ++i) {
+            const int64_t e = base + i * 256 + tid;
+            if (e < p.n) {
+                float d;
+                one(p.a[e], p.g[e], d);
+                if (p.da) p.da[e] = d;
+            }
+        }
+    }
+    sg = wave_sum(sg);
+    sb = wave_sum(sb);
+    if ((tid & 63) == 0) red[0][tid >> 6] = sg, red[1][tid >> 6] = sb;
+    __syncthreads();
+    if (tid == 0) {
+        p.partials[2 * (int64_t)blockIdx.x] = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
+        p.partials[2 * (int64_t)blockIdx.x + 1] = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
+    }
+}
+
+__global__ __launch_bounds__(256) void k_sum_partials(const double* partials, int64_t nblocks, double* out)
+{
+    __shared__ double red[2][4];
+    const int tid = threadIdx.x;
+    double sg = 0.0, sb = 0.0;
+    for (int64_t b = tid; b < nblocks; b += 256) sg += partials[2 * b], sb += partials[2 * b + 1];
+    sg = wave_sum(sg);
+    sb = wave_sum(sb);
+    if ((tid & 63) == 0) red[0][tid >> 6] = sg, red[1][tid >> 6] = sb;
+    __syncthreads();
+    if (tid == 0) {
+        out[0] = (red[0][0] + red[0][1]) + (red[0][2] + red[0][3]);
+        out[1] = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
+    }
+}
+}  // namespace
+
+int64_t act_backward_blocks(int64_t n) { return (n + kBwdPerBlock - 1) / kBwdPerBlock; }
+
+hipError_t launch_act_backward(const ActBwdArgs& p, hipStream_t st)
+{
+    const int64_t nb = act_backward_blocks(p.n);
+    const bool vec = (((uintptr_t)p.a | (uintptr_t)p.g | (uintptr_t)p.da) & 15) == 0;
+    if (vec)
+        hipLaunchKernelGGL(k_act_backward<true>, dim3((unsigned)nb), dim3(256), 0, st, p);
+    else
+        hipLaunchKernelGGL(k_act_backward<false>, dim3((unsigned)nb), dim3(256), 0, st, p);
+    hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(256), 0, st, p.partials, nb, p.sums);
+    return hipGetLastError();
+}
+
+
 }  // namespace rtn

@@ -251,3 +251,27 @@ def test_weight_conv_rejects(L):
     assert with_(_17=None) == B.RTN_ERR_WORKSPACE
     assert with_(_18=100) == B.RTN_ERR_WORKSPACE
     assert with_(_17=ODD) == B.RTN_ERR_ALIGN
+
+
+def test_activation_backward_rejects(L):
+    call = L.rtn_activation_backward
+    lo, hi, gm = _f(-0.5), _f(0.5), _f(1.0)
+    ok = [FAKE, FAKE, 100, lo, hi, gm, FAKE, FAKE, FAKE, 1 << 10, None]
+
+    def with_(**kw):
+        a = list(ok)
+        for i, v in kw.items():
+            a[int(i[1:])] = v
+        return call(*a)
+    assert L.rtn_activation_backward_workspace_bytes(1) == 16
+    assert L.rtn_activation_backward_workspace_bytes(4097) == 32
+    assert L.rtn_activation_backward_workspace_bytes(0) == 0
+    assert with_(_0=None) == B.RTN_ERR_NULL
+    assert with_(_5=None) == B.RTN_ERR_NULL                     # gamma
+    assert with_(_7=None) == B.RTN_ERR_NULL                     # the sums are not optional
+    assert with_(_2=0) == B.RTN_ERR_SHAPE
+    assert with_(_3=_f(0.5), _4=_f(-0.5)) == B.RTN_ERR_SHAPE    # lo > hi
+    assert with_(_6=ODD) == B.RTN_ERR_ALIGN
+    assert with_(_7=C.c_void_p(0x10004)) == B.RTN_ERR_ALIGN     # doubles need 8-byte alignment
+    assert with_(_8=None) == B.RTN_ERR_WORKSPACE
+    assert with_(_9=8) == B.RTN_ERR_WORKSPACE

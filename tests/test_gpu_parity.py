@@ -941,3 +941,51 @@ def test_weight_conv_resnet18_layers_batch64_sampled_images(idx):
     shape = wl.resnet18_ternary_layers()[idx]
     _say("weight-only conv, resnet18 b64 %s" % (shape,))
     _wconv_check(shape, 64, seed=800 + idx, relu=True, bn=True, images=[0, 63], what=shape.name)
+
+
+# ------------------ backward of the reparameterized ternary activation ---------
+def _act_bwd_check(n, seed, offset=0, want_da=True):
+    rng = np.random.default_rng(seed)
+    a = (rng.standard_normal(n + offset) * 0.8).astype(np.float32)
+    g = rng.standard_normal(n + offset).astype(np.float32)
+    if n >= 8:
+        a[offset:offset + 6] = [1.0, -1.0, 0.5, -0.5, np.nan, 2.0]     # inclusive clip, threshold ties, NaN
+    lo, hi, gamma = np.float32(-0.5), np.float32(0.5), np.float32(1.37)
+    ad, gd = T.dev(a)[offset:], T.dev(g)[offset:]                       # offset != 0: unaligned views
+    out = torch.full((n + offset,), 7.0, dtype=torch.float32, device=T.DEV)[offset:] if want_da else None
+    da, sums = B.activation_backward(ad, gd, float(lo), float(hi), float(gamma), want_grad_in=want_da, grad_in=out)
+    torch.cuda.synchronize()
+    rda, rg, rb = orc.act_backward(a[offset:], g[offset:], lo, hi, gamma, want_da)
+    s = sums.cpu().numpy()
+    scale = float(np.abs(g[offset:]).astype(np.float64).sum()) + 1e-30
+    assert abs(s[0] - rg) <= 1e-12 * scale and abs(s[1] - rb) <= 1e-12 * scale, (s, rg, rb)
+    if want_da:
+        assert (da.cpu().numpy() == rda).all()                          # bit-exact
+
+
+@pytest.mark.parametrize("n", [1, 5, 255, 4095, 4096, 4097, 100003, 1 << 20])
+def test_activation_backward_vs_oracle(n):
+    _say("activation backward n=%d" % n)
+    _act_bwd_check(n, seed=n)
+    _act_bwd_check(n, seed=n + 1, offset=1)           # 4-byte-aligned pointers: the scalar path
+    _act_bwd_check(n, seed=n + 2, want_da=False)
+
+
+def test_activation_backward_layer1_tensor_and_reproducible():
+    """The largest activation tensor of the ResNet-18 stack at batch 256 (51.4 M elements);
+    the sums must also be identical run to run."""
+    _say("activation backward, 256x64x56x56")
+    n = 256 * 64 * 56 * 56
+    rng = np.random.default_rng(5)
+    a = rng.standard_normal(n, dtype=np.float32)
+    g = rng.standard_normal(n, dtype=np.float32)
+    ad, gd = T.dev(a), T.dev(g)
+    da, s1 = B.activation_backward(ad, gd, -0.5, 0.5, 0.9)
+    _, s2 = B.activation_backward(ad, gd, -0.5, 0.5, 0.9, want_grad_in=False)
+    torch.cuda.synchronize()
+    rda, rg, rb = orc.act_backward(a, g, -0.5, 0.5, 0.9)
+    assert torch.equal(s1, s2)
+    s = s1.cpu().numpy()
+    scale = float(np.abs(g).astype(np.float64).sum())
+    assert abs(s[0] - rg) <= 1e-12 * scale and abs(s[1] - rb) <= 1e-12 * scale
+    assert (da.cpu().numpy() == rda).all()
