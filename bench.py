@@ -32,7 +32,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--batch", type=int, default=256)
     ap.add_argument("--workload", default="resnet18_ternary_convs",
-                    choices=["resnet18_ternary_convs", "gemm4096", "wgemm4096", "resnet18_weight_only_convs"])
+                    choices=["resnet18_ternary_convs", "gemm4096", "wgemm4096", "resnet18_weight_only_convs",
+                             "act_backward"])
     ap.add_argument("--tile", type=int, default=-1, help="force an MFMA tile configuration (tuning)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-images", type=int, default=128,
@@ -174,6 +175,29 @@ def main():
         macs_step = sum(l["sh"].macs(args.batch) for l in layers)
         workload = "ResNet-18 ternary conv stack (19 layers), batch %d, fp32 NCHW in/out" % args.batch
         nlaunch = len(layers)
+    elif args.workload == "act_backward":
+        # backward of the reparameterized ternary activation over the largest activation tensor of
+        # the stack (batch x 64 x 56 x 56): reads a and g, writes dL/da, reduces dgamma and dbeta
+        nel = args.batch * 64 * 56 * 56
+        rng = np.random.Generator(np.random.PCG64(11))
+        ba_, bg_ = rng.standard_normal(nel, dtype=np.float32), rng.standard_normal(nel, dtype=np.float32)
+        ad, gd = to_dev(ba_), to_dev(bg_)
+        dad = torch.empty_like(ad)
+        sums = torch.empty(2, dtype=torch.float64, device=dev)
+        wsp = torch.empty(B.lib().rtn_activation_backward_workspace_bytes(nel), dtype=torch.uint8, device=dev)
+
+        def step(timers=None):
+            if timers is not None:
+                timers[0][0].record()
+                timers[0][1].record()
+            B.activation_backward(ad, gd, -0.5, 0.5, 0.9, grad_in=dad, sums=sums, workspace=wsp)
+            if timers is not None:
+                timers[0][2].record()
+
+        macs_step = nel          # "MACs" here: elements (one multiply-add into each of the two sums)
+        workload = "backward of the reparameterized ternary activation, %d x 64 x 56 x 56 fp32" % args.batch
+        nlaunch = 1
+        layers = [dict(sh=None)]
     elif args.workload == "resnet18_weight_only_convs":
         # the same 19 layer shapes with ternary weights and fp32 activations (one call per layer:
         # activation split, weight copy, epilogue table, bf16 matrix-core conv)
@@ -366,6 +390,12 @@ def main():
                         launches_per_step=nlaunch, avg_launch_us=round(conv_total_s / nlaunch * 1e6, 1),
                         bytes_per_launch=round(alg_bytes_launch, 0),
                         mfma_tops=round(achieved_tops, 1), mfma_frac=round(achieved_tops / INT8_PEAK_TOPS, 4))
+    elif args.workload == "act_backward":
+        gbs = 12.0 * macs_step / conv_total_s / 1e9      # 4 B a + 4 B g read, 4 B dL/da written per element
+        roofline = dict(bound="hbm", kernel="k_act_backward (+ k_sum_partials)", achieved=round(gbs, 1),
+                        peak=HBM_PEAK_GBS, unit="GB/s", frac=round(gbs / HBM_PEAK_GBS, 4), traffic=None,
+                        launches_per_step=nlaunch, avg_launch_us=round(conv_total_s / nlaunch * 1e6, 1),
+                        bytes_per_launch=12.0 * macs_step)
     elif args.workload == "resnet18_weight_only_convs":
         bf16_tflops = 3 * achieved_tops
         roofline = dict(bound="mfma", kernel="activation split + k_tmm (bf16 MFMA implicit-GEMM conv, fp32 accumulate)",
@@ -410,6 +440,12 @@ def main():
                 t_cpu += time.perf_counter() - c0
                 macs_cpu += sh.macs(n_img)
             sample = "all 19 layers, %d images each (of %d)" % (n_img, args.batch)
+        elif args.workload == "act_backward":
+            c0 = time.perf_counter()
+            orc.act_backward(ba_, bg_, -0.5, 0.5, 0.9)
+            t_cpu = time.perf_counter() - c0
+            macs_cpu = nel
+            sample = "the whole tensor (%d elements), single thread as the oracle is written" % nel
         elif args.workload == "resnet18_weight_only_convs":
             n_img = max(1, args.cpu_images // 8)
             for i, sh in enumerate(wl.resnet18_ternary_layers()):
@@ -440,19 +476,23 @@ def main():
             t_cpu = time.perf_counter() - c0
             macs_cpu = rows.size * 4096 * 4096
             sample = "64 of 4096 output rows, all columns"
-        cpu = dict(value=round(macs_cpu / t_cpu / 1e12, 6), unit="TMAC/s", cores=orc.num_threads(),
+        cpu = dict(value=round(macs_cpu / t_cpu / 1e12, 6), unit="TMAC/s",
+                   cores=1 if args.workload == "act_backward" else orc.num_threads(),
                    kind="oracle", sample=sample, seconds=round(t_cpu, 2))
 
     value = macs_step / (ms_per_step * 1e-3) / 1e12
     out = {
         "metric": "effective ternary MAC/s (dense MAC count, S1+S2+S3+S4 per layer), ResNet-18 ternary layers"
         if args.workload == "resnet18_ternary_convs" else
-        ("effective MAC/s, weight-only ternary GEMM" if args.workload == "wgemm4096"
+        ("elements/s (in units of 1e12), backward of the reparameterized ternary activation"
+         if args.workload == "act_backward" else
+         "effective MAC/s, weight-only ternary GEMM" if args.workload == "wgemm4096"
          else ("effective MAC/s, weight-only ternary convs of ResNet-18"
                if args.workload == "resnet18_weight_only_convs" else "effective ternary MAC/s, ternary GEMM")),
         "value": round(value, 3), "unit": "TMAC/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
-        "vs_baseline": None, "dtype": "bf16x3" if args.workload in ("wgemm4096", "resnet18_weight_only_convs") else "i8", "data": "synthetic",
+        "vs_baseline": None, "dtype": "bf16x3" if args.workload in ("wgemm4096", "resnet18_weight_only_convs") else
+        ("f32" if args.workload == "act_backward" else "i8"), "data": "synthetic",
         "config": {"workload": workload, "batch": args.batch, "tile": args.tile},
         "tops": round(2 * value, 1), "pct_int8_mfma_peak": round(100 * 2 * value / INT8_PEAK_TOPS, 2),
         "contraction_only": {"tmacs": round(macs_step / conv_total_s / 1e12, 3),

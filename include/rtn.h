@@ -275,7 +275,7 @@ int rtn_ternary_weight_conv2d(const float *x, const void *w_codes, int64_t Nb, i
  * with t = (a > thr_hi) - (a < thr_lo) as in rtn_ternarize_pack and g = grad_out.
  * a, grad_out, grad_in (nullable): DEVICE fp32 [n]; thr_lo, thr_hi, gamma: HOST
  * floats; grad_gamma_beta: DEVICE double[2], overwritten.  The sums are formed in
- * double, per 4096-element block and then in block order, so they are reproducible
+ * double, per 16384-element block and then in block order, so they are reproducible
  * run to run; gamma*g is one fp32 product.  workspace:
  * rtn_activation_backward_workspace_bytes(n) bytes, 8-byte aligned.             */
 size_t rtn_activation_backward_workspace_bytes(int64_t n);

@@ -428,11 +428,11 @@ hipError_t launch_pack_nchw_planes(const PackArgs& a, hipStream_t st)
 }
 
 // ---- backward of the reparameterized ternary activation (Eq.6, Eq.7) -----------
-// One block: 4096 consecutive elements (16 per thread).  Writes dL/dAbar and the
+// One block: 16384 consecutive elements (64 per thread).  Writes dL/dAbar and the
 // block's two partial sums (dgamma, dbeta) in double; a second single-block kernel
 // adds the partials in index order, so the result does not depend on scheduling.
 namespace {
-constexpr int kBwdPerBlock = 4096;
+constexpr int kBwdPerBlock = 16384;
 
 __device__ __forceinline__ double wave_sum(double v)
 {
@@ -456,8 +456,8 @@ __global__ __launch_bounds__(256) void k_act_backward(ActBwdArgs p)
         da = (a <= 1.0f && a >= -1.0f) ? prod : 0.0f;
     };
     if (VEC) {
-#pragma unroll
-        for (int i = 0; i < 4; ++i) {
+#pragma unroll 4
+        for (int i = 0; i < kBwdPerBlock / 1024; ++i) {
             const int64_t e = base + (int64_t)(i * 256 + tid) * 4;
             if (e + 4 <= p.n) {
                 const float4 a = *(const float4*)(p.a + e), g = *(const float4*)(p.g + e);
@@ -474,7 +474,7 @@ __global__ __launch_bounds__(256) void k_act_backward(ActBwdArgs p)
         }
     } else {
 #pragma unroll 4
-        for (int i = 0; i < 16; ++i) {
+        for (int i = 0; i < kBwdPerBlock / 256; ++i) {
             const int64_t e = base + i * 256 + tid;
             if (e < p.n) {
                 float d;

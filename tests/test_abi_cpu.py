@@ -264,7 +264,7 @@ def test_activation_backward_rejects(L):
             a[int(i[1:])] = v
         return call(*a)
     assert L.rtn_activation_backward_workspace_bytes(1) == 16
-    assert L.rtn_activation_backward_workspace_bytes(4097) == 32
+    assert L.rtn_activation_backward_workspace_bytes(16385) == 32
     assert L.rtn_activation_backward_workspace_bytes(0) == 0
     assert with_(_0=None) == B.RTN_ERR_NULL
     assert with_(_5=None) == B.RTN_ERR_NULL                     # gamma

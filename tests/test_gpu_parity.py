@@ -963,7 +963,7 @@ def _act_bwd_check(n, seed, offset=0, want_da=True):
         assert (da.cpu().numpy() == rda).all()                          # bit-exact
 
 
-@pytest.mark.parametrize("n", [1, 5, 255, 4095, 4096, 4097, 100003, 1 << 20])
+@pytest.mark.parametrize("n", [1, 5, 255, 4095, 16384, 16385, 100003, 1 << 20])
 def test_activation_backward_vs_oracle(n):
     _say("activation backward n=%d" % n)
     _act_bwd_check(n, seed=n)
