@@ -25,6 +25,16 @@
 // direct load writes 1 KiB of LDS, lane l at +16*l, i.e. 16 rows of 64 bytes;
 // which global 16-byte chunk a lane fetches is permuted (XOR swizzle by row) so
 // that the 16-byte fragment reads of 16 consecutive rows hit all 64 banks.
+//
+// Variants of the same kernel (template parameters of k_tmm):
+//   HC   conv tiles that keep their run of input pixels in LDS (stride 1, centred window);
+//   TERN conv whose epilogue ternarizes its output for the next layer (1), also after
+//        the residual add and second ReLU of a block tail (2);
+//   DT   bf16 operands with fp32 accumulators (v_mfma_f32_32x32x16_bf16) for the
+//        weight-only ternary GEMM / conv, whose fp32 activations are split exactly
+//        into three bf16 terms laid along K.
+// This file also holds the small kernels around them: the conv's per-layer epilogue
+// table, the fp32 -> 3 x bf16 splits and the int8 -> bf16 weight copy.
 #include <type_traits>
 
 #include "epilogue_math.h"
