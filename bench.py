@@ -7,7 +7,13 @@ implicit-GEMM ternary convolution on the int8 matrix cores (S2+S3) with the
 fused four-term reparameterization + ReLU + BN epilogue (S4) writing fp32 NCHW.
 Inputs are resident in HBM before the timed region.
 
-Prints ONE JSON line (see README for the fields).
+Prints ONE JSON line: metric / value / unit / ms_per_step and the run parameters,
+`roofline` (the dominant kernel's achieved rate against the MI355X peak that bounds
+it, from HIP events on the launch stream), `cpu_baseline` (the CPU oracle timed on a
+bounded sample of the same workload), `fused_blocks` (the same convs with the
+ternarizing epilogue, and the trunk as one chained forward pass) and `layers`
+(per-layer times).  Other workloads: --workload gemm4096 | wgemm4096 |
+resnet18_weight_only_convs | act_backward.
 """
 import argparse
 import json
