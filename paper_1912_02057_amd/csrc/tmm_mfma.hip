@@ -92,7 +92,30 @@ __host__ __device__ inline int conv_classes(int pad)
     const int p1 = pad + 1;
     return p1 * p1 * p1 * p1;
 }
-__host__ __device__ inline int conv_table_bytes(int bp, int pad) { return (4 + conv_classes(pad)) * bp * 8; }
+// The copy of that table a block keeps in LDS holds only the classes that can occur.
+// Along one axis a window is cut by tcut taps at the low end and bcut at the high end;
+// when the image is at least as long as the window it is never cut at both ends, which
+// leaves 2 pad + 1 axis classes (0 = uncut, 1 .. pad = tcut, pad + 1 .. 2 pad = pad + bcut)
+// instead of (pad+1)^2 (tcut + (pad+1) bcut, the numbering of the prepared table).
+__host__ __device__ inline bool conv_compact(const ConvGeom& g) { return g.H >= g.KH && g.W >= g.KW; }
+__host__ __device__ inline int conv_axis_classes(const ConvGeom& g)
+{
+    return conv_compact(g) ? 2 * g.pad + 1 : (g.pad + 1) * (g.pad + 1);
+}
+__host__ __device__ inline int conv_lds_classes(const ConvGeom& g)
+{
+    return conv_axis_classes(g) * conv_axis_classes(g);
+}
+__host__ __device__ inline int conv_axis_class(bool compact, int pad, int tcut, int bcut)
+{
+    return compact ? (bcut ? pad + bcut : tcut) : tcut + (pad + 1) * bcut;
+}
+// axis class of the LDS copy -> axis class of the prepared table
+__host__ __device__ inline int conv_axis_global(bool compact, int pad, int a)
+{
+    return compact ? (a <= pad ? a : (pad + 1) * (a - pad)) : a;
+}
+__host__ __device__ inline int conv_table_bytes(int bp, const ConvGeom& g) { return (4 + conv_lds_classes(g)) * bp * 8; }
 
 // chunk swizzle of a 64-byte LDS row (depends on row & 15 only)
 __device__ __forceinline__ int swz(int row) { return ((row >> 1) & 3) ^ ((row >> 3) & 1); }
@@ -224,7 +247,7 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
     const int zoff = HALO ? prm.hrows * HC : 0;
     const int roff = HALO ? zoff + 128 : 0;
     const int toff = roff + NS * STAGE;
-    const int tab_kib = CONV ? (conv_table_bytes(BP, g.pad) + 1023) >> 10 : 0;
+    const int tab_kib = CONV ? (conv_table_bytes(BP, g) + 1023) >> 10 : 0;
     const bool want_ep = TERN || prm.y != nullptr;
 
     // ---- loader state ------------------------------------------------------
@@ -469,12 +492,19 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
     if (CONV && want_ep) {
         // epilogue table: rows [g1, c2, bn scale, bn shift, class constants...] of the
         // prepared per-layer table, columns p0 .. p0+BP-1, copied as they are
+        // (the class rows that can occur here, see conv_lds_classes)
         const int nrows = 4 + conv_classes(g.pad), opitch = (g.O + 1) & ~1;
+        const bool compact = conv_compact(g);
+        const int nax = conv_axis_classes(g), lrows = 4 + nax * nax, pp = (g.pad + 1) * (g.pad + 1);
         for (int n = wave; n < tab_kib; n += 4) {
             const int lin = n * 64 + lane;  // 16-byte unit = 2 doubles
             int row = lin / (BP / 2);
             const int u = lin - row * (BP / 2);
-            row = row < nrows ? row : nrows - 1;
+            row = row < lrows ? row : lrows - 1;
+            if (row >= 4) {
+                const int c = row - 4, ra = c / nax, ca = c - ra * nax;
+                row = 4 + conv_axis_global(compact, g.pad, ra) * pp + conv_axis_global(compact, g.pad, ca);
+            }
             int64_t idx = (int64_t)row * opitch + p0 + 2 * u;
             const int64_t last = (int64_t)nrows * opitch - 2;
             idx = idx < last ? idx : last;  // columns past O are never used
@@ -531,7 +561,7 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
 #pragma unroll
     for (int j = 0; j < TQ; ++j) pixcls[j] = 0;
     if (CONV && want_ep && !g.code_zero_pad) {
-        const int ohw = g.OH * g.OW, p1 = g.pad + 1;
+        const int ohw = g.OH * g.OW;
 #pragma unroll
         for (int j = 0; j < TQ; ++j) {
             int m = q0 + wq * WQ + j * 32 + (lane & 31);
@@ -541,7 +571,9 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
             int khl, khh, kwl, kwh;
             tap_range(oh, g.stride, g.pad, g.KH, g.H, khl, khh);
             tap_range(ow, g.stride, g.pad, g.KW, g.W, kwl, kwh);
-            pixcls[j] = (khl + p1 * (g.KH - 1 - khh)) * p1 * p1 + (kwl + p1 * (g.KW - 1 - kwh));
+            const bool compact = conv_compact(g);
+            pixcls[j] = conv_axis_class(compact, g.pad, khl, g.KH - 1 - khh) * conv_axis_classes(g) +
+                        conv_axis_class(compact, g.pad, kwl, g.KW - 1 - kwh);
         }
     }
     __builtin_amdgcn_s_setprio(2);
@@ -882,9 +914,9 @@ __global__ __launch_bounds__(256) void k_conv_class_consts(const int32_t* tap, C
 }
 
 // LDS bytes of the epilogue tables of a BP-row tile.
-inline int64_t table_bytes(int bp, bool conv, int pad)
+inline int64_t table_bytes(int bp, bool conv, const ConvGeom& g)
 {
-    return conv ? (int64_t)conv_table_bytes(bp, pad) : (int64_t)3 * bp * 8;
+    return conv ? (int64_t)conv_table_bytes(bp, g) : (int64_t)3 * bp * 8;
 }
 constexpr int64_t kMaxLds = 160 * 1024;
 
@@ -909,10 +941,10 @@ hipError_t launch_cfg(TmmParams& prm, hipStream_t st)
     int64_t smem;
     if (CONV) {
         // ring (+ halo), then the epilogue table in whole KiB
-        smem = stage_bytes + ((table_bytes(BP, true, prm.g.pad) + 1023) & ~(int64_t)1023);
+        smem = stage_bytes + ((table_bytes(BP, true, prm.g) + 1023) & ~(int64_t)1023);
         if (TERN) smem += BP * 8;  // threshold pairs of the ternarizing epilogue
     } else {
-        const int64_t tb = table_bytes(BP, false, 0);
+        const int64_t tb = table_bytes(BP, false, prm.g);
         smem = stage_bytes > tb ? stage_bytes : tb;
     }
     if (smem > kMaxLds) return hipErrorInvalidValue;
@@ -966,7 +998,7 @@ hipError_t launch_index_raw(int cfg, TmmParams& prm, hipStream_t st)
 {
     // conv with a large pad: the per-class constant table of a tall tile does
     // not fit in LDS; fall back to the tile of the same width class with BP = 64.
-    if (CONV && table_bytes(kTileBP[cfg], true, prm.g.pad) > 48 * 1024) cfg = 0;
+    if (CONV && table_bytes(kTileBP[cfg], true, prm.g) > 48 * 1024) cfg = 0;
     // waves per SIMD the 64-accumulator tiles are compiled for: the ternarizing epilogue
     // needs a few registers more than the plain one, its block-tail form about 50 more
     constexpr int W3 = TERN == 2 ? 2 : 3, W4 = TERN == 2 ? 2 : (TERN == 1 ? 3 : 4);
@@ -995,7 +1027,13 @@ hipError_t launch_index_raw(int cfg, TmmParams& prm, hipStream_t st)
         if (ok && hc == 64) {
             switch (cfg) {
                 case 14: return launch_cfg<64, 256, 1, 4, 9, 2, CONV, TERN, 64>(prm, st);
-                case 15: return launch_cfg<64, 256, 1, 4, 3, W3, CONV, TERN, 64>(prm, st);
+                case 15:
+                    // plain epilogue: with the compact class table and a two-stage weight ring four
+                    // blocks fit a CU (38.5 KB of LDS each), which hides more of the 3136 short
+                    // tiles' load latency (measured 59 -> 57.5 us per layer); the ternarizing
+                    // epilogues need the registers of three blocks per CU anyway
+                    if constexpr (TERN == 0) return launch_cfg<64, 256, 1, 4, 2, 4, CONV, TERN, 64>(prm, st);
+                    return launch_cfg<64, 256, 1, 4, 3, W3, CONV, TERN, 64>(prm, st);
                 case 16: return launch_cfg<64, 128, 1, 4, 9, 3, CONV, TERN, 64>(prm, st);
                 case 17: return launch_cfg<64, 128, 1, 4, 3, 4, CONV, TERN, 64>(prm, st);
                 default: break;
