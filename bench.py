@@ -28,7 +28,7 @@ INT8_PEAK_TOPS = 5000.0   # MI355X dense int8 MFMA, TOP/s (2 ops per MAC)
 BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
 HBM_PEAK_GBS = 8000.0
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this file's default run (see profiles/)
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 129.8e6
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 129.6e6
 
 
 def main():
