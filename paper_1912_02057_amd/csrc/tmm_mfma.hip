@@ -1263,11 +1263,16 @@ hipError_t launch_wconv(const WConvArgs& a, hipStream_t st)
     prm.ep = a.ep;
     const int cfg = g_forced_tile >= 0 ? g_forced_tile : pick_tile(g0.O, prm.RQ, true);
     const int bp = kTileBP[cfg];
-    if (cfg == 13 || cfg == 4 || cfg == 19) return launch_cfg<128, 256, 2, 2, 2, 2, true, 0, 0, 1>(prm, st);
-    if (bp >= 128) return launch_cfg<128, 128, 2, 2, 3, 2, true, 0, 0, 1>(prm, st);
-    if (cfg == 3 || cfg == 7 || cfg == 9 || cfg == 14 || cfg == 15)
-        return launch_cfg<64, 256, 1, 4, 2, 3, true, 0, 0, 1>(prm, st);
-    return launch_cfg<64, 64, 2, 2, 4, 4, true, 0, 0, 1>(prm, st);
+    e = hipErrorInvalidValue;
+    if (cfg == 13 || cfg == 4 || cfg == 19)
+        e = launch_cfg<128, 256, 2, 2, 2, 2, true, 0, 0, 1>(prm, st);
+    else if (bp >= 128)
+        e = launch_cfg<128, 128, 2, 2, 3, 2, true, 0, 0, 1>(prm, st);
+    else if (cfg == 3 || cfg == 7 || cfg == 9 || cfg == 14 || cfg == 15)
+        e = launch_cfg<64, 256, 1, 4, 2, 3, true, 0, 0, 1>(prm, st);
+    // the smallest tile also serves a table too large for the others (wide pad, tiny image)
+    if (e == hipErrorInvalidValue) e = launch_cfg<64, 64, 2, 2, 4, 4, true, 0, 0, 1>(prm, st);
+    return e;
 }
 
 hipError_t launch_wgemm(const WGemmArgs& a, hipStream_t st)
