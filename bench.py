@@ -12,7 +12,7 @@ Prints ONE JSON line: metric / value / unit / ms_per_step and the run parameters
 it, from HIP events on the launch stream), `cpu_baseline` (the CPU oracle timed on a
 bounded sample of the same workload), `fused_blocks` (the same convs with the
 ternarizing epilogue, and the trunk as one chained forward pass) and `layers`
-(per-layer times).  Other workloads: --workload gemm4096 | wgemm4096 |
+(per-layer times).  Other workloads: --workload gemm4096 | gemm_sweep | wgemm4096 |
 resnet18_weight_only_convs | act_backward.
 """
 import argparse
@@ -39,7 +39,7 @@ def main():
     ap.add_argument("--batch", type=int, default=256)
     ap.add_argument("--workload", default="resnet18_ternary_convs",
                     choices=["resnet18_ternary_convs", "gemm4096", "wgemm4096", "resnet18_weight_only_convs",
-                             "act_backward"])
+                             "act_backward", "gemm_sweep"])
     ap.add_argument("--tile", type=int, default=-1, help="force an MFMA tile configuration (tuning)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-images", type=int, default=128,
@@ -70,6 +70,58 @@ def main():
         return float(v) if v.ndim == 0 else to_dev(v)
 
     ev = torch.cuda.Event
+    if args.workload == "gemm_sweep":
+        # M x N x K sweep of the ternary GEMM over sparsity, on both contraction paths: codes resident,
+        # one timed call = contraction + fused epilogue (the pack of the activations is timed beside it)
+        rows = []
+        tot_macs, tot_s = 0.0, 0.0
+        for M in (8192, 16384):
+            for NK in (4096, 8192):
+                for p0 in (0.2, 0.5, 0.8):
+                    case = wl.gemm_case(M, NK, NK, p_zero=p0, seed=int(1000 * p0) + 3)
+                    xa, xw = to_dev(case["xa"]), to_dev(case["xw"])
+                    for fmt, name in ((B.RTN_CODE_I8, "mfma_i8"), (B.RTN_CODE_BITPLANE, "popcount")):
+                        ca, sa = B.ternarize_pack(xa, -0.5, 0.5, fmt)
+                        cw, sw = B.ternarize_pack(xw, -0.5, 0.5, fmt)
+                        ep = B.Epilogue(garg(case["alpha_a"]), garg(case["beta_a"]), garg(case["alpha_w"]),
+                                        garg(case["beta_w"]), sa, sw)
+                        y = torch.empty((M, NK), dtype=torch.float32, device=dev)
+                        reps = 5 if name == "mfma_i8" else 2
+                        for _ in range(2):
+                            B.ternary_gemm(ca, cw, M, NK, NK, fmt=fmt, ep=ep, y_out=y)
+                        e0, e1, e2 = ev(enable_timing=True), ev(enable_timing=True), ev(enable_timing=True)
+                        e0.record()
+                        for _ in range(reps):
+                            B.ternary_gemm(ca, cw, M, NK, NK, fmt=fmt, ep=ep, y_out=y)
+                        e1.record()
+                        for _ in range(reps):
+                            B.ternarize_pack(xa, -0.5, 0.5, fmt)
+                        e2.record()
+                        torch.cuda.synchronize()
+                        us, pus = e0.elapsed_time(e1) * 1e3 / reps, e1.elapsed_time(e2) * 1e3 / reps
+                        macs = float(M) * NK * NK
+                        rows.append(dict(M=M, N=NK, K=NK, p_zero=p0, path=name, gemm_us=round(us, 1),
+                                         pack_us=round(pus, 1), tmacs=round(macs / us / 1e6, 1),
+                                         pct_int8_mfma_peak=round(100 * 2 * macs / us / 1e6 / INT8_PEAK_TOPS, 1)))
+                        if name == "mfma_i8":
+                            tot_macs += macs
+                            tot_s += (us + pus) * 1e-6
+                        del ca, cw, sa, sw, y, ep
+                    del xa, xw, case
+        mf = [r for r in rows if r["path"] == "mfma_i8"]
+        best = max(mf, key=lambda r: r["tmacs"])
+        print(json.dumps({
+            "metric": "effective ternary MAC/s, ternary GEMM sweep (pack + contraction + epilogue, matrix-core path)",
+            "value": round(tot_macs / tot_s / 1e12, 3), "unit": "TMAC/s", "n_gpus": 1, "steps": 5, "warmup": 2,
+            "ms_per_step": round(tot_s * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": "i8", "data": "synthetic",
+            "config": {"workload": "ternary GEMM sweep: M in {8192,16384} x N=K in {4096,8192} x P(0) in {0.2,0.5,0.8}, "
+                                   "int8 matrix-core and bit-plane popcount paths"},
+            "roofline": {"bound": "mfma", "kernel": "k_tmm (int8 MFMA GEMM + fused epilogue), best point",
+                         "achieved": round(2 * best["tmacs"], 1), "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
+                         "frac": round(2 * best["tmacs"] / INT8_PEAK_TOPS, 4), "traffic": None},
+            "cpu_baseline": None, "sweep": rows}))
+        return
     if args.workload == "resnet18_ternary_convs":
         shapes = wl.resnet18_ternary_layers()
         layers = []
