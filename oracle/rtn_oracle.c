@@ -17,6 +17,7 @@
 #include <stdint.h>
 #include <stddef.h>
 #include <stdlib.h>
+#include <math.h>
 #ifdef _OPENMP
 #include <omp.h>
 #endif
@@ -469,6 +470,45 @@ void orc_act_backward(const float *a, const float *g, int64_t n, float lo, float
     }
     sums[0] = sg;
     sums[1] = sb;
+}
+
+/* ----------------------------------------------------------------- O11 --
+ * Backward of the reparameterized ternary weights, one filter (row of K values) at a
+ * time (Section "Weight Ternarization": Wbar = k_W*W + b_W, W^t = Q(Wbar),
+ * Wbar^t = alpha*W^t, all three parameters per filter).  The paper prints the
+ * derivatives for the activation only (Eq.6, Eq.7); these are the same two rules
+ * applied to the weight transform by the chain rule.  With g = dL/dWbar^t:
+ *   dL/dalpha = sum_k W^t_k * g_k                                  (as Eq.6)
+ *   dL/dWbar_k = alpha * 1[|Wbar_k| <= 1] * g_k                     (as Eq.7)
+ *   dL/dk_W = sum_k W_k * dL/dWbar_k,  dL/db_W = sum_k dL/dWbar_k,  dL/dW_k = k_W * dL/dWbar_k
+ * Wbar is ONE fused multiply-add in fp32, W^t = (Wbar > hi) - (Wbar < lo); alpha*g and
+ * k_W*(alpha*g) are one fp32 product each; the sums are taken in double in index order.
+ * sums[3*o + 0..2] = dalpha, dk_W, db_W of filter o.                              */
+void orc_weight_backward(const float *w, const float *g, int64_t O, int64_t K, float lo, float hi,
+                         const float *kw, const float *bw, const float *alpha, float *dw, double *sums)
+{
+    for (int64_t o = 0; o < O; ++o) {
+        double sa = 0.0, sk = 0.0, sb = 0.0;
+        for (int64_t k = 0; k < K; ++k) {
+            const int64_t i = o * K + k;
+            float wbar = fmaf(kw[o], w[i], bw[o]);
+            int t = (wbar > hi) - (wbar < lo);
+            sa += (double)t * (double)g[i];
+            volatile float p = alpha[o] * g[i]; /* volatile: one fp32 rounding per product */
+            float q = p;
+            int inside = (wbar <= 1.0f) && (wbar >= -1.0f); /* NaN is outside */
+            float dwbar = inside ? q : 0.0f;
+            sk += (double)w[i] * (double)dwbar;
+            sb += (double)dwbar;
+            if (dw) {
+                volatile float r = kw[o] * dwbar;
+                dw[i] = r;
+            }
+        }
+        sums[3 * o + 0] = sa;
+        sums[3 * o + 1] = sk;
+        sums[3 * o + 2] = sb;
+    }
 }
 
 /* Conv form of O6: direct conv of the reparameterized values in double.

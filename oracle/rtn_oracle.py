@@ -21,7 +21,7 @@ def build(force=False):
     if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
         tmp = _LIB + ".tmp.%d" % os.getpid()
         subprocess.check_call(["gcc", "-O2", "-fopenmp", "-shared", "-fPIC", "-Wall", "-Wextra",
-                               "-o", tmp, _SRC])
+                               "-o", tmp, _SRC, "-lm"])
         os.replace(tmp, _LIB)
     return _LIB
 
@@ -365,3 +365,18 @@ def act_backward(a, g, lo, hi, gamma, want_da=True):
     lib().orc_act_backward(_p(a), _p(g), _i64(a.size), _f32(float(lo)), _f32(float(hi)), _f32(float(gamma)),
                            _p(da), _p(sums))
     return da, float(sums[0]), float(sums[1])
+
+
+def weight_backward(w, g, lo, hi, kw, bw, alpha, want_dw=True):
+    """O11.  w, g: float32 [O][K]; kw, bw, alpha: float32 [O]
+    -> (dw float32 [O][K] or None, sums float64 [O][3] = dalpha, dk_W, db_W per filter)."""
+    w, g = _c(w, np.float32), _c(g, np.float32)
+    assert w.ndim == 2 and w.shape == g.shape
+    O, K = w.shape
+    kw, bw, alpha = _c(kw, np.float32), _c(bw, np.float32), _c(alpha, np.float32)
+    assert kw.shape == bw.shape == alpha.shape == (O,)
+    dw = np.empty(w.shape, dtype=np.float32) if want_dw else None
+    sums = np.zeros((O, 3), dtype=np.float64)
+    lib().orc_weight_backward(_p(w), _p(g), _i64(O), _i64(K), _f32(float(lo)), _f32(float(hi)), _p(kw), _p(bw),
+                              _p(alpha), _p(dw), _p(sums))
+    return dw, sums

@@ -523,3 +523,74 @@ def test_act_backward_vs_torch_autograd_of_the_ste_form():
     assert np.abs(da - ta.grad.numpy()).max() <= 1e-6 * np.abs(ta.grad.numpy()).max()
     # gamma * g is ONE fp32 product
     assert (da[np.abs(a) <= 1] == (np.float32(gamma) * g)[np.abs(a) <= 1]).all()
+
+
+# ----------------------------------------------------------------- O11 ----
+def test_weight_backward_hand_listed():
+    # two filters of four weights; every value dyadic, so each step is exact
+    w = np.array([[0.5, -1.0, 2.0, 0.25], [1.0, 1.0, -0.5, 4.0]], np.float32)
+    g = np.array([[1.0, 2.0, 4.0, 8.0], [16.0, 32.0, 64.0, 128.0]], np.float32)
+    kw, bw, al = np.array([2.0, 0.5], np.float32), np.array([-0.5, 0.25], np.float32), np.array([0.5, 2.0], np.float32)
+    # Wbar = k*W + b:        0.5  -2.5   3.5   0.0   |  0.75  0.75  0.0   2.25
+    # W^t at Delta = 0.5:    0    -1     1     0     |  1     1     0     1
+    # |Wbar| <= 1:           yes  no     no    yes   |  yes   yes   yes   no
+    # dWbar = alpha*g*mask:  0.5  0      0     4     |  32    64    128   0
+    dw, sums = orc.weight_backward(w, g, -0.5, 0.5, kw, bw, al)
+    assert sums[0].tolist() == [-2.0 + 4.0, 0.5 * 0.5 + 0.25 * 4.0, 4.5]
+    assert sums[1].tolist() == [16.0 + 32.0 + 128.0, 32.0 + 64.0 - 64.0, 224.0]
+    assert dw.tolist() == [[1.0, 0.0, 0.0, 8.0], [16.0, 32.0, 64.0, 0.0]]
+    _, sums2 = orc.weight_backward(w, g, -0.5, 0.5, kw, bw, al, want_dw=False)
+    assert (sums2 == sums).all()
+
+
+def test_weight_backward_vs_torch_autograd_of_the_ste_form():
+    # Wbar = k*W + b;  Wbar^t = alpha * (Q(Wbar) + hardtanh(Wbar) - hardtanh(Wbar).detach()) has the forward
+    # value alpha*Q(Wbar) and the clipped straight-through derivative; autograd applies the chain rule.
+    rng = np.random.default_rng(61)
+    O, K = 7, 333
+    w = (rng.standard_normal((O, K)) * 0.6).astype(np.float32)
+    g = rng.standard_normal((O, K)).astype(np.float32)
+    kw = (0.7 + rng.random(O)).astype(np.float32)
+    bw = np.array([0.05, -0.1, 0.2, 0.0, -0.3, 0.13, 0.31], np.float32)
+    al = (0.2 + rng.random(O)).astype(np.float32)
+    wbar = kw[:, None].astype(np.float64) * w + bw[:, None]
+    near = (np.abs(np.abs(wbar) - 1.0) < 1e-3) | (np.abs(np.abs(wbar) - 0.5) < 1e-3)
+    w[near] = 0.0                                      # Wbar = b there, clear of both boundaries
+    tw = torch.tensor(w, dtype=torch.float64, requires_grad=True)
+    tk, tb, ta = (torch.tensor(v.astype(np.float64), requires_grad=True) for v in (kw, bw, al))
+    wb = tk[:, None] * tw + tb[:, None]
+    q = (wb > 0.5).double() - (wb < -0.5).double()
+    ht = torch.nn.functional.hardtanh(wb)
+    y = ta[:, None] * (q.detach() + ht - ht.detach())
+    y.backward(torch.tensor(g, dtype=torch.float64))
+    dw, sums = orc.weight_backward(w, g, -0.5, 0.5, kw, bw, al)
+    for col, ref in ((0, ta.grad), (1, tk.grad), (2, tb.grad)):
+        ref = ref.numpy()
+        assert np.abs(sums[:, col] - ref).max() <= 2e-6 * max(1.0, np.abs(ref).max()), col
+    assert np.abs(dw - tw.grad.numpy()).max() <= 2e-7 * np.abs(tw.grad.numpy()).max()
+
+
+def test_weight_backward_reduces_to_the_activation_rule_and_rounds_as_stated():
+    rng = np.random.default_rng(62)
+    O, K = 3, 500
+    w = (rng.standard_normal((O, K)) * 0.9).astype(np.float32)
+    g = rng.standard_normal((O, K)).astype(np.float32)
+    al = np.array([0.3, 1.7, 0.9], np.float32)
+    one, zero = np.ones(O, np.float32), np.zeros(O, np.float32)
+    dw, sums = orc.weight_backward(w, g, -0.5, 0.5, one, zero, al)
+    for o in range(O):                                  # k = 1, b = 0: Eq.6 / Eq.7 with gamma = alpha
+        da, dgam, _ = orc.act_backward(w[o], g[o], -0.5, 0.5, al[o])
+        assert (dw[o] == da).all() and sums[o, 0] == dgam
+        da64 = da.astype(np.float64)                    # numpy sums pairwise, the oracle in index order
+        assert abs(sums[o, 2] - da64.sum()) <= 1e-12 * np.abs(da64).sum()
+        assert abs(sums[o, 1] - (w[o] * da64).sum()) <= 1e-12 * np.abs(w[o] * da64).sum()
+    # alpha*g and k*(alpha*g) are one fp32 product each
+    kw = np.array([1.1, 0.7, 1.3], np.float32)
+    dw2, _ = orc.weight_backward(w, g, -0.5, 0.5, kw, zero, al)
+    inside = np.abs(kw[:, None] * w) <= 1
+    assert (dw2[inside] == (kw[:, None] * (al[:, None] * g))[inside]).all() and (dw2[~inside] == 0).all()
+    # Wbar is ONE fused multiply-add: (1+2^-12)^2 - 1 = 2^-11 + 2^-24 exactly, 2^-11 if the product were rounded
+    e = np.float32(1 + 2.0 ** -12)
+    _, s = orc.weight_backward(np.array([[e]], np.float32), np.array([[1.0]], np.float32), -1.0, 2.0 ** -11,
+                               np.array([e], np.float32), np.array([-1.0], np.float32), np.array([1.0], np.float32))
+    assert s[0, 0] == 1.0
