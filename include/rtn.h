@@ -284,6 +284,27 @@ int rtn_activation_backward(const float *a, const float *grad_out, int64_t n, co
                             double *grad_gamma_beta, void *workspace, size_t workspace_bytes,
                             void *stream);
 
+/* Backward of the reparameterized ternary weights (Section "Weight Ternarization":
+ * Wbar = k_W*W + b_W, W^t = Q(Wbar), Wbar^t = alpha*W^t, the three parameters per
+ * filter), for O filters of K weights each.  The paper prints the derivatives for the
+ * activation (Eq.6, Eq.7); these are the same rules taken through the weight
+ * transform by the chain rule.  With g = grad_out = dL/dWbar^t and
+ * d[k] = alpha[o]*g[o][k] if |Wbar[o][k]| <= 1, else 0:
+ *   grad_params[3*o + 0] = sum_k t[o][k]*g[o][k]        (dL/dalpha)
+ *   grad_params[3*o + 1] = sum_k W[o][k]*d[k]           (dL/dk_W)
+ *   grad_params[3*o + 2] = sum_k d[k]                   (dL/db_W)
+ *   grad_w[o][k] = k_W[o]*d[k]                          (dL/dW)
+ * Wbar is one fp32 fused multiply-add, t = (Wbar > thr_hi) - (Wbar < thr_lo); alpha*g
+ * and k_W*d are one fp32 product each; the sums are formed in double in a fixed
+ * order (reproducible run to run); a weight outside the clip, a NaN included, adds
+ * nothing to the second and third sum.
+ * w, grad_out, grad_w (nullable): DEVICE fp32 [O][K] row-major; k_w, b_w, alpha: DEVICE
+ * fp32 [O]; thr_lo <= thr_hi: HOST floats; grad_params: DEVICE double [O][3],
+ * overwritten.  Needs no workspace.                                            */
+int rtn_weight_backward(const float *w, const float *grad_out, int64_t O, int64_t K,
+                        const float *thr_lo, const float *thr_hi, const float *k_w, const float *b_w,
+                        const float *alpha, float *grad_w, double *grad_params, void *stream);
+
 /* Stand-alone epilogue on stored accumulators (Eq.9 generalised, see
  * rtn_epilogue).  GEMM form: acc, y_out are [M][N] row-major.               */
 int rtn_epilogue_reparam(const int32_t *acc, int64_t M, int64_t N, int64_t K,

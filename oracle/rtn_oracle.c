@@ -498,8 +498,10 @@ void orc_weight_backward(const float *w, const float *g, int64_t O, int64_t K, f
             float q = p;
             int inside = (wbar <= 1.0f) && (wbar >= -1.0f); /* NaN is outside */
             float dwbar = inside ? q : 0.0f;
-            sk += (double)w[i] * (double)dwbar;
-            sb += (double)dwbar;
+            if (inside) { /* a clipped (or NaN) weight adds nothing, not NaN * 0 */
+                sk += (double)w[i] * (double)dwbar;
+                sb += (double)dwbar;
+            }
             if (dw) {
                 volatile float r = kw[o] * dwbar;
                 dw[i] = r;

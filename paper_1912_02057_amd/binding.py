@@ -27,7 +27,8 @@ EXPORTS = ["rtn_status_string", "rtn_last_hip_error", "rtn_num_tile_configs", "r
            "rtn_ternary_conv2d_implicit_gemm", "rtn_ternary_conv2d_ternarize",
            "rtn_weight_gemm_workspace_bytes", "rtn_ternary_weight_gemm",
            "rtn_weight_conv2d_workspace_bytes", "rtn_ternary_weight_conv2d",
-           "rtn_activation_backward_workspace_bytes", "rtn_activation_backward", "rtn_epilogue_reparam",
+           "rtn_activation_backward_workspace_bytes", "rtn_activation_backward", "rtn_weight_backward",
+           "rtn_epilogue_reparam",
            "rtn_epilogue_reparam_conv2d"]
 
 
@@ -93,6 +94,8 @@ def lib():
         L.rtn_activation_backward_workspace_bytes.argtypes = [i64]
         L.rtn_activation_backward.restype = ci
         L.rtn_activation_backward.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+        L.rtn_weight_backward.restype = ci
+        L.rtn_weight_backward.argtypes = [vp, vp, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp]
         L.rtn_epilogue_reparam.restype = ci
         L.rtn_epilogue_reparam.argtypes = [vp, i64, i64, i64, vp, vp, vp]
         L.rtn_epilogue_reparam_conv2d.restype = ci
@@ -330,6 +333,24 @@ def activation_backward(a, grad_out, lo, hi, gamma, want_grad_in=True, grad_in=N
                                        workspace.numel(), _stream())
     _check(rc, "rtn_activation_backward")
     return grad_in, sums
+
+
+def weight_backward(w, grad_out, lo, hi, k_w, b_w, alpha, want_grad_w=True, grad_w=None, sums=None):
+    """Backward of alpha*Q(k_w*w + b_w) per filter: w, grad_out cuda float32 [O][K]; k_w, b_w, alpha cuda
+    float32 [O].  Returns (grad_w or None, sums) with sums a cuda float64 [O][3] tensor holding
+    (dL/dalpha, dL/dk_w, dL/db_w) per filter."""
+    O, K = w.shape
+    if want_grad_w and grad_w is None:
+        grad_w = torch.empty_like(w)
+    if sums is None:
+        sums = torch.empty((O, 3), dtype=torch.float64, device=w.device)
+    glo, ghi = _Gran(lo), _Gran(hi)
+    rc = lib().rtn_weight_backward(_dev(w, torch.float32), _dev(grad_out, torch.float32), O, K, glo.ptr, ghi.ptr,
+                                   _dev(k_w, torch.float32), _dev(b_w, torch.float32), _dev(alpha, torch.float32),
+                                   None if grad_w is None else _dev(grad_w, torch.float32),
+                                   _dev(sums, torch.float64), _stream())
+    _check(rc, "rtn_weight_backward")
+    return grad_w, sums
 
 
 def epilogue_reparam(acc, K, ep, y_out=None):

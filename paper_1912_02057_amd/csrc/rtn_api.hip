@@ -415,6 +415,26 @@ int rtn_activation_backward(const float* a, const float* grad_out, int64_t n, co
     return he == hipSuccess ? RTN_OK : hip_fail(he);
 }
 
+int rtn_weight_backward(const float* w, const float* grad_out, int64_t O, int64_t K, const float* thr_lo,
+                        const float* thr_hi, const float* k_w, const float* b_w, const float* alpha,
+                        float* grad_w, double* grad_params, void* stream)
+{
+    if (!w || !grad_out || !thr_lo || !thr_hi || !k_w || !b_w || !alpha || !grad_params) return RTN_ERR_NULL;
+    if (O <= 0 || K <= 0 || O > kMaxDim || K > kMaxK) return RTN_ERR_SHAPE;
+    if (!(*thr_lo <= *thr_hi)) return RTN_ERR_SHAPE;
+    if (!aligned(w, 4) || !aligned(grad_out, 4) || !aligned(grad_w, 4) || !aligned(k_w, 4) || !aligned(b_w, 4) ||
+        !aligned(alpha, 4) || !aligned(grad_params, 8))
+        return RTN_ERR_ALIGN;
+    rtn::WeightBwdArgs p = {};
+    p.w = w, p.g = grad_out, p.O = O, p.K = K;
+    p.lo = *thr_lo, p.hi = *thr_hi;
+    p.kw = k_w, p.bw = b_w, p.alpha = alpha;
+    p.dw = grad_w;
+    p.sums = grad_params;
+    const hipError_t he = rtn::launch_weight_backward(p, (hipStream_t)stream);
+    return he == hipSuccess ? RTN_OK : hip_fail(he);
+}
+
 int rtn_epilogue_reparam(const int32_t* acc, int64_t M, int64_t N, int64_t K, const rtn_epilogue* ep,
                          float* y_out, void* stream)
 {

@@ -40,6 +40,20 @@ struct ActBwdArgs {
 int64_t act_backward_blocks(int64_t n);
 hipError_t launch_act_backward(const ActBwdArgs& p, hipStream_t st);
 
+// Backward of the reparameterized ternary weights, one filter per row.
+struct WeightBwdArgs {
+    const float* w;      // [O][K] latent weights
+    const float* g;      // [O][K] dL/d(alpha * t_w)
+    int64_t O, K;
+    float lo, hi;        // thresholds on k_W * w + b_W
+    const float* kw;     // [O]
+    const float* bw;     // [O]
+    const float* alpha;  // [O]
+    float* dw;           // nullable [O][K]
+    double* sums;        // out [O][3]: dalpha, dk_W, db_W
+};
+hipError_t launch_weight_backward(const WeightBwdArgs& p, hipStream_t st);
+
 // Epilogue parameters as the kernels see them.
 struct EpiArgs {
     Param alpha_a, beta_a;  // vector: per GEMM row m (GEMM only)

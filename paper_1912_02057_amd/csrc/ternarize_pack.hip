@@ -508,6 +508,49 @@ __global__ __launch_bounds__(256) void k_sum_partials(const double* partials, in
         out[1] = (red[1][0] + red[1][1]) + (red[1][2] + red[1][3]);
     }
 }
+
+// Weight side (Section "Weight Ternarization": Wbar = k_W*W + b_W per filter, W^t = Q(Wbar),
+// Wbar^t = alpha*W^t): the rules of Eq.6 / Eq.7 carried through the weight transform by the
+// chain rule.  One block per filter; a lane walks the filter with stride 256, so a wave
+// reads whole lines.  The three sums are formed in double, per lane in index order, then
+// over the wave and over the four waves in a fixed order: reproducible run to run.
+__global__ __launch_bounds__(256) void k_weight_backward(WeightBwdArgs p)
+{
+    __shared__ double red[3][4];
+    const int64_t o = blockIdx.x;
+    const float kw = p.kw[o], bw = p.bw[o], al = p.alpha[o];
+    const float* w = p.w + o * p.K;
+    const float* g = p.g + o * p.K;
+    float* dw = p.dw ? p.dw + o * p.K : nullptr;
+    double sa = 0.0, sk = 0.0, sb = 0.0;
+    for (int64_t k = threadIdx.x; k < p.K; k += 256) {
+        const float wv = w[k], gv = g[k];
+        const float wbar = __fmaf_rn(kw, wv, bw);
+        const int t = (int)(wbar > p.hi) - (int)(wbar < p.lo);
+        sa += (double)t * (double)gv;
+        const bool inside = wbar <= 1.0f && wbar >= -1.0f;  // NaN is outside
+        const float dwbar = inside ? __fmul_rn(al, gv) : 0.0f;
+        if (inside) {  // a clipped (or NaN) weight adds nothing, not NaN * 0
+            sk += (double)wv * (double)dwbar;
+            sb += (double)dwbar;
+        }
+        if (dw) dw[k] = __fmul_rn(kw, dwbar);
+    }
+    sa = wave_sum(sa);
+    sk = wave_sum(sk);
+    sb = wave_sum(sb);
+    const int wave = threadIdx.x >> 6;
+    if ((threadIdx.x & 63) == 0) {
+        red[0][wave] = sa;
+        red[1][wave] = sk;
+        red[2][wave] = sb;
+    }
+    __syncthreads();
+    if (threadIdx.x < 3) {
+        const int c = threadIdx.x;
+        p.sums[3 * o + c] = (red[c][0] + red[c][1]) + (red[c][2] + red[c][3]);
+    }
+}
 }  // namespace
 
 int64_t act_backward_blocks(int64_t n) { return (n + kBwdPerBlock - 1) / kBwdPerBlock; }
@@ -521,6 +564,12 @@ hipError_t launch_act_backward(const ActBwdArgs& p, hipStream_t st)
     else
         hipLaunchKernelGGL(k_act_backward<false>, dim3((unsigned)nb), dim3(256), 0, st, p);
     hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(256), 0, st, p.partials, nb, p.sums);
+    return hipGetLastError();
+}
+
+hipError_t launch_weight_backward(const WeightBwdArgs& p, hipStream_t st)
+{
+    hipLaunchKernelGGL(k_weight_backward, dim3((unsigned)p.O), dim3(256), 0, st, p);
     return hipGetLastError();
 }
 

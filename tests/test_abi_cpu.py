@@ -253,6 +253,27 @@ def test_weight_conv_rejects(L):
     assert with_(_17=ODD) == B.RTN_ERR_ALIGN
 
 
+def test_weight_backward_rejects(L):
+    call = L.rtn_weight_backward
+    lo, hi = _f(-0.5), _f(0.5)
+    ok = [FAKE, FAKE, 64, 576, lo, hi, FAKE, FAKE, FAKE, FAKE, FAKE, None]
+
+    def with_(**kw):
+        a = list(ok)
+        for i, v in kw.items():
+            a[int(i[1:])] = v
+        return call(*a)
+    for i in (0, 1, 4, 5, 6, 7, 8, 10):                         # everything but grad_w is required
+        assert with_(**{"_%d" % i: None}) == B.RTN_ERR_NULL, i
+    assert with_(_2=0) == B.RTN_ERR_SHAPE
+    assert with_(_3=0) == B.RTN_ERR_SHAPE
+    assert with_(_3=(1 << 22) + 1) == B.RTN_ERR_SHAPE
+    assert with_(_4=_f(0.5), _5=_f(-0.5)) == B.RTN_ERR_SHAPE    # lo > hi
+    assert with_(_4=_f(float("nan"))) == B.RTN_ERR_SHAPE
+    assert with_(_9=ODD) == B.RTN_ERR_ALIGN
+    assert with_(_10=C.c_void_p(0x10004)) == B.RTN_ERR_ALIGN    # doubles need 8-byte alignment
+
+
 def test_activation_backward_rejects(L):
     call = L.rtn_activation_backward
     lo, hi, gm = _f(-0.5), _f(0.5), _f(1.0)

@@ -989,3 +989,48 @@ def test_activation_backward_layer1_tensor_and_reproducible():
     scale = float(np.abs(g).astype(np.float64).sum())
     assert abs(s[0] - rg) <= 1e-12 * scale and abs(s[1] - rb) <= 1e-12 * scale
     assert (da.cpu().numpy() == rda).all()
+
+
+# ------------------ backward of the reparameterized ternary weights -------------
+def _weight_bwd_check(O, K, seed, want_dw=True):
+    rng = np.random.default_rng(seed)
+    w = (rng.standard_normal((O, K)) * 0.6).astype(np.float32)
+    g = rng.standard_normal((O, K)).astype(np.float32)
+    kw = (0.7 + rng.random(O)).astype(np.float32)
+    bw = (rng.standard_normal(O) * 0.1).astype(np.float32)
+    al = (0.2 + rng.random(O)).astype(np.float32)
+    if K >= 8:                                         # inclusive clip, threshold ties, NaN: k = 1, b = 0 in filter 0
+        kw[0], bw[0] = 1.0, 0.0
+        w[0, :6] = [1.0, -1.0, 0.5, -0.5, np.nan, 2.0]
+    out = torch.full((O, K), 7.0, dtype=torch.float32, device=T.DEV) if want_dw else None
+    dw, sums = B.weight_backward(T.dev(w), T.dev(g), -0.5, 0.5, T.dev(kw), T.dev(bw), T.dev(al),
+                                 want_grad_w=want_dw, grad_w=out)
+    torch.cuda.synchronize()
+    rdw, rs = orc.weight_backward(w, g, -0.5, 0.5, kw, bw, al, want_dw)
+    s = sums.cpu().numpy()
+    ok = ~np.isnan(w)
+    gabs = np.where(ok, np.abs(g), 0).astype(np.float64)
+    scale_a = gabs.sum(axis=1) + 1e-30
+    scale_b = al.astype(np.float64) * scale_a
+    scale_k = (np.where(ok, np.abs(w), 0) * gabs).sum(axis=1) * al + 1e-30
+    for col, scale in ((0, scale_a), (1, scale_k), (2, scale_b)):
+        assert (np.abs(s[:, col] - rs[:, col]) <= 1e-12 * scale).all(), (col, O, K)
+    if want_dw:
+        assert (dw.cpu().numpy() == rdw).all()                          # bit-exact
+    return sums
+
+
+@pytest.mark.parametrize("O,K", [(1, 1), (3, 7), (2, 255), (5, 257), (64, 576), (130, 1153), (512, 4608),
+                                 (3, 70001)])
+def test_weight_backward_vs_oracle(O, K):
+    _say("weight backward O=%d K=%d" % (O, K))
+    s1 = _weight_bwd_check(O, K, seed=O * 7 + K)
+    s2 = _weight_bwd_check(O, K, seed=O * 7 + K, want_dw=False)
+    assert torch.equal(s1, s2)                                          # reproducible, with or without dW
+
+
+def test_weight_backward_all_resnet18_ternary_filters():
+    for i, shape in enumerate(wl.resnet18_ternary_layers()):
+        _say("weight backward %s" % (shape,))
+        _weight_bwd_check(shape.O, shape.C * shape.k * shape.k, seed=900 + i)
+

@@ -541,6 +541,10 @@ def test_weight_backward_hand_listed():
     assert dw.tolist() == [[1.0, 0.0, 0.0, 8.0], [16.0, 32.0, 64.0, 0.0]]
     _, sums2 = orc.weight_backward(w, g, -0.5, 0.5, kw, bw, al, want_dw=False)
     assert (sums2 == sums).all()
+    # a NaN weight is outside the clip: code 0, no gradient, and it adds nothing to any sum
+    w[0, 1] = np.nan
+    dw, sums3 = orc.weight_backward(w, g, -0.5, 0.5, kw, bw, al)
+    assert sums3[0].tolist() == [4.0, 0.5 * 0.5 + 0.25 * 4.0, 4.5] and dw[0].tolist() == [1.0, 0.0, 0.0, 8.0]
 
 
 def test_weight_backward_vs_torch_autograd_of_the_ste_form():
