@@ -13,7 +13,7 @@ it, from HIP events on the launch stream), `cpu_baseline` (the CPU oracle timed 
 bounded sample of the same workload), `fused_blocks` (the same convs with the
 ternarizing epilogue, and the trunk as one chained forward pass) and `layers`
 (per-layer times).  Other workloads: --workload gemm4096 | gemm_sweep | wgemm4096 |
-resnet18_weight_only_convs | act_backward.
+resnet18_weight_only_convs | act_backward | weight_backward.
 """
 import argparse
 import json
@@ -39,7 +39,7 @@ def main():
     ap.add_argument("--batch", type=int, default=256)
     ap.add_argument("--workload", default="resnet18_ternary_convs",
                     choices=["resnet18_ternary_convs", "gemm4096", "wgemm4096", "resnet18_weight_only_convs",
-                             "act_backward", "gemm_sweep"])
+                             "act_backward", "weight_backward", "gemm_sweep"])
     ap.add_argument("--tile", type=int, default=-1, help="force an MFMA tile configuration (tuning)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-images", type=int, default=128,
@@ -256,6 +256,36 @@ def main():
         workload = "backward of the reparameterized ternary activation, %d x 64 x 56 x 56 fp32" % args.batch
         nlaunch = 1
         layers = [dict(sh=None)]
+    elif args.workload == "weight_backward":
+        # backward of the ternary weight transform over the filters of the 19 ternary conv layers (one call
+        # per layer): reads W and g, writes dL/dW, reduces dalpha, dk_W, db_W per filter
+        wb = []
+        rng = np.random.Generator(np.random.PCG64(12))
+        for sh in wl.resnet18_ternary_layers():
+            O_, K_ = sh.O, sh.C * sh.k * sh.k
+            hw = (rng.standard_normal((O_, K_), dtype=np.float32) * np.float32(0.6))
+            hg = rng.standard_normal((O_, K_), dtype=np.float32)
+            hk = (0.7 + rng.random(O_)).astype(np.float32)
+            hb = (rng.standard_normal(O_) * 0.1).astype(np.float32)
+            ha = (0.2 + rng.random(O_)).astype(np.float32)
+            wb.append(dict(host=(hw, hg, hk, hb, ha), dev=[to_dev(v) for v in (hw, hg, hk, hb, ha)],
+                           dw=torch.empty((O_, K_), dtype=torch.float32, device=dev),
+                           sums=torch.empty((O_, 3), dtype=torch.float64, device=dev)))
+
+        def step(timers=None):
+            for i, l in enumerate(wb):
+                if timers is not None:
+                    timers[i][0].record()
+                    timers[i][1].record()
+                w_, g_, k_, b_, a_ = l["dev"]
+                B.weight_backward(w_, g_, -0.5, 0.5, k_, b_, a_, grad_w=l["dw"], sums=l["sums"])
+                if timers is not None:
+                    timers[i][2].record()
+
+        macs_step = sum(l["host"][0].size for l in wb)   # "MACs" here: weight elements
+        workload = "backward of the ternary weight transform, the filters of the 19 ternary convs of ResNet-18"
+        nlaunch = len(wb)
+        layers = [dict(sh=None)] * nlaunch
     elif args.workload == "resnet18_weight_only_convs":
         # the same 19 layer shapes with ternary weights and fp32 activations (one call per layer:
         # activation split, weight copy, epilogue table, bf16 matrix-core conv)
@@ -454,6 +484,12 @@ def main():
                         peak=HBM_PEAK_GBS, unit="GB/s", frac=round(gbs / HBM_PEAK_GBS, 4), traffic=None,
                         launches_per_step=nlaunch, avg_launch_us=round(conv_total_s / nlaunch * 1e6, 1),
                         bytes_per_launch=12.0 * macs_step)
+    elif args.workload == "weight_backward":
+        gbs = 12.0 * macs_step / conv_total_s / 1e9      # 4 B W + 4 B g read, 4 B dL/dW written per element
+        roofline = dict(bound="hbm", kernel="k_weight_backward", achieved=round(gbs, 1),
+                        peak=HBM_PEAK_GBS, unit="GB/s", frac=round(gbs / HBM_PEAK_GBS, 4), traffic=None,
+                        launches_per_step=nlaunch, avg_launch_us=round(conv_total_s / nlaunch * 1e6, 1),
+                        bytes_per_launch=round(12.0 * macs_step / nlaunch, 0))
     elif args.workload == "resnet18_weight_only_convs":
         bf16_tflops = 3 * achieved_tops
         roofline = dict(bound="mfma", kernel="activation split + k_tmm (bf16 MFMA implicit-GEMM conv, fp32 accumulate)",
@@ -504,6 +540,14 @@ def main():
             t_cpu = time.perf_counter() - c0
             macs_cpu = nel
             sample = "the whole tensor (%d elements), single thread as the oracle is written" % nel
+        elif args.workload == "weight_backward":
+            c0 = time.perf_counter()
+            for l in wb:
+                hw, hg, hk, hb, ha = l["host"]
+                orc.weight_backward(hw, hg, -0.5, 0.5, hk, hb, ha)
+            t_cpu = time.perf_counter() - c0
+            macs_cpu = macs_step
+            sample = "all 19 weight tensors (%d elements), single thread as the oracle is written" % macs_step
         elif args.workload == "resnet18_weight_only_convs":
             n_img = max(1, args.cpu_images // 8)
             for i, sh in enumerate(wl.resnet18_ternary_layers()):
@@ -535,7 +579,7 @@ def main():
             macs_cpu = rows.size * 4096 * 4096
             sample = "64 of 4096 output rows, all columns"
         cpu = dict(value=round(macs_cpu / t_cpu / 1e12, 6), unit="TMAC/s",
-                   cores=1 if args.workload == "act_backward" else orc.num_threads(),
+                   cores=1 if args.workload in ("act_backward", "weight_backward") else orc.num_threads(),
                    kind="oracle", sample=sample, seconds=round(t_cpu, 2))
 
     value = macs_step / (ms_per_step * 1e-3) / 1e12
@@ -544,13 +588,15 @@ def main():
         if args.workload == "resnet18_ternary_convs" else
         ("elements/s (in units of 1e12), backward of the reparameterized ternary activation"
          if args.workload == "act_backward" else
+         "elements/s (in units of 1e12), backward of the ternary weight transform"
+         if args.workload == "weight_backward" else
          "effective MAC/s, weight-only ternary GEMM" if args.workload == "wgemm4096"
          else ("effective MAC/s, weight-only ternary convs of ResNet-18"
                if args.workload == "resnet18_weight_only_convs" else "effective ternary MAC/s, ternary GEMM")),
         "value": round(value, 3), "unit": "TMAC/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16x3" if args.workload in ("wgemm4096", "resnet18_weight_only_convs") else
-        ("f32" if args.workload == "act_backward" else "i8"), "data": "synthetic",
+        ("f32" if args.workload in ("act_backward", "weight_backward") else "i8"), "data": "synthetic",
         "config": {"workload": workload, "batch": args.batch, "tile": args.tile},
         "tops": round(2 * value, 1), "pct_int8_mfma_peak": round(100 * 2 * value / INT8_PEAK_TOPS, 2),
         "contraction_only": {"tmacs": round(macs_step / conv_total_s / 1e12, 3),

@@ -511,9 +511,11 @@ __global__ __launch_bounds__(256) void k_sum_partials(const double* partials, in
 
 // Weight side (Section "Weight Ternarization": Wbar = k_W*W + b_W per filter, W^t = Q(Wbar),
 // Wbar^t = alpha*W^t): the rules of Eq.6 / Eq.7 carried through the weight transform by the
-// chain rule.  One block per filter; a lane walks the filter with stride 256, so a wave
-// reads whole lines.  The three sums are formed in double, per lane in index order, then
-// over the wave and over the four waves in a fixed order: reproducible run to run.
+// chain rule.  One block per filter; a lane walks the filter with stride 256 (elements, or
+// groups of four where the layout allows 16-byte accesses), so a wave reads whole lines.
+// The three sums are formed in double, per lane in index order, then over the wave and
+// over the four waves in a fixed order: reproducible run to run.
+template <bool VEC>
 __global__ __launch_bounds__(256) void k_weight_backward(WeightBwdArgs p)
 {
     __shared__ double red[3][4];
@@ -523,8 +525,7 @@ __global__ __launch_bounds__(256) void k_weight_backward(WeightBwdArgs p)
     const float* g = p.g + o * p.K;
     float* dw = p.dw ? p.dw + o * p.K : nullptr;
     double sa = 0.0, sk = 0.0, sb = 0.0;
-    for (int64_t k = threadIdx.x; k < p.K; k += 256) {
-        const float wv = w[k], gv = g[k];
+    auto element = [&](float wv, float gv) -> float {
         const float wbar = __fmaf_rn(kw, wv, bw);
         const int t = (int)(wbar > p.hi) - (int)(wbar < p.lo);
         sa += (double)t * (double)gv;
@@ -534,7 +535,25 @@ __global__ __launch_bounds__(256) void k_weight_backward(WeightBwdArgs p)
             sk += (double)wv * (double)dwbar;
             sb += (double)dwbar;
         }
-        if (dw) dw[k] = __fmul_rn(kw, dwbar);
+        return __fmul_rn(kw, dwbar);
+    };
+    if (VEC) {  // K % 4 == 0 and 16-byte aligned tensors: every filter starts on a 16-byte boundary
+        const int64_t k4n = p.K >> 2;
+#pragma unroll 2
+        for (int64_t k4 = threadIdx.x; k4 < k4n; k4 += 256) {
+            const float4 wv = ((const float4*)w)[k4], gv = ((const float4*)g)[k4];
+            float4 d;
+            d.x = element(wv.x, gv.x);
+            d.y = element(wv.y, gv.y);
+            d.z = element(wv.z, gv.z);
+            d.w = element(wv.w, gv.w);
+            if (dw) ((float4*)dw)[k4] = d;
+        }
+    } else {
+        for (int64_t k = threadIdx.x; k < p.K; k += 256) {
+            const float d = element(w[k], g[k]);
+            if (dw) dw[k] = d;
+        }
     }
     sa = wave_sum(sa);
     sk = wave_sum(sk);
@@ -569,7 +588,11 @@ hipError_t launch_act_backward(const ActBwdArgs& p, hipStream_t st)
 
 hipError_t launch_weight_backward(const WeightBwdArgs& p, hipStream_t st)
 {
-    hipLaunchKernelGGL(k_weight_backward, dim3((unsigned)p.O), dim3(256), 0, st, p);
+    const bool vec = (p.K & 3) == 0 && (((uintptr_t)p.w | (uintptr_t)p.g | (uintptr_t)p.dw) & 15) == 0;
+    if (vec)
+        hipLaunchKernelGGL(k_weight_backward<true>, dim3((unsigned)p.O), dim3(256), 0, st, p);
+    else
+        hipLaunchKernelGGL(k_weight_backward<false>, dim3((unsigned)p.O), dim3(256), 0, st, p);
     return hipGetLastError();
 }
 
