@@ -296,3 +296,14 @@ def test_activation_backward_rejects(L):
     assert with_(_7=C.c_void_p(0x10004)) == B.RTN_ERR_ALIGN     # doubles need 8-byte alignment
     assert with_(_8=None) == B.RTN_ERR_WORKSPACE
     assert with_(_9=8) == B.RTN_ERR_WORKSPACE
+
+
+def test_bench_refuses_more_than_one_gpu():
+    """bench.py measures one GPU; asked for more it exits with status 2 and says so, before touching a device."""
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    r = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--gpus", "2"], capture_output=True,
+                       text=True, timeout=300)
+    assert r.returncode == 2
+    assert "ONE GPU" in (r.stdout + r.stderr)
