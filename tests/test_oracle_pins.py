@@ -13,7 +13,7 @@ import torch
 
 from oracle import rtn_oracle as orc
 
-GOLD = os.path.join(os.path.dirname(__file__), "golden")
+from golden_io import GOLD, table4_params
 
 
 def _rand_t(rng, shape, p0=0.4):
@@ -299,6 +299,17 @@ def test_conv_epilogue_equals_direct_float_conv(true_zero):
                                   bw.astype(np.float64)[:, None, None, None])
             lib = torch.nn.functional.conv2d(va, vw, stride=s, padding=p).numpy()
             assert np.allclose(direct, lib, rtol=1e-12, atol=1e-12)
+        else:
+            # code-zero padding: the border holds code 0, i.e. the value beta_a -- the same
+            # framework conv, without padding, of the value tensor padded with beta_a
+            va = torch.from_numpy(float(aa) * ta.astype(np.float64) + float(ba))
+            va = torch.nn.functional.pad(va, (p, p, p, p), value=float(ba))
+            vw = torch.from_numpy(aw.astype(np.float64)[:, None, None, None] * tw +
+                                  bw.astype(np.float64)[:, None, None, None])
+            lib = torch.nn.functional.conv2d(va, vw, stride=s, padding=0).numpy()
+            assert np.allclose(direct, lib, rtol=1e-12, atol=1e-12)
+            # ... and Eq.9's claim that C is one constant per filter holds in this mode
+            assert (Kv == C * k * k).all() and (Sw == Sw[..., :1, :1]).all()
 
 
 # ------------------------------------------------------------------ O7 ----
@@ -598,3 +609,33 @@ def test_weight_backward_reduces_to_the_activation_rule_and_rounds_as_stated():
     _, s = orc.weight_backward(np.array([[e]], np.float32), np.array([[1.0]], np.float32), -1.0, 2.0 ** -11,
                                np.array([e], np.float32), np.array([-1.0], np.float32), np.array([1.0], np.float32))
     assert s[0, 0] == 1.0
+
+
+# ----------------------------------------------- Table 4 as a worked case ----
+def test_table4_rows_are_the_ternary_layers_and_eq9_holds_with_printed_values():
+    """Table 4 lists gamma, beta and the mean alpha of the 19 ternary convs of ResNet-18.
+    The layer list of the workloads must be exactly those rows, and with the printed
+    values (the paper's case: a weight scale, no weight offset) the oracle's epilogue must
+    equal Eq.9 written out, z = alpha*gamma*D + alpha*beta*(1 (x) W^t), and the direct
+    product of the reparameterized values."""
+    from paper_1912_02057_amd import workloads as wl
+    rows = table4_params()
+    layers = wl.resnet18_ternary_layers()
+    assert [r[0] for r in rows] == [l.name for l in layers] and len(rows) == 19
+    g = np.array([r[1] for r in rows]); b = np.array([r[2] for r in rows]); a = np.array([r[3] for r in rows])
+    # the ranges the synthetic recipe draws from with table4=True are the printed extremes
+    assert (round(g.min(), 2), round(g.max(), 2)) == (0.77, 2.47)
+    assert (round(b.min(), 2), round(b.max(), 2)) == (-0.23, 1.48)
+    assert (round(a.min(), 2), round(a.max(), 2)) == (0.85, 3.05)
+    rng = np.random.default_rng(4)
+    for (name, gamma, beta, alpha), sh in zip(rows, layers):
+        C, k = 6, sh.k                  # the layer's window, stride and pad on a small tensor
+        ta, tw = _rand_t(rng, (1, C, 9, 9)), _rand_t(rng, (3, C, k, k))
+        D = orc.conv_acc(ta, tw, sh.stride, sh.pad)
+        Sa, Sw, Kv = orc.conv_sums(ta, tw, sh.stride, sh.pad, False)
+        y = orc.conv_epilogue(D, Sa, Sw, Kv, gamma, beta, alpha, None)
+        f32 = lambda v: float(np.float32(v))
+        z9 = f32(alpha) * f32(gamma) * D + f32(alpha) * f32(beta) * Sw[None].astype(np.float64)
+        assert np.abs(y - z9).max() <= 1e-6 * np.abs(z9).max(), name
+        direct = orc.conv_direct(ta, tw, sh.stride, sh.pad, gamma, beta, alpha, None, False)
+        assert np.abs(y - direct).max() <= 1e-5, name
