@@ -18,6 +18,20 @@ def _say(msg):
     print("[case] " + msg, flush=True)
 
 
+def _sample_images(batch, n, seed):
+    """n seeded images spread over the batch: first, last, the two in the middle and
+    random ones between (tiles in the middle of the remapped grid included)."""
+    fixed = [0, batch // 2 - 1, batch // 2, batch - 1]
+    rest = np.random.default_rng(seed).choice(np.setdiff1d(np.arange(batch), fixed), n - len(fixed), replace=False)
+    return sorted(set(fixed) | set(int(i) for i in rest))
+
+
+def _sample_rows(M, n, seed):
+    """n seeded rows of an M-row problem, first and last included, sorted."""
+    rows = np.random.default_rng(seed).choice(np.arange(1, M - 1), n - 2, replace=False)
+    return np.sort(np.concatenate([[0, M - 1], rows])).astype(np.int64)
+
+
 # ------------------------------------------------------------ S1: pack ------
 @pytest.mark.parametrize("rows,K", [(1, 1), (5, 63), (4, 64), (7, 65), (9, 200), (37, 1000), (3, 4096),
                                     (130, 258)])
@@ -444,7 +458,7 @@ CONV2_OF_BLOCK = [1, 3, 5, 8, 10, 13, 15, 18]
 def test_resnet18_conv2_layers_batch256_block_tail_sampled_images(idx):
     """The last conv of each ResNet-18 block at batch 256 with the block-tail epilogue
     (residual add, ReLU, fp32 output and the next block's codes), in the launch
-    configuration of the benchmark's trunk forward; the oracle recomputes two images."""
+    configuration of the benchmark's trunk forward; the oracle recomputes eight images spread over the batch."""
     shape = wl.resnet18_ternary_layers()[idx]
     _say("resnet18 b256 block tail %s" % (shape,))
     case = wl.conv_case(shape, batch=256, seed=600 + idx, per_channel=True, bn=True)
@@ -452,7 +466,7 @@ def test_resnet18_conv2_layers_batch256_block_tail_sampled_images(idx):
     rng = np.random.default_rng(idx)
     res = rng.standard_normal((256, shape.O, shape.OH, shape.OH)).astype(np.float32)
     codes, y = T.hip_conv_ternarize(case, lo, hi, True, relu=False, residual=res, relu_out=True, want_y=True)
-    imgs = [0, 255]
+    imgs = _sample_images(256, 8, 600 + idx)
     ref = T.oracle_conv(case, True, relu=False, images=imgs)
     s = orc.add_relu(ref["y"], res[imgs], True)
     want = orc.nchw_to_nhwc_i8(orc.ternarize_nchw(s, lo, hi), (shape.O + 63) // 64 * 64)
@@ -469,13 +483,13 @@ CONV1_OF_BLOCK = [0, 2, 4, 7, 9, 12, 14, 17]
 def test_resnet18_conv1_layers_batch256_ternarize_sampled_images(idx):
     """The first conv of each ResNet-18 block at batch 256 (the shapes whose output
     feeds another ternary conv), ternarizing epilogue, launch configuration as the
-    benchmark's fused workload; the oracle recomputes two whole images."""
+    benchmark's fused workload; the oracle recomputes eight whole images spread over the batch."""
     shape = wl.resnet18_ternary_layers()[idx]
     _say("resnet18 b256 conv+ternarize %s" % (shape,))
     case = wl.conv_case(shape, batch=256, seed=500 + idx, per_channel=True, bn=True)
     lo, hi = np.float32(-0.5), np.float32(0.5)
     got = T.hip_conv_ternarize(case, lo, hi, True, relu=True)
-    imgs = [0, 255]
+    imgs = _sample_images(256, 8, 500 + idx)
     ref = T.oracle_conv(case, True, relu=True, images=imgs)
     T.assert_codes_match(got[imgs].cpu().numpy(), T.oracle_next_codes(ref, lo, hi), ref["y"], lo, hi, shape.name)
     # properties at any size: only codes, zero padding channels, a plausible mix
@@ -487,7 +501,7 @@ def test_resnet18_conv1_layers_batch256_ternarize_sampled_images(idx):
 # ----------------------------------------------------- full-size checks ------
 def test_config2_gemm_4096_sampled_rows():
     """M = N = K = 4096 in the launch configuration the benchmark times; the
-    oracle computes 48 sampled rows (all columns) plus every code and side sum."""
+    oracle computes 1024 sampled rows (all columns) plus every code and side sum."""
     _say("config 2: 4096^3, sampled rows")
     case = wl.gemm_case(4096, 4096, 4096, p_zero=0.4, seed=1)
     got = T.hip_gemm(case, want_acc="separate")
@@ -496,8 +510,7 @@ def test_config2_gemm_4096_sampled_rows():
     assert (got["ca"].cpu().numpy() == ta).all() and (got["cw"].cpu().numpy() == tw).all()
     Sa, Sw = orc.row_sums(ta), orc.row_sums(tw)
     assert (got["Sa"].cpu().numpy() == Sa).all() and (got["Sw"].cpu().numpy() == Sw).all()
-    rows = np.sort(np.random.default_rng(0).choice(4096, 48, replace=False)).astype(np.int64)
-    rows[0], rows[-1] = 0, 4095
+    rows = _sample_rows(4096, 1024, 0)
     D = orc.gemm_acc_rows(ta, tw, rows)
     assert (got["D"].cpu().numpy()[rows] == D).all()
     y = orc.gemm_epilogue(D, 4096, Sa[rows], Sw, case["alpha_a"][rows], case["beta_a"][rows],
@@ -512,12 +525,12 @@ def test_config2_gemm_4096_sampled_rows():
 @pytest.mark.parametrize("idx", range(19))
 def test_resnet18_layers_batch256_sampled_images(idx):
     """Each ternary ResNet-18 layer at batch 256 (the benchmark's shape and launch
-    configuration); the oracle recomputes two whole images of the batch."""
+    configuration); the oracle recomputes eight whole images spread over the batch."""
     shape = wl.resnet18_ternary_layers()[idx]
     _say("resnet18 b256 %s" % (shape,))
     case = wl.conv_case(shape, batch=256, seed=100 + idx, per_channel=True, bn=True)
     got = T.hip_conv(case, True, relu=True, want_acc="separate")
-    imgs = [0, 255]
+    imgs = _sample_images(256, 8, 100 + idx)
     ref = T.oracle_conv(case, True, relu=True, images=imgs)
     assert (got["D"][imgs].cpu().numpy() == ref["D"]).all()
     T.assert_y_close(got["y"][imgs].cpu().numpy(), ref["y"], shape.name)
@@ -530,17 +543,36 @@ def test_resnet18_layers_batch256_sampled_images(idx):
 def test_resnet18_layers_batch64_sampled_images(idx):
     """The 19 ternary ResNet-18 layer shapes at batch 64, each standalone, per-filter
     thresholds and scales, one activation threshold per tensor; single-output launches
-    as the benchmark issues them.  The oracle recomputes two whole images."""
+    as the benchmark issues them.  The oracle recomputes six whole images spread over the batch."""
     shape = wl.resnet18_ternary_layers()[idx]
     _say("resnet18 b64 %s" % (shape,))
     case = wl.conv_case(shape, batch=64, seed=400 + idx, per_channel=True)
     got = T.hip_conv(case, True, want_acc="separate")
-    imgs = [3, 63]
+    imgs = _sample_images(64, 6, 400 + idx)
     ref = T.oracle_conv(case, True, images=imgs)
     assert (got["ca"][imgs].cpu().numpy() == orc.nchw_to_nhwc_i8(ref["ta"], got["ca"].shape[-1])).all()
     assert (got["D"][imgs].cpu().numpy() == ref["D"]).all()
     T.assert_y_close(got["y"][imgs].cpu().numpy(), ref["y"], shape.name)
     assert int(got["D"].abs().max()) <= shape.K
+
+
+@pytest.mark.parametrize("idx", range(19))
+def test_resnet18_layers_table4_parameters(idx):
+    """Each ternary ResNet-18 layer with the activation scale gamma, offset beta and
+    (mean) weight scale alpha the paper prints for it in Table 4, no weight offset
+    (Eq.9 as printed, ReLU included), batch 3, both pad modes."""
+    from golden_io import table4_params
+    name, gamma, beta, alpha = table4_params()[idx]
+    shape = wl.resnet18_ternary_layers()[idx]
+    assert shape.name == name
+    _say("resnet18 Table 4 parameters %s gamma=%g beta=%g alpha=%g" % (name, gamma, beta, alpha))
+    case = wl.conv_case(shape, batch=3, seed=800 + idx, per_channel=False)
+    case.update(alpha_a=np.float32(gamma), beta_a=np.float32(beta), alpha_w=np.float32(alpha), beta_w=None)
+    for true_zero in (True, False):
+        ref = T.oracle_conv(case, true_zero, relu=True)
+        got = T.hip_conv(case, true_zero, relu=True)
+        assert (got["D"].cpu().numpy() == ref["D"]).all()
+        T.assert_y_close(got["y"].cpu().numpy(), ref["y"], name)
 
 
 # ------------------------------------ config 5: the large GEMM sweep -------------
@@ -550,8 +582,7 @@ SWEEP = [(M, NK, p0) for M in (8192, 16384) for NK in (4096, 8192) for p0 in (0.
 def _sweep_check(M, NK, p0, fmt, seed):
     case = wl.gemm_case(M, NK, NK, p_zero=p0, seed=seed)
     got = T.hip_gemm(case, fmt=fmt, want_acc="separate")
-    rows = np.sort(np.random.default_rng(seed).choice(M, 12, replace=False)).astype(np.int64)
-    rows[0], rows[-1] = 0, M - 1
+    rows = _sample_rows(M, 1024, seed)
     ta = orc.ternarize(case["xa"][rows], -0.5, 0.5)
     tw = orc.ternarize(case["xw"], -0.5, 0.5)
     Sa, Sw = orc.row_sums(ta), orc.row_sums(tw)
@@ -572,16 +603,15 @@ def _sweep_check(M, NK, p0, fmt, seed):
 
 @pytest.mark.parametrize("M,NK,p0", SWEEP)
 def test_config5_gemm_sweep_mfma(M, NK, p0):
-    """Large ternary GEMMs at three sparsities on the matrix-core path: 12 sampled
+    """Large ternary GEMMs at three sparsities on the matrix-core path: 1024 sampled
     rows (all columns) against the oracle, all side sums, all weight codes."""
     _say("sweep mfma M=%d N=K=%d P(0)=%.1f" % (M, NK, p0))
     _sweep_check(M, NK, p0, B.RTN_CODE_I8, seed=int(1000 * p0) + M // 1024 + NK // 512)
 
 
-@pytest.mark.parametrize("M,NK,p0", [(8192, 4096, 0.2), (8192, 4096, 0.5), (8192, 4096, 0.8), (16384, 8192, 0.5)])
+@pytest.mark.parametrize("M,NK,p0", SWEEP)
 def test_config5_gemm_sweep_popcount(M, NK, p0):
-    """The same sweep on the bit-plane popcount path (Eq.8): every sparsity at the
-    smallest size, and the largest size once."""
+    """The same sweep, all twelve points, on the bit-plane popcount path (Eq.8)."""
     _say("sweep popc M=%d N=K=%d P(0)=%.1f" % (M, NK, p0))
     _sweep_check(M, NK, p0, B.RTN_CODE_BITPLANE, seed=int(1000 * p0) + 7)
 
@@ -832,8 +862,21 @@ def _wgemm_check(M, N, K, seed, vector_alpha=True, relu=False, bn=False, rows=No
         scale = scale * np.abs(bs.astype(np.float64))[None, :]
     tol = (4.0 * np.sqrt(3.0 * K) + 8.0) * 2.0 ** -24 * scale + 1.2e-7 * np.abs(ref) + 1e-30
     err = np.abs(y[sel].astype(np.float64) - ref)
+    _report_rel(err, ref, scale, tol, what)
     assert (err <= tol).all(), "%s: worst err/tol %.3g" % (what, float((err / tol).max()))
     return float((err / tol).max())
+
+
+def _report_rel(err, ref, scale, tol, what):
+    """Prints what the weight-only path achieved next to its bound: the largest error
+    relative to the output over the outputs that are not cancelled (|y| above 1 % of
+    alpha * sum|x|), relative to alpha * sum|x| over all outputs, and the worst
+    err / bound."""
+    big = np.abs(ref) > 1e-2 * np.broadcast_to(scale, ref.shape)
+    rel_y = float((err[big] / np.abs(ref[big])).max()) if big.any() else 0.0
+    rel_s = float((err / np.maximum(np.broadcast_to(scale, ref.shape), 1e-300)).max())
+    print("[weight-only] %s: max |err|/|y| %.3g (uncancelled outputs), max |err|/(alpha*sum|x|) %.3g, "
+          "worst err/bound %.3g" % (what, rel_y, rel_s, float((err / tol).max())), flush=True)
 
 
 WGEMM_SHAPES = [(1, 1, 1), (37, 19, 131), (64, 64, 64), (65, 33, 64), (300, 200, 576), (129, 257, 1000),
@@ -904,6 +947,7 @@ def _wconv_check(shape, batch, seed, relu=False, bn=False, Wx=None, images=None,
     tol = (4.0 * np.sqrt(3.0 * K) + 8.0) * 2.0 ** -24 * scale + 1.2e-7 * np.abs(ref) + 1e-30
     err = np.abs(y[sel].astype(np.float64) - ref)
     assert y.shape[1:] == ref.shape[1:]
+    _report_rel(err, ref, scale, tol, what)
     assert (err <= tol).all(), "%s: worst err/tol %.3g" % (what, float((err / tol).max()))
 
 
