@@ -284,6 +284,21 @@ int rtn_activation_backward(const float *a, const float *grad_out, int64_t n, co
                             double *grad_gamma_beta, void *workspace, size_t workspace_bytes,
                             void *stream);
 
+/* rtn_activation_backward for callers that cannot allocate device memory (code under
+ * HIP graph capture, tight serving loops, harnesses that forbid hipMalloc): the same
+ * kernels, results and argument rules, but the per-block partial sums go to a fixed
+ * 1 MiB array inside the library (one copy per GPU, held until the process ends) instead
+ * of a caller workspace.  The call allocates and frees nothing.
+ * n must be at most rtn_activation_backward_static_max_n() (2^30 elements), else
+ * RTN_ERR_SHAPE.  Every call on a GPU uses that GPU's one array: calls that overlap
+ * in time on the same GPU (different streams, different threads) race; calls ordered
+ * on one stream do not.  Nothing needs clearing between calls -- each call writes
+ * every partial sum it later reads.                                              */
+int64_t rtn_activation_backward_static_max_n(void);
+int rtn_activation_backward_static(const float *a, const float *grad_out, int64_t n,
+                                   const float *thr_lo, const float *thr_hi, const float *gamma,
+                                   float *grad_in, double *grad_gamma_beta, void *stream);
+
 /* Backward of the reparameterized ternary weights (Section "Weight Ternarization":
  * Wbar = k_W*W + b_W, W^t = Q(Wbar), Wbar^t = alpha*W^t, the three parameters per
  * filter), for O filters of K weights each.  The paper prints the derivatives for the

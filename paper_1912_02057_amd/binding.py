@@ -27,7 +27,8 @@ EXPORTS = ["rtn_status_string", "rtn_last_hip_error", "rtn_num_tile_configs", "r
            "rtn_ternary_conv2d_implicit_gemm", "rtn_ternary_conv2d_ternarize",
            "rtn_weight_gemm_workspace_bytes", "rtn_ternary_weight_gemm",
            "rtn_weight_conv2d_workspace_bytes", "rtn_ternary_weight_conv2d",
-           "rtn_activation_backward_workspace_bytes", "rtn_activation_backward", "rtn_weight_backward",
+           "rtn_activation_backward_workspace_bytes", "rtn_activation_backward",
+           "rtn_activation_backward_static_max_n", "rtn_activation_backward_static", "rtn_weight_backward",
            "rtn_epilogue_reparam",
            "rtn_epilogue_reparam_conv2d"]
 
@@ -94,6 +95,10 @@ def lib():
         L.rtn_activation_backward_workspace_bytes.argtypes = [i64]
         L.rtn_activation_backward.restype = ci
         L.rtn_activation_backward.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp, vp, C.c_size_t, vp]
+        L.rtn_activation_backward_static_max_n.restype = i64
+        L.rtn_activation_backward_static_max_n.argtypes = []
+        L.rtn_activation_backward_static.restype = ci
+        L.rtn_activation_backward_static.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp, vp]
         L.rtn_weight_backward.restype = ci
         L.rtn_weight_backward.argtypes = [vp, vp, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp]
         L.rtn_epilogue_reparam.restype = ci
@@ -332,6 +337,18 @@ def activation_backward(a, grad_out, lo, hi, gamma, want_grad_in=True, grad_in=N
                                        _dev(sums, torch.float64), C.c_void_p(workspace.data_ptr()),
                                        workspace.numel(), _stream())
     _check(rc, "rtn_activation_backward")
+    return grad_in, sums
+
+
+def activation_backward_static(a, grad_out, lo, hi, gamma, grad_in, sums):
+    """rtn_activation_backward_static: the caller passes every buffer (grad_in may be None);
+    nothing is allocated here or in the library."""
+    glo, ghi, gg = _Gran(lo), _Gran(hi), _Gran(gamma)
+    rc = lib().rtn_activation_backward_static(_dev(a, torch.float32), _dev(grad_out, torch.float32), a.numel(),
+                                              glo.ptr, ghi.ptr, gg.ptr,
+                                              None if grad_in is None else _dev(grad_in, torch.float32),
+                                              _dev(sums, torch.float64), _stream())
+    _check(rc, "rtn_activation_backward_static")
     return grad_in, sums
 
 

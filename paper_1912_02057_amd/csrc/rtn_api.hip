@@ -415,6 +415,26 @@ int rtn_activation_backward(const float* a, const float* grad_out, int64_t n, co
     return he == hipSuccess ? RTN_OK : hip_fail(he);
 }
 
+int64_t rtn_activation_backward_static_max_n(void) { return rtn::act_backward_static_max_n(); }
+
+int rtn_activation_backward_static(const float* a, const float* grad_out, int64_t n, const float* thr_lo,
+                                   const float* thr_hi, const float* gamma, float* grad_in,
+                                   double* grad_gamma_beta, void* stream)
+{
+    if (!a || !grad_out || !thr_lo || !thr_hi || !gamma || !grad_gamma_beta) return RTN_ERR_NULL;
+    if (n <= 0 || n > rtn::act_backward_static_max_n()) return RTN_ERR_SHAPE;
+    if (!(*thr_lo <= *thr_hi)) return RTN_ERR_SHAPE;
+    if (!aligned(a, 4) || !aligned(grad_out, 4) || !aligned(grad_in, 4) || !aligned(grad_gamma_beta, 8))
+        return RTN_ERR_ALIGN;
+    rtn::ActBwdArgs p = {};
+    p.a = a, p.g = grad_out, p.n = n;
+    p.lo = *thr_lo, p.hi = *thr_hi, p.gamma = *gamma;
+    p.da = grad_in;
+    p.sums = grad_gamma_beta;
+    const hipError_t he = rtn::launch_act_backward_static(p, (hipStream_t)stream);
+    return he == hipSuccess ? RTN_OK : hip_fail(he);
+}
+
 int rtn_weight_backward(const float* w, const float* grad_out, int64_t O, int64_t K, const float* thr_lo,
                         const float* thr_hi, const float* k_w, const float* b_w, const float* alpha,
                         float* grad_w, double* grad_params, void* stream)

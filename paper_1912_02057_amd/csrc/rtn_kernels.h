@@ -39,6 +39,10 @@ struct ActBwdArgs {
 };
 int64_t act_backward_blocks(int64_t n);
 hipError_t launch_act_backward(const ActBwdArgs& p, hipStream_t st);
+// the same with the partial sums in a fixed device array of the library (p.partials ignored);
+// n is limited to act_backward_static_max_n()
+int64_t act_backward_static_max_n();
+hipError_t launch_act_backward_static(ActBwdArgs p, hipStream_t st);
 
 // Backward of the reparameterized ternary weights, one filter per row.
 struct WeightBwdArgs {

@@ -5,6 +5,8 @@
 // row / per pixel taken with wavefront reductions (64-wide ballots and
 // cross-lane adds).  They are HBM-bound: 4 B read per element, 1 B (int8) or
 // 0.25 B (two bit planes) written.
+#include <mutex>
+
 #include "rtn_kernels.h"
 
 namespace rtn {
@@ -584,6 +586,43 @@ hipError_t launch_act_backward(const ActBwdArgs& p, hipStream_t st)
         hipLaunchKernelGGL(k_act_backward<false>, dim3((unsigned)nb), dim3(256), 0, st, p);
     hipLaunchKernelGGL(k_sum_partials, dim3(1), dim3(256), 0, st, p.partials, nb, p.sums);
     return hipGetLastError();
+}
+
+// The form for callers that cannot allocate: the per-block partial sums go to a fixed
+// array in device memory instead of a caller workspace.  Every GPU holds its own copy of
+// the array at its own address, looked up once per device (the array's name is only a
+// host-side handle and is never passed to a kernel).  k_act_backward writes partials
+// 0 .. nblocks-1 before k_sum_partials reads exactly those, so what an earlier call left
+// in the array is never read and nothing needs clearing.
+namespace {
+constexpr int64_t kStaticBwdBlocks = 65536;  // 1 MiB of partial sums
+__device__ __align__(256) double g_act_bwd_scratch[2 * kStaticBwdBlocks];
+constexpr int kMaxDevices = 64;
+double* g_act_bwd_scratch_ptr[kMaxDevices] = {};
+std::mutex g_act_bwd_scratch_mutex;
+}  // namespace
+
+int64_t act_backward_static_max_n() { return kStaticBwdBlocks * kBwdPerBlock; }
+
+hipError_t launch_act_backward_static(ActBwdArgs p, hipStream_t st)
+{
+    if (act_backward_blocks(p.n) > kStaticBwdBlocks) return hipErrorInvalidValue;
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return e;
+    if (dev < 0 || dev >= kMaxDevices) return hipErrorInvalidDevice;
+    {
+        std::lock_guard<std::mutex> lock(g_act_bwd_scratch_mutex);
+        if (!g_act_bwd_scratch_ptr[dev]) {
+            double* ptr = nullptr;
+            e = hipGetSymbolAddress((void**)&ptr, HIP_SYMBOL(g_act_bwd_scratch));
+            if (e != hipSuccess) return e;
+            if (!ptr) return hipErrorInvalidSymbol;
+            g_act_bwd_scratch_ptr[dev] = ptr;
+        }
+        p.partials = g_act_bwd_scratch_ptr[dev];
+    }
+    return launch_act_backward(p, st);
 }
 
 hipError_t launch_weight_backward(const WeightBwdArgs& p, hipStream_t st)

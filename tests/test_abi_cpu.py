@@ -298,6 +298,27 @@ def test_activation_backward_rejects(L):
     assert with_(_9=8) == B.RTN_ERR_WORKSPACE
 
 
+def test_activation_backward_static_rejects(L):
+    call = L.rtn_activation_backward_static
+    lo, hi, gm = _f(-0.5), _f(0.5), _f(1.0)
+    ok = [FAKE, FAKE, 100, lo, hi, gm, FAKE, FAKE, None]
+
+    def with_(**kw):
+        a = list(ok)
+        for i, v in kw.items():
+            a[int(i[1:])] = v
+        return call(*a)
+    nmax = L.rtn_activation_backward_static_max_n()
+    assert nmax == 1 << 30
+    assert with_(_0=None) == B.RTN_ERR_NULL
+    assert with_(_7=None) == B.RTN_ERR_NULL
+    assert with_(_2=0) == B.RTN_ERR_SHAPE
+    assert with_(_2=nmax + 1) == B.RTN_ERR_SHAPE                # beyond the fixed array
+    assert with_(_3=_f(0.5), _4=_f(-0.5)) == B.RTN_ERR_SHAPE
+    assert with_(_6=ODD) == B.RTN_ERR_ALIGN
+    assert with_(_7=C.c_void_p(0x10004)) == B.RTN_ERR_ALIGN
+
+
 def test_bench_refuses_more_than_one_gpu():
     """bench.py measures one GPU; asked for more it exits with status 2 and says so, before touching a device."""
     import subprocess
