@@ -150,7 +150,7 @@ def padded_k(K):
     return lib().rtn_padded_k(K)
 
 
-def ternarize_pack(x, lo, hi, fmt=RTN_CODE_I8, layout=None, want_sum=True):
+def ternarize_pack(x, lo, hi, fmt=RTN_CODE_I8, layout=None, want_sum=True, codes=None, sum_t=None):
     """x: cuda float32 [rows,K] (RTN_ROWS_K_CONTIG) or [N,C,H,W] (RTN_NCHW).
     lo/hi: python floats, or cuda float32 vectors (per row / per leading index).
     Returns (codes, sum_t).  codes: int8 [rows,Kpad] / [N,H,W,Cpad], or for
@@ -164,11 +164,15 @@ def ternarize_pack(x, lo, hi, fmt=RTN_CODE_I8, layout=None, want_sum=True):
         d = tuple(x.shape)
         lead = (x.shape[0], x.shape[2], x.shape[3])
     kp = padded_k(d[1])
-    if fmt == RTN_CODE_I8:
+    if codes is not None:
+        assert tuple(codes.shape) == (lead + (kp,) if fmt == RTN_CODE_I8 else (2,) + lead + (kp // 64,))
+        assert codes.is_cuda and codes.is_contiguous() and codes.dtype == (torch.int8 if fmt == RTN_CODE_I8 else torch.int64)
+    elif fmt == RTN_CODE_I8:
         codes = torch.empty(lead + (kp,), dtype=torch.int8, device=x.device)
     else:
         codes = torch.empty((2,) + lead + (kp // 64,), dtype=torch.int64, device=x.device)
-    sum_t = torch.empty(lead, dtype=torch.int32, device=x.device) if want_sum else None
+    if sum_t is None and want_sum:
+        sum_t = torch.empty(lead, dtype=torch.int32, device=x.device)
     glo, ghi = _Gran(lo), _Gran(hi)
     assert glo.gran == ghi.gran
     rc = lib().rtn_ternarize_pack(_dev(x, torch.float32), layout, d[0], d[1], d[2], d[3], glo.ptr,

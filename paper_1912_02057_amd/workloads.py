@@ -164,3 +164,35 @@ CONFIG1_SHAPE = ConvShape("config1", 64, 56, 64, 3, 1, 1)
 
 def config1_case():
     return conv_case(CONFIG1_SHAPE, batch=1, seed=0, per_channel=False, delta_a=0.5)
+
+
+def resnet18_block_topology():
+    """(conv1, conv2, downsample or None) indices into resnet18_ternary_layers() of the 8
+    residual blocks, in forward order."""
+    blocks = [(0, 1, None), (2, 3, None)]
+    for s in range(3):
+        b = 4 + 5 * s
+        blocks += [(b, b + 1, b + 2), (b + 3, b + 4, None)]
+    return blocks
+
+
+def resnet18_network_params(seed=0, num_classes=1000):
+    """Random-init parameters of the whole network of the full-forward configuration: the
+    fp32 stem (7x7/2 conv 3->64 + BN), the 19 ternary convs (He-init weights, per-filter
+    TWN thresholds, layer-wise activation scale/offset, per-filter weight scale/offset, BN
+    affine from random running statistics) and the fp32 classifier (512 -> num_classes)."""
+    rng = _rng(seed)
+    stem_w = rng.standard_normal((64, 3, 7, 7), dtype=np.float32) * np.float32(np.sqrt(2.0 / (3 * 49)))
+    g = rng.uniform(0.5, 1.5, 64)
+    var = rng.uniform(0.5, 1.5, 64)
+    stem_scale = (g / np.sqrt(var + 1e-5)).astype(np.float32)
+    stem_shift = (rng.normal(0.0, 0.1, 64) - rng.normal(0.0, 0.1, 64) * stem_scale).astype(np.float32)
+    layers = []
+    for i, sh in enumerate(resnet18_ternary_layers()):
+        c = conv_case(sh, batch=1, seed=seed * 1000 + 700 + i, per_channel=True, bn=True)
+        layers.append(dict(sh=sh, w=c["w"], dw=c["delta_w"], aa=c["alpha_a"], ba=c["beta_a"], aw=c["alpha_w"],
+                           bw=c["beta_w"], bs=c["bn_scale"], bh=c["bn_shift"]))
+    fc_w = rng.standard_normal((num_classes, 512), dtype=np.float32) * np.float32(np.sqrt(1.0 / 512))
+    fc_b = (rng.standard_normal(num_classes) * 0.01).astype(np.float32)
+    return dict(stem_w=stem_w, stem_scale=stem_scale, stem_shift=stem_shift, layers=layers, fc_w=fc_w, fc_b=fc_b,
+                delta_a=np.float32(0.5))

@@ -830,6 +830,63 @@ def test_config4_trunk_forward_fully_fused():
     assert xo.shape == (2, 512, 7, 7)
 
 
+def test_config4_full_forward_batch256_sampled_images():
+    """The full-network configuration at its stated size: 256 images of 3x224x224, fp32
+    stem and classifier (torch, outside the ternary library), the 8 residual blocks of 19
+    ternary convs through the C ABI with every hand-over fused (1 pack + 19 convs).  Images
+    are independent, so the oracle runs the step-by-step chain on six images spread over
+    the batch, starting from the trunk input the stem produced, and every block's input
+    codes, hand-over codes and fp32 output are compared.  The block topology is this
+    repository's reading (the paper's figure is not in its text): chain parity is
+    unpinned by the paper, the per-layer arithmetic it is made of is pinned."""
+    from paper_1912_02057_amd.resnet18 import TernaryResNet18
+    _say("config 4: full forward, batch 256, six sampled images")
+    prm = wl.resnet18_network_params(seed=4)
+    rng = np.random.Generator(np.random.PCG64(44))
+    images = rng.standard_normal((256, 3, 224, 224), dtype=np.float32)
+    net = TernaryResNet18(prm, 256, T.DEV)
+    x0 = net.stem(T.dev(images))
+    assert tuple(x0.shape) == (256, 64, 56, 56)
+    keep = []
+    out = net.trunk(x0, keep)
+    logits = net.head(out)
+    torch.cuda.synchronize()
+    assert tuple(out.shape) == (256, 512, 7, 7) and tuple(logits.shape) == (256, 1000)
+    assert bool(torch.isfinite(logits).all())
+    imgs = _sample_images(256, 6, 4)
+    lo, hi = -prm["delta_a"], prm["delta_a"]
+
+    def oracle_layer(ta, p, relu):
+        sh = p["sh"]
+        tw = orc.ternarize(p["w"], -np.asarray(p["dw"]), p["dw"])
+        D = orc.conv_acc(ta, tw, sh.stride, sh.pad)
+        Sa, Sw, Kv = orc.conv_sums(ta, tw, sh.stride, sh.pad, True)
+        return orc.conv_epilogue(D, Sa, Sw, Kv, p["aa"], p["ba"], p["aw"], p["bw"], relu=relu,
+                                 bn_scale=p["bs"], bn_shift=p["bh"])
+
+    P = prm["layers"]
+    xo = x0[imgs].cpu().numpy()
+    ta_o = orc.ternarize(xo, lo, hi)
+    for bi, (i1, i2, ids) in enumerate(wl.resnet18_block_topology()):
+        c1, c2, yb = (t[imgs].cpu().numpy() for t in keep[bi])
+        assert (c1 == orc.nchw_to_nhwc_i8(ta_o, c1.shape[-1])).all(), "block %d input codes" % bi
+        y1 = oracle_layer(ta_o, P[i1], True)
+        ta2 = orc.ternarize_nchw(y1, lo, hi)
+        T.assert_codes_match(c2, orc.nchw_to_nhwc_i8(ta2, c2.shape[-1]), y1, lo, hi, "block %d hand-over codes" % bi)
+        assert (c2 == orc.nchw_to_nhwc_i8(ta2, c2.shape[-1])).all(), "block %d hand-over codes" % bi
+        y2 = oracle_layer(ta2, P[i2], False)
+        sc = xo if ids is None else oracle_layer(ta_o, P[ids], False)
+        xo = orc.add_relu(y2, sc, True)
+        T.assert_y_close(yb, xo, "block %d output" % bi)
+        ta_o = orc.ternarize_nchw(xo, lo, hi)
+    last = net.last_codes[imgs].cpu().numpy()
+    T.assert_codes_match(last, orc.nchw_to_nhwc_i8(ta_o, 512), xo, lo, hi, "trunk output codes")
+    # the fp32 head on the oracle's trunk output (plain numpy): average pool + FC
+    want = xo.astype(np.float64).mean(axis=(2, 3)) @ prm["fc_w"].astype(np.float64).T + prm["fc_b"]
+    got = logits[imgs].cpu().numpy()
+    assert np.abs(got - want).max() <= 1e-4 * max(1.0, np.abs(want).max())
+
+
 # ------------------------- weight-only ternary GEMM (fp32 activations) ----------
 def _wgemm_check(M, N, K, seed, vector_alpha=True, relu=False, bn=False, rows=None, what=""):
     """HIP weight-only GEMM against the oracle.  The kernel sums 3K exact bf16 products
