@@ -99,6 +99,59 @@ void orc_decode_planes(const uint64_t *mask, const uint64_t *sign, int64_t rows,
 }
 
 /* Layout only (no arithmetic): int8 codes, rows padded with code 0 to Kpad. */
+/* ----------------------------------------------------------------- O2b --
+ * FP4 storage of the same ternary values.  Not the paper's: the paper's code is
+ * the 2-bit one of Table 1; this is the 4-bit float of the OCP microscaling
+ * formats (E2M1: 1 sign bit s, 2 exponent bits e, 1 mantissa bit m, bias 1, no
+ * infinities or NaNs), which MI355X's matrix cores multiply natively:
+ *   value = (-1)^s * 2^(e-1) * (1 + m/2)  for e > 0,   (-1)^s * m/2  for e = 0.
+ * Its 16 code points include -1, 0, +1 exactly; a ternary value is stored as the
+ * nibble that decodes to it with a canonical zero (0x0): +1 -> 0x2, -1 -> 0xA.
+ * Two elements per byte, element 2j in the low nibble of byte j; a row holds
+ * Kpad elements (Kpad/2 bytes), the padding is 0.                             */
+double orc_e2m1_value(int nibble)
+{
+    int s = (nibble >> 3) & 1, e = (nibble >> 1) & 3, m = nibble & 1;
+    double mag = e > 0 ? ldexp(1.0 + 0.5 * m, e - 1) : 0.5 * m;
+    return s ? -mag : mag;
+}
+
+void orc_encode_fp4(const int8_t *t, int64_t rows, int64_t K, int64_t Kpad, uint8_t *out)
+{
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t j = 0; j < Kpad / 2; ++j) {
+            int byte = 0;
+            for (int h = 0; h < 2; ++h) {
+                int64_t k = 2 * j + h;
+                int v = k < K ? t[r * K + k] : 0;
+                int nib = 0;
+                /* the code point whose value is v (zero: the one without the sign bit) */
+                for (int c = 15; c >= 0; --c)
+                    if (orc_e2m1_value(c) == (double)v && !(v == 0 && c == 8)) nib = c;
+                byte |= nib << (4 * h);
+            }
+            out[r * (Kpad / 2) + j] = (uint8_t)byte;
+        }
+}
+
+/* returns the number of nibbles that do not decode to -1, 0 or +1 (they are written as 0) */
+int64_t orc_decode_fp4(const uint8_t *codes, int64_t rows, int64_t K, int64_t Kpad, int8_t *t)
+{
+    int64_t bad = 0;
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t k = 0; k < K; ++k) {
+            int nib = (codes[r * (Kpad / 2) + k / 2] >> (4 * (k & 1))) & 15;
+            double v = orc_e2m1_value(nib);
+            if (v == 1.0 || v == -1.0 || v == 0.0) {
+                t[r * K + k] = (int8_t)v;
+            } else {
+                t[r * K + k] = 0;
+                ++bad;
+            }
+        }
+    return bad;
+}
+
 void orc_pad_rows_i8(const int8_t *t, int64_t rows, int64_t K, int64_t Kpad, int8_t *out)
 {
     for (int64_t r = 0; r < rows; ++r)

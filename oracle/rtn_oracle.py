@@ -102,6 +102,35 @@ def decode_planes(mask, sign, K):
     return t
 
 
+def e2m1_value(nibble):
+    """O2b: value of an FP4 (E2M1) code point."""
+    f = lib().orc_e2m1_value
+    f.restype = C.c_double
+    return f(C.c_int(int(nibble)))
+
+
+def encode_fp4(t, Kpad=None):
+    """O2b: t int8 [rows, K] -> uint8 [rows, Kpad/2], two E2M1 nibbles per byte (Kpad: K
+    rounded up to a multiple of 128 unless given)."""
+    t = _c(t, np.int8)
+    rows, K = t.shape
+    Kpad = (K + 127) // 128 * 128 if Kpad is None else Kpad
+    out = np.empty((rows, Kpad // 2), dtype=np.uint8)
+    lib().orc_encode_fp4(_p(t), _i64(rows), _i64(K), _i64(Kpad), _p(out))
+    return out
+
+
+def decode_fp4(codes, K):
+    """O2b: uint8 [rows, Kpad/2] -> (t int8 [rows, K], count of nibbles that are not ternary)."""
+    codes = _c(codes, np.uint8)
+    rows, half = codes.shape
+    t = np.empty((rows, K), dtype=np.int8)
+    f = lib().orc_decode_fp4
+    f.restype = C.c_int64
+    bad = f(_p(codes), _i64(rows), _i64(K), _i64(2 * half), _p(t))
+    return t, int(bad)
+
+
 def pad_rows_i8(t, Kpad):
     t = _c(t, np.int8)
     rows, K = t.shape

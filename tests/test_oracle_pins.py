@@ -123,6 +123,55 @@ def test_layout_helpers():
     assert (q[..., :5] == t4.transpose(0, 2, 3, 1)).all() and (q[..., 5:] == 0).all()
 
 
+# ----------------------------------------------------------------- O2b ----
+def test_fp4_e2m1_code_points_and_ternary_storage():
+    """The FP4 storage is the E2M1 format of the OCP microscaling specification, whose 16
+    code points are hand-listed here (sign, then magnitudes 0, 0.5, 1, 1.5, 2, 3, 4, 6).
+    +1 and -1 are the code points 0x2 and 0xA; zero is stored without the sign bit."""
+    mags = [0.0, 0.5, 1.0, 1.5, 2.0, 3.0, 4.0, 6.0]
+    for c in range(16):
+        v = orc.e2m1_value(c)
+        assert abs(v) == mags[c & 7] and (np.signbit(v) == bool(c >> 3) or mags[c & 7] == 0.0)
+    t = np.array([[1, -1, 0, 0, -1, 1, 1]], dtype=np.int8)
+    enc = orc.encode_fp4(t)
+    assert enc.shape == (1, 64)                       # 7 elements -> one 128-code row of 64 bytes
+    assert enc[0, :4].tolist() == [0xA2, 0x00, 0x2A, 0x02] and not enc[0, 4:].any()
+    # element 2j is the low nibble of byte j; round trip on random data, ragged K
+    rng = np.random.default_rng(3)
+    for K in (1, 127, 128, 129, 300):
+        tt = _rand_t(rng, (5, K))
+        e = orc.encode_fp4(tt)
+        assert e.shape == (5, (K + 127) // 128 * 64)
+        back, bad = orc.decode_fp4(e, K)
+        assert bad == 0 and (back == tt).all()
+        lo_n, hi_n = (e & 15).astype(np.int64), (e >> 4).astype(np.int64)
+        assert set(np.unique(lo_n)) <= {0x0, 0x2, 0xA} and set(np.unique(hi_n)) <= {0x0, 0x2, 0xA}
+        # non-zero count and sum from the nibble bits: bit 1 marks +-1, bit 3 marks -1
+        nz = ((lo_n >> 1) & 1).sum(1) + ((hi_n >> 1) & 1).sum(1)
+        ng = ((lo_n >> 3) & 1).sum(1) + ((hi_n >> 3) & 1).sum(1)
+        assert (nz == np.abs(tt).sum(1)).all() and (nz - 2 * ng == tt.sum(1, dtype=np.int64)).all()
+    # the decoder takes negative zero (0x8) as 0 and reports anything that is not ternary
+    back, bad = orc.decode_fp4(np.array([[0x28, 0x31] + [0] * 62], dtype=np.uint8), 4)
+    assert back.tolist() == [[0, 1, 0, 0]] and bad == 2          # 0x1 = 0.5 and 0x3 = 1.5
+
+
+def test_fp4_products_of_ternary_values_are_exact_in_fp32():
+    """What makes the FP4 matrix path exact: the decoded operands are -1, 0, +1, so a dot
+    product accumulated in fp32 in any order is the integer sum while it stays below
+    2^24 -- checked against the integer contraction in several summation orders."""
+    rng = np.random.default_rng(5)
+    ta, tw = _rand_t(rng, (3, 5000)), _rand_t(rng, (4, 5000))
+    da, _ = orc.decode_fp4(orc.encode_fp4(ta), 5000)
+    dw, _ = orc.decode_fp4(orc.encode_fp4(tw), 5000)
+    want = orc.gemm_acc(ta, tw)
+    prod = da[:, None, :].astype(np.float32) * dw[None, :, :].astype(np.float32)
+    for order in (np.arange(5000), np.arange(5000)[::-1], rng.permutation(5000)):
+        acc = np.zeros((3, 4), np.float32)
+        for blk in np.array_split(order, 79):             # 64-wide partial sums, as a matrix core forms them
+            acc = (acc + prod[:, :, blk].sum(axis=2, dtype=np.float32)).astype(np.float32)
+        assert (acc.astype(np.int64) == want).all()
+
+
 # ------------------------------------------------------------------ O3 ----
 def test_dot_exhaustive_small_k_both_routes():
     # every pair of ternary vectors for K <= 4 (3^K x 3^K), pure-Python sum as truth
