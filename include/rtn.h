@@ -60,8 +60,17 @@ typedef enum {
  *   The buffer holds the whole mask plane [rows][Kpad/64] followed by the
  *   whole sign plane [rows][Kpad/64].
  * In both formats a row holds Kpad = rtn_padded_k(K) elements (K rounded up
- * to a multiple of 64); the padding is code 0.                              */
-typedef enum { RTN_CODE_I8 = 0, RTN_CODE_BITPLANE = 1 } rtn_code_format;
+ * to a multiple of 64); the padding is code 0.
+ * RTN_CODE_FP4: one 4-bit float (E2M1: sign, 2 exponent bits, 1 mantissa bit)
+ *   per element, holding t itself: 0 -> 0x0, +1 -> 0x2, -1 -> 0xA; two elements
+ *   per byte, element 2j in the low nibble of byte j of the row.  This is the
+ *   storage of the primary path on MI355X: -1, 0, +1 are exact in E2M1, so the
+ *   FP4 matrix cores (twice the int8 rate, half the operand bytes) form the
+ *   ternary dot product exactly.  A row holds rtn_padded_k_format(RTN_CODE_FP4,
+ *   K) elements (K rounded up to a multiple of 128, i.e. whole 64-byte steps);
+ *   the padding is code 0.  The same ternary values as the paper's 2-bit code
+ *   of Table 1, in the 4-bit form this hardware multiplies natively.        */
+typedef enum { RTN_CODE_I8 = 0, RTN_CODE_BITPLANE = 1, RTN_CODE_FP4 = 2 } rtn_code_format;
 typedef enum { RTN_SCALAR = 0, RTN_VECTOR = 1 } rtn_gran;
 typedef enum { RTN_ROWS_K_CONTIG = 0, RTN_NCHW = 1 } rtn_layout;
 
@@ -76,8 +85,10 @@ typedef enum { RTN_PAD_TRUE_ZERO = 0, RTN_PAD_CODE_ZERO = 1 } rtn_pad_mode;
 
 /* Contraction strategy.  MFMA_I8: int8 matrix cores on RTN_CODE_I8 codes.
  * POPC: Eq.8 (AND / XOR / popcount) on RTN_CODE_BITPLANE codes.
+ * MFMA_FP4: FP4 matrix cores with fp32 accumulation on RTN_CODE_FP4 codes (every
+ * product is exact and the sums are integers below 2^24, so D is the same integer).
  * AUTO picks the one that matches the code format.                           */
-typedef enum { RTN_PATH_AUTO = 0, RTN_PATH_MFMA_I8 = 1, RTN_PATH_POPC = 2 } rtn_path;
+typedef enum { RTN_PATH_AUTO = 0, RTN_PATH_MFMA_I8 = 1, RTN_PATH_POPC = 2, RTN_PATH_MFMA_FP4 = 3 } rtn_path;
 
 /* Four-term reparameterization applied to an accumulator D (Eq.9 with a weight
  * offset added; phi = ReLU; the BN affine follows ReLU in RTN's layer order):
@@ -127,6 +138,8 @@ int rtn_set_tile_config(int index);
 
 /* K rounded up to the row length of a code tensor (a multiple of 64). */
 int64_t rtn_padded_k(int64_t K);
+/* The same per format: 128 for RTN_CODE_FP4, 64 otherwise (0 on invalid arguments). */
+int64_t rtn_padded_k_format(rtn_code_format fmt, int64_t K);
 /* Bytes of a code tensor of `rows` rows of K elements in format `fmt`
  * (0 on invalid arguments). */
 size_t rtn_codes_bytes(rtn_code_format fmt, int64_t rows, int64_t K);
@@ -143,7 +156,8 @@ size_t rtn_codes_bytes(rtn_code_format fmt, int64_t rows, int64_t K);
  *   [O][I][KH][KW] (weights).  codes are written channel-innermost,
  *   [N][H][W][Cpad]; sum_t[N][H][W] = sum of t over the channels of a pixel
  *   (for weights: per filter and tap).  RTN_VECTOR thresholds: one (lo, hi)
- *   per d0 index (per filter).  RTN_CODE_I8 needs C <= 2048 in this layout.
+ *   per d0 index (per filter).  RTN_CODE_I8 and RTN_CODE_FP4 need C <= 2048 in
+ *   this layout; with RTN_CODE_FP4 a row / pixel is Kpad / 2 bytes.
  * sum_t may be NULL.  d0*d2*d3 and d0*d1*d2*d3 must be below 2^31 resp. 2^40. */
 int rtn_ternarize_pack(const float *x, rtn_layout layout, int64_t d0, int64_t d1, int64_t d2,
                        int64_t d3, const float *thr_lo, const float *thr_hi, rtn_gran thr_gran,
@@ -151,7 +165,7 @@ int rtn_ternarize_pack(const float *x, rtn_layout layout, int64_t d0, int64_t d1
 
 /* Ternary contraction D[m][n] = sum_k t_a[m][k]*t_w[n][k] (the dot product
  * W^t (x) A^t of Eq.8/Eq.9), optionally followed by the fused epilogue.
- *   a_codes: [M][Kpad], w_codes: [N][Kpad] in format `fmt`.
+ *   a_codes: [M][Kpad], w_codes: [N][Kpad] in format `fmt` (Kpad per format).
  *   acc_out: int32 [M][N] row-major, or NULL.
  *   ep + y_out: fp32 [M][N] row-major through the four-term formula, or both
  *   NULL.  At least one of acc_out / (ep, y_out) must be given.
@@ -165,7 +179,8 @@ int rtn_ternary_gemm(rtn_code_format fmt, rtn_path path, const void *a_codes, co
  *   M = Nb*OH*OW, N = O, K = KH*KW*C, cross-correlation,
  *   ih = oh*stride - pad + kh, iw = ow*stride - pad + kw,
  *   OH = (H + 2*pad - KH)/stride + 1; a tap outside the image adds 0 to D.
- *   a_codes: [Nb][H][W][Cpad]; w_codes: [O][KH][KW][Cpad] (RTN_CODE_I8 only).
+ *   a_codes: [Nb][H][W][Cpad]; w_codes: [O][KH][KW][Cpad], RTN_CODE_I8 or
+ *   RTN_CODE_FP4 (Cpad = rtn_padded_k_format(fmt, C), both tensors in `fmt`).
  *   acc_out: int32 [Nb][O][OH][OW] or NULL; y_out: fp32 [Nb][O][OH][OW] (NCHW).
  *   KH, KW in 1..7, stride in 1..64, 0 <= pad < min(KH, KW), pad <= 2.
  *   workspace (needed when an epilogue is given): the table written by

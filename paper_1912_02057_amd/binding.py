@@ -15,13 +15,14 @@ LIB_PATH = os.path.join(_HERE, "librtn.so")
 RTN_OK = 0
 RTN_ERR_NULL, RTN_ERR_SHAPE, RTN_ERR_ALIGN, RTN_ERR_UNSUPPORTED, RTN_ERR_WORKSPACE, RTN_ERR_HIP = \
     -1, -2, -3, -4, -5, -6
-RTN_CODE_I8, RTN_CODE_BITPLANE = 0, 1
+RTN_CODE_I8, RTN_CODE_BITPLANE, RTN_CODE_FP4 = 0, 1, 2
 RTN_SCALAR, RTN_VECTOR = 0, 1
 RTN_ROWS_K_CONTIG, RTN_NCHW = 0, 1
 RTN_PAD_TRUE_ZERO, RTN_PAD_CODE_ZERO = 0, 1
-RTN_PATH_AUTO, RTN_PATH_MFMA_I8, RTN_PATH_POPC = 0, 1, 2
+RTN_PATH_AUTO, RTN_PATH_MFMA_I8, RTN_PATH_POPC, RTN_PATH_MFMA_FP4 = 0, 1, 2, 3
 
-EXPORTS = ["rtn_status_string", "rtn_last_hip_error", "rtn_num_tile_configs", "rtn_set_tile_config", "rtn_padded_k", "rtn_codes_bytes",
+EXPORTS = ["rtn_status_string", "rtn_last_hip_error", "rtn_num_tile_configs", "rtn_set_tile_config", "rtn_padded_k", "rtn_padded_k_format",
+           "rtn_codes_bytes",
            "rtn_ternarize_pack", "rtn_ternary_gemm", "rtn_conv2d_workspace_bytes",
            "rtn_conv2d_prepare_constants",
            "rtn_ternary_conv2d_implicit_gemm", "rtn_ternary_conv2d_ternarize",
@@ -66,6 +67,8 @@ def lib():
         L.rtn_last_hip_error.restype = ci
         L.rtn_padded_k.restype = i64
         L.rtn_padded_k.argtypes = [i64]
+        L.rtn_padded_k_format.restype = i64
+        L.rtn_padded_k_format.argtypes = [ci, i64]
         L.rtn_codes_bytes.restype = C.c_size_t
         L.rtn_codes_bytes.argtypes = [ci, i64, i64]
         L.rtn_ternarize_pack.restype = ci
@@ -146,15 +149,16 @@ def set_tile_config(index):
     _check(lib().rtn_set_tile_config(int(index)), "rtn_set_tile_config")
 
 
-def padded_k(K):
-    return lib().rtn_padded_k(K)
+def padded_k(K, fmt=RTN_CODE_I8):
+    return lib().rtn_padded_k_format(fmt, K)
 
 
 def ternarize_pack(x, lo, hi, fmt=RTN_CODE_I8, layout=None, want_sum=True, codes=None, sum_t=None):
     """x: cuda float32 [rows,K] (RTN_ROWS_K_CONTIG) or [N,C,H,W] (RTN_NCHW).
     lo/hi: python floats, or cuda float32 vectors (per row / per leading index).
-    Returns (codes, sum_t).  codes: int8 [rows,Kpad] / [N,H,W,Cpad], or for
-    bit planes uint64-as-int64 [2, rows, Kpad/64] / [2, N,H,W, Cpad/64]."""
+    Returns (codes, sum_t).  codes: int8 [rows,Kpad] / [N,H,W,Cpad]; for FP4 uint8
+    [rows,Kpad/2] / [N,H,W,Cpad/2] (two nibbles per byte); for bit planes
+    uint64-as-int64 [2, rows, Kpad/64] / [2, N,H,W, Cpad/64]."""
     if layout is None:
         layout = RTN_NCHW if x.dim() == 4 else RTN_ROWS_K_CONTIG
     if layout == RTN_ROWS_K_CONTIG:
@@ -163,14 +167,14 @@ def ternarize_pack(x, lo, hi, fmt=RTN_CODE_I8, layout=None, want_sum=True, codes
     else:
         d = tuple(x.shape)
         lead = (x.shape[0], x.shape[2], x.shape[3])
-    kp = padded_k(d[1])
+    kp = padded_k(d[1], fmt)
+    cshape = {RTN_CODE_I8: lead + (kp,), RTN_CODE_FP4: lead + (kp // 2,),
+              RTN_CODE_BITPLANE: (2,) + lead + (kp // 64,)}[fmt]
+    cdtype = {RTN_CODE_I8: torch.int8, RTN_CODE_FP4: torch.uint8, RTN_CODE_BITPLANE: torch.int64}[fmt]
     if codes is not None:
-        assert tuple(codes.shape) == (lead + (kp,) if fmt == RTN_CODE_I8 else (2,) + lead + (kp // 64,))
-        assert codes.is_cuda and codes.is_contiguous() and codes.dtype == (torch.int8 if fmt == RTN_CODE_I8 else torch.int64)
-    elif fmt == RTN_CODE_I8:
-        codes = torch.empty(lead + (kp,), dtype=torch.int8, device=x.device)
+        assert tuple(codes.shape) == cshape and codes.dtype == cdtype and codes.is_cuda and codes.is_contiguous()
     else:
-        codes = torch.empty((2,) + lead + (kp // 64,), dtype=torch.int64, device=x.device)
+        codes = torch.empty(cshape, dtype=cdtype, device=x.device)
     if sum_t is None and want_sum:
         sum_t = torch.empty(lead, dtype=torch.int32, device=x.device)
     glo, ghi = _Gran(lo), _Gran(hi)

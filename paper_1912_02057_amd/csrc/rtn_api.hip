@@ -22,6 +22,8 @@ constexpr int kMaxPad = 2;
 
 bool aligned(const void* p, size_t a) { return ((uintptr_t)p % a) == 0; }
 int64_t pad64(int64_t k) { return (k + 63) / 64 * 64; }
+// row length of a code tensor: FP4 rows are whole 64-byte K-steps of 128 codes
+int64_t padk(rtn_code_format fmt, int64_t k) { return fmt == RTN_CODE_FP4 ? (k + 127) / 128 * 128 : pad64(k); }
 
 // Host scalar or device vector -> kernel parameter.
 int make_param(const float* p, rtn_gran gran, bool nullable, rtn::Param& out)
@@ -67,7 +69,7 @@ int make_epilogue(const rtn_epilogue* ep, bool conv, rtn::EpiArgs& out, bool nee
 }
 
 int make_geom(int64_t Nb, int64_t C, int64_t H, int64_t W, int64_t O, int KH, int KW, int stride,
-              int pad, rtn_pad_mode pad_mode, rtn::ConvGeom& g)
+              int pad, rtn_pad_mode pad_mode, rtn::ConvGeom& g, rtn_code_format fmt = RTN_CODE_I8)
 {
     if (Nb <= 0 || C <= 0 || H <= 0 || W <= 0 || O <= 0) return RTN_ERR_SHAPE;
     if (Nb > kMaxDim || C > kMaxDim || H > kMaxDim || W > kMaxDim || O > kMaxDim) return RTN_ERR_SHAPE;
@@ -76,7 +78,7 @@ int make_geom(int64_t Nb, int64_t C, int64_t H, int64_t W, int64_t O, int KH, in
     if (pad_mode != RTN_PAD_TRUE_ZERO && pad_mode != RTN_PAD_CODE_ZERO) return RTN_ERR_UNSUPPORTED;
     if (H + 2 * pad < KH || W + 2 * pad < KW) return RTN_ERR_SHAPE;
     const int64_t OH = (H + 2 * pad - KH) / stride + 1, OW = (W + 2 * pad - KW) / stride + 1;
-    const int64_t Cpad = pad64(C);
+    const int64_t Cpad = padk(fmt, C);
     if (Cpad * KH * KW > kMaxK) return RTN_ERR_SHAPE;
     if (Nb * H * W > kMaxDim || Nb * OH * OW > kMaxDim) return RTN_ERR_SHAPE;
     g.Nb = (int)Nb, g.C = (int)C, g.Cpad = (int)Cpad, g.H = (int)H, g.W = (int)W, g.O = (int)O;
@@ -118,12 +120,19 @@ int rtn_set_tile_config(int index)
 
 int64_t rtn_padded_k(int64_t K) { return K <= 0 ? 0 : pad64(K); }
 
+int64_t rtn_padded_k_format(rtn_code_format fmt, int64_t K)
+{
+    if (K <= 0 || (fmt != RTN_CODE_I8 && fmt != RTN_CODE_BITPLANE && fmt != RTN_CODE_FP4)) return 0;
+    return padk(fmt, K);
+}
+
 size_t rtn_codes_bytes(rtn_code_format fmt, int64_t rows, int64_t K)
 {
     if (rows <= 0 || K <= 0) return 0;
     const int64_t kp = pad64(K);
     if (fmt == RTN_CODE_I8) return (size_t)rows * (size_t)kp;
     if (fmt == RTN_CODE_BITPLANE) return (size_t)rows * (size_t)(kp / 64) * 8u * 2u;
+    if (fmt == RTN_CODE_FP4) return (size_t)rows * (size_t)(padk(fmt, K) / 2);
     return 0;
 }
 
@@ -133,7 +142,7 @@ int rtn_ternarize_pack(const float* x, rtn_layout layout, int64_t d0, int64_t d1
 {
     if (!x || !codes || !thr_lo || !thr_hi) return RTN_ERR_NULL;
     if (layout != RTN_ROWS_K_CONTIG && layout != RTN_NCHW) return RTN_ERR_UNSUPPORTED;
-    if (fmt != RTN_CODE_I8 && fmt != RTN_CODE_BITPLANE) return RTN_ERR_UNSUPPORTED;
+    if (fmt != RTN_CODE_I8 && fmt != RTN_CODE_BITPLANE && fmt != RTN_CODE_FP4) return RTN_ERR_UNSUPPORTED;
     if (d0 <= 0 || d1 <= 0 || d2 <= 0 || d3 <= 0) return RTN_ERR_SHAPE;
     if (d0 > kMaxDim || d1 > kMaxDim || d2 > kMaxDim || d3 > kMaxDim) return RTN_ERR_SHAPE;
     if (layout == RTN_ROWS_K_CONTIG && (d2 != 1 || d3 != 1)) return RTN_ERR_SHAPE;
@@ -150,19 +159,23 @@ int rtn_ternarize_pack(const float* x, rtn_layout layout, int64_t d0, int64_t d1
     a.codes = codes;
     a.sum_t = sum_t;
     a.K = d1;
-    a.Kpad = pad64(d1);
+    a.Kpad = padk(fmt, d1);
     hipStream_t st = (hipStream_t)stream;
     hipError_t e;
     if (layout == RTN_ROWS_K_CONTIG) {
         a.rows = d0;
-        e = fmt == RTN_CODE_I8 ? rtn::launch_pack_rows_i8(a, st) : rtn::launch_pack_rows_planes(a, st);
+        e = fmt == RTN_CODE_I8    ? rtn::launch_pack_rows_i8(a, st)
+            : fmt == RTN_CODE_FP4 ? rtn::launch_pack_rows_fp4(a, st)
+                                  : rtn::launch_pack_rows_planes(a, st);
     } else {
         a.N = d0;
         a.HW = d2 * d3;
-        if (fmt == RTN_CODE_I8 && a.Kpad > 2048) return RTN_ERR_UNSUPPORTED;
+        if (fmt != RTN_CODE_BITPLANE && a.Kpad > 2048) return RTN_ERR_UNSUPPORTED;
         const int64_t tiles = (a.HW + 63) / 64;
         if (tiles * a.N > kMaxDim) return RTN_ERR_SHAPE;
-        e = fmt == RTN_CODE_I8 ? rtn::launch_pack_nchw_i8(a, st) : rtn::launch_pack_nchw_planes(a, st);
+        e = fmt == RTN_CODE_I8    ? rtn::launch_pack_nchw_i8(a, st)
+            : fmt == RTN_CODE_FP4 ? rtn::launch_pack_nchw_fp4(a, st)
+                                  : rtn::launch_pack_nchw_planes(a, st);
     }
     return e == hipSuccess ? RTN_OK : hip_fail(e);
 }
@@ -176,11 +189,13 @@ int rtn_ternary_gemm(rtn_code_format fmt, rtn_path path, const void* a_codes, co
     if (!a_codes || !w_codes) return RTN_ERR_NULL;
     if ((ep == nullptr) != (y_out == nullptr)) return RTN_ERR_NULL;
     if (!acc_out && !y_out) return RTN_ERR_NULL;
-    if (fmt != RTN_CODE_I8 && fmt != RTN_CODE_BITPLANE) return RTN_ERR_UNSUPPORTED;
-    if (path != RTN_PATH_AUTO && path != RTN_PATH_MFMA_I8 && path != RTN_PATH_POPC)
+    if (fmt != RTN_CODE_I8 && fmt != RTN_CODE_BITPLANE && fmt != RTN_CODE_FP4) return RTN_ERR_UNSUPPORTED;
+    if (path != RTN_PATH_AUTO && path != RTN_PATH_MFMA_I8 && path != RTN_PATH_POPC && path != RTN_PATH_MFMA_FP4)
         return RTN_ERR_UNSUPPORTED;
-    if (path == RTN_PATH_AUTO) path = fmt == RTN_CODE_I8 ? RTN_PATH_MFMA_I8 : RTN_PATH_POPC;
+    if (path == RTN_PATH_AUTO)
+        path = fmt == RTN_CODE_I8 ? RTN_PATH_MFMA_I8 : (fmt == RTN_CODE_FP4 ? RTN_PATH_MFMA_FP4 : RTN_PATH_POPC);
     if ((path == RTN_PATH_MFMA_I8) != (fmt == RTN_CODE_I8)) return RTN_ERR_UNSUPPORTED;
+    if ((path == RTN_PATH_MFMA_FP4) != (fmt == RTN_CODE_FP4)) return RTN_ERR_UNSUPPORTED;
     if (M <= 0 || N <= 0 || K <= 0 || M > kMaxDim || N > kMaxDim || K > kMaxK) return RTN_ERR_SHAPE;
     if (!aligned(a_codes, 16) || !aligned(w_codes, 16) || !aligned(acc_out, 4) || !aligned(y_out, 4))
         return RTN_ERR_ALIGN;
@@ -191,11 +206,12 @@ int rtn_ternary_gemm(rtn_code_format fmt, rtn_path path, const void* a_codes, co
     }
     hipStream_t st = (hipStream_t)stream;
     hipError_t he;
-    if (path == RTN_PATH_MFMA_I8) {
+    if (path == RTN_PATH_MFMA_I8 || path == RTN_PATH_MFMA_FP4) {
         rtn::GemmArgs g = {};
         g.a = (const int8_t*)a_codes;
         g.w = (const int8_t*)w_codes;
-        g.M = M, g.N = N, g.K = K, g.Kpad = pad64(K);
+        g.M = M, g.N = N, g.K = K, g.Kpad = padk(fmt, K);
+        g.fp4 = fmt == RTN_CODE_FP4;
         g.acc = acc_out;
         g.y = y_out;
         g.ep = e;
@@ -248,11 +264,13 @@ int rtn_ternary_conv2d_implicit_gemm(rtn_code_format fmt, rtn_path path, const v
     if (!a_codes || !w_codes) return RTN_ERR_NULL;
     if ((ep == nullptr) != (y_out == nullptr)) return RTN_ERR_NULL;
     if (!acc_out && !y_out) return RTN_ERR_NULL;
-    if (fmt != RTN_CODE_I8) return RTN_ERR_UNSUPPORTED;
-    if (path != RTN_PATH_AUTO && path != RTN_PATH_MFMA_I8) return RTN_ERR_UNSUPPORTED;
+    if (fmt != RTN_CODE_I8 && fmt != RTN_CODE_FP4) return RTN_ERR_UNSUPPORTED;
+    if (path != RTN_PATH_AUTO && path != (fmt == RTN_CODE_I8 ? RTN_PATH_MFMA_I8 : RTN_PATH_MFMA_FP4))
+        return RTN_ERR_UNSUPPORTED;
     rtn::ConvArgs c = {};
-    int rc = make_geom(Nb, C, H, W, O, KH, KW, stride, pad, pad_mode, c.g);
+    int rc = make_geom(Nb, C, H, W, O, KH, KW, stride, pad, pad_mode, c.g, fmt);
     if (rc != RTN_OK) return rc;
+    c.fp4 = fmt == RTN_CODE_FP4;
     if (!aligned(a_codes, 16) || !aligned(w_codes, 16) || !aligned(acc_out, 4) || !aligned(y_out, 4))
         return RTN_ERR_ALIGN;
     if (ep) {

@@ -23,6 +23,9 @@ struct PackArgs {
 };
 
 hipError_t launch_pack_rows_i8(const PackArgs& a, hipStream_t st);
+// FP4 (E2M1) codes, two per byte (element 2j in the low nibble of byte j); Kpad % 128 == 0
+hipError_t launch_pack_rows_fp4(const PackArgs& a, hipStream_t st);
+hipError_t launch_pack_nchw_fp4(const PackArgs& a, hipStream_t st);
 hipError_t launch_pack_rows_planes(const PackArgs& a, hipStream_t st);
 hipError_t launch_pack_nchw_i8(const PackArgs& a, hipStream_t st);
 hipError_t launch_pack_nchw_planes(const PackArgs& a, hipStream_t st);
@@ -100,9 +103,10 @@ struct ConvGeom {
 };
 
 struct GemmArgs {
-    const int8_t* a;  // [M][Kpad]
+    const int8_t* a;  // [M][Kpad] int8, or [M][Kpad / 2] bytes of FP4 nibbles
     const int8_t* w;  // [N][Kpad]
     int64_t M, N, K, Kpad;
+    int fp4;          // 1: FP4 codes (Kpad % 128 == 0)
     int32_t* acc;  // nullable
     float* y;      // nullable (then `ep` unused)
     EpiArgs ep;
@@ -111,7 +115,8 @@ struct GemmArgs {
 struct ConvArgs {
     const int8_t* a;  // [Nb][H][W][Cpad]
     const int8_t* w;  // [O][KH][KW][Cpad]
-    ConvGeom g;
+    ConvGeom g;       // g.Cpad in codes
+    int fp4;          // 1: both code tensors hold FP4 nibbles, Cpad / 2 bytes per pixel (Cpad % 128 == 0)
     int32_t* acc;          // nullable, [Nb][O][OH][OW]
     float* y;              // nullable
     const double* cst_cls; // workspace: the prepared per-layer epilogue table (when y or codes)

@@ -17,6 +17,17 @@ __device__ __forceinline__ float thr(const Param& p, int64_t i) { return p.ptr ?
 
 __device__ __forceinline__ int tern(float v, float lo, float hi) { return (int)(v > hi) - (int)(v < lo); }
 
+// FP4 (E2M1) code of a ternary value: +1 -> 0x2, -1 -> 0xA, 0 -> 0x0.
+__device__ __forceinline__ uint32_t nib(int t) { return (uint32_t)((t & 1) << 1) | (uint32_t)((t >> 28) & 8); }
+// Four int8 codes in a dword (bytes 0x00, 0x01, 0xFF) -> their four FP4 nibbles in 16 bits,
+// element 0 in the lowest nibble.
+__device__ __forceinline__ uint32_t i8x4_to_fp4(uint32_t w)
+{
+    const uint32_t t = ((w << 1) & 0x02020202u) | ((w >> 4) & 0x08080808u);  // one nibble per byte
+    const uint32_t r = (t | (t >> 4)) & 0x00ff00ffu;
+    return (r | (r >> 8)) & 0xffffu;
+}
+
 __device__ __forceinline__ int wave_sum(int v)
 {
 #pragma unroll
@@ -60,6 +71,53 @@ __global__ __launch_bounds__(256) void k_pack_rows_i8(PackArgs a)
         const uint32_t packed = (uint32_t)(t0 & 0xff) | ((uint32_t)(t1 & 0xff) << 8) |
                                 ((uint32_t)(t2 & 0xff) << 16) | ((uint32_t)(t3 & 0xff) << 24);
         *(uint32_t*)(cr + k) = packed;
+    }
+    if (a.sum_t) {
+        sum = wave_sum(sum);
+        if (lane == 0) a.sum_t[row] = sum;
+    }
+}
+
+// ---- rows layout, FP4 codes ------------------------------------------------
+// As above with two codes per byte: a lane handles 8 consecutive elements per step and
+// writes one dword, so a wave reads 2 KiB and writes 256 B per step.  Kpad % 128 == 0.
+template <bool VEC4>
+__global__ __launch_bounds__(256) void k_pack_rows_fp4(PackArgs a)
+{
+    const int lane = threadIdx.x & 63;
+    const int64_t row = (int64_t)blockIdx.x * 4 + (threadIdx.x >> 6);
+    if (row >= a.rows) return;
+    const float lo = thr(a.lo, row), hi = thr(a.hi, row);
+    const float* xr = a.x + row * a.K;
+    uint8_t* cr = (uint8_t*)a.codes + row * (a.Kpad >> 1);
+    int sum = 0;
+    for (int64_t k0 = 0; k0 < a.Kpad; k0 += 512) {
+        const int64_t k = k0 + 8 * lane;
+        if (k >= a.Kpad) break;
+        float v[8];
+        bool ok[8];
+        if (VEC4) {  // K % 4 == 0: each quad is wholly in or out of range
+            const bool q0 = k < a.K, q1 = k + 4 < a.K;
+            const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
+            const float4 u0 = q0 ? *(const float4*)(xr + k) : z, u1 = q1 ? *(const float4*)(xr + k + 4) : z;
+            v[0] = u0.x, v[1] = u0.y, v[2] = u0.z, v[3] = u0.w, v[4] = u1.x, v[5] = u1.y, v[6] = u1.z, v[7] = u1.w;
+#pragma unroll
+            for (int e = 0; e < 8; ++e) ok[e] = e < 4 ? q0 : q1;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                ok[e] = k + e < a.K;
+                v[e] = ok[e] ? xr[k + e] : 0.0f;
+            }
+        }
+        uint32_t packed = 0;
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+            const int t = ok[e] ? tern(v[e], lo, hi) : 0;
+            sum += t;
+            packed |= nib(t) << (4 * e);
+        }
+        *(uint32_t*)(cr + (k >> 1)) = packed;
     }
     if (a.sum_t) {
         sum = wave_sum(sum);
@@ -120,9 +178,10 @@ __global__ __launch_bounds__(256) void k_pack_rows_planes(PackArgs a)
 // and parks them in an LDS image of the output run, which the block then
 // streams out with consecutive lanes writing consecutive 16-byte chunks (full
 // cache lines).  Channel sums are combined through LDS.
+template <bool FP4>
 __global__ __launch_bounds__(256) void k_pack_nchw_i8(PackArgs a)
 {
-    extern __shared__ __attribute__((aligned(16))) uint8_t tile[];  // [64][Cpad]
+    extern __shared__ __attribute__((aligned(16))) uint8_t tile[];  // [64][Cpad], FP4: [64][Cpad / 2]
     __shared__ int part[4][64];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     const int64_t total = a.N * a.HW;
@@ -133,6 +192,7 @@ __global__ __launch_bounds__(256) void k_pack_nchw_i8(PackArgs a)
     const float lo = thr(a.lo, n), hi = thr(a.hi, n);
     const float* xn = a.x + n * a.K * a.HW + p;
     const int groups = (int)(a.Kpad >> 4);
+    const int64_t rowb = FP4 ? a.Kpad >> 1 : a.Kpad;  // bytes of a pixel's code row
     int sum = 0;
     for (int g = wave; g < groups; g += 4) {
         uint32_t w4[4] = {0, 0, 0, 0};
@@ -149,14 +209,18 @@ __global__ __launch_bounds__(256) void k_pack_nchw_i8(PackArgs a)
             sum += t;
             w4[j >> 2] |= (uint32_t)(t & 0xff) << (8 * (j & 3));
         }
-        *(uint4*)(tile + (size_t)lane * a.Kpad + g * 16) = make_uint4(w4[0], w4[1], w4[2], w4[3]);
+        if (FP4)
+            *(uint2*)(tile + (size_t)lane * rowb + g * 8) =
+                make_uint2(i8x4_to_fp4(w4[0]) | (i8x4_to_fp4(w4[1]) << 16), i8x4_to_fp4(w4[2]) | (i8x4_to_fp4(w4[3]) << 16));
+        else
+            *(uint4*)(tile + (size_t)lane * rowb + g * 16) = make_uint4(w4[0], w4[1], w4[2], w4[3]);
     }
     part[wave][lane] = sum;
     __syncthreads();
     if (a.sum_t && wave == 0 && pin) a.sum_t[q] = part[0][lane] + part[1][lane] + part[2][lane] + part[3][lane];
     const int64_t valid = total - q0 < 64 ? total - q0 : 64;
-    const int chunks = (int)(valid * groups);
-    uint8_t* out = (uint8_t*)a.codes + q0 * a.Kpad;
+    const int chunks = (int)(valid * (rowb >> 4));
+    uint8_t* out = (uint8_t*)a.codes + q0 * rowb;
     for (int e = threadIdx.x; e < chunks; e += 256) *(uint4*)(out + (size_t)e * 16) = *(const uint4*)(tile + (size_t)e * 16);
 }
 
@@ -173,10 +237,12 @@ __global__ __launch_bounds__(256) void k_pack_nchw_i8(PackArgs a)
 // writing consecutive 16-byte pieces of a pixel's 64*SUBS contiguous bytes.
 // LPR = 64 gives the widest pixel runs; the smaller ones trade them for more
 // blocks (a tensor with few pixels and many channels) and fewer passes.
-template <int LPR>
+// FP4: the same with 8-byte slots (16 channels = 8 bytes), i.e. an 8 KiB LDS image.
+template <int LPR, bool FP4>
 __global__ __launch_bounds__(256) void k_pack_nchw_i8_v4(PackArgs a)
 {
-    constexpr int SUBS = 64 / LPR, PB = 4 * LPR, RB = 64 * SUBS, NSLOT = RB / 16;
+    constexpr int SUBS = 64 / LPR, PB = 4 * LPR, SLOT = FP4 ? 8 : 16, NSLOT = 4 * SUBS, RB = SLOT * NSLOT;
+    constexpr int CG = 64 * SUBS;  // channels per group
     __shared__ __attribute__((aligned(16))) uint8_t tile[PB * RB];
     __shared__ int part[4 * SUBS][PB];
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
@@ -188,15 +254,16 @@ __global__ __launch_bounds__(256) void k_pack_nchw_i8_v4(PackArgs a)
     const int64_t p = pin ? q - n * a.HW : 0;
     const float lo = thr(a.lo, n), hi = thr(a.hi, n);
     const float* xn = a.x + n * a.K * a.HW + p;
-    const int ngroup = (int)((a.Kpad + RB - 1) / RB);
+    const int ngroup = (int)((a.Kpad + CG - 1) / CG);
     const int64_t valid = total - q0 < PB ? total - q0 : PB;
-    uint8_t* out = (uint8_t*)a.codes + q0 * a.Kpad;
+    const int64_t rowb = FP4 ? a.Kpad >> 1 : a.Kpad;
+    uint8_t* out = (uint8_t*)a.codes + q0 * rowb;
     int sum[4] = {0, 0, 0, 0};
     for (int cg = 0; cg < ngroup; ++cg) {
         float4 v[16];
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
-            const int64_t c = (int64_t)cg * RB + cblk * 16 + j;
+            const int64_t c = (int64_t)cg * CG + cblk * 16 + j;
             v[j] = (pin && c < a.K) ? *(const float4*)(xn + c * a.HW) : make_float4(0.f, 0.f, 0.f, 0.f);
         }
         uint32_t w4[4][4];
@@ -206,29 +273,40 @@ __global__ __launch_bounds__(256) void k_pack_nchw_i8_v4(PackArgs a)
             for (int k = 0; k < 4; ++k) w4[i][k] = 0;
 #pragma unroll
         for (int j = 0; j < 16; ++j) {
-            const int64_t c = (int64_t)cg * RB + cblk * 16 + j;
+            const int64_t c = (int64_t)cg * CG + cblk * 16 + j;
             const bool ok = pin && c < a.K;
             const float e[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
 #pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int t = ok ? tern(e[i], lo, hi) : 0;
                 sum[i] += t;
-                w4[i][j >> 2] |= (uint32_t)(t & 0xff) << (8 * (j & 3));
+                if (FP4)
+                    w4[i][j >> 3] |= nib(t) << (4 * (j & 7));
+                else
+                    w4[i][j >> 2] |= (uint32_t)(t & 0xff) << (8 * (j & 3));
             }
         }
         if (cg > 0) __syncthreads();  // previous group fully streamed out
 #pragma unroll
-        for (int i = 0; i < 4; ++i)
-            *(uint4*)(tile + (4 * quad + i) * RB + ((cblk ^ (quad & (NSLOT - 1))) << 4)) =
-                make_uint4(w4[i][0], w4[i][1], w4[i][2], w4[i][3]);
+        for (int i = 0; i < 4; ++i) {
+            uint8_t* slot = tile + (4 * quad + i) * RB + (cblk ^ (quad & (NSLOT - 1))) * SLOT;
+            if (FP4)
+                *(uint2*)slot = make_uint2(w4[i][0], w4[i][1]);
+            else
+                *(uint4*)slot = make_uint4(w4[i][0], w4[i][1], w4[i][2], w4[i][3]);
+        }
         __syncthreads();
 #pragma unroll
         for (int k = 0; k < PB * NSLOT / 256; ++k) {
             const int e = tid + 256 * k, px = e / NSLOT, pp = e % NSLOT;
             const int logical = pp ^ ((px >> 2) & (NSLOT - 1));
-            const int64_t cbyte = (int64_t)cg * RB + logical * 16;  // the last group may overhang Kpad
-            if (px < valid && cbyte < a.Kpad)
-                *(uint4*)(out + (size_t)px * a.Kpad + cbyte) = *(const uint4*)(tile + e * 16);
+            const int64_t cbyte = (int64_t)cg * RB + logical * SLOT;  // the last group may overhang the row
+            if (px < valid && cbyte < rowb) {
+                if (FP4)
+                    *(uint2*)(out + (size_t)px * rowb + cbyte) = *(const uint2*)(tile + e * SLOT);
+                else
+                    *(uint4*)(out + (size_t)px * rowb + cbyte) = *(const uint4*)(tile + e * SLOT);
+            }
         }
     }
     if (a.sum_t) {
@@ -251,6 +329,7 @@ __global__ __launch_bounds__(256) void k_pack_nchw_i8_v4(PackArgs a)
 // are dropped byte by byte into an LDS image [HW][Cpad + 4] (the 4 pad bytes put
 // consecutive pixels of a channel on consecutive banks), which is then streamed
 // out in 16-byte pieces, every piece adding its 16 codes to its pixel's sum.
+template <bool FP4>
 __global__ __launch_bounds__(1024) void k_pack_nchw_i8_flat(PackArgs a, FastDiv div_hw)
 {
     extern __shared__ __attribute__((aligned(16))) uint8_t img[];  // [HW][Cpad + 4], then int psum[HW]
@@ -294,12 +373,17 @@ __global__ __launch_bounds__(1024) void k_pack_nchw_i8_flat(PackArgs a, FastDiv 
     }
     __syncthreads();
     const int np = Kpad / 16;
-    uint8_t* out = (uint8_t*)a.codes + n * a.HW * a.Kpad;
+    const int rowb = FP4 ? Kpad >> 1 : Kpad;
+    uint8_t* out = (uint8_t*)a.codes + n * a.HW * rowb;
     for (int e = tid; e < HW * np; e += 1024) {
         const int p = e / np, piece = e - p * np;
         const uint32_t* src = (const uint32_t*)(img + p * pitch + piece * 16);
         const uint4 w = make_uint4(src[0], src[1], src[2], src[3]);
-        *(uint4*)(out + (size_t)p * Kpad + piece * 16) = w;
+        if (FP4)
+            *(uint2*)(out + (size_t)p * rowb + piece * 8) =
+                make_uint2(i8x4_to_fp4(w.x) | (i8x4_to_fp4(w.y) << 16), i8x4_to_fp4(w.z) | (i8x4_to_fp4(w.w) << 16));
+        else
+            *(uint4*)(out + (size_t)p * rowb + piece * 16) = w;
         if (a.sum_t) {
             int s = 0;
             s = __builtin_amdgcn_sdot4((int)w.x, 0x01010101, s, false);
@@ -378,6 +462,17 @@ hipError_t launch_pack_rows_i8(const PackArgs& a, hipStream_t st)
     return hipGetLastError();
 }
 
+hipError_t launch_pack_rows_fp4(const PackArgs& a, hipStream_t st)
+{
+    const dim3 grid((unsigned)((a.rows + 3) / 4)), block(256);
+    const bool vec4 = (a.K % 4 == 0) && (((uintptr_t)a.x) % 16 == 0);
+    if (vec4)
+        hipLaunchKernelGGL(k_pack_rows_fp4<true>, grid, block, 0, st, a);
+    else
+        hipLaunchKernelGGL(k_pack_rows_fp4<false>, grid, block, 0, st, a);
+    return hipGetLastError();
+}
+
 hipError_t launch_pack_rows_planes(const PackArgs& a, hipStream_t st)
 {
     const dim3 grid((unsigned)((a.rows + 3) / 4)), block(256);
@@ -385,13 +480,14 @@ hipError_t launch_pack_rows_planes(const PackArgs& a, hipStream_t st)
     return hipGetLastError();
 }
 
-hipError_t launch_pack_nchw_i8(const PackArgs& a, hipStream_t st)
+template <bool FP4>
+hipError_t launch_pack_nchw_codes(const PackArgs& a, hipStream_t st)
 {
-    const size_t smem = (size_t)64 * a.Kpad;  // LDS image of the block's output run
+    const size_t smem = (size_t)64 * (FP4 ? a.Kpad / 2 : a.Kpad);  // LDS image of the block's output run
     if (smem > 128 * 1024) return hipErrorInvalidValue;
     static bool attr_done = false;
     if (!attr_done) {
-        hipError_t e = hipFuncSetAttribute((const void*)k_pack_nchw_i8,
+        hipError_t e = hipFuncSetAttribute((const void*)k_pack_nchw_i8<FP4>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
         if (e != hipSuccess) return e;
         attr_done = true;
@@ -401,11 +497,11 @@ hipError_t launch_pack_nchw_i8(const PackArgs& a, hipStream_t st)
         // the channels where the row is long enough
         const int64_t px = a.N * a.HW;
         if (a.Kpad >= 256 && px < 2048 * 256) {
-            hipLaunchKernelGGL(k_pack_nchw_i8_v4<16>, dim3((unsigned)((px + 63) / 64)), dim3(256), 0, st, a);
+            hipLaunchKernelGGL((k_pack_nchw_i8_v4<16, FP4>), dim3((unsigned)((px + 63) / 64)), dim3(256), 0, st, a);
         } else if (a.Kpad >= 128 && px < 4096 * 256) {
-            hipLaunchKernelGGL(k_pack_nchw_i8_v4<32>, dim3((unsigned)((px + 127) / 128)), dim3(256), 0, st, a);
+            hipLaunchKernelGGL((k_pack_nchw_i8_v4<32, FP4>), dim3((unsigned)((px + 127) / 128)), dim3(256), 0, st, a);
         } else {
-            hipLaunchKernelGGL(k_pack_nchw_i8_v4<64>, dim3((unsigned)((px + 255) / 256)), dim3(256), 0, st, a);
+            hipLaunchKernelGGL((k_pack_nchw_i8_v4<64, FP4>), dim3((unsigned)((px + 255) / 256)), dim3(256), 0, st, a);
         }
         return hipGetLastError();
     }
@@ -413,14 +509,17 @@ hipError_t launch_pack_nchw_i8(const PackArgs& a, hipStream_t st)
     const size_t flat_smem = (size_t)a.HW * (a.Kpad + 4) + (size_t)a.HW * 4;
     if ((a.K * a.HW) % 4 == 0 && ((uintptr_t)a.x) % 16 == 0 && flat_smem <= 64 * 1024 && a.HW >= 4 &&
         a.K * a.HW < ((int64_t)1 << 30) && a.N <= 0x7fffffff) {
-        hipLaunchKernelGGL(k_pack_nchw_i8_flat, dim3((unsigned)a.N), dim3(1024), flat_smem, st, a,
+        hipLaunchKernelGGL(k_pack_nchw_i8_flat<FP4>, dim3((unsigned)a.N), dim3(1024), flat_smem, st, a,
                            make_fastdiv((uint32_t)a.HW));
         return hipGetLastError();
     }
     const dim3 grid((unsigned)((a.N * a.HW + 63) / 64)), block(256);
-    hipLaunchKernelGGL(k_pack_nchw_i8, grid, block, smem, st, a);
+    hipLaunchKernelGGL(k_pack_nchw_i8<FP4>, grid, block, smem, st, a);
     return hipGetLastError();
 }
+
+hipError_t launch_pack_nchw_i8(const PackArgs& a, hipStream_t st) { return launch_pack_nchw_codes<false>(a, st); }
+hipError_t launch_pack_nchw_fp4(const PackArgs& a, hipStream_t st) { return launch_pack_nchw_codes<true>(a, st); }
 
 hipError_t launch_pack_nchw_planes(const PackArgs& a, hipStream_t st)
 {

@@ -2,5 +2,5 @@
 #include "tmm_dispatch.inc"
 
 namespace rtn {
-template hipError_t tmm_launch_index_raw<true, 0>(int, TmmParams&, hipStream_t);
+template hipError_t tmm_launch_index_raw<true, 0, 0>(int, TmmParams&, hipStream_t);
 }

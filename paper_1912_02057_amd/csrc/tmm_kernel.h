@@ -30,9 +30,14 @@
 //   HC   conv tiles that keep their run of input pixels in LDS (stride 1, centred window);
 //   TERN conv whose epilogue ternarizes its output for the next layer (1), also after
 //        the residual add and second ReLU of a block tail (2);
-//   DT   bf16 operands with fp32 accumulators (v_mfma_f32_32x32x16_bf16) for the
+//   DT   1: bf16 operands with fp32 accumulators (v_mfma_f32_32x32x16_bf16) for the
 //        weight-only ternary GEMM / conv, whose fp32 activations are split exactly
-//        into three bf16 terms laid along K.
+//        into three bf16 terms laid along K;
+//        2: codes stored as FP4 (E2M1) nibbles, two per byte, multiplied by
+//        v_mfma_f32_32x32x64_f8f6f4 with fp32 accumulators.  -1, 0, +1 are exact in
+//        E2M1 (0xA, 0x0, 0x2), every product is exact and the fp32 sums are integers
+//        below 2^24, so D is the same integer the int8 form produces -- at twice the
+//        matrix-core rate and half the operand bytes (a 64-byte K-step is 128 codes).
 // This header holds the kernel template and its launcher; the instantiations are spread
 // over several translation units (tmm_inst_*.hip) so that they compile in parallel.
 #pragma once
@@ -77,10 +82,11 @@ struct TmmParams {
 };
 
 // Launch of tile configuration `cfg` (the numbering rtn_set_tile_config() documents) of the
-// int8 kernel, GEMM (CONV = false) or conv with the plain (TERN = 0), ternarizing (1) or
-// block-tail (2) epilogue.  hipErrorInvalidValue: the configuration does not fit this problem.
-// Defined in tmm_dispatch.inc, instantiated one (CONV, TERN) pair per translation unit.
-template <bool CONV, int TERN>
+// kernel on int8 (DT = 0) or FP4 (DT = 2) codes, GEMM (CONV = false) or conv with the plain
+// (TERN = 0), ternarizing (1) or block-tail (2) epilogue.  hipErrorInvalidValue: the
+// configuration does not fit this problem.  Defined in tmm_dispatch.inc, instantiated one
+// (CONV, TERN, DT) triple per translation unit.
+template <bool CONV, int TERN, int DT>
 hipError_t tmm_launch_index_raw(int cfg, TmmParams& prm, hipStream_t st);
 // The bf16-operand variants of the weight-only path: variant 0 = 64x64, 1 = 128x128,
 // 2 = the largest (conv: 128x256, GEMM: 256x256), conv only: 3 = 64x256.
@@ -89,6 +95,7 @@ hipError_t tmm_launch_bf16(bool conv, int variant, TmmParams& prm, hipStream_t s
 namespace {
 
 typedef int v4i __attribute__((ext_vector_type(4)));
+typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v16f __attribute__((ext_vector_type(16)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
@@ -211,10 +218,14 @@ __device__ __forceinline__ void wait_groups(int groups)
 // lane's 16 operand bytes are 8 bf16 of the same row, so tiles, ring and fragment
 // addressing are those of the int8 form): the weight-only ternary GEMM, whose
 // activations are fp32 values split into three bf16 terms laid side by side along K.
+// DT = 2 multiplies FP4 (E2M1) codes (v_mfma_f32_32x32x64_f8f6f4, both operands FP4,
+// no scaling): a lane's 16 operand bytes are 32 codes of one row, everything else is
+// byte for byte the int8 form.  Which 32 of a K-step's 128 codes a lane holds, and in
+// which nibble order, is the same for both operands, so the sum over k is unaffected.
 template <int BP, int BQ, int WGP, int WGQ, int NS, int MINW, bool CONV, int TERN = 0, int HC = 0, int DT = 0>
 __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
 {
-    static_assert(DT == 0 || (TERN == 0 && HC == 0), "bf16 operands: plain GEMM and plain conv only");
+    static_assert(DT != 1 || (TERN == 0 && HC == 0), "bf16 operands: plain GEMM and plain conv only");
     static_assert(!TERN || CONV, "the ternarizing epilogue belongs to the conv");
     static_assert(WGP * WGQ == 4, "4 waves per block");
     constexpr bool HALO = HC != 0;
@@ -440,10 +451,10 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
     // bytes), i.e. of the Q fragments this lane multiplies anyway: 4 byte-sum dot
     // products per fragment, added up beside the MFMAs.  A lane holds half of a
     // row's bytes (the other k-chunks sit in lane ^ 32); the halves meet in the epilogue.
-    int sa_part[TQ];
+    int sa_part[TQ], sa_neg[TQ];  // DT = 2: count of non-zero codes and of -1 codes
 #pragma unroll
-    for (int j = 0; j < TQ; ++j) sa_part[j] = 0;
-    using AccV = std::conditional_t<DT == 1, v16f, v16i>;
+    for (int j = 0; j < TQ; ++j) sa_part[j] = sa_neg[j] = 0;
+    using AccV = std::conditional_t<DT != 0, v16f, v16i>;
     AccV acc[TP][TQ];
 #pragma unroll
     for (int i = 0; i < TP; ++i)
@@ -466,7 +477,13 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
                 acc[n / TQ][n % TQ] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(
                     __builtin_bit_cast(v8bf, fa[ks][n / TQ]), __builtin_bit_cast(v8bf, fb[ks][n % TQ]),
                     acc[n / TQ][n % TQ], 0, 0, 0);
-            else
+            else if constexpr (DT == 2) {
+                // cbsz = blgp = 4: both operands FP4; the upper half of the 8-register operand is unused
+                const v4i pa = fa[ks][n / TQ], pb = fb[ks][n % TQ];
+                const v8i A8 = {pa[0], pa[1], pa[2], pa[3], 0, 0, 0, 0}, B8 = {pb[0], pb[1], pb[2], pb[3], 0, 0, 0, 0};
+                acc[n / TQ][n % TQ] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(A8, B8, acc[n / TQ][n % TQ], 4, 4, 0,
+                                                                                      0, 0, 0);
+            } else
                 acc[n / TQ][n % TQ] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[ks][n / TQ], fb[ks][n % TQ],
                                                                             acc[n / TQ][n % TQ], 0, 0, 0);
             if (FRAGS) {
@@ -487,6 +504,17 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
             for (int j = 0; j < TQ; ++j)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) sa_part[j] = __builtin_amdgcn_sdot4(fb[ks][j][e], 0x01010101, sa_part[j], false);
+        }
+        if (CONV && DT == 2) {
+            // FP4 nibbles: bit 1 is set for +1 (0x2) and -1 (0xA), bit 3 for -1 only
+#pragma unroll
+            for (int j = 0; j < TQ; ++j)
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const unsigned w = (unsigned)fb[ks][j][e];
+                    sa_part[j] += __builtin_popcount(w & 0x22222222u);
+                    sa_neg[j] += __builtin_popcount(w & 0x88888888u);
+                }
         }
     };
     const std::true_type yes{};
@@ -671,7 +699,7 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
                 if (m < prm.RP) {
                     aa = pval(ep.alpha_a, m);
                     ba = pval(ep.beta_a, m);
-                    if (DT == 0) r2 = aa * (double)ep.sum_ta[m] + (double)prm.Klogical * ba;
+                    if (DT != 1) r2 = aa * (double)ep.sum_ta[m] + (double)prm.Klogical * ba;
                 }
                 tab[t] = aa;
                 tab[BP + t] = ba;
@@ -698,7 +726,7 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
                 if (Y && nok[j]) {
                     aw[j] = pval(ep.alpha_w, ncol);
                     bw[j] = pval(ep.beta_w, ncol);
-                    if (DT == 0) sw[j] = (double)ep.sum_tw[ncol];
+                    if (DT != 1) sw[j] = (double)ep.sum_tw[ncol];
                     if (has_bn) {
                         bs[j] = ep.bn_scale[ncol];
                         bh[j] = ep.bn_shift ? (double)ep.bn_shift[ncol] : 0.0;
@@ -746,7 +774,10 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
         // (the table was copied into LDS by the prologue's direct loads)
         int sa_full[TQ];
 #pragma unroll
-        for (int j = 0; j < TQ; ++j) sa_full[j] = sa_part[j] + __shfl_xor(sa_part[j], 32, 64);
+        for (int j = 0; j < TQ; ++j) {
+            const int mine = DT == 2 ? sa_part[j] - 2 * sa_neg[j] : sa_part[j];
+            sa_full[j] = mine + __shfl_xor(mine, 32, 64);
+        }
         if constexpr (TERN) {
             // Ternarizing epilogue (Eq.1 / Eq.3 applied to the activation of Eq.9): the
             // fp32 value z is formed exactly as below, compared with the channel's

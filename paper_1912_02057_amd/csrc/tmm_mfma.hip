@@ -65,11 +65,11 @@ int g_forced_tile = -1;
 
 // A configuration whose LDS need (ring + the conv's table, which grows with the
 // pad) exceeds the CU's falls back to the smallest tile.
-template <bool CONV, int TERN = 0>
+template <bool CONV, int TERN = 0, int DT = 0>
 hipError_t launch_index(int cfg, TmmParams& prm, hipStream_t st)
 {
-    hipError_t e = tmm_launch_index_raw<CONV, TERN>(cfg, prm, st);
-    if (e == hipErrorInvalidValue && cfg != 0) e = tmm_launch_index_raw<CONV, TERN>(0, prm, st);
+    hipError_t e = tmm_launch_index_raw<CONV, TERN, DT>(cfg, prm, st);
+    if (e == hipErrorInvalidValue && cfg != 0) e = tmm_launch_index_raw<CONV, TERN, DT>(0, prm, st);
     return e;
 }
 
@@ -117,14 +117,14 @@ hipError_t launch_gemm_mfma(const GemmArgs& a, hipStream_t st)
     prm.Q = a.w;
     prm.RP = (int)a.M;
     prm.RQ = (int)a.N;
-    prm.ldP = prm.ldQ = a.Kpad;
-    prm.nk = (int)(a.Kpad / 64);
+    prm.ldP = prm.ldQ = a.fp4 ? a.Kpad / 2 : a.Kpad;  // bytes per row
+    prm.nk = (int)(prm.ldP / 64);
     prm.Klogical = (int)a.K;
     prm.acc = a.acc;
     prm.y = a.y;
     prm.ep = a.ep;
     const int cfg = g_forced_tile >= 0 ? g_forced_tile : pick_tile(a.M, a.N, false);
-    return launch_index<false>(cfg, prm, st);
+    return a.fp4 ? launch_index<false, 0, 2>(cfg, prm, st) : launch_index<false>(cfg, prm, st);
 }
 
 // ---- weight-only ternary GEMM: fp32 activations x (alpha * t_w) ----------------
@@ -326,11 +326,12 @@ hipError_t launch_conv_mfma(const ConvArgs& a, hipStream_t st)
     prm.Q = a.a;
     prm.RP = g.O;
     prm.RQ = g.Nb * g.OH * g.OW;
-    prm.ldP = (int64_t)g.KH * g.KW * g.Cpad;
+    prm.g = g;
+    if (a.fp4) prm.g.Cpad = g.Cpad / 2;  // the kernel's K bookkeeping is in bytes
+    prm.ldP = (int64_t)g.KH * g.KW * prm.g.Cpad;
     prm.ldQ = 0;
     prm.nk = (int)(prm.ldP / 64);
     prm.Klogical = g.C * g.KH * g.KW;
-    prm.g = g;
     prm.acc = a.acc;
     prm.y = a.y;
     prm.cst_cls = a.cst_cls;
@@ -345,6 +346,10 @@ hipError_t launch_conv_mfma(const ConvArgs& a, hipStream_t st)
     // a 64-filter layer with a centred stride-1 window: the variant that keeps the
     // tile's input pixel run in LDS (measured faster there; on par or slower elsewhere)
     if (g_forced_tile < 0 && cfg == 7 && halo_eligible(prm, 64)) cfg = 15;
+    if (a.fp4) {
+        if (a.codes) return hipErrorInvalidValue;  // the ternarizing epilogues write int8 codes only
+        return launch_index<true, 0, 2>(cfg, prm, st);
+    }
     if (!a.codes) return launch_index<true>(cfg, prm, st);
     const bool tail = a.res != nullptr || a.y != nullptr || a.relu_out;
     // the block-tail epilogue prefetches its residual values only for the tiles with

@@ -30,6 +30,13 @@ def planes_from_dev(codes):
     return c[0].reshape(-1, words), c[1].reshape(-1, words)
 
 
+def fp4_rows(t, Kpad=None):
+    """Oracle FP4 bytes of an int8 code tensor whose last axis is the row (any leading shape)."""
+    t = np.ascontiguousarray(t)
+    e = orc.encode_fp4(t.reshape(-1, t.shape[-1]), Kpad)
+    return e.reshape(t.shape[:-1] + (e.shape[-1],))
+
+
 def assert_y_close(y, yhat, what=""):
     """The stated bar: 1e-5 relative on the reparameterized outputs.  The HIP
     epilogue evaluates the four terms in fp64 and rounds once, so it sits within
@@ -89,12 +96,12 @@ def oracle_conv(case, pad_true_zero=True, relu=False, images=None):
     return dict(ta=ta, tw=tw, D=D, y=y)
 
 
-def hip_conv(case, pad_true_zero=True, relu=False, want_acc=True):
+def hip_conv(case, pad_true_zero=True, relu=False, want_acc=True, fmt=B.RTN_CODE_I8):
     sh = case["shape"]
     da, dw = case["delta_a"], case["delta_w"]
     x, w = dev(case["x"]), dev(case["w"])
-    ca, pa = B.ternarize_pack(x, thr_arg(-da), thr_arg(da))
-    cw, pw = B.ternarize_pack(w, thr_arg(-np.asarray(dw)), thr_arg(dw))
+    ca, pa = B.ternarize_pack(x, thr_arg(-da), thr_arg(da), fmt)
+    cw, pw = B.ternarize_pack(w, thr_arg(-np.asarray(dw)), thr_arg(dw), fmt)
     ep = B.Epilogue(gran_arg(case["alpha_a"]), gran_arg(case["beta_a"]), gran_arg(case["alpha_w"]),
                     gran_arg(case["beta_w"]), pa, pw, relu=relu,
                     bn_scale=None if "bn_scale" not in case else dev(case["bn_scale"]),
@@ -103,12 +110,12 @@ def hip_conv(case, pad_true_zero=True, relu=False, want_acc=True):
     pm = B.RTN_PAD_TRUE_ZERO if pad_true_zero else B.RTN_PAD_CODE_ZERO
     if want_acc == "separate":      # the two single-output launches (accumulators only, then y only)
         acc, _ = B.ternary_conv2d(ca, cw, Nb, Cc, H, W, sh.O, sh.k, sh.k, sh.stride, sh.pad, pm,
-                                  ep=None, want_acc=True)
+                                  ep=None, want_acc=True, fmt=fmt)
         _, y = B.ternary_conv2d(ca, cw, Nb, Cc, H, W, sh.O, sh.k, sh.k, sh.stride, sh.pad, pm,
-                                ep=ep, want_acc=False)
+                                ep=ep, want_acc=False, fmt=fmt)
     else:
         acc, y = B.ternary_conv2d(ca, cw, Nb, Cc, H, W, sh.O, sh.k, sh.k, sh.stride, sh.pad, pm,
-                                  ep=ep, want_acc=want_acc)
+                                  ep=ep, want_acc=want_acc, fmt=fmt)
     torch.cuda.synchronize()
     return dict(ca=ca, cw=cw, pa=pa, pw=pw, D=acc, y=y, ep=ep)
 

@@ -62,6 +62,10 @@ def test_pack_rows(rows, K, per_row):
     em, es = orc.encode_planes(t, Kp // 64)
     assert (m == em).all() and (sg == es).all()
     assert (s2.cpu().numpy() == orc.row_sums(t)).all()
+    nibbles, s3 = B.ternarize_pack(xd, T.thr_arg(lo), T.thr_arg(hi), B.RTN_CODE_FP4)
+    assert nibbles.shape == (rows, (K + 127) // 128 * 64)
+    assert (nibbles.cpu().numpy() == orc.encode_fp4(t)).all()
+    assert (s3.cpu().numpy() == orc.row_sums(t)).all()
 
 
 def test_pack_rows_unaligned_base():
@@ -106,6 +110,10 @@ def test_pack_nchw(shape, per_lead):
     em, es = orc.encode_planes(orc.nchw_to_nhwc_i8(t, shape[1]).reshape(-1, shape[1]), Cp // 64)
     assert (m == em).all() and (sg == es).all()
     assert (s2.cpu().numpy() == orc.pixel_sums(t)).all()
+    nibbles, s3 = B.ternarize_pack(xd, T.thr_arg(lo), T.thr_arg(hi), B.RTN_CODE_FP4)
+    assert tuple(nibbles.shape) == (shape[0], shape[2], shape[3], (shape[1] + 127) // 128 * 64)
+    assert (nibbles.cpu().numpy() == T.fp4_rows(orc.nchw_to_nhwc_i8(t, shape[1]))).all()
+    assert (s3.cpu().numpy() == orc.pixel_sums(t)).all()
 
 
 # ------------------------------------------------------ S2 + S4: GEMM -------
@@ -323,6 +331,95 @@ def test_halo_variants(cfg, hs, tile_reset):
             T.assert_y_close(got["y"].cpu().numpy(), ref["y"], "%s cfg %d" % (name, cfg))
 
 
+# --------------- the FP4 matrix path (codes stored as E2M1 nibbles) ---------------
+FP4 = B.RTN_CODE_FP4
+
+
+@pytest.mark.parametrize("M,N,K", GEMM_SHAPES + [(200, 136, 129), (70, 300, 4096)])
+def test_gemm_fp4_vs_oracle(M, N, K):
+    _say("gemm fp4 M=%d N=%d K=%d" % (M, N, K))
+    case = wl.gemm_case(M, N, K, p_zero=0.4, seed=M + N + K + 1)
+    ref = T.oracle_gemm(case)
+    for mode in (True, "separate"):
+        got = T.hip_gemm(case, fmt=FP4, want_acc=mode)
+        assert (got["ca"].cpu().numpy() == orc.encode_fp4(ref["ta"])).all()
+        assert (got["Sa"].cpu().numpy() == ref["Sa"]).all() and (got["Sw"].cpu().numpy() == ref["Sw"]).all()
+        assert (got["D"].cpu().numpy() == ref["D"]).all()
+        T.assert_y_close(got["y"].cpu().numpy(), ref["y"], "gemm fp4 y")
+
+
+def test_gemm_fp4_extreme_sums_are_exact():
+    """All-ones rows against all-ones and all-minus-ones rows: |D| = K at the largest K the
+    sweep uses, the case where fp32 accumulation has the least headroom."""
+    _say("gemm fp4, |D| = K = 8192")
+    K = 8192
+    xa = np.ones((96, K), np.float32)
+    xw = np.ones((80, K), np.float32)
+    xw[1::2] = -1.0
+    xw[5, 17] = 0.0
+    case = dict(xa=xa, xw=xw, delta_a=np.float32(0.5), delta_w=np.float32(0.5), alpha_a=np.float32(1.0),
+                beta_a=np.float32(0.0), alpha_w=np.float32(1.0), beta_w=np.float32(0.0), M=96, N=80, K=K)
+    ref, got = T.oracle_gemm(case), T.hip_gemm(case, fmt=FP4)
+    assert int(np.abs(ref["D"]).max()) == K
+    assert (got["D"].cpu().numpy() == ref["D"]).all()
+    assert (got["y"].cpu().numpy() == ref["D"].astype(np.float32)).all()
+
+
+@pytest.mark.parametrize("shape", CONV_SHAPES, ids=lambda s: s.name)
+@pytest.mark.parametrize("true_zero", [True, False])
+def test_conv_fp4_vs_oracle(shape, true_zero):
+    _say("conv fp4 %s true_zero=%s" % (shape, true_zero))
+    case = wl.conv_case(shape, batch=3, seed=len(shape.name) + 9, per_channel=True, bn=True)
+    ref = T.oracle_conv(case, true_zero, relu=True)
+    got = T.hip_conv(case, true_zero, relu=True, fmt=FP4)
+    assert (got["ca"].cpu().numpy() == T.fp4_rows(orc.nchw_to_nhwc_i8(ref["ta"], shape.C))).all()
+    assert (got["cw"].cpu().numpy() == T.fp4_rows(orc.nchw_to_nhwc_i8(ref["tw"], shape.C))).all()
+    assert (got["D"].cpu().numpy() == ref["D"]).all()
+    T.assert_y_close(got["y"].cpu().numpy(), ref["y"], "conv fp4 y")
+
+
+@pytest.mark.parametrize("cfg", range(20))
+def test_all_tile_configs_fp4(cfg, tile_reset):
+    _say("tile config %d, fp4" % cfg)
+    B.set_tile_config(cfg)
+    case = wl.gemm_case(300, 530, 700, seed=cfg + 3)
+    ref = T.oracle_gemm(case)
+    for mode in (True, "separate"):
+        got = T.hip_gemm(case, fmt=FP4, want_acc=mode)
+        assert (got["D"].cpu().numpy() == ref["D"]).all()
+        T.assert_y_close(got["y"].cpu().numpy(), ref["y"], "gemm fp4 cfg %d" % cfg)
+    for shape, batch in [(wl.ConvShape("t", 64, 13, 200, 3, 2, 1), 7), (wl.ConvShape("u", 192, 16, 264, 3, 1, 1), 3)]:
+        ccase = wl.conv_case(shape, batch=batch, seed=cfg + 5, bn=True)
+        cref = T.oracle_conv(ccase, True, relu=True)
+        for mode in (True, "separate"):
+            cgot = T.hip_conv(ccase, True, relu=True, want_acc=mode, fmt=FP4)
+            assert (cgot["D"].cpu().numpy() == cref["D"]).all()
+            T.assert_y_close(cgot["y"].cpu().numpy(), cref["y"], "conv fp4 cfg %d" % cfg)
+
+
+FP4_HALO_SHAPES = HALO_SHAPES + [
+    ("h256", 256, 10, 136, 3, 1, 1, 3, None),      # 128 bytes per pixel: two K-steps per tap
+    ("h200r", 200, 7, 130, 3, 1, 1, 9, 10),        # C padded to 256, ragged in O and pixels
+]
+
+
+@pytest.mark.parametrize("cfg", range(14, 20))
+@pytest.mark.parametrize("hs", FP4_HALO_SHAPES, ids=[h[0] for h in FP4_HALO_SHAPES])
+def test_halo_variants_fp4(cfg, hs, tile_reset):
+    """The pixel-run-in-LDS variants on FP4 codes: 64 bytes per pixel are up to 128 channels,
+    128 bytes up to 256."""
+    name, Cc, H, O, k, stride, pad, batch, W = hs
+    _say("halo fp4 cfg %d shape %s" % (cfg, name))
+    B.set_tile_config(cfg)
+    shape = wl.ConvShape(name, Cc, H, O, k, stride, pad)
+    case = wl.conv_case(shape, batch=batch, seed=310 + cfg, bn=True, Wx=W)
+    for tz in (True, False):
+        ref = T.oracle_conv(case, tz, relu=True)
+        got = T.hip_conv(case, tz, relu=True, fmt=FP4)
+        assert (got["D"].cpu().numpy() == ref["D"]).all(), (name, tz)
+        T.assert_y_close(got["y"].cpu().numpy(), ref["y"], "%s fp4 cfg %d" % (name, cfg))
+
+
 # ---------------------- conv with the ternarizing epilogue (next layer's codes) ----
 def _thresholds(kind, case, O, seed):
     """scalar: one Delta for the layer; vector: Eq.3's BN-folded pair per channel."""
@@ -538,6 +635,39 @@ def test_resnet18_layers_batch256_sampled_images(idx):
     assert int(got["D"].abs().max()) <= shape.K
 
 
+@pytest.mark.parametrize("idx", range(19))
+def test_resnet18_layers_batch256_fp4_sampled_images(idx):
+    """The same layers on the FP4 matrix path (the launch configuration the benchmark
+    times): all activation codes of the sampled images, accumulators and outputs."""
+    shape = wl.resnet18_ternary_layers()[idx]
+    _say("resnet18 b256 fp4 %s" % (shape,))
+    case = wl.conv_case(shape, batch=256, seed=100 + idx, per_channel=True, bn=True)
+    got = T.hip_conv(case, True, relu=True, want_acc="separate", fmt=FP4)
+    imgs = _sample_images(256, 8, 100 + idx)
+    ref = T.oracle_conv(case, True, relu=True, images=imgs)
+    assert (got["ca"][imgs].cpu().numpy() == T.fp4_rows(orc.nchw_to_nhwc_i8(ref["ta"], shape.C))).all()
+    assert (got["D"][imgs].cpu().numpy() == ref["D"]).all()
+    T.assert_y_close(got["y"][imgs].cpu().numpy(), ref["y"], shape.name)
+    assert int(got["D"].abs().max()) <= shape.K
+
+
+def test_config2_gemm_4096_fp4_sampled_rows():
+    _say("config 2 on the FP4 path: 4096^3, 1024 sampled rows")
+    case = wl.gemm_case(4096, 4096, 4096, p_zero=0.4, seed=1)
+    got = T.hip_gemm(case, fmt=FP4, want_acc="separate")
+    ta = orc.ternarize(case["xa"], -0.5, 0.5)
+    tw = orc.ternarize(case["xw"], -0.5, 0.5)
+    assert (got["ca"].cpu().numpy() == orc.encode_fp4(ta)).all() and (got["cw"].cpu().numpy() == orc.encode_fp4(tw)).all()
+    Sa, Sw = orc.row_sums(ta), orc.row_sums(tw)
+    assert (got["Sa"].cpu().numpy() == Sa).all() and (got["Sw"].cpu().numpy() == Sw).all()
+    rows = _sample_rows(4096, 1024, 2)
+    D = orc.gemm_acc_rows(ta, tw, rows)
+    assert (got["D"].cpu().numpy()[rows] == D).all()
+    y = orc.gemm_epilogue(D, 4096, Sa[rows], Sw, case["alpha_a"][rows], case["beta_a"][rows],
+                          case["alpha_w"], case["beta_w"])
+    T.assert_y_close(got["y"].cpu().numpy()[rows], y, "config2 fp4 y")
+
+
 # ------------------------------------ config 3: the conv stack at batch 64 ------
 @pytest.mark.parametrize("idx", range(19))
 def test_resnet18_layers_batch64_sampled_images(idx):
@@ -590,6 +720,9 @@ def _sweep_check(M, NK, p0, fmt, seed):
     if fmt == B.RTN_CODE_I8:
         assert (got["ca"][torch.as_tensor(rows)].cpu().numpy() == ta).all()
         assert (got["cw"].cpu().numpy() == tw).all()
+    if fmt == B.RTN_CODE_FP4:
+        assert (got["ca"][torch.as_tensor(rows)].cpu().numpy() == orc.encode_fp4(ta)).all()
+        assert (got["cw"].cpu().numpy() == orc.encode_fp4(tw)).all()
     D = orc.gemm_acc_rows(ta, tw, np.arange(rows.size, dtype=np.int64))
     assert (got["D"].cpu().numpy()[rows] == D).all()
     y = orc.gemm_epilogue(D, NK, Sa, Sw, case["alpha_a"][rows], case["beta_a"][rows],
@@ -607,6 +740,13 @@ def test_config5_gemm_sweep_mfma(M, NK, p0):
     rows (all columns) against the oracle, all side sums, all weight codes."""
     _say("sweep mfma M=%d N=K=%d P(0)=%.1f" % (M, NK, p0))
     _sweep_check(M, NK, p0, B.RTN_CODE_I8, seed=int(1000 * p0) + M // 1024 + NK // 512)
+
+
+@pytest.mark.parametrize("M,NK,p0", SWEEP)
+def test_config5_gemm_sweep_fp4(M, NK, p0):
+    """The same sweep, all twelve points, on the FP4 matrix path."""
+    _say("sweep fp4 M=%d N=K=%d P(0)=%.1f" % (M, NK, p0))
+    _sweep_check(M, NK, p0, B.RTN_CODE_FP4, seed=int(1000 * p0) + M // 1024 + NK // 512 + 1)
 
 
 @pytest.mark.parametrize("M,NK,p0", SWEEP)
