@@ -41,6 +41,9 @@ def main():
                     choices=["resnet18_ternary_convs", "gemm4096", "wgemm4096", "resnet18_weight_only_convs",
                              "act_backward", "weight_backward", "gemm_sweep"])
     ap.add_argument("--tile", type=int, default=-1, help="force an MFMA tile configuration (tuning)")
+    ap.add_argument("--format", default="fp4", choices=["fp4", "i8"],
+                    help="storage of the ternary codes on the matrix-core path: FP4 (E2M1) nibbles on the FP4 "
+                         "matrix cores (default), or int8 on the int8 matrix cores")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cpu-images", type=int, default=128,
                     help="images per layer the oracle is timed on (cpu_baseline sample)")
@@ -70,6 +73,7 @@ def main():
         return float(v) if v.ndim == 0 else to_dev(v)
 
     ev = torch.cuda.Event
+    FMT = B.RTN_CODE_FP4 if args.format == "fp4" else B.RTN_CODE_I8
     if args.workload == "gemm_sweep":
         # M x N x K sweep of the ternary GEMM over sparsity, on both contraction paths: codes resident,
         # one timed call = contraction + fused epilogue (the pack of the activations is timed beside it)
@@ -131,8 +135,12 @@ def main():
             w = to_dev(case["w"])
             dw = np.asarray(case["delta_w"])
             cw, pw = B.ternarize_pack(w, garg(-dw), garg(dw))            # S0, offline
+            cw_h = cw if FMT == B.RTN_CODE_I8 else B.ternarize_pack(w, garg(-dw), garg(dw), FMT)[0]
             Cp = B.padded_k(sh.C)
             ca = torch.empty((args.batch, sh.H, sh.H, Cp), dtype=torch.int8, device=dev)
+            # the headline step's own code tensor (FP4: two codes per byte)
+            ca_h = ca if FMT == B.RTN_CODE_I8 else torch.empty(
+                (args.batch, sh.H, sh.H, B.padded_k(sh.C, FMT) // 2), dtype=torch.uint8, device=dev)
             pa = torch.empty((args.batch, sh.H, sh.H), dtype=torch.int32, device=dev)
             y = torch.empty((args.batch, sh.O, sh.OH, sh.OH), dtype=torch.float32, device=dev)
             ws = torch.empty(B.conv2d_workspace_bytes(sh.O, sh.k, sh.k, sh.pad), dtype=torch.uint8, device=dev)
@@ -146,26 +154,29 @@ def main():
                                  bn_scale=to_dev(case["bn_scale"]), bn_shift=to_dev(case["bn_shift"]))
             ws_tail = torch.empty_like(ws)
             B.conv2d_prepare_constants(sh.C, sh.O, sh.k, sh.k, sh.pad, ep_tail, ws_tail)
-            layers.append(dict(sh=sh, x=x, cw=cw, pw=pw, ca=ca, pa=pa, y=y, ws=ws, ep=ep,
+            layers.append(dict(sh=sh, x=x, cw=cw, pw=pw, ca=ca, pa=pa, y=y, ws=ws, ep=ep, cw_h=cw_h, ca_h=ca_h,
                                ep_tail=ep_tail, ws_tail=ws_tail,
                                da=float(case["delta_a"]), case=case if i < 0 else None))
             del case
         L = B.lib()
         import ctypes as C
 
-        def pack(l):
+        def pack(l, fmt=B.RTN_CODE_I8):
             sh = l["sh"]
             lo, hi = C.c_float(-l["da"]), C.c_float(l["da"])
             rc = L.rtn_ternarize_pack(l["x"].data_ptr(), B.RTN_NCHW, args.batch, sh.C, sh.H, sh.H,
-                                      C.addressof(lo), C.addressof(hi), B.RTN_SCALAR, B.RTN_CODE_I8,
-                                      l["ca"].data_ptr(), l["pa"].data_ptr(), stream)
+                                      C.addressof(lo), C.addressof(hi), B.RTN_SCALAR, fmt,
+                                      (l["ca"] if fmt == B.RTN_CODE_I8 else l["ca_h"]).data_ptr(),
+                                      l["pa"].data_ptr(), stream)
             assert rc == 0, rc
 
-        def conv(l, ca=None):
+        def conv(l, ca=None, fmt=B.RTN_CODE_I8):
             sh = l["sh"]
-            B.ternary_conv2d(l["ca"] if ca is None else ca, l["cw"], args.batch, sh.C, sh.H, sh.H, sh.O,
+            own = l["ca"] if fmt == B.RTN_CODE_I8 else l["ca_h"]
+            B.ternary_conv2d(own if ca is None else ca, l["cw"] if fmt == B.RTN_CODE_I8 else l["cw_h"],
+                             args.batch, sh.C, sh.H, sh.H, sh.O,
                              sh.k, sh.k, sh.stride, sh.pad, B.RTN_PAD_TRUE_ZERO, ep=l["ep"], y_out=l["y"],
-                             workspace=l["ws"])
+                             workspace=l["ws"], fmt=fmt)
 
         # The same 19 convs arranged as ResNet-18's 8 residual blocks, with the first conv
         # of each block handing its output to the second as codes (ternarizing epilogue):
@@ -223,10 +234,10 @@ def main():
             for i, l in enumerate(layers):
                 if timers is not None:
                     timers[i][0].record()
-                pack(l)
+                pack(l, FMT)
                 if timers is not None:
                     timers[i][1].record()
-                conv(l)
+                conv(l, fmt=FMT)
                 if timers is not None:
                     timers[i][2].record()
 

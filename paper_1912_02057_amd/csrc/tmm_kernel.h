@@ -74,6 +74,7 @@ struct TmmParams {
     // ReLU; the fp32 value that is ternarized is also stored when y is given
     const float* res;
     int relu_out;
+    int nt_out;  // conv: store the fp32 / int32 outputs with the non-temporal hint
     // bf16 operands (DT = 1): the weight rows (GEMM: Q, conv: P) are wwrap bytes long and
     // are walked again from the start each time the K offset passes their end; the
     // conv's three activation planes lie qplane bytes apart
@@ -650,15 +651,20 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
 
     __builtin_amdgcn_s_setprio(0);
     // ---- epilogue ---------------------------------------------------------------
-    // The conv's outputs are written with the non-temporal hint: they are not read again here,
-    // and a plain store leaves its dirty lines to be written back while the *next*
-    // kernel runs (measured: a 205 MB read kernel takes 57 us right after 205 MB of
-    // plain stores, 32 us after the same stores marked non-temporal; over the
-    // ResNet-18 stack the hint shortens the step by 6 %, the small layers included).
+    // Large conv outputs are written with the non-temporal hint, small ones plainly.  A plain
+    // store leaves its dirty lines in the cache hierarchy; when the output is larger than
+    // what the memory-side cache holds they are written back while the *next* kernel
+    // runs and slow it more than the hint slows this one (205 MB stored, then 205 MB
+    // read: 92 us plain, 75 us with the hint).  An output that fits is stored about twice
+    // as fast without the hint, and the kernel after it is not slowed (51 MB: 25 us
+    // against 39 us for the pair).  The launch code decides (prm.nt_out).
     // The GEMM keeps plain stores: its 256 tiles finish together, and the cache
     // absorbs that burst faster than HBM takes it.
-    auto put = [&](auto value, auto* ptr) {
-        if (CONV)
+    // (a tag type, not a run-time test at the store: the compiler merges the two arms of such
+    // a test into one plain store)
+    const bool nt_out = CONV && prm.nt_out;
+    auto put = [&](auto nt, auto value, auto* ptr) {
+        if constexpr (decltype(nt)::value)
             __builtin_nontemporal_store(value, ptr);
         else
             *ptr = value;
@@ -672,22 +678,31 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
     const bool full_tile = p0 + BP <= prm.RP && q0 + BQ <= prm.RQ;
     // The element loops exist in 6 straight-line variants (interior / ragged
     // tile) x (acc only / y only / both), picked once per block.
-    auto dispatch = [&](auto&& run) {
+    auto dispatch3 = [&](auto&& run, auto nt) {
         if (full_tile) {
             if (!prm.y)
-                run(std::true_type{}, std::true_type{}, std::false_type{});
+                run(std::true_type{}, std::true_type{}, std::false_type{}, nt);
             else if (!prm.acc)
-                run(std::true_type{}, std::false_type{}, std::true_type{});
+                run(std::true_type{}, std::false_type{}, std::true_type{}, nt);
             else
-                run(std::true_type{}, std::true_type{}, std::true_type{});
+                run(std::true_type{}, std::true_type{}, std::true_type{}, nt);
         } else {
             if (!prm.y)
-                run(std::false_type{}, std::true_type{}, std::false_type{});
+                run(std::false_type{}, std::true_type{}, std::false_type{}, nt);
             else if (!prm.acc)
-                run(std::false_type{}, std::false_type{}, std::true_type{});
+                run(std::false_type{}, std::false_type{}, std::true_type{}, nt);
             else
-                run(std::false_type{}, std::true_type{}, std::true_type{});
+                run(std::false_type{}, std::true_type{}, std::true_type{}, nt);
         }
+    };
+    auto dispatch = [&](auto&& run) {
+        if constexpr (CONV) {
+            if (nt_out) {
+                dispatch3(run, std::true_type{});
+                return;
+            }
+        }
+        dispatch3(run, std::false_type{});
     };
     if (!CONV) {
         __syncthreads();  // all waves are done with the operand stages
@@ -708,7 +723,7 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
         }
         __syncthreads();
         const int64_t N = prm.RQ;
-        dispatch([&](auto full, auto want_acc, auto want_y) {
+        dispatch([&](auto full, auto want_acc, auto want_y, auto nt) {
             constexpr bool FULL = decltype(full)::value, ACC = decltype(want_acc)::value,
                            Y = decltype(want_y)::value;
             // per lane: its TQ output columns, their factors and base pointers.  Set up
@@ -753,11 +768,11 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
                     for (int j = 0; j < TQ; ++j) {
                         if (FULL || (mok && nok[j])) {
                             const auto D = acc[i][j][r];
-                            if (ACC) put((int)D, accp[j] + rowoff);
+                            if (ACC) put(nt, (int)D, accp[j] + rowoff);
                             if (Y) {
                                 double v = aw[j] * (aa * (double)D + ba * sw[j]) + bw[j] * r2;
                                 v = __builtin_fmax(v, relu_floor);
-                                put((float)(bs[j] * v + bh[j]), yp[j] + rowoff);
+                                put(nt, (float)(bs[j] * v + bh[j]), yp[j] + rowoff);
                             }
                         }
                     }
@@ -788,7 +803,7 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
             // STREAM: the block-tail form -- z + residual (fp32 add, as a separate add
             // kernel would do it), a second ReLU, and the fp32 result stored as well.
             const float relu_out_floor = __builtin_canonicalizef(prm.relu_out ? 0.0f : -__builtin_inff());
-            auto run_codes = [&](auto full, auto stream) {
+            auto run_codes = [&](auto full, auto stream, auto nt) {
                 constexpr bool FULL = decltype(full)::value, STREAM = decltype(stream)::value;
 #pragma unroll
                 for (int j = 0; j < TQ; ++j) {
@@ -836,8 +851,7 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
                                 float z = (float)(bs * v + bh);
                                 if (STREAM) {
                                     z = __builtin_fmaxf(z + rv[4 * r4 + b], relu_out_floor);
-                                    if (prm.y && (FULL || (mok && ook)))
-                                        __builtin_nontemporal_store(z, prm.y + obase + (int64_t)(o0 + b) * ohw);
+                                    if (prm.y && (FULL || (mok && ook))) put(nt, z, prm.y + obase + (int64_t)(o0 + b) * ohw);
                                 }
                                 int code = (int)(z > th.y) - (int)(z < th.x);
                                 if (!FULL && !ook) code = 0;
@@ -849,13 +863,21 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
                     }
                 }
             };
-            if (full_tile)
-                run_codes(std::true_type{}, std::integral_constant<bool, TERN == 2>{});
-            else
-                run_codes(std::false_type{}, std::integral_constant<bool, TERN == 2>{});
+            constexpr std::integral_constant<bool, TERN == 2> tail{};
+            if (TERN == 2 && nt_out) {
+                if (full_tile)
+                    run_codes(std::true_type{}, tail, std::true_type{});
+                else
+                    run_codes(std::false_type{}, tail, std::true_type{});
+            } else {
+                if (full_tile)
+                    run_codes(std::true_type{}, tail, std::false_type{});
+                else
+                    run_codes(std::false_type{}, tail, std::false_type{});
+            }
             return;
         }
-        dispatch([&](auto full, auto want_acc, auto want_y) {
+        dispatch([&](auto full, auto want_acc, auto want_y, auto nt) {
             constexpr bool FULL = decltype(full)::value, ACC = decltype(want_acc)::value,
                            Y = decltype(want_y)::value;
             // per lane: its TQ output pixels -> Sa, class constants, output base pointers
@@ -897,11 +919,11 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
                     for (int j = 0; j < TQ; ++j) {
                         if (FULL || (ook && mok[j])) {
                             const auto D = acc[i][j][r];
-                            if (ACC) put((int)D, accp[j] + rowoff);
+                            if (ACC) put(nt, (int)D, accp[j] + rowoff);
                             if (Y) {
                                 double v = g1 * (double)D + (c2 * Sa[j] + cc[j]);
                                 v = __builtin_fmax(v, relu_floor);
-                                put((float)(bs * v + bh), yp[j] + rowoff);
+                                put(nt, (float)(bs * v + bh), yp[j] + rowoff);
                             }
                         }
                     }

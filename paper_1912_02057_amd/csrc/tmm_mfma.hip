@@ -2,6 +2,8 @@
 // GEMM, the conv and the weight-only forms, plus the small kernels around them -- the
 // conv's per-layer epilogue table, the fp32 -> 3 x bf16 splits and the int8 -> bf16
 // weight copy.  The contraction kernel itself is in tmm_kernel.h.
+#include <cstdlib>
+
 #include "tmm_kernel.h"
 
 namespace rtn {
@@ -342,6 +344,12 @@ hipError_t launch_conv_mfma(const ConvArgs& a, hipStream_t st)
     prm.thr_hi = a.thr_hi;
     prm.res = a.res;
     prm.relu_out = a.relu_out;
+    // outputs beyond what stays in the memory-side cache take the non-temporal hint
+    {
+        const int64_t out_bytes = (int64_t)g.Nb * g.O * g.OH * g.OW * 4 * ((a.acc ? 1 : 0) + (a.y ? 1 : 0));
+        const char* force = getenv("RTN_CONV_NT");
+        prm.nt_out = force ? atoi(force) : out_bytes > (int64_t)128 << 20;
+    }
     int cfg = g_forced_tile >= 0 ? g_forced_tile : pick_tile(g.O, prm.RQ, true);
     // a 64-filter layer with a centred stride-1 window: the variant that keeps the
     // tile's input pixel run in LDS (measured faster there; on par or slower elsewhere)
