@@ -74,6 +74,13 @@ def main():
 
     ev = torch.cuda.Event
     FMT = B.RTN_CODE_FP4 if args.format == "fp4" else B.RTN_CODE_I8
+
+    def code_row_bytes(channels):
+        return B.padded_k(channels, FMT) // (2 if FMT == B.RTN_CODE_FP4 else 1)
+
+    def code_tensor(n, hw, channels):
+        return torch.empty((n, hw, hw, code_row_bytes(channels)),
+                           dtype=torch.uint8 if FMT == B.RTN_CODE_FP4 else torch.int8, device=dev)
     if args.workload == "gemm_sweep":
         # M x N x K sweep of the ternary GEMM over sparsity, on both contraction paths: codes resident,
         # one timed call = contraction + fused epilogue (the pack of the activations is timed beside it)
@@ -134,13 +141,8 @@ def main():
             x = to_dev(case["x"])
             w = to_dev(case["w"])
             dw = np.asarray(case["delta_w"])
-            cw, pw = B.ternarize_pack(w, garg(-dw), garg(dw))            # S0, offline
-            cw_h = cw if FMT == B.RTN_CODE_I8 else B.ternarize_pack(w, garg(-dw), garg(dw), FMT)[0]
-            Cp = B.padded_k(sh.C)
-            ca = torch.empty((args.batch, sh.H, sh.H, Cp), dtype=torch.int8, device=dev)
-            # the headline step's own code tensor (FP4: two codes per byte)
-            ca_h = ca if FMT == B.RTN_CODE_I8 else torch.empty(
-                (args.batch, sh.H, sh.H, B.padded_k(sh.C, FMT) // 2), dtype=torch.uint8, device=dev)
+            cw, pw = B.ternarize_pack(w, garg(-dw), garg(dw), FMT)       # S0, offline
+            ca = code_tensor(args.batch, sh.H, sh.C)
             pa = torch.empty((args.batch, sh.H, sh.H), dtype=torch.int32, device=dev)
             y = torch.empty((args.batch, sh.O, sh.OH, sh.OH), dtype=torch.float32, device=dev)
             ws = torch.empty(B.conv2d_workspace_bytes(sh.O, sh.k, sh.k, sh.pad), dtype=torch.uint8, device=dev)
@@ -154,29 +156,26 @@ def main():
                                  bn_scale=to_dev(case["bn_scale"]), bn_shift=to_dev(case["bn_shift"]))
             ws_tail = torch.empty_like(ws)
             B.conv2d_prepare_constants(sh.C, sh.O, sh.k, sh.k, sh.pad, ep_tail, ws_tail)
-            layers.append(dict(sh=sh, x=x, cw=cw, pw=pw, ca=ca, pa=pa, y=y, ws=ws, ep=ep, cw_h=cw_h, ca_h=ca_h,
+            layers.append(dict(sh=sh, x=x, cw=cw, pw=pw, ca=ca, pa=pa, y=y, ws=ws, ep=ep,
                                ep_tail=ep_tail, ws_tail=ws_tail,
                                da=float(case["delta_a"]), case=case if i < 0 else None))
             del case
         L = B.lib()
         import ctypes as C
 
-        def pack(l, fmt=B.RTN_CODE_I8):
+        def pack(l):
             sh = l["sh"]
             lo, hi = C.c_float(-l["da"]), C.c_float(l["da"])
             rc = L.rtn_ternarize_pack(l["x"].data_ptr(), B.RTN_NCHW, args.batch, sh.C, sh.H, sh.H,
-                                      C.addressof(lo), C.addressof(hi), B.RTN_SCALAR, fmt,
-                                      (l["ca"] if fmt == B.RTN_CODE_I8 else l["ca_h"]).data_ptr(),
-                                      l["pa"].data_ptr(), stream)
+                                      C.addressof(lo), C.addressof(hi), B.RTN_SCALAR, FMT,
+                                      l["ca"].data_ptr(), l["pa"].data_ptr(), stream)
             assert rc == 0, rc
 
-        def conv(l, ca=None, fmt=B.RTN_CODE_I8):
+        def conv(l, ca=None):
             sh = l["sh"]
-            own = l["ca"] if fmt == B.RTN_CODE_I8 else l["ca_h"]
-            B.ternary_conv2d(own if ca is None else ca, l["cw"] if fmt == B.RTN_CODE_I8 else l["cw_h"],
-                             args.batch, sh.C, sh.H, sh.H, sh.O,
+            B.ternary_conv2d(l["ca"] if ca is None else ca, l["cw"], args.batch, sh.C, sh.H, sh.H, sh.O,
                              sh.k, sh.k, sh.stride, sh.pad, B.RTN_PAD_TRUE_ZERO, ep=l["ep"], y_out=l["y"],
-                             workspace=l["ws"], fmt=fmt)
+                             workspace=l["ws"], fmt=FMT)
 
         # The same 19 convs arranged as ResNet-18's 8 residual blocks, with the first conv
         # of each block handing its output to the second as codes (ternarizing epilogue):
@@ -194,7 +193,7 @@ def main():
                 pack(l1)
                 B.ternary_conv2d_ternarize(l1["ca"], l1["cw"], args.batch, sh.C, sh.H, sh.H, sh.O, sh.k, sh.k,
                                            sh.stride, sh.pad, l1["ep"], -l2["da"], l2["da"],
-                                           codes_out=l2["ca"], workspace=l1["ws"])
+                                           codes_out=l2["ca"], workspace=l1["ws"], fmt=FMT)
                 conv(l2)
                 if ids is not None:
                     conv(layers[ids], ca=l1["ca"])
@@ -203,7 +202,7 @@ def main():
         # conv2's codes; conv2's block-tail epilogue adds the shortcut (the block input, or
         # the downsample conv's output), applies the ReLU and writes both the fp32 block
         # output (the next shortcut) and the next block's codes.  1 pack + 19 convs.
-        last_codes = torch.empty((args.batch, 7, 7, 512), dtype=torch.int8, device=dev)
+        last_codes = code_tensor(args.batch, 7, 512)
 
         def trunk_forward():
             pack(layers[0])
@@ -213,7 +212,7 @@ def main():
                 sh, sh2 = l1["sh"], l2["sh"]
                 B.ternary_conv2d_ternarize(cur_codes, l1["cw"], args.batch, sh.C, sh.H, sh.H, sh.O, sh.k, sh.k,
                                            sh.stride, sh.pad, l1["ep"], -l2["da"], l2["da"],
-                                           codes_out=l2["ca"], workspace=l1["ws"])
+                                           codes_out=l2["ca"], workspace=l1["ws"], fmt=FMT)
                 if ids is not None:
                     conv(layers[ids], ca=cur_codes)
                     res = layers[ids]["y"]
@@ -225,7 +224,7 @@ def main():
                 B.ternary_conv2d_ternarize(l2["ca"], l2["cw"], args.batch, sh2.C, sh2.H, sh2.H, sh2.O, sh2.k,
                                            sh2.k, sh2.stride, sh2.pad, l2["ep_tail"], -nda, nda,
                                            codes_out=nxt_codes, workspace=l2["ws_tail"], residual=res,
-                                           relu_out=True, y_out=l2["y"])
+                                           relu_out=True, y_out=l2["y"], fmt=FMT)
                 cur_x, cur_codes = l2["y"], nxt_codes
 
         stream = C.c_void_p(torch.cuda.current_stream().cuda_stream)
@@ -234,10 +233,10 @@ def main():
             for i, l in enumerate(layers):
                 if timers is not None:
                     timers[i][0].record()
-                pack(l, FMT)
+                pack(l)
                 if timers is not None:
                     timers[i][1].record()
-                conv(l, fmt=FMT)
+                conv(l)
                 if timers is not None:
                     timers[i][2].record()
 
@@ -452,20 +451,32 @@ def main():
         for i, l in enumerate(layers):
             sh = l["sh"]
             macs = sh.macs(args.batch)
-            Cp = B.padded_k(sh.C)
-            in_b = args.batch * sh.H * sh.H * Cp + args.batch * sh.H * sh.H * 4     # codes + pixel sums
-            w_b = sh.O * sh.k * sh.k * Cp
+            Cb = code_row_bytes(sh.C)                               # bytes of a pixel's code row
+            in_b = args.batch * sh.H * sh.H * Cb                    # (the conv forms the pixel sums itself)
+            w_b = sh.O * sh.k * sh.k * Cb
             out_b = args.batch * sh.O * sh.OH * sh.OH * 4
             conv_bytes = in_b + w_b + out_b
-            pack_bytes = args.batch * sh.C * sh.H * sh.H * 4 + args.batch * sh.H * sh.H * (Cp + 4)
+            pack_bytes = args.batch * sh.C * sh.H * sh.H * 4 + args.batch * sh.H * sh.H * (Cb + 4)
             tot_bytes_conv += conv_bytes
+            # in-bounds MACs: taps that fall into the zero padding are counted by the dense figure only
+            taps = sum(1 for o in range(sh.OH) for k in range(sh.k) if 0 <= o * sh.stride - sh.pad + k < sh.H)
+            macs_inb = args.batch * sh.O * sh.C * taps * taps
+            # which roof bounds the layer (MACs per algorithmic byte against the ridge of the int8 peak,
+            # 2.5e15 MAC/s / 8e12 B/s = 312 MAC/B) and the target that goes with it
+            pct_mfma = 100 * 2 * macs / (conv_ms[i] * 1e-3) / 1e12 / INT8_PEAK_TOPS
+            pct_hbm = 100 * conv_bytes / (conv_ms[i] * 1e-3) / 1e9 / HBM_PEAK_GBS
+            bound = "mfma" if macs / conv_bytes >= 312.0 else "hbm"
+            frac, target = (pct_mfma, 50.0) if bound == "mfma" else (pct_hbm, 70.0)
             per_layer.append(dict(
                 layer=sh.name, M=args.batch * sh.OH * sh.OH, N=sh.O, K=sh.K,
                 conv_us=round(conv_ms[i] * 1e3, 1), pack_us=round(pack_ms[i] * 1e3, 1),
                 conv_tops=round(2 * macs / (conv_ms[i] * 1e-3) / 1e12, 1),
-                conv_pct_int8_peak=round(100 * 2 * macs / (conv_ms[i] * 1e-3) / 1e12 / INT8_PEAK_TOPS, 1),
+                conv_pct_int8_peak=round(pct_mfma, 1),
                 conv_gbs=round(conv_bytes / (conv_ms[i] * 1e-3) / 1e9, 0),
-                conv_pct_hbm=round(100 * conv_bytes / (conv_ms[i] * 1e-3) / 1e9 / HBM_PEAK_GBS, 1),
+                conv_pct_hbm=round(pct_hbm, 1),
+                mac_per_byte=round(macs / conv_bytes, 0), bound=bound, frac=round(frac / 100, 3),
+                target=target / 100, target_met=bool(frac >= target),
+                macs_dense=macs, macs_in_bounds=macs_inb,
                 pack_gbs=round(pack_bytes / (pack_ms[i] * 1e-3) / 1e9, 0),
                 pack_pct_hbm=round(100 * pack_bytes / (pack_ms[i] * 1e-3) / 1e9 / HBM_PEAK_GBS, 1)))
     conv_total_s = float(conv_ms.sum()) * 1e-3

@@ -215,9 +215,10 @@ int rtn_ternary_conv2d_implicit_gemm(rtn_code_format fmt, rtn_path path, const v
  * is conv -> ReLU -> BN -> ternarize, so with z the fp32 value the epilogue of
  * rtn_ternary_conv2d_implicit_gemm would have stored for output channel o,
  *   t = (z > thr_hi[o]) - (z < thr_lo[o])            (Eq.1, strict, NaN -> 0)
- * is written channel-innermost as the next layer's input:
- *   codes_out: int8 [Nb][OH][OW][rtn_padded_k(O)], 16-byte aligned; the padding
- *   channels O .. rtn_padded_k(O)-1 are written as code 0.
+ * is written channel-innermost as the next layer's input, in the format `fmt` of
+ * the inputs (RTN_CODE_I8 or RTN_CODE_FP4):
+ *   codes_out: [Nb][OH][OW][rtn_padded_k_format(fmt, O)] codes (one byte each, or
+ *   two per byte), 16-byte aligned; the padding channels are written as code 0.
  * Thresholds: RTN_SCALAR (host pointers, lo <= hi) or RTN_VECTOR (device, one
  * pair per output channel).  The per-channel form is Eq.3: a BN affine k*z + b
  * with k > 0 need not be applied (leave ep->bn_scale NULL) when the caller

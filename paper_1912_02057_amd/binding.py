@@ -211,6 +211,9 @@ def ternary_gemm(a_codes, w_codes, M, N, K, fmt=RTN_CODE_I8, path=RTN_PATH_AUTO,
                  want_acc=False, acc_out=None, y_out=None):
     """Returns (acc or None, y or None)."""
     dev = a_codes.device
+    if fmt != RTN_CODE_BITPLANE:
+        _check_codes(a_codes, M, K, fmt, "a_codes")
+        _check_codes(w_codes, N, K, fmt, "w_codes")
     if want_acc and acc_out is None:
         acc_out = torch.empty((M, N), dtype=torch.int32, device=dev)
     if ep is not None and y_out is None:
@@ -221,6 +224,22 @@ def ternary_gemm(a_codes, w_codes, M, N, K, fmt=RTN_CODE_I8, path=RTN_PATH_AUTO,
                                 None if y_out is None else _dev(y_out, torch.float32), None, 0, _stream())
     _check(rc, "rtn_ternary_gemm")
     return acc_out, y_out
+
+
+def code_row_bytes(K, fmt=RTN_CODE_I8):
+    """Bytes of one row of K codes (a pixel's channels, a GEMM row) in format fmt."""
+    return lib().rtn_codes_bytes(fmt, 1, K) // (2 if fmt == RTN_CODE_BITPLANE else 1)
+
+
+def _check_codes(t, rows, K, fmt, what):
+    """The library takes raw pointers: make sure the tensor really holds `rows` rows of K codes in
+    format fmt, so that a tensor packed in another format cannot be read out of bounds."""
+    need = lib().rtn_codes_bytes(fmt, rows, K)
+    have = t.numel() * t.element_size()
+    if not (t.is_cuda and t.is_contiguous() and have >= need):
+        raise ValueError("%s: %d bytes, but %d rows of %d codes in format %d need %d" % (what, have, rows, K, fmt, need))
+    if fmt == RTN_CODE_FP4 and t.dtype != torch.uint8 or fmt == RTN_CODE_I8 and t.dtype != torch.int8:
+        raise ValueError("%s: dtype %s does not match code format %d" % (what, t.dtype, fmt))
 
 
 def conv2d_workspace_bytes(O, KH, KW, pad):
@@ -247,6 +266,8 @@ def ternary_conv2d(a_codes, w_codes, Nb, Cc, H, W, O, KH, KW, stride, pad, pad_m
                    fmt=RTN_CODE_I8, path=RTN_PATH_AUTO):
     """a_codes: int8 [Nb,H,W,Cpad]; w_codes: int8 [O,KH,KW,Cpad].  Returns (acc, y) in NCHW."""
     dev = a_codes.device
+    _check_codes(a_codes, Nb * H * W, Cc, fmt, "a_codes")
+    _check_codes(w_codes, O * KH * KW, Cc, fmt, "w_codes")
     OH, OW = conv_out_hw(H, W, KH, KW, stride, pad)
     if want_acc and acc_out is None:
         acc_out = torch.empty((Nb, O, OH, OW), dtype=torch.int32, device=dev)
@@ -272,8 +293,14 @@ def ternary_conv2d_ternarize(a_codes, w_codes, Nb, Cc, H, W, O, KH, KW, stride, 
     vectors (one per output channel).  residual / relu_out / y_out: the block-tail
     form (fp32 NCHW tensors).  Returns int8 codes [Nb,OH,OW,padded_k(O)]."""
     OH, OW = conv_out_hw(H, W, KH, KW, stride, pad)
+    _check_codes(a_codes, Nb * H * W, Cc, fmt, "a_codes")
+    _check_codes(w_codes, O * KH * KW, Cc, fmt, "w_codes")
+    if codes_out is not None:
+        _check_codes(codes_out, Nb * OH * OW, O, fmt, "codes_out")
     if codes_out is None:
-        codes_out = torch.empty((Nb, OH, OW, padded_k(O)), dtype=torch.int8, device=a_codes.device)
+        codes_out = (torch.empty((Nb, OH, OW, padded_k(O)), dtype=torch.int8, device=a_codes.device)
+                     if fmt == RTN_CODE_I8 else
+                     torch.empty((Nb, OH, OW, padded_k(O, fmt) // 2), dtype=torch.uint8, device=a_codes.device))
     if workspace is None:
         workspace = conv2d_prepare_constants(Cc, O, KH, KW, pad, ep)
     glo, ghi = _Gran(lo), _Gran(hi)
@@ -282,7 +309,8 @@ def ternary_conv2d_ternarize(a_codes, w_codes, Nb, Cc, H, W, O, KH, KW, stride, 
         fmt, path, C.c_void_p(a_codes.data_ptr()), C.c_void_p(w_codes.data_ptr()), Nb, Cc, H, W, O, KH, KW,
         stride, pad, pad_mode, ep.ref(), None if residual is None else _dev(residual, torch.float32),
         int(bool(relu_out)), glo.ptr, ghi.ptr, glo.gran,
-        None if y_out is None else _dev(y_out, torch.float32), _dev(codes_out, torch.int8),
+        None if y_out is None else _dev(y_out, torch.float32),
+        _dev(codes_out, torch.int8 if fmt == RTN_CODE_I8 else torch.uint8),
         C.c_void_p(workspace.data_ptr()), workspace.numel() * workspace.element_size(), _stream())
     _check(rc, "rtn_ternary_conv2d_ternarize")
     return codes_out

@@ -297,11 +297,13 @@ int rtn_ternary_conv2d_ternarize(rtn_code_format fmt, rtn_path path, const void*
                                  void* codes_out, void* workspace, size_t workspace_bytes, void* stream)
 {
     if (!a_codes || !w_codes || !codes_out || !ep || !thr_lo || !thr_hi) return RTN_ERR_NULL;
-    if (fmt != RTN_CODE_I8) return RTN_ERR_UNSUPPORTED;
-    if (path != RTN_PATH_AUTO && path != RTN_PATH_MFMA_I8) return RTN_ERR_UNSUPPORTED;
+    if (fmt != RTN_CODE_I8 && fmt != RTN_CODE_FP4) return RTN_ERR_UNSUPPORTED;
+    if (path != RTN_PATH_AUTO && path != (fmt == RTN_CODE_I8 ? RTN_PATH_MFMA_I8 : RTN_PATH_MFMA_FP4))
+        return RTN_ERR_UNSUPPORTED;
     rtn::ConvArgs c = {};
-    int rc = make_geom(Nb, C, H, W, O, KH, KW, stride, pad, pad_mode, c.g);
+    int rc = make_geom(Nb, C, H, W, O, KH, KW, stride, pad, pad_mode, c.g, fmt);
     if (rc != RTN_OK) return rc;
+    c.fp4 = fmt == RTN_CODE_FP4;
     if (!aligned(a_codes, 16) || !aligned(w_codes, 16) || !aligned(codes_out, 16)) return RTN_ERR_ALIGN;
     if (!aligned(residual, 4) || !aligned(y_out, 4)) return RTN_ERR_ALIGN;
     if ((rc = make_epilogue(ep, true, c.ep, false)) != RTN_OK) return rc;
@@ -310,7 +312,7 @@ int rtn_ternary_conv2d_ternarize(rtn_code_format fmt, rtn_path path, const void*
     if (thr_gran == RTN_SCALAR && !(c.thr_lo.s <= c.thr_hi.s)) return RTN_ERR_SHAPE;
     if (!workspace || workspace_bytes < rtn_conv2d_workspace_bytes(O, KH, KW, pad)) return RTN_ERR_WORKSPACE;
     if (!aligned(workspace, 16)) return RTN_ERR_ALIGN;
-    const int64_t ldc = pad64(O);
+    const int64_t ldc = c.fp4 ? padk(fmt, O) / 2 : pad64(O);  // bytes of an output pixel's code row
     if (ldc > kMaxDim || (double)c.g.Nb * c.g.OH * c.g.OW * (double)ldc >= 1099511627776.0) return RTN_ERR_SHAPE;
     c.a = (const int8_t*)a_codes;
     c.w = (const int8_t*)w_codes;

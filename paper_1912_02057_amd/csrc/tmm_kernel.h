@@ -452,7 +452,7 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
     // bytes), i.e. of the Q fragments this lane multiplies anyway: 4 byte-sum dot
     // products per fragment, added up beside the MFMAs.  A lane holds half of a
     // row's bytes (the other k-chunks sit in lane ^ 32); the halves meet in the epilogue.
-    int sa_part[TQ], sa_neg[TQ];  // DT = 2: count of non-zero codes and of -1 codes
+    int sa_part[TQ], sa_neg[TQ];  // DT = 2: signed and unsigned sums of the nibbles
 #pragma unroll
     for (int j = 0; j < TQ; ++j) sa_part[j] = sa_neg[j] = 0;
     using AccV = std::conditional_t<DT != 0, v16f, v16i>;
@@ -507,14 +507,16 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
                 for (int e = 0; e < 4; ++e) sa_part[j] = __builtin_amdgcn_sdot4(fb[ks][j][e], 0x01010101, sa_part[j], false);
         }
         if (CONV && DT == 2) {
-            // FP4 nibbles: bit 1 is set for +1 (0x2) and -1 (0xA), bit 3 for -1 only
+            // FP4 nibbles read as 4-bit integers: +1 (0x2) is 2 signed and unsigned, -1 (0xA) is
+            // -6 signed and 10 unsigned.  Two 8-way nibble dot products per dword accumulate
+            // S = 2 pos - 6 neg and U = 2 pos + 10 neg; the epilogue solves for pos - neg.
 #pragma unroll
             for (int j = 0; j < TQ; ++j)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) {
                     const unsigned w = (unsigned)fb[ks][j][e];
-                    sa_part[j] += __builtin_popcount(w & 0x22222222u);
-                    sa_neg[j] += __builtin_popcount(w & 0x88888888u);
+                    sa_part[j] = __builtin_amdgcn_sdot8((int)w, 0x11111111, sa_part[j], false);
+                    sa_neg[j] = (int)__builtin_amdgcn_udot8(w, 0x11111111u, (unsigned)sa_neg[j], false);
                 }
         }
     };
@@ -790,7 +792,11 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
         int sa_full[TQ];
 #pragma unroll
         for (int j = 0; j < TQ; ++j) {
-            const int mine = DT == 2 ? sa_part[j] - 2 * sa_neg[j] : sa_part[j];
+            int mine = sa_part[j];
+            if (DT == 2) {
+                const int neg = (sa_neg[j] - sa_part[j]) >> 4, pos = (sa_part[j] + 6 * neg) >> 1;
+                mine = pos - neg;
+            }
             sa_full[j] = mine + __shfl_xor(mine, 32, 64);
         }
         if constexpr (TERN) {
@@ -834,6 +840,7 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
                                     rv[r] = __builtin_nontemporal_load(prm.res + obase + (int64_t)o * ohw);
                             }
                         }
+                        unsigned half4[4];  // FP4 output: this lane's 4 nibbles of each channel group
 #pragma unroll
                         for (int r4 = 0; r4 < 4; ++r4) {
                             const int t0 = wp * WP + i * 32 + 8 * r4 + 4 * (lane >> 5);
@@ -853,13 +860,45 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
                                     z = __builtin_fmaxf(z + rv[4 * r4 + b], relu_out_floor);
                                     if (prm.y && (FULL || (mok && ook))) put(nt, z, prm.y + obase + (int64_t)(o0 + b) * ohw);
                                 }
-                                int code = (int)(z > th.y) - (int)(z < th.x);
-                                if (!FULL && !ook) code = 0;
-                                word |= (unsigned)(code & 0xff) << (8 * b);
+                                if constexpr (DT == 2) {
+                                    // E2M1 nibble: +1 -> 0x2, -1 -> 0xA
+                                    const bool pos = z > th.y, neg = z < th.x;
+                                    unsigned nb4 = ((unsigned)(pos | neg) << 1) | ((unsigned)neg << 3);
+                                    if (!FULL && !ook) nb4 = 0;
+                                    word |= nb4 << (4 * b);
+                                } else {
+                                    int code = (int)(z > th.y) - (int)(z < th.x);
+                                    if (!FULL && !ook) code = 0;
+                                    word |= (unsigned)(code & 0xff) << (8 * b);
+                                }
                             }
-                            if (FULL || (mok && o0 < prm.ldc)) *(unsigned*)(cp + o0) = word;
+                            if constexpr (DT == 2) {
+                                half4[r4] = word;
+                            } else {
+                                if (FULL || (mok && o0 < prm.ldc)) *(unsigned*)(cp + o0) = word;
+                            }
                             __builtin_amdgcn_sched_barrier(0);
                         }
+                        if constexpr (DT == 2) {
+                            // A dword of the FP4 code tensor is 8 consecutive channels: the 4 of this
+                            // lane and the 4 of lane ^ 32 (same pixel).  The lower lane half assembles
+                            // channel groups 0 and 2, the upper half groups 1 and 3; each sends the
+                            // other the two 16-bit halves it needs in one cross-lane move.
+                            const bool upper = (lane >> 5) != 0;
+                            const unsigned send = upper ? (half4[0] | (half4[2] << 16)) : (half4[1] | (half4[3] << 16));
+                            const unsigned recv = (unsigned)__shfl_xor((int)send, 32, 64);
+                            const unsigned wa = upper ? ((recv & 0xffffu) | (half4[1] << 16)) : (half4[0] | (recv << 16));
+                            const unsigned wb = upper ? ((recv >> 16) | (half4[3] << 16)) : (half4[2] | (recv & 0xffff0000u));
+                            const int c0 = p0 + wp * WP + i * 32 + (upper ? 8 : 0);  // first channel of word wa
+                            if (FULL || (mok && (c0 >> 1) < prm.ldc)) *(unsigned*)(cp + (c0 >> 1)) = wa;
+                            if (FULL || (mok && ((c0 + 16) >> 1) < prm.ldc)) *(unsigned*)(cp + ((c0 + 16) >> 1)) = wb;
+                        }
+                    }
+                    if constexpr (DT == 2) {
+                        // a 64-row tile covers half of a 128-code row: the last tile along the
+                        // channels also writes the zero codes of the other half
+                        if (BP == 64 && wp == 0 && (p0 + BP) / 2 < prm.ldc && p0 + BP >= prm.RP && mok)
+                            *(uint4*)(cp + (p0 + BP) / 2 + 16 * (lane >> 5)) = make_uint4(0, 0, 0, 0);
                     }
                 }
             };

@@ -354,15 +354,22 @@ hipError_t launch_conv_mfma(const ConvArgs& a, hipStream_t st)
     // a 64-filter layer with a centred stride-1 window: the variant that keeps the
     // tile's input pixel run in LDS (measured faster there; on par or slower elsewhere)
     if (g_forced_tile < 0 && cfg == 7 && halo_eligible(prm, 64)) cfg = 15;
-    if (a.fp4) {
-        if (a.codes) return hipErrorInvalidValue;  // the ternarizing epilogues write int8 codes only
-        return launch_index<true, 0, 2>(cfg, prm, st);
+    // ... and up to 128 filters (FP4 codes: 128 channels are 64 bytes per pixel) the 64 x 128 form of it
+    // Two more choices measured on the 128- and 512-filter layers (not for the block-tail
+    // epilogue, which prefers the deeper ring): the two-stage ring with four blocks per CU
+    // instead of the three-stage one, and, up to 128 filters with 64-byte pixels (FP4
+    // codes: 128 channels), the 64 x 128 form of the pixel-run variant.
+    const bool tail_form = a.codes && (a.res != nullptr || a.y != nullptr || a.relu_out);
+    if (g_forced_tile < 0 && !tail_form) {
+        if (cfg == 1 && nblocks(g.O, prm.RQ, 128, 128) >= 256) cfg = 12;
+        if (cfg == 12 && g.O <= 128 && halo_eligible(prm, 64)) cfg = 17;
     }
-    if (!a.codes) return launch_index<true>(cfg, prm, st);
+    if (!a.codes) return a.fp4 ? launch_index<true, 0, 2>(cfg, prm, st) : launch_index<true>(cfg, prm, st);
     const bool tail = a.res != nullptr || a.y != nullptr || a.relu_out;
     // the block-tail epilogue prefetches its residual values only for the tiles with
     // 64 accumulators per lane: prefer 128x128 over 128x256 there
     if (tail && g_forced_tile < 0 && cfg == 13) cfg = 12;
+    if (a.fp4) return tail ? launch_index<true, 2, 2>(cfg, prm, st) : launch_index<true, 1, 2>(cfg, prm, st);
     return tail ? launch_index<true, 2>(cfg, prm, st) : launch_index<true, 1>(cfg, prm, st);
 }
 

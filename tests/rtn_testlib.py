@@ -126,15 +126,30 @@ def oracle_next_codes(ref, lo, hi):
     return orc.nchw_to_nhwc_i8(orc.ternarize_nchw(ref["y"], lo, hi), (O + 63) // 64 * 64)
 
 
+def codes_as_i8(codes, fmt, O):
+    """Device code tensor [Nb,OH,OW,*] written by the ternarizing conv -> numpy int8 [Nb,OH,OW,pad64(O)].
+    FP4 tensors are decoded with the oracle's decoder; every nibble must be a ternary code and
+    every channel past O zero."""
+    c = codes.cpu().numpy()
+    if fmt == B.RTN_CODE_I8:
+        return c
+    assert c.dtype == np.uint8 and c.shape[-1] * 2 == (O + 127) // 128 * 128
+    t, bad = orc.decode_fp4(c.reshape(-1, c.shape[-1]), c.shape[-1] * 2)
+    assert bad == 0, "%d nibbles are not ternary codes" % bad
+    t = t.reshape(c.shape[:-1] + (c.shape[-1] * 2,))
+    assert (t[..., O:] == 0).all(), "padding channels must be code 0"
+    return np.ascontiguousarray(t[..., :(O + 63) // 64 * 64])
+
+
 def hip_conv_ternarize(case, lo, hi, pad_true_zero=True, relu=False, residual=None, relu_out=False,
-                       want_y=False):
+                       want_y=False, fmt=B.RTN_CODE_I8):
     """pack -> conv with the ternarizing epilogue; returns the int8 code tensor (device),
     or (codes, y) with want_y (the block-tail form's fp32 output)."""
     sh = case["shape"]
     da, dw = case["delta_a"], case["delta_w"]
     x, w = dev(case["x"]), dev(case["w"])
-    ca, _ = B.ternarize_pack(x, thr_arg(-da), thr_arg(da), want_sum=False)
-    cw, pw = B.ternarize_pack(w, thr_arg(-np.asarray(dw)), thr_arg(dw))
+    ca, _ = B.ternarize_pack(x, thr_arg(-da), thr_arg(da), fmt, want_sum=False)
+    cw, pw = B.ternarize_pack(w, thr_arg(-np.asarray(dw)), thr_arg(dw), fmt)
     ep = B.Epilogue(gran_arg(case["alpha_a"]), gran_arg(case["beta_a"]), gran_arg(case["alpha_w"]),
                     gran_arg(case["beta_w"]), None, pw, relu=relu,
                     bn_scale=None if "bn_scale" not in case else dev(case["bn_scale"]),
@@ -143,12 +158,15 @@ def hip_conv_ternarize(case, lo, hi, pad_true_zero=True, relu=False, residual=No
     pm = B.RTN_PAD_TRUE_ZERO if pad_true_zero else B.RTN_PAD_CODE_ZERO
     # poison the output so that unwritten bytes (padding channels included) show
     OH, OW = B.conv_out_hw(H, W, sh.k, sh.k, sh.stride, sh.pad)
-    out = torch.full((Nb, OH, OW, B.padded_k(sh.O)), 77, dtype=torch.int8, device=DEV)
+    if fmt == B.RTN_CODE_I8:
+        out = torch.full((Nb, OH, OW, B.padded_k(sh.O)), 77, dtype=torch.int8, device=DEV)
+    else:       # 0x77: both nibbles the code point 6.0, never a ternary code
+        out = torch.full((Nb, OH, OW, B.padded_k(sh.O, fmt) // 2), 0x77, dtype=torch.uint8, device=DEV)
     y = torch.full((Nb, sh.O, OH, OW), float("nan"), dtype=torch.float32, device=DEV) if want_y else None
     codes = B.ternary_conv2d_ternarize(ca, cw, Nb, Cc, H, W, sh.O, sh.k, sh.k, sh.stride, sh.pad, ep,
                                        thr_arg(lo), thr_arg(hi), pad_mode=pm, codes_out=out,
                                        residual=None if residual is None else dev(residual),
-                                       relu_out=relu_out, y_out=y)
+                                       relu_out=relu_out, y_out=y, fmt=fmt)
     torch.cuda.synchronize()
     return (codes, y) if want_y else codes
 

@@ -420,6 +420,70 @@ def test_halo_variants_fp4(cfg, hs, tile_reset):
         T.assert_y_close(got["y"].cpu().numpy(), ref["y"], "%s fp4 cfg %d" % (name, cfg))
 
 
+def test_binding_rejects_code_tensors_of_another_format():
+    """The C ABI takes raw pointers; the binding refuses, before any launch, a code tensor whose
+    size or dtype does not fit the format the call names (an FP4 tensor is half the bytes of
+    an int8 one, so the int8 kernels would read past its end)."""
+    _say("binding: code tensor / format mismatch is refused")
+    shape = wl.ConvShape("m", 128, 8, 64, 3, 1, 1)
+    case = wl.conv_case(shape, batch=2, seed=1)
+    x, w = T.dev(case["x"]), T.dev(case["w"])
+    ca4, _ = B.ternarize_pack(x, -0.5, 0.5, FP4)
+    cw4, _ = B.ternarize_pack(w, -0.05, 0.05, FP4)
+    ca8, _ = B.ternarize_pack(x, -0.5, 0.5)
+    cw8, _ = B.ternarize_pack(w, -0.05, 0.05)
+    for a, wt, fmt in [(ca4, cw4, B.RTN_CODE_I8), (ca8, cw4, B.RTN_CODE_I8), (ca8, cw8, FP4), (ca4, cw8, FP4)]:
+        with pytest.raises(ValueError):
+            B.ternary_conv2d(a, wt, 2, 128, 8, 8, 64, 3, 3, 1, 1, want_acc=True, fmt=fmt)
+    g4, _ = B.ternarize_pack(T.dev(case["x"].reshape(2 * 128, 64)), -0.5, 0.5, FP4)
+    with pytest.raises(ValueError):
+        B.ternary_gemm(g4, g4, 256, 256, 64, want_acc=True)
+
+
+@pytest.mark.parametrize("shape", CONV_SHAPES, ids=lambda s: s.name)
+@pytest.mark.parametrize("kind", ["scalar", "vector"])
+def test_conv_ternarize_fp4_vs_oracle(shape, kind):
+    """The ternarizing epilogue and its block-tail form on FP4 codes in, FP4 codes out."""
+    _say("conv+ternarize fp4 %s thresholds=%s" % (shape, kind))
+    true_zero = kind == "scalar"
+    relu = kind == "vector"
+    case = wl.conv_case(shape, batch=3, seed=41 + len(shape.name), per_channel=True, bn=(kind == "scalar"))
+    lo, hi = _thresholds(kind, case, shape.O, 6)
+    ref = T.oracle_conv(case, true_zero, relu=relu)
+    got = T.codes_as_i8(T.hip_conv_ternarize(case, lo, hi, true_zero, relu=relu, fmt=FP4), FP4, shape.O)
+    T.assert_codes_match(got, T.oracle_next_codes(ref, lo, hi), ref["y"], lo, hi, shape.name)
+    rng = np.random.default_rng(8)
+    res = rng.standard_normal(ref["y"].shape).astype(np.float32)
+    codes, y = T.hip_conv_ternarize(case, lo, hi, true_zero, relu=relu, residual=res, relu_out=True, want_y=True,
+                                    fmt=FP4)
+    s = orc.add_relu(ref["y"], res, True)
+    want = orc.nchw_to_nhwc_i8(orc.ternarize_nchw(s, lo, hi), (shape.O + 63) // 64 * 64)
+    T.assert_codes_match(T.codes_as_i8(codes, FP4, shape.O), want, s, lo, hi, shape.name + " tail")
+    tol = 1e-5 * np.abs(ref["y"]) + 1e-9 * max(1.0, float(np.abs(ref["y"]).max())) + 1e-6 * np.abs(res)
+    assert (np.abs(y.cpu().numpy().astype(np.float64) - s) <= tol).all()
+
+
+@pytest.mark.parametrize("cfg", range(20))
+def test_all_tile_configs_conv_ternarize_fp4(cfg, tile_reset):
+    _say("tile config %d, ternarizing epilogues, fp4" % cfg)
+    B.set_tile_config(cfg)
+    for shape, batch in [(wl.ConvShape("t", 64, 13, 200, 3, 2, 1), 7),       # ragged in O and pixels
+                         (wl.ConvShape("u", 64, 16, 64, 3, 1, 1), 3),        # O = 64: half a 128-code row
+                         (wl.ConvShape("v", 192, 12, 136, 3, 1, 1), 3)]:
+        case = wl.conv_case(shape, batch=batch, seed=290 + cfg, bn=True)
+        lo, hi = _thresholds("scalar", case, shape.O, cfg)
+        ref = T.oracle_conv(case, True, relu=True)
+        got = T.codes_as_i8(T.hip_conv_ternarize(case, lo, hi, True, relu=True, fmt=FP4), FP4, shape.O)
+        T.assert_codes_match(got, T.oracle_next_codes(ref, lo, hi), ref["y"], lo, hi, "cfg %d %s" % (cfg, shape.name))
+        res = np.random.default_rng(cfg).standard_normal(ref["y"].shape).astype(np.float32)
+        codes, y = T.hip_conv_ternarize(case, lo, hi, True, relu=True, residual=res, relu_out=True, want_y=True,
+                                        fmt=FP4)
+        s = orc.add_relu(ref["y"], res, True)
+        want = orc.nchw_to_nhwc_i8(orc.ternarize_nchw(s, lo, hi), (shape.O + 63) // 64 * 64)
+        T.assert_codes_match(T.codes_as_i8(codes, FP4, shape.O), want, s, lo, hi, "cfg %d %s tail" % (cfg, shape.name))
+        T.assert_y_close(y.cpu().numpy(), s, "cfg %d %s tail y" % (cfg, shape.name))
+
+
 # ---------------------- conv with the ternarizing epilogue (next layer's codes) ----
 def _thresholds(kind, case, O, seed):
     """scalar: one Delta for the layer; vector: Eq.3's BN-folded pair per channel."""
@@ -970,7 +1034,8 @@ def test_config4_trunk_forward_fully_fused():
     assert xo.shape == (2, 512, 7, 7)
 
 
-def test_config4_full_forward_batch256_sampled_images():
+@pytest.mark.parametrize("fmt", [B.RTN_CODE_FP4, B.RTN_CODE_I8], ids=["fp4", "i8"])
+def test_config4_full_forward_batch256_sampled_images(fmt):
     """The full-network configuration at its stated size: 256 images of 3x224x224, fp32
     stem and classifier (torch, outside the ternary library), the 8 residual blocks of 19
     ternary convs through the C ABI with every hand-over fused (1 pack + 19 convs).  Images
@@ -980,11 +1045,11 @@ def test_config4_full_forward_batch256_sampled_images():
     repository's reading (the paper's figure is not in its text): chain parity is
     unpinned by the paper, the per-layer arithmetic it is made of is pinned."""
     from paper_1912_02057_amd.resnet18 import TernaryResNet18
-    _say("config 4: full forward, batch 256, six sampled images")
+    _say("config 4: full forward, batch 256, six sampled images, code format %d" % fmt)
     prm = wl.resnet18_network_params(seed=4)
     rng = np.random.Generator(np.random.PCG64(44))
     images = rng.standard_normal((256, 3, 224, 224), dtype=np.float32)
-    net = TernaryResNet18(prm, 256, T.DEV)
+    net = TernaryResNet18(prm, 256, T.DEV, fmt)
     x0 = net.stem(T.dev(images))
     assert tuple(x0.shape) == (256, 64, 56, 56)
     keep = []
@@ -1008,7 +1073,10 @@ def test_config4_full_forward_batch256_sampled_images():
     xo = x0[imgs].cpu().numpy()
     ta_o = orc.ternarize(xo, lo, hi)
     for bi, (i1, i2, ids) in enumerate(wl.resnet18_block_topology()):
-        c1, c2, yb = (t[imgs].cpu().numpy() for t in keep[bi])
+        sh1, sh2 = P[i1]["sh"], P[i2]["sh"]
+        c1 = T.codes_as_i8(keep[bi][0][imgs], fmt, sh1.C)
+        c2 = T.codes_as_i8(keep[bi][1][imgs], fmt, sh2.C)
+        yb = keep[bi][2][imgs].cpu().numpy()
         assert (c1 == orc.nchw_to_nhwc_i8(ta_o, c1.shape[-1])).all(), "block %d input codes" % bi
         y1 = oracle_layer(ta_o, P[i1], True)
         ta2 = orc.ternarize_nchw(y1, lo, hi)
@@ -1019,7 +1087,7 @@ def test_config4_full_forward_batch256_sampled_images():
         xo = orc.add_relu(y2, sc, True)
         T.assert_y_close(yb, xo, "block %d output" % bi)
         ta_o = orc.ternarize_nchw(xo, lo, hi)
-    last = net.last_codes[imgs].cpu().numpy()
+    last = T.codes_as_i8(net.last_codes[imgs], fmt, 512)
     T.assert_codes_match(last, orc.nchw_to_nhwc_i8(ta_o, 512), xo, lo, hi, "trunk output codes")
     # the fp32 head on the oracle's trunk output (plain numpy): average pool + FC
     want = xo.astype(np.float64).mean(axis=(2, 3)) @ prm["fc_w"].astype(np.float64).T + prm["fc_b"]
