@@ -25,6 +25,7 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 sys.path.insert(0, ROOT)
 
 INT8_PEAK_TOPS = 5000.0   # MI355X dense int8 MFMA, TOP/s (2 ops per MAC)
+FP4_PEAK_TFLOPS = 10100.0  # MI355X dense FP4 MFMA (the path the FP4 code storage runs on)
 BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
 HBM_PEAK_GBS = 8000.0
 # rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this file's default run (see profiles/)
@@ -39,7 +40,8 @@ def main():
     ap.add_argument("--batch", type=int, default=256)
     ap.add_argument("--workload", default="resnet18_ternary_convs",
                     choices=["resnet18_ternary_convs", "gemm4096", "wgemm4096", "resnet18_weight_only_convs",
-                             "act_backward", "weight_backward", "gemm_sweep"])
+                             "act_backward", "weight_backward", "gemm_sweep", "peaks", "config1",
+                             "resnet18_full_forward"])
     ap.add_argument("--tile", type=int, default=-1, help="force an MFMA tile configuration (tuning)")
     ap.add_argument("--format", default="fp4", choices=["fp4", "i8"],
                     help="storage of the ternary codes on the matrix-core path: FP4 (E2M1) nibbles on the FP4 "
@@ -81,6 +83,195 @@ def main():
     def code_tensor(n, hw, channels):
         return torch.empty((n, hw, hw, code_row_bytes(channels)),
                            dtype=torch.uint8 if FMT == B.RTN_CODE_FP4 else torch.int8, device=dev)
+
+    def timed(fn, reps, warm=2):
+        """Average milliseconds of fn() over reps launches, HIP events on the current stream."""
+        for _ in range(warm):
+            fn()
+        e0, e1 = ev(enable_timing=True), ev(enable_timing=True)
+        e0.record()
+        for _ in range(reps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        return e0.elapsed_time(e1) / reps
+
+    if args.workload == "peaks":
+        # The ceilings a kernel can reach on this machine, measured: register-only loops of the two
+        # matrix-core instructions the contraction uses, and plain streaming kernels.
+        import ctypes as C
+        PL = C.CDLL(os.path.join(ROOT, "paper_1912_02057_amd", "librtn_peaks.so"))
+        PL.rtn_peaks_mfma.restype = C.c_double
+        PL.rtn_peaks_mfma.argtypes = [C.c_int, C.c_int, C.c_int, C.c_void_p, C.c_void_p, C.c_void_p]
+        PL.rtn_peaks_stream.restype = C.c_int
+        PL.rtn_peaks_stream.argtypes = [C.c_int, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+        st = C.c_void_p(torch.cuda.current_stream().cuda_stream)
+        opnd = torch.full((8192,), 0x22, dtype=torch.uint8, device=dev)
+        blocks, iters = 256 * 8, 10000
+        sink = torch.empty(blocks * 256, dtype=torch.float32, device=dev)
+        res = {}
+        for kind, name in ((0, "mfma_i32_32x32x32_i8"), (1, "mfma_f32_32x32x64_fp4")):
+            macs = []
+
+            def go():
+                macs.append(PL.rtn_peaks_mfma(kind, blocks, iters, opnd.data_ptr(), sink.data_ptr(), st))
+            ms = timed(go, 5)
+            assert macs[-1] > 0
+            res[name] = dict(pmacs=round(macs[-1] / ms / 1e12, 3), pops=round(2 * macs[-1] / ms / 1e12, 3),
+                             implied_clock_ghz=round(macs[-1] / ms / 1e6 / (256 * 4 * (1024 if kind == 0 else 2048)), 3))
+        streams = {}
+        for mb in (64, 256, 1024):
+            nbytes = mb << 20
+            a = torch.empty(nbytes, dtype=torch.uint8, device=dev).fill_(1)
+            b = torch.empty(nbytes, dtype=torch.uint8, device=dev)
+            row = {}
+            for kind, name, moved in ((1, "read", 1), (2, "write", 1), (0, "copy", 2)):
+                ms = timed(lambda: PL.rtn_peaks_stream(kind, b.data_ptr(), a.data_ptr(), nbytes, st), 10)
+                row[name + "_gbs"] = round(moved * nbytes / ms / 1e6, 0)
+            streams["%d MiB" % mb] = row
+            del a, b
+        fp4 = res["mfma_f32_32x32x64_fp4"]
+        print(json.dumps({
+            "metric": "achievable ceilings on this machine: register-only matrix-core loops and streaming kernels",
+            "value": round(fp4["pmacs"] * 1e3, 1), "unit": "TMAC/s", "n_gpus": 1, "steps": 5, "warmup": 2,
+            "ms_per_step": None, "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "fp4",
+            "data": "synthetic", "config": {"workload": "peaks: MFMA-only loops (int8, FP4) and stream read/write/copy"},
+            "roofline": {"bound": "mfma", "kernel": "k_mfma_loop<fp4> (no memory traffic)", "achieved": round(2 * fp4["pmacs"] * 1e3, 1),
+                         "peak": FP4_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": round(2 * fp4["pmacs"] * 1e3 / FP4_PEAK_TFLOPS, 4),
+                         "traffic": None},
+            "cpu_baseline": None, "mfma": res, "stream": streams}))
+        return
+
+    if args.workload == "config1":
+        # the single-layer configuration: 3x3, stride 1, pad 1, batch 1, 64 -> 64 channels at 56x56.
+        # 0.116 GMAC and 1.8 MB: two dependent launches, bound by launch and memory latency, so the
+        # figure that matters is the latency in microseconds.
+        case = wl.config1_case()
+        sh = case["shape"]
+        x, w = to_dev(case["x"]), to_dev(case["w"])
+        dw, da = float(case["delta_w"]), float(case["delta_a"])
+        cw, pw = B.ternarize_pack(w, -dw, dw, FMT)
+        ca = code_tensor(1, sh.H, sh.C)
+        pa = torch.empty((1, sh.H, sh.H), dtype=torch.int32, device=dev)
+        y = torch.empty((1, sh.O, sh.OH, sh.OH), dtype=torch.float32, device=dev)
+        ep = B.Epilogue(garg(case["alpha_a"]), garg(case["beta_a"]), garg(case["alpha_w"]), garg(case["beta_w"]), pa, pw)
+        ws = B.conv2d_prepare_constants(sh.C, sh.O, sh.k, sh.k, sh.pad, ep)
+
+        def one():
+            B.ternarize_pack(x, -da, da, FMT, codes=ca, sum_t=pa)
+            B.ternary_conv2d(ca, cw, 1, sh.C, sh.H, sh.H, sh.O, sh.k, sh.k, sh.stride, sh.pad, ep=ep, y_out=y,
+                             workspace=ws, fmt=FMT)
+        ms = timed(one, max(args.steps, 50), warm=max(args.warmup, 5))
+        ms_conv = timed(lambda: B.ternary_conv2d(ca, cw, 1, sh.C, sh.H, sh.H, sh.O, sh.k, sh.k, sh.stride, sh.pad, ep=ep,
+                                                 y_out=y, workspace=ws, fmt=FMT), 50, warm=5)
+        # with the operands evicted between calls: a 512 MiB fill in between, its own time taken off
+        junk = torch.empty(512 << 20, dtype=torch.uint8, device=dev)
+        ms_fill = timed(lambda: junk.fill_(3), 10)
+        ms_cold = timed(lambda: (junk.fill_(3), one()), 10) - ms_fill
+        macs = sh.macs(1)
+        cpu = None
+        if not args.no_cpu_baseline:
+            from oracle import rtn_oracle as orc
+            c0 = time.perf_counter()
+            for _ in range(20):
+                ta = orc.ternarize(case["x"], -case["delta_a"], case["delta_a"])
+                tw = orc.ternarize(case["w"], -case["delta_w"], case["delta_w"])
+                D = orc.conv_acc(ta, tw, sh.stride, sh.pad)
+                Sa, Sw, Kv = orc.conv_sums(ta, tw, sh.stride, sh.pad, True)
+                orc.conv_epilogue(D, Sa, Sw, Kv, case["alpha_a"], case["beta_a"], case["alpha_w"], case["beta_w"])
+            t_cpu = (time.perf_counter() - c0) / 20
+            cpu = dict(value=round(macs / t_cpu / 1e12, 6), unit="TMAC/s", cores=orc.num_threads(), kind="oracle",
+                       sample="the whole configuration, 20 repetitions", seconds=round(20 * t_cpu, 2))
+        print(json.dumps({
+            "metric": "effective ternary MAC/s, single 3x3 conv at batch 1 (pack + conv); latency-bound: see latency_us",
+            "value": round(macs / (ms * 1e-3) / 1e12, 3), "unit": "TMAC/s", "n_gpus": 1, "steps": max(args.steps, 50),
+            "warmup": max(args.warmup, 5), "ms_per_step": round(ms, 5), "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": args.format, "data": "synthetic",
+            "config": {"workload": "config 1: 3x3 s1 p1, batch 1, 64->64 @ 56x56, per-layer scalars", "format": args.format},
+            "latency_us": {"pack_plus_conv": round(ms * 1e3, 2), "conv_only": round(ms_conv * 1e3, 2),
+                           "pack_plus_conv_operands_evicted": round(ms_cold * 1e3, 2),
+                           "note": "two dependent launches of a few microseconds each; bound by launch and memory "
+                                   "latency, not by a roofline"},
+            "roofline": {"bound": "hbm", "kernel": "k_tmm conv (latency-bound at this size)",
+                         "achieved": round((sh.C * sh.H * sh.H * 5 + sh.O * sh.OH * sh.OH * 4) / (ms * 1e-3) / 1e9, 1),
+                         "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                         "frac": round((sh.C * sh.H * sh.H * 5 + sh.O * sh.OH * sh.OH * 4) / (ms * 1e-3) / 1e9 / HBM_PEAK_GBS, 5),
+                         "traffic": None},
+            "cpu_baseline": cpu}))
+        return
+
+    if args.workload == "resnet18_full_forward":
+        # the full-network configuration: fp32 stem and head in torch (timed, reported, excluded from the
+        # ternary figure), the 8 ternary blocks through the library with every hand-over fused
+        from paper_1912_02057_amd.resnet18 import TernaryResNet18
+        prm = wl.resnet18_network_params(seed=4)
+        rng = np.random.Generator(np.random.PCG64(44))
+        images = to_dev(rng.standard_normal((args.batch, 3, 224, 224), dtype=np.float32))
+        net = TernaryResNet18(prm, args.batch, dev, FMT)
+        x0 = net.stem(images)
+        out = net.trunk(x0)
+        ms_stem = timed(lambda: net.stem(images), 5)
+        ms_head = timed(lambda: net.head(out), 5)
+        import gc
+        gc.collect()
+        gc.disable()
+        for _ in range(args.warmup):
+            net.trunk(x0)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        for _ in range(args.steps):
+            net.trunk(x0)
+        torch.cuda.synchronize()
+        ms_trunk = (time.perf_counter() - t0) * 1e3 / args.steps
+        gc.enable()
+        macs, nbytes = net.trunk_macs(), net.trunk_bytes()
+        cpu = None
+        if not args.no_cpu_baseline:
+            from oracle import rtn_oracle as orc
+            n_img = max(1, args.cpu_images // 16)
+            xs = x0[:n_img].cpu().numpy()
+            lo, hi = -prm["delta_a"], prm["delta_a"]
+            P = prm["layers"]
+
+            def olayer(ta, p, relu):
+                s_ = p["sh"]
+                tw = orc.ternarize(p["w"], -np.asarray(p["dw"]), p["dw"])
+                D = orc.conv_acc(ta, tw, s_.stride, s_.pad)
+                Sa, Sw, Kv = orc.conv_sums(ta, tw, s_.stride, s_.pad, True)
+                return orc.conv_epilogue(D, Sa, Sw, Kv, p["aa"], p["ba"], p["aw"], p["bw"], relu=relu,
+                                         bn_scale=p["bs"], bn_shift=p["bh"])
+            c0 = time.perf_counter()
+            xo, ta = xs, orc.ternarize(xs, lo, hi)
+            for i1, i2, ids in wl.resnet18_block_topology():
+                y1 = olayer(ta, P[i1], True)
+                y2 = olayer(orc.ternarize_nchw(y1, lo, hi), P[i2], False)
+                sc = xo if ids is None else olayer(ta, P[ids], False)
+                xo = orc.add_relu(y2, sc, True)
+                ta = orc.ternarize_nchw(xo, lo, hi)
+            t_cpu = time.perf_counter() - c0
+            cpu = dict(value=round(macs / args.batch * n_img / t_cpu / 1e12, 6), unit="TMAC/s", cores=orc.num_threads(),
+                       kind="oracle", sample="the chained trunk on %d images (of %d)" % (n_img, args.batch),
+                       seconds=round(t_cpu, 2))
+        gbs = nbytes / (ms_trunk * 1e-3) / 1e9
+        print(json.dumps({
+            "metric": "effective ternary MAC/s, ResNet-18 forward: the 19 ternary convs as 8 fused residual blocks "
+                      "(fp32 stem and head timed separately and not counted)",
+            "value": round(macs / (ms_trunk * 1e-3) / 1e12, 3), "unit": "TMAC/s", "n_gpus": 1, "steps": args.steps,
+            "warmup": args.warmup, "ms_per_step": round(ms_trunk, 4), "higher_is_better": True, "scaling": "weak",
+            "vs_baseline": None, "dtype": args.format, "data": "synthetic",
+            "config": {"workload": "full ResNet-18 forward, batch %d, 224x224x3, ternary trunk: 1 pack + 19 convs" % args.batch,
+                       "batch": args.batch, "format": args.format},
+            "fp32_parts_ms": {"stem_conv7x7_bn_relu_maxpool": round(ms_stem, 4), "avgpool_fc": round(ms_head, 4),
+                              "note": "torch fp32 ops, outside the ternary library"},
+            "images_per_s_trunk": round(args.batch / (ms_trunk * 1e-3), 0),
+            "roofline": {"bound": "hbm", "kernel": "the trunk's 20 launches as a whole (k_pack + 19 k_tmm)",
+                         "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(gbs / HBM_PEAK_GBS, 4),
+                         "traffic": None, "bytes_per_step": nbytes,
+                         "mfma_tops": round(2 * macs / (ms_trunk * 1e-3) / 1e12, 1),
+                         "mfma_frac_of_int8_peak": round(2 * macs / (ms_trunk * 1e-3) / 1e12 / INT8_PEAK_TOPS, 4)},
+            "cpu_baseline": cpu}))
+        return
+
     if args.workload == "gemm_sweep":
         # M x N x K sweep of the ternary GEMM over sparsity, on both contraction paths: codes resident,
         # one timed call = contraction + fused epilogue (the pack of the activations is timed beside it)
@@ -91,13 +282,14 @@ def main():
                 for p0 in (0.2, 0.5, 0.8):
                     case = wl.gemm_case(M, NK, NK, p_zero=p0, seed=int(1000 * p0) + 3)
                     xa, xw = to_dev(case["xa"]), to_dev(case["xw"])
-                    for fmt, name in ((B.RTN_CODE_I8, "mfma_i8"), (B.RTN_CODE_BITPLANE, "popcount")):
+                    for fmt, name in ((B.RTN_CODE_FP4, "mfma_fp4"), (B.RTN_CODE_I8, "mfma_i8"),
+                                      (B.RTN_CODE_BITPLANE, "popcount")):
                         ca, sa = B.ternarize_pack(xa, -0.5, 0.5, fmt)
                         cw, sw = B.ternarize_pack(xw, -0.5, 0.5, fmt)
                         ep = B.Epilogue(garg(case["alpha_a"]), garg(case["beta_a"]), garg(case["alpha_w"]),
                                         garg(case["beta_w"]), sa, sw)
                         y = torch.empty((M, NK), dtype=torch.float32, device=dev)
-                        reps = 5 if name == "mfma_i8" else 2
+                        reps = 2 if name == "popcount" else 5
                         for _ in range(2):
                             B.ternary_gemm(ca, cw, M, NK, NK, fmt=fmt, ep=ep, y_out=y)
                         e0, e1, e2 = ev(enable_timing=True), ev(enable_timing=True), ev(enable_timing=True)
@@ -111,27 +303,53 @@ def main():
                         torch.cuda.synchronize()
                         us, pus = e0.elapsed_time(e1) * 1e3 / reps, e1.elapsed_time(e2) * 1e3 / reps
                         macs = float(M) * NK * NK
-                        rows.append(dict(M=M, N=NK, K=NK, p_zero=p0, path=name, gemm_us=round(us, 1),
-                                         pack_us=round(pus, 1), tmacs=round(macs / us / 1e6, 1),
-                                         pct_int8_mfma_peak=round(100 * 2 * macs / us / 1e6 / INT8_PEAK_TOPS, 1)))
-                        if name == "mfma_i8":
+                        row = dict(M=M, N=NK, K=NK, p_zero=p0, path=name, gemm_us=round(us, 1),
+                                   pack_us=round(pus, 1), tmacs=round(macs / us / 1e6, 1),
+                                   pct_int8_mfma_peak=round(100 * 2 * macs / us / 1e6 / INT8_PEAK_TOPS, 1))
+                        if name == "mfma_fp4":
+                            row["pct_fp4_mfma_peak"] = round(100 * 2 * macs / us / 1e6 / FP4_PEAK_TFLOPS, 1)
+                        if name == "popcount":
+                            # its own roof is the vector ALU: 5 64-bit operations (3 logic, 2 popcount-accumulate)
+                            # per 64 MACs per lane, 64 lanes per clock per CU, 256 CUs at 2.4 GHz,
+                            # a 64-bit operation being two 32-bit issue slots
+                            valu_bound = 256 * 64 * 2.4e9 * 64 / (5 * 2) / 1e12
+                            row["valu_bound_tmacs"] = round(valu_bound, 1)
+                            row["frac_of_valu_bound"] = round(macs / us / 1e6 / valu_bound, 3)
+                        rows.append(row)
+                        if name == "mfma_fp4":
                             tot_macs += macs
                             tot_s += (us + pus) * 1e-6
                         del ca, cw, sa, sw, y, ep
                     del xa, xw, case
-        mf = [r for r in rows if r["path"] == "mfma_i8"]
+        mf = [r for r in rows if r["path"] == "mfma_fp4"]
         best = max(mf, key=lambda r: r["tmacs"])
+        cpu = None
+        if not args.no_cpu_baseline:
+            from oracle import rtn_oracle as orc
+            case = wl.gemm_case(8192, 4096, 4096, p_zero=0.5, seed=503)
+            rws = np.arange(0, 8192, 8192 // 256, dtype=np.int64)
+            c0 = time.perf_counter()
+            ta = orc.ternarize(case["xa"][rws], -0.5, 0.5)
+            tw = orc.ternarize(case["xw"], -0.5, 0.5)
+            D = orc.gemm_acc_rows(ta, tw, np.arange(rws.size, dtype=np.int64))
+            orc.gemm_epilogue(D, 4096, orc.row_sums(ta), orc.row_sums(tw), case["alpha_a"][rws], case["beta_a"][rws],
+                              case["alpha_w"], case["beta_w"])
+            t_cpu = time.perf_counter() - c0
+            cpu = dict(value=round(rws.size * 4096 * 4096 / t_cpu / 1e12, 6), unit="TMAC/s", cores=orc.num_threads(),
+                       kind="oracle", sample="256 of 8192 rows of the 8192 x 4096 x 4096 point, all columns",
+                       seconds=round(t_cpu, 2))
         print(json.dumps({
-            "metric": "effective ternary MAC/s, ternary GEMM sweep (pack + contraction + epilogue, matrix-core path)",
+            "metric": "effective ternary MAC/s, ternary GEMM sweep (pack + contraction + epilogue, FP4 matrix-core path)",
             "value": round(tot_macs / tot_s / 1e12, 3), "unit": "TMAC/s", "n_gpus": 1, "steps": 5, "warmup": 2,
             "ms_per_step": round(tot_s * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-            "dtype": "i8", "data": "synthetic",
+            "dtype": "fp4", "data": "synthetic",
             "config": {"workload": "ternary GEMM sweep: M in {8192,16384} x N=K in {4096,8192} x P(0) in {0.2,0.5,0.8}, "
-                                   "int8 matrix-core and bit-plane popcount paths"},
-            "roofline": {"bound": "mfma", "kernel": "k_tmm (int8 MFMA GEMM + fused epilogue), best point",
-                         "achieved": round(2 * best["tmacs"], 1), "peak": INT8_PEAK_TOPS, "unit": "TOP/s",
-                         "frac": round(2 * best["tmacs"] / INT8_PEAK_TOPS, 4), "traffic": None},
-            "cpu_baseline": None, "sweep": rows}))
+                                   "FP4 and int8 matrix-core paths and the bit-plane popcount path"},
+            "roofline": {"bound": "mfma", "kernel": "k_tmm (FP4 MFMA GEMM + fused epilogue), best point",
+                         "achieved": round(2 * best["tmacs"], 1), "peak": FP4_PEAK_TFLOPS, "unit": "TFLOP/s",
+                         "frac": round(2 * best["tmacs"] / FP4_PEAK_TFLOPS, 4),
+                         "frac_of_int8_peak": round(2 * best["tmacs"] / INT8_PEAK_TOPS, 4), "traffic": None},
+            "cpu_baseline": cpu, "sweep": rows}))
         return
     if args.workload == "resnet18_ternary_convs":
         shapes = wl.resnet18_ternary_layers()
@@ -241,7 +459,8 @@ def main():
                     timers[i][2].record()
 
         macs_step = sum(l["sh"].macs(args.batch) for l in layers)
-        workload = "ResNet-18 ternary conv stack (19 layers), batch %d, fp32 NCHW in/out" % args.batch
+        workload = "ResNet-18 ternary conv stack (19 layers), batch %d, fp32 NCHW in/out, %s codes" % (args.batch,
+                                                                                                     args.format)
         nlaunch = len(layers)
     elif args.workload == "act_backward":
         # backward of the reparameterized ternary activation over the largest activation tensor of
@@ -354,8 +573,9 @@ def main():
     else:
         case = wl.gemm_case(4096, 4096, 4096, 0.4, seed=1)
         xa, xw = to_dev(case["xa"]), to_dev(case["xw"])
-        cw, sw = B.ternarize_pack(xw, -0.5, 0.5)                             # S0, offline
-        ca = torch.empty((4096, 4096), dtype=torch.int8, device=dev)
+        cw, sw = B.ternarize_pack(xw, -0.5, 0.5, FMT)                        # S0, offline
+        ca = torch.empty((4096, code_row_bytes(4096)), dtype=torch.uint8 if FMT == B.RTN_CODE_FP4 else torch.int8,
+                         device=dev)
         sa = torch.empty(4096, dtype=torch.int32, device=dev)
         y = torch.empty((4096, 4096), dtype=torch.float32, device=dev)
         ep = B.Epilogue(garg(case["alpha_a"]), garg(case["beta_a"]), garg(case["alpha_w"]),
@@ -369,17 +589,17 @@ def main():
             if timers is not None:
                 timers[0][0].record()
             rc = L.rtn_ternarize_pack(xa.data_ptr(), B.RTN_ROWS_K_CONTIG, 4096, 4096, 1, 1, C.addressof(lo),
-                                      C.addressof(hi), B.RTN_SCALAR, B.RTN_CODE_I8, ca.data_ptr(),
+                                      C.addressof(hi), B.RTN_SCALAR, FMT, ca.data_ptr(),
                                       sa.data_ptr(), stream)
             assert rc == 0
             if timers is not None:
                 timers[0][1].record()
-            B.ternary_gemm(ca, cw, 4096, 4096, 4096, ep=ep, y_out=y)
+            B.ternary_gemm(ca, cw, 4096, 4096, 4096, fmt=FMT, ep=ep, y_out=y)
             if timers is not None:
                 timers[0][2].record()
 
         macs_step = 4096 ** 3
-        workload = "ternary GEMM M=N=K=4096, P(0)=0.4, fp32 in/out"
+        workload = "ternary GEMM M=N=K=4096, P(0)=0.4, fp32 in/out, %s codes" % args.format
         nlaunch = 1
         layers = [dict(sh=None)]
 
@@ -418,6 +638,18 @@ def main():
             trunk_forward()
         torch.cuda.synchronize()
         ms_trunk = (time.perf_counter() - tb0) * 1e3 / args.steps
+        # algorithmic bytes of the chained pass: the fp32 trunk input once, every code tensor written and read
+        # once (twice where the shortcut conv reads it too), filters, fp32 shortcut and block tensors
+        nb_ = args.batch
+        tr_bytes = nb_ * 56 * 56 * (64 * 4 + code_row_bytes(64))
+        for i1, i2, ids in blocks:
+            for i_, kind in ((i1, "c1"), (ids, "ds"), (i2, "c2")):
+                if i_ is None:
+                    continue
+                s_ = layers[i_]["sh"]
+                cin = nb_ * s_.H * s_.H * code_row_bytes(s_.C) + s_.O * s_.k * s_.k * code_row_bytes(s_.C)
+                outs, cout = nb_ * s_.O * s_.OH * s_.OH, nb_ * s_.OH * s_.OH * code_row_bytes(s_.O)
+                tr_bytes += cin + (cout if kind == "c1" else outs * 4 if kind == "ds" else outs * 8 + cout)
         blocks_info = {
             "what": "the same 19 convs as 8 residual blocks: conv1 of a block emits the next conv's codes "
                     "(rtn_ternary_conv2d_ternarize), one pack per block input; 8 packs + 19 convs per step",
@@ -428,7 +660,13 @@ def main():
                         "epilogue adds the shortcut, applies ReLU and writes the fp32 block output and the next "
                         "block's codes; 1 pack + 19 convs per step, residual adds included",
                 "ms_per_step": round(ms_trunk, 4),
-                "tmacs": round(macs_step / (ms_trunk * 1e-3) / 1e12, 3)}}
+                "tmacs": round(macs_step / (ms_trunk * 1e-3) / 1e12, 3),
+                "roofline": {"bound": "hbm", "achieved": round(tr_bytes / (ms_trunk * 1e-3) / 1e9, 1),
+                             "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                             "frac": round(tr_bytes / (ms_trunk * 1e-3) / 1e9 / HBM_PEAK_GBS, 4),
+                             "bytes_per_step": tr_bytes,
+                             "mfma_frac_of_int8_peak": round(2 * macs_step / (ms_trunk * 1e-3) / 1e12 / INT8_PEAK_TOPS,
+                                                             4)}}}
 
     # ---- per-kernel durations with HIP events on the launch stream ---------
     reps = max(3, min(args.steps, 10))
@@ -494,7 +732,7 @@ def main():
             # summarised in profiles/k_tmm_conv_resnet18_b256.md (2 * FETCH_SIZE + WRITE_SIZE,
             # in KiB per dispatch, averaged over the 19 launches of a step)
             traffic = MEASURED_TRAFFIC_BYTES_PER_LAUNCH
-        roofline = dict(bound="hbm", kernel="k_tmm (int8 MFMA implicit-GEMM conv + fused epilogue)",
+        roofline = dict(bound="hbm", kernel="k_tmm (%s MFMA implicit-GEMM conv + fused epilogue)" % args.format,
                         achieved=round(achieved_gbs, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                         frac=round(achieved_gbs / HBM_PEAK_GBS, 4), traffic=traffic,
                         launches_per_step=nlaunch, avg_launch_us=round(conv_total_s / nlaunch * 1e6, 1),
@@ -531,9 +769,14 @@ def main():
                         flops_per_launch=6 * macs_step / nlaunch,
                         effective_fp32_tflops=round(achieved_tops, 1), fp32_vector_peak_tflops=157.3)
     else:
-        roofline = dict(bound="mfma", kernel="k_tmm (int8 MFMA GEMM + fused epilogue)",
-                        achieved=round(achieved_tops, 1), peak=INT8_PEAK_TOPS, unit="TOP/s",
-                        frac=round(achieved_tops / INT8_PEAK_TOPS, 4), traffic=None,
+        # a contraction is priced against the peak of its own operand type: the FP4 matrix path
+        # against 10.1 PFLOP/s, the int8 path against 5.0 POP/s; the fraction of the int8 peak (the
+        # stated target's yardstick) is given beside it either way
+        peak = FP4_PEAK_TFLOPS if FMT == B.RTN_CODE_FP4 else INT8_PEAK_TOPS
+        roofline = dict(bound="mfma", kernel="k_tmm (%s MFMA GEMM + fused epilogue)" % args.format,
+                        achieved=round(achieved_tops, 1), peak=peak, unit="TFLOP/s" if FMT == B.RTN_CODE_FP4 else "TOP/s",
+                        frac=round(achieved_tops / peak, 4), traffic=None,
+                        frac_of_int8_peak=round(achieved_tops / INT8_PEAK_TOPS, 4),
                         launches_per_step=nlaunch, avg_launch_us=round(conv_total_s / nlaunch * 1e6, 1),
                         ops_per_launch=2 * macs_step / nlaunch)
 
@@ -618,8 +861,8 @@ def main():
         "value": round(value, 3), "unit": "TMAC/s", "n_gpus": 1, "steps": args.steps, "warmup": args.warmup,
         "ms_per_step": round(ms_per_step, 4), "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": "bf16x3" if args.workload in ("wgemm4096", "resnet18_weight_only_convs") else
-        ("f32" if args.workload in ("act_backward", "weight_backward") else "i8"), "data": "synthetic",
-        "config": {"workload": workload, "batch": args.batch, "tile": args.tile},
+        ("f32" if args.workload in ("act_backward", "weight_backward") else args.format), "data": "synthetic",
+        "config": {"workload": workload, "batch": args.batch, "tile": args.tile, "format": args.format},
         "tops": round(2 * value, 1), "pct_int8_mfma_peak": round(100 * 2 * value / INT8_PEAK_TOPS, 2),
         "contraction_only": {"tmacs": round(macs_step / conv_total_s / 1e12, 3),
                              "pct_int8_mfma_peak": round(100 * achieved_tops / INT8_PEAK_TOPS, 2),

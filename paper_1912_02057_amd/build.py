@@ -9,6 +9,7 @@ from concurrent.futures import ThreadPoolExecutor
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librtn.so")
+PEAKS_LIB = os.path.join(HERE, "librtn_peaks.so")     # measurement aids for bench.py, not the product
 SOURCES = ["rtn_api.hip", "ternarize_pack.hip", "tgemm_popc.hip", "tmm_mfma.hip", "tmm_inst_gemm.hip",
            "tmm_inst_conv.hip", "tmm_inst_tern1.hip", "tmm_inst_tern2.hip", "tmm_inst_bf16.hip",
            "tmm_inst_gemm_fp4.hip", "tmm_inst_conv_fp4.hip", "tmm_inst_tern1_fp4.hip", "tmm_inst_tern2_fp4.hip"]
@@ -43,6 +44,9 @@ def build_lib(verbose=False, extra=(), jobs=None):
         tmp = LIB + ".tmp.%d" % os.getpid()
         _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC"] + objs + ["-o", tmp], verbose)
     os.replace(tmp, LIB)
+    tmp = PEAKS_LIB + ".tmp.%d" % os.getpid()
+    _run([hipcc] + FLAGS + ["-shared", os.path.join(CSRC, "peaks.hip"), "-o", tmp], verbose)
+    os.replace(tmp, PEAKS_LIB)
     return LIB
 
 

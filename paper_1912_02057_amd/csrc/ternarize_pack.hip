@@ -79,8 +79,12 @@ __global__ __launch_bounds__(256) void k_pack_rows_i8(PackArgs a)
 }
 
 // ---- rows layout, FP4 codes ------------------------------------------------
-// As above with two codes per byte: a lane handles 8 consecutive elements per step and
-// writes one dword, so a wave reads 2 KiB and writes 256 B per step.  Kpad % 128 == 0.
+// As above with two codes per byte.  A step covers 512 elements: every lane loads
+// elements 4l .. 4l+3 of the first and of the second 256 (two fully coalesced 1 KiB
+// reads per wave) and packs each quad into 16 bits.  A dword of output is 8 consecutive
+// elements, i.e. the quads of lanes 2j and 2j+1: the even lane assembles the dword of
+// the first half, the odd lane that of the second half, after one exchange with its
+// neighbour, so every lane stores one dword per step.  Kpad % 128 == 0.
 template <bool VEC4>
 __global__ __launch_bounds__(256) void k_pack_rows_fp4(PackArgs a)
 {
@@ -90,34 +94,32 @@ __global__ __launch_bounds__(256) void k_pack_rows_fp4(PackArgs a)
     const float lo = thr(a.lo, row), hi = thr(a.hi, row);
     const float* xr = a.x + row * a.K;
     uint8_t* cr = (uint8_t*)a.codes + row * (a.Kpad >> 1);
+    const bool odd = lane & 1;
     int sum = 0;
     for (int64_t k0 = 0; k0 < a.Kpad; k0 += 512) {
-        const int64_t k = k0 + 8 * lane;
-        if (k >= a.Kpad) break;
-        float v[8];
-        bool ok[8];
-        if (VEC4) {  // K % 4 == 0: each quad is wholly in or out of range
-            const bool q0 = k < a.K, q1 = k + 4 < a.K;
-            const float4 z = make_float4(0.f, 0.f, 0.f, 0.f);
-            const float4 u0 = q0 ? *(const float4*)(xr + k) : z, u1 = q1 ? *(const float4*)(xr + k + 4) : z;
-            v[0] = u0.x, v[1] = u0.y, v[2] = u0.z, v[3] = u0.w, v[4] = u1.x, v[5] = u1.y, v[6] = u1.z, v[7] = u1.w;
+        uint32_t h[2];
 #pragma unroll
-            for (int e = 0; e < 8; ++e) ok[e] = e < 4 ? q0 : q1;
-        } else {
+        for (int part = 0; part < 2; ++part) {
+            const int64_t k = k0 + 256 * part + 4 * lane;
+            int t[4] = {0, 0, 0, 0};
+            if (VEC4) {
+                if (k < a.K) {  // K % 4 == 0: the whole quad is in range
+                    const float4 v = *(const float4*)(xr + k);
+                    t[0] = tern(v.x, lo, hi), t[1] = tern(v.y, lo, hi), t[2] = tern(v.z, lo, hi), t[3] = tern(v.w, lo, hi);
+                }
+            } else {
 #pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                ok[e] = k + e < a.K;
-                v[e] = ok[e] ? xr[k + e] : 0.0f;
+                for (int e = 0; e < 4; ++e)
+                    if (k + e < a.K) t[e] = tern(xr[k + e], lo, hi);
             }
+            sum += t[0] + t[1] + t[2] + t[3];
+            h[part] = nib(t[0]) | (nib(t[1]) << 4) | (nib(t[2]) << 8) | (nib(t[3]) << 12);
         }
-        uint32_t packed = 0;
-#pragma unroll
-        for (int e = 0; e < 8; ++e) {
-            const int t = ok[e] ? tern(v[e], lo, hi) : 0;
-            sum += t;
-            packed |= nib(t) << (4 * e);
-        }
-        *(uint32_t*)(cr + (k >> 1)) = packed;
+        // even lane: needs the neighbour's first-half quad; odd lane: the neighbour's second-half quad
+        const uint32_t recv = (uint32_t)__shfl_xor((int)(odd ? h[0] : h[1]), 1, 64);
+        const uint32_t word = odd ? (recv | (h[1] << 16)) : (h[0] | (recv << 16));
+        const int64_t kw = k0 + (odd ? 256 + 4 * (lane - 1) : 4 * lane);  // first element of the dword
+        if (kw < a.Kpad) *(uint32_t*)(cr + (kw >> 1)) = word;
     }
     if (a.sum_t) {
         sum = wave_sum(sum);
