@@ -617,6 +617,89 @@ int orc_gemm_acc_rows(const int8_t *ta, const int8_t *tw, const int64_t *rows, i
     return bad ? -1 : 0;
 }
 
+/* ----------------------------------------------------------------- O12 --
+ * The comparison system of Section "How to Compute Dot Product between Two Ternary
+ * Vectors" (second half) and Fig.3(b): 2-bit quaternary weights and activations,
+ * value = 2*(1st bit) + (2nd bit) in {0,1,2,3} (Table 1's "2-bit network true
+ * value" column), multiplied in the bit-serial pattern of DoReFa-Net: AND between
+ * each bit of the one input and each bit of the other, a count of ones per pair of
+ * bit planes, a left shift by the two bit weights, and the four partial results
+ * added:   sum_k qw[k]*qa[k] = sum_{i,j in {0,1}} 2^(i+j) * bC(W_i AND A_j),
+ * W_1 / A_1 the planes of the first (more significant) bits, W_0 / A_0 of the second.
+ * The quantizer is not the paper's subject; the plain form used here is three
+ * strict thresholds on the stored value, q = (x > t1) + (x > t2) + (x > t3).      */
+void orc_quantize4(const float *x, int64_t n, float t1, float t2, float t3, int8_t *q)
+{
+    for (int64_t i = 0; i < n; ++i) q[i] = (int8_t)((x[i] > t1) + (x[i] > t2) + (x[i] > t3));
+}
+
+/* the definition: a plain sum of products */
+int orc_qgemm_acc(const int8_t *qa, const int8_t *qw, int64_t M, int64_t N, int64_t K, int32_t *D)
+{
+    int bad = 0;
+#pragma omp parallel for
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            int64_t acc = 0;
+            for (int64_t k = 0; k < K; ++k) acc += (int64_t)qa[m * K + k] * (int64_t)qw[n * K + k];
+            if (acc < 0 || acc > 9 * K) bad = 1;
+            D[m * N + n] = (int32_t)acc;
+        }
+    return bad;
+}
+
+/* bit planes of quaternary values: hi = plane of first bits (weight 2), lo = plane of second
+ * bits (weight 1); bit j of word w of a row is element 64*w + j, as for the ternary planes */
+void orc_encode_qplanes(const int8_t *q, int64_t rows, int64_t K, int64_t words, uint64_t *hi, uint64_t *lo)
+{
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t w = 0; w < words; ++w) {
+            uint64_t h = 0, l = 0;
+            for (int j = 0; j < 64; ++j) {
+                int64_t k = 64 * w + j;
+                int v = k < K ? q[r * K + k] : 0;
+                h |= (uint64_t)((v >> 1) & 1) << j;
+                l |= (uint64_t)(v & 1) << j;
+            }
+            hi[r * words + w] = h;
+            lo[r * words + w] = l;
+        }
+}
+
+/* the circuit of Fig.3(b): four AND / count pairs, shifts, four adders */
+void orc_qgemm_bitserial(const uint64_t *ah, const uint64_t *al, const uint64_t *wh, const uint64_t *wl,
+                         int64_t M, int64_t N, int64_t words, int32_t *D)
+{
+    for (int64_t m = 0; m < M; ++m)
+        for (int64_t n = 0; n < N; ++n) {
+            int64_t c11 = 0, c10 = 0, c01 = 0, c00 = 0;
+            for (int64_t w = 0; w < words; ++w) {
+                c11 += __builtin_popcountll(wh[n * words + w] & ah[m * words + w]);
+                c10 += __builtin_popcountll(wh[n * words + w] & al[m * words + w]);
+                c01 += __builtin_popcountll(wl[n * words + w] & ah[m * words + w]);
+                c00 += __builtin_popcountll(wl[n * words + w] & al[m * words + w]);
+            }
+            D[m * N + n] = (int32_t)((c11 << 2) + (c10 << 1) + (c01 << 1) + c00);
+        }
+}
+
+/* FP4 nibbles that hold small integers (0..3 are code points of E2M1 too): decoded values,
+ * and the number of nibbles whose value is not an integer in [-6, 6] */
+int64_t orc_decode_fp4_int(const uint8_t *codes, int64_t rows, int64_t K, int64_t Kpad, int8_t *v)
+{
+    int64_t bad = 0;
+    for (int64_t r = 0; r < rows; ++r)
+        for (int64_t k = 0; k < K; ++k) {
+            double x = orc_e2m1_value((codes[r * (Kpad / 2) + k / 2] >> (4 * (k & 1))) & 15);
+            if (x != floor(x)) {
+                ++bad;
+                x = 0;
+            }
+            v[r * K + k] = (int8_t)x;
+        }
+    return bad;
+}
+
 int orc_num_threads(void)
 {
     int n = 1;

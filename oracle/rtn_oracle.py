@@ -409,3 +409,54 @@ def weight_backward(w, g, lo, hi, kw, bw, alpha, want_dw=True):
     lib().orc_weight_backward(_p(w), _p(g), _i64(O), _i64(K), _f32(float(lo)), _f32(float(hi)), _p(kw), _p(bw),
                               _p(alpha), _p(dw), _p(sums))
     return dw, sums
+
+
+def quantize4(x, t1, t2, t3):
+    """O12: q = (x > t1) + (x > t2) + (x > t3), int8 in {0,1,2,3}, same shape."""
+    x = _c(x, np.float32)
+    q = np.empty(x.shape, dtype=np.int8)
+    lib().orc_quantize4(_p(x), _i64(x.size), _f32(float(t1)), _f32(float(t2)), _f32(float(t3)), _p(q))
+    return q
+
+
+def qgemm_acc(qa, qw):
+    """O12: D[m][n] = sum_k qa[m][k] * qw[n][k] for quaternary codes."""
+    qa, qw = _c(qa, np.int8), _c(qw, np.int8)
+    M, K = qa.shape
+    N = qw.shape[0]
+    D = np.empty((M, N), dtype=np.int32)
+    lib().orc_qgemm_acc.restype = C.c_int
+    assert lib().orc_qgemm_acc(_p(qa), _p(qw), _i64(M), _i64(N), _i64(K), _p(D)) == 0
+    return D
+
+
+def encode_qplanes(q, words=None):
+    """O12: int8 [rows, K] in {0..3} -> (hi, lo) uint64 [rows, words]."""
+    q = _c(q, np.int8)
+    rows, K = q.shape
+    words = (K + 63) // 64 if words is None else words
+    hi = np.empty((rows, words), dtype=np.uint64)
+    lo = np.empty((rows, words), dtype=np.uint64)
+    lib().orc_encode_qplanes(_p(q), _i64(rows), _i64(K), _i64(words), _p(hi), _p(lo))
+    return hi, lo
+
+
+def qgemm_bitserial(ah, al, wh, wl):
+    """O12: Fig.3(b)'s pattern on the bit planes."""
+    ah, al, wh, wl = (_c(a, np.uint64) for a in (ah, al, wh, wl))
+    M, words = ah.shape
+    N = wh.shape[0]
+    D = np.empty((M, N), dtype=np.int32)
+    lib().orc_qgemm_bitserial(_p(ah), _p(al), _p(wh), _p(wl), _i64(M), _i64(N), _i64(words), _p(D))
+    return D
+
+
+def decode_fp4_int(codes, K):
+    """uint8 [rows, Kpad/2] -> (int8 [rows, K] values, count of non-integer code points)."""
+    codes = _c(codes, np.uint8)
+    rows, half = codes.shape
+    v = np.empty((rows, K), dtype=np.int8)
+    f = lib().orc_decode_fp4_int
+    f.restype = C.c_int64
+    bad = f(_p(codes), _i64(rows), _i64(K), _i64(2 * half), _p(v))
+    return v, int(bad)

@@ -688,3 +688,47 @@ def test_table4_rows_are_the_ternary_layers_and_eq9_holds_with_printed_values():
         assert np.abs(y - z9).max() <= 1e-6 * np.abs(z9).max(), name
         direct = orc.conv_direct(ta, tw, sh.stride, sh.pad, gamma, beta, alpha, None, False)
         assert np.abs(y - direct).max() <= 1e-5, name
+
+
+# ------------------------------------------------ O12: the quaternary comparison ----
+def test_quaternary_values_follow_table1_and_the_bit_serial_pattern_is_the_product():
+    """Table 1's last column: the 2-bit code (1st bit, 2nd bit) has the value 2*first + second.
+    Fig.3(b)'s AND / shift / add pattern on the two bit planes must equal the plain sum of
+    products: exhaustively over all pairs of quaternary vectors of length 1..3, then against
+    numpy's integer matmul on random data with a ragged last word."""
+    rows = [l.split() for l in open(os.path.join(GOLD, "table1_encoding.txt")) if not l.startswith("#")]
+    for b1, b2, _, qv in rows:
+        hi, lo = orc.encode_qplanes(np.array([[int(qv)]], np.int8))
+        assert (int(hi[0, 0]), int(lo[0, 0])) == (int(b1), int(b2))
+    for K in (1, 2, 3):
+        vecs = np.array(list(itertools.product(range(4), repeat=K)), dtype=np.int8)      # 4^K vectors
+        h, l = orc.encode_qplanes(vecs)
+        D = orc.qgemm_bitserial(h, l, h, l)
+        assert (D == vecs.astype(np.int64) @ vecs.astype(np.int64).T).all()
+        assert (orc.qgemm_acc(vecs, vecs) == D).all()
+    rng = np.random.default_rng(12)
+    qa, qw = rng.integers(0, 4, (9, 200)).astype(np.int8), rng.integers(0, 4, (7, 200)).astype(np.int8)
+    want = qa.astype(np.int64) @ qw.astype(np.int64).T
+    assert (orc.qgemm_acc(qa, qw) == want).all()
+    ah, al = orc.encode_qplanes(qa)
+    wh, wl = orc.encode_qplanes(qw)
+    assert ah.shape == (9, 4) and (orc.qgemm_bitserial(ah, al, wh, wl) == want).all()
+    # closed forms: all threes -> 9 K; a zero vector -> 0
+    ones3 = np.full((1, 130), 3, np.int8)
+    assert orc.qgemm_acc(ones3, ones3)[0, 0] == 9 * 130
+    assert orc.qgemm_acc(ones3, np.zeros((1, 130), np.int8))[0, 0] == 0
+
+
+def test_quantize4_thresholds_and_fp4_storage_of_quaternary_values():
+    x = np.array([-1.0, 0.1, 1 / 6, 0.2, 0.5, 0.6, 5 / 6, 0.9, np.nan, np.inf], np.float32)
+    t1, t2, t3 = np.float32(1 / 6), np.float32(0.5), np.float32(5 / 6)
+    q = orc.quantize4(x, t1, t2, t3)
+    assert q.tolist() == [0, 0, 0, 1, 1, 2, 2, 3, 0, 3]          # strict: a tie stays below, NaN -> 0
+    # 0..3 are E2M1 code points (0x0, 0x2, 0x4, 0x5): the FP4 storage holds them exactly
+    assert [orc.e2m1_value(c) for c in (0x0, 0x2, 0x4, 0x5)] == [0.0, 1.0, 2.0, 3.0]
+    rng = np.random.default_rng(2)
+    qq = rng.integers(0, 4, (3, 77)).astype(np.int8)
+    enc = orc.encode_fp4(qq)
+    back, bad = orc.decode_fp4_int(enc, 77)
+    assert bad == 0 and (back == qq).all()
+    assert set(np.unique(enc & 15)) <= {0x0, 0x2, 0x4, 0x5}
