@@ -336,6 +336,29 @@ int rtn_weight_backward(const float *w, const float *grad_out, int64_t O, int64_
                         const float *thr_lo, const float *thr_hi, const float *k_w, const float *b_w,
                         const float *alpha, float *grad_w, double *grad_params, void *stream);
 
+/* The paper's comparison system: 2-bit quaternary weights and activations, values
+ * q in {0,1,2,3} = 2*(1st bit) + (2nd bit) (Table 1, last column), and their dot
+ * product D[m][n] = sum_k qa[m][k]*qw[n][k] (Section "How to Compute Dot Product
+ * between Two Ternary Vectors", second half; Fig.3(b)).
+ * rtn_quaternary_pack: x fp32 [rows][K] row-major (DEVICE) -> codes, with
+ *   q = (x > t1) + (x > t2) + (x > t3), strict compares on the stored value, NaN -> 0,
+ *   t1 <= t2 <= t3 (the usual uniform 2-bit quantizer of [0,1] is 1/6, 1/2, 5/6).
+ *   fmt RTN_CODE_I8: int8 [rows][rtn_padded_k(K)] holding q; RTN_CODE_FP4: E2M1 nibbles
+ *   holding q (0x0, 0x2, 0x4, 0x5), [rows][rtn_padded_k_format(FP4, K)/2] bytes;
+ *   RTN_CODE_BITPLANE: the plane of first bits of all rows, uint64 [rows][Kpad/64], then
+ *   the plane of second bits (bit j of word w = element 64*w + j).  Padding is 0.
+ * rtn_quaternary_gemm: a_codes [M] rows, w_codes [N] rows of K codes in `fmt`;
+ *   acc_out int32 [M][N].  RTN_CODE_BITPLANE runs the paper's bit-serial pattern on the
+ *   vector ALU (four AND + popcount pairs per 64 products, shifts, four adders:
+ *   RTN_PATH_POPC); RTN_CODE_I8 / RTN_CODE_FP4 run the matrix cores on the values
+ *   (0..3 and their products are exact in both; RTN_PATH_MFMA_I8 / RTN_PATH_MFMA_FP4).
+ *   K <= 2^20 so that 9*K is exact in int32 and in fp32.  No epilogue: the comparison
+ *   circuit has none.                                                           */
+int rtn_quaternary_pack(const float *x, int64_t rows, int64_t K, float t1, float t2, float t3,
+                        rtn_code_format fmt, void *codes, void *stream);
+int rtn_quaternary_gemm(rtn_code_format fmt, rtn_path path, const void *a_codes, const void *w_codes,
+                        int64_t M, int64_t N, int64_t K, int32_t *acc_out, void *stream);
+
 /* Stand-alone epilogue on stored accumulators (Eq.9 generalised, see
  * rtn_epilogue).  GEMM form: acc, y_out are [M][N] row-major.               */
 int rtn_epilogue_reparam(const int32_t *acc, int64_t M, int64_t N, int64_t K,

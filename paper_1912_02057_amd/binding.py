@@ -31,7 +31,7 @@ EXPORTS = ["rtn_status_string", "rtn_last_hip_error", "rtn_num_tile_configs", "r
            "rtn_activation_backward_workspace_bytes", "rtn_activation_backward",
            "rtn_activation_backward_static_max_n", "rtn_activation_backward_static", "rtn_weight_backward",
            "rtn_epilogue_reparam",
-           "rtn_epilogue_reparam_conv2d"]
+           "rtn_epilogue_reparam_conv2d", "rtn_quaternary_pack", "rtn_quaternary_gemm"]
 
 
 class RtnEpilogue(C.Structure):
@@ -104,6 +104,10 @@ def lib():
         L.rtn_activation_backward_static.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp, vp]
         L.rtn_weight_backward.restype = ci
         L.rtn_weight_backward.argtypes = [vp, vp, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.rtn_quaternary_pack.restype = ci
+        L.rtn_quaternary_pack.argtypes = [vp, i64, i64, C.c_float, C.c_float, C.c_float, ci, vp, vp]
+        L.rtn_quaternary_gemm.restype = ci
+        L.rtn_quaternary_gemm.argtypes = [ci, ci, vp, vp, i64, i64, i64, vp, vp]
         L.rtn_epilogue_reparam.restype = ci
         L.rtn_epilogue_reparam.argtypes = [vp, i64, i64, i64, vp, vp, vp]
         L.rtn_epilogue_reparam_conv2d.restype = ci
@@ -424,3 +428,32 @@ def epilogue_reparam_conv2d(acc, Cc, H, W, KH, KW, stride, pad, pad_mode, ep, y_
                                            pad_mode, ep.ref(), _dev(y_out, torch.float32), _stream())
     _check(rc, "rtn_epilogue_reparam_conv2d")
     return y_out
+
+
+def quaternary_pack(x, t1, t2, t3, fmt=RTN_CODE_I8):
+    """x cuda float32 [rows, K] -> quaternary codes (values 0..3) in format fmt."""
+    rows, K = x.shape
+    kp = padded_k(K, fmt)
+    if fmt == RTN_CODE_I8:
+        codes = torch.empty((rows, kp), dtype=torch.int8, device=x.device)
+    elif fmt == RTN_CODE_FP4:
+        codes = torch.empty((rows, kp // 2), dtype=torch.uint8, device=x.device)
+    else:
+        codes = torch.empty((2, rows, kp // 64), dtype=torch.int64, device=x.device)
+    rc = lib().rtn_quaternary_pack(_dev(x, torch.float32), rows, K, float(t1), float(t2), float(t3), fmt,
+                                   C.c_void_p(codes.data_ptr()), _stream())
+    _check(rc, "rtn_quaternary_pack")
+    return codes
+
+
+def quaternary_gemm(a_codes, w_codes, M, N, K, fmt=RTN_CODE_I8, path=RTN_PATH_AUTO, acc_out=None):
+    """D[m][n] = sum_k qa*qw on quaternary codes; returns int32 [M, N]."""
+    if fmt != RTN_CODE_BITPLANE:
+        _check_codes(a_codes, M, K, fmt, "a_codes")
+        _check_codes(w_codes, N, K, fmt, "w_codes")
+    if acc_out is None:
+        acc_out = torch.empty((M, N), dtype=torch.int32, device=a_codes.device)
+    rc = lib().rtn_quaternary_gemm(fmt, path, C.c_void_p(a_codes.data_ptr()), C.c_void_p(w_codes.data_ptr()), M, N, K,
+                                   _dev(acc_out, torch.int32), _stream())
+    _check(rc, "rtn_quaternary_gemm")
+    return acc_out

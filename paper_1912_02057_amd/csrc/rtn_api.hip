@@ -475,6 +475,52 @@ int rtn_weight_backward(const float* w, const float* grad_out, int64_t O, int64_
     return he == hipSuccess ? RTN_OK : hip_fail(he);
 }
 
+int rtn_quaternary_pack(const float* x, int64_t rows, int64_t K, float t1, float t2, float t3,
+                        rtn_code_format fmt, void* codes, void* stream)
+{
+    if (!x || !codes) return RTN_ERR_NULL;
+    if (fmt != RTN_CODE_I8 && fmt != RTN_CODE_BITPLANE && fmt != RTN_CODE_FP4) return RTN_ERR_UNSUPPORTED;
+    if (rows <= 0 || K <= 0 || rows > kMaxDim || K > kMaxK) return RTN_ERR_SHAPE;
+    if (!(t1 <= t2 && t2 <= t3)) return RTN_ERR_SHAPE;
+    if (!aligned(x, 4) || !aligned(codes, 16)) return RTN_ERR_ALIGN;
+    rtn::QPackArgs a = {};
+    a.x = x, a.rows = rows, a.K = K, a.Kpad = padk(fmt, K);
+    a.t1 = t1, a.t2 = t2, a.t3 = t3;
+    a.codes = codes;
+    const hipError_t he = rtn::launch_pack_rows_q4(a, (int)fmt, (hipStream_t)stream);
+    return he == hipSuccess ? RTN_OK : hip_fail(he);
+}
+
+int rtn_quaternary_gemm(rtn_code_format fmt, rtn_path path, const void* a_codes, const void* w_codes, int64_t M,
+                        int64_t N, int64_t K, int32_t* acc_out, void* stream)
+{
+    if (!a_codes || !w_codes || !acc_out) return RTN_ERR_NULL;
+    if (fmt != RTN_CODE_I8 && fmt != RTN_CODE_BITPLANE && fmt != RTN_CODE_FP4) return RTN_ERR_UNSUPPORTED;
+    const rtn_path want = fmt == RTN_CODE_I8 ? RTN_PATH_MFMA_I8 : (fmt == RTN_CODE_FP4 ? RTN_PATH_MFMA_FP4 : RTN_PATH_POPC);
+    if (path != RTN_PATH_AUTO && path != want) return RTN_ERR_UNSUPPORTED;
+    // 9 K must stay an exact int32 and, on the FP4 path, an exact fp32 integer
+    if (M <= 0 || N <= 0 || K <= 0 || M > kMaxDim || N > kMaxDim || K > ((int64_t)1 << 20)) return RTN_ERR_SHAPE;
+    if (!aligned(a_codes, 16) || !aligned(w_codes, 16) || !aligned(acc_out, 4)) return RTN_ERR_ALIGN;
+    hipError_t he;
+    if (fmt == RTN_CODE_BITPLANE) {
+        rtn::QPopcArgs p = {};
+        const int64_t words = pad64(K) / 64;
+        p.a_hi = (const uint64_t*)a_codes, p.a_lo = p.a_hi + M * words;
+        p.w_hi = (const uint64_t*)w_codes, p.w_lo = p.w_hi + N * words;
+        p.M = M, p.N = N, p.words = words;
+        p.acc = acc_out;
+        he = rtn::launch_qgemm_popc(p, (hipStream_t)stream);
+    } else {
+        rtn::GemmArgs g = {};
+        g.a = (const int8_t*)a_codes, g.w = (const int8_t*)w_codes;
+        g.M = M, g.N = N, g.K = K, g.Kpad = padk(fmt, K);
+        g.fp4 = fmt == RTN_CODE_FP4;
+        g.acc = acc_out;
+        he = rtn::launch_gemm_mfma(g, (hipStream_t)stream);
+    }
+    return he == hipSuccess ? RTN_OK : hip_fail(he);
+}
+
 int rtn_epilogue_reparam(const int32_t* acc, int64_t M, int64_t N, int64_t K, const rtn_epilogue* ep,
                          float* y_out, void* stream)
 {

@@ -171,6 +171,23 @@ struct PopcArgs {
 };
 hipError_t launch_gemm_popc(const PopcArgs& a, hipStream_t st);
 
+// The quaternary comparison system (values 0..3): quantize + pack of rows, and the bit-serial
+// dot product on bit planes.  The matrix-core forms go through launch_gemm_mfma.
+struct QPackArgs {
+    const float* x;   // [rows][K]
+    int64_t rows, K, Kpad;
+    float t1, t2, t3;  // q = (x > t1) + (x > t2) + (x > t3)
+    void* codes;
+};
+hipError_t launch_pack_rows_q4(const QPackArgs& a, int fmt, hipStream_t st);  // fmt as rtn_code_format
+struct QPopcArgs {
+    const uint64_t *a_hi, *a_lo;  // [M][words]: planes of the first / second bits
+    const uint64_t *w_hi, *w_lo;  // [N][words]
+    int64_t M, N, words;
+    int32_t* acc;
+};
+hipError_t launch_qgemm_popc(const QPopcArgs& a, hipStream_t st);
+
 hipError_t launch_epilogue_gemm(const int32_t* acc, int64_t M, int64_t N, int64_t K,
                                 const EpiArgs& ep, float* y, hipStream_t st);
 hipError_t launch_epilogue_conv(const int32_t* acc, const ConvGeom& g, const EpiArgs& ep, float* y,

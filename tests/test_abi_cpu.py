@@ -319,6 +319,40 @@ def test_activation_backward_static_rejects(L):
     assert with_(_7=C.c_void_p(0x10004)) == B.RTN_ERR_ALIGN
 
 
+def test_quaternary_rejects(L):
+    pack, gemm = L.rtn_quaternary_pack, L.rtn_quaternary_gemm
+    f = C.c_float
+    assert pack(None, 4, 100, f(0.1), f(0.5), f(0.9), B.RTN_CODE_I8, FAKE, None) == B.RTN_ERR_NULL
+    assert pack(FAKE, 0, 100, f(0.1), f(0.5), f(0.9), B.RTN_CODE_I8, FAKE, None) == B.RTN_ERR_SHAPE
+    assert pack(FAKE, 4, 100, f(0.6), f(0.5), f(0.9), B.RTN_CODE_I8, FAKE, None) == B.RTN_ERR_SHAPE     # t1 > t2
+    assert pack(FAKE, 4, 100, f(0.1), f(0.5), f(0.9), 7, FAKE, None) == B.RTN_ERR_UNSUPPORTED
+    assert pack(FAKE, 4, 100, f(0.1), f(0.5), f(0.9), B.RTN_CODE_I8, ODD, None) == B.RTN_ERR_ALIGN
+    assert gemm(B.RTN_CODE_I8, B.RTN_PATH_AUTO, FAKE, FAKE, 8, 8, 64, None, None) == B.RTN_ERR_NULL
+    assert gemm(B.RTN_CODE_I8, B.RTN_PATH_POPC, FAKE, FAKE, 8, 8, 64, FAKE, None) == B.RTN_ERR_UNSUPPORTED
+    assert gemm(B.RTN_CODE_FP4, B.RTN_PATH_MFMA_I8, FAKE, FAKE, 8, 8, 64, FAKE, None) == B.RTN_ERR_UNSUPPORTED
+    assert gemm(B.RTN_CODE_FP4, B.RTN_PATH_AUTO, FAKE, FAKE, 8, 8, (1 << 20) + 1, FAKE, None) == B.RTN_ERR_SHAPE
+    assert gemm(B.RTN_CODE_BITPLANE, B.RTN_PATH_AUTO, FAKE, ODD, 8, 8, 64, FAKE, None) == B.RTN_ERR_ALIGN
+
+
+def test_fp4_format_rejects(L):
+    lo, hi = _f(-0.5), _f(0.5)
+    assert L.rtn_padded_k_format(B.RTN_CODE_FP4, 1) == 128 and L.rtn_padded_k_format(B.RTN_CODE_I8, 65) == 128
+    assert L.rtn_padded_k_format(5, 64) == 0
+    assert L.rtn_codes_bytes(B.RTN_CODE_FP4, 3, 129) == 3 * 128
+    # the path must match the code format
+    assert L.rtn_ternary_gemm(B.RTN_CODE_FP4, B.RTN_PATH_MFMA_I8, FAKE, FAKE, 8, 8, 64, FAKE, None, None, None, 0,
+                              None) == B.RTN_ERR_UNSUPPORTED
+    assert L.rtn_ternary_gemm(B.RTN_CODE_I8, B.RTN_PATH_MFMA_FP4, FAKE, FAKE, 8, 8, 64, FAKE, None, None, None, 0,
+                              None) == B.RTN_ERR_UNSUPPORTED
+    assert L.rtn_ternary_conv2d_implicit_gemm(B.RTN_CODE_FP4, B.RTN_PATH_MFMA_I8, FAKE, FAKE, 1, 64, 8, 8, 64, 3, 3, 1, 1,
+                                              0, FAKE, None, None, None, 0, None) == B.RTN_ERR_UNSUPPORTED
+    assert L.rtn_ternary_conv2d_implicit_gemm(B.RTN_CODE_BITPLANE, B.RTN_PATH_AUTO, FAKE, FAKE, 1, 64, 8, 8, 64, 3, 3, 1,
+                                              1, 0, FAKE, None, None, None, 0, None) == B.RTN_ERR_UNSUPPORTED
+    # NCHW packing of FP4 codes has the same channel limit as int8
+    assert L.rtn_ternarize_pack(FAKE, B.RTN_NCHW, 1, 4096, 4, 4, lo, hi, B.RTN_SCALAR, B.RTN_CODE_FP4, FAKE, None,
+                                None) == B.RTN_ERR_UNSUPPORTED
+
+
 def test_bench_refuses_more_than_one_gpu():
     """bench.py measures one GPU; asked for more it exits with status 2 and says so, before touching a device."""
     import subprocess

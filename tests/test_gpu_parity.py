@@ -1346,3 +1346,48 @@ def test_weight_backward_all_resnet18_ternary_filters():
         _say("weight backward %s" % (shape,))
         _weight_bwd_check(shape.O, shape.C * shape.k * shape.k, seed=900 + i)
 
+
+
+# ------------------- the comparison system: quaternary (2-bit) codes and dot product -------
+QT = (np.float32(1 / 6), np.float32(0.5), np.float32(5 / 6))
+
+
+@pytest.mark.parametrize("M,N,K", [(1, 1, 1), (37, 19, 131), (64, 64, 64), (65, 33, 200), (300, 200, 576),
+                                   (129, 257, 1000), (1024, 1024, 4096)])
+def test_quaternary_pack_and_gemm_vs_oracle(M, N, K):
+    """Quantize + pack in the three storage forms and the dot product on the three paths
+    (bit-serial AND/popcount on planes, int8 matrix cores, FP4 matrix cores): codes and
+    accumulators bit-exact against the oracle's plain sum of products."""
+    _say("quaternary M=%d N=%d K=%d" % (M, N, K))
+    rng = np.random.default_rng(M + N + K)
+    xa = rng.uniform(-0.2, 1.2, (M, K)).astype(np.float32)
+    xw = rng.uniform(-0.2, 1.2, (N, K)).astype(np.float32)
+    xa.flat[:: max(1, xa.size // 11)] = QT[1]              # exact ties stay below the threshold
+    if xa.size > 1:
+        xa.flat[1] = np.nan
+    qa, qw = orc.quantize4(xa, *QT), orc.quantize4(xw, *QT)
+    D = orc.qgemm_acc(qa, qw)
+    xad, xwd = T.dev(xa), T.dev(xw)
+    for fmt in (B.RTN_CODE_I8, B.RTN_CODE_FP4, B.RTN_CODE_BITPLANE):
+        ca, cw = B.quaternary_pack(xad, *QT, fmt), B.quaternary_pack(xwd, *QT, fmt)
+        if fmt == B.RTN_CODE_I8:
+            assert (ca.cpu().numpy() == orc.pad_rows_i8(qa, ca.shape[1])).all()
+        elif fmt == B.RTN_CODE_FP4:
+            assert (ca.cpu().numpy() == orc.encode_fp4(qa)).all()
+        else:
+            hi, lo = T.planes_from_dev(ca)
+            eh, el = orc.encode_qplanes(qa, ca.shape[-1])
+            assert (hi == eh).all() and (lo == el).all()
+        got = B.quaternary_gemm(ca, cw, M, N, K, fmt)
+        torch.cuda.synchronize()
+        assert (got.cpu().numpy() == D).all(), "format %d" % fmt
+
+
+def test_quaternary_extreme_sum_is_exact_on_the_fp4_path():
+    _say("quaternary all threes, K = 65536")
+    K = 65536
+    x = np.ones((64, K), np.float32)
+    c = B.quaternary_pack(T.dev(x), *QT, B.RTN_CODE_FP4)
+    got = B.quaternary_gemm(c, c, 64, 64, K, B.RTN_CODE_FP4)
+    torch.cuda.synchronize()
+    assert (got.cpu().numpy() == 9 * K).all()
