@@ -683,6 +683,52 @@ void orc_qgemm_bitserial(const uint64_t *ah, const uint64_t *al, const uint64_t 
         }
 }
 
+/* ----------------------------------------------------------------- O13 --
+ * Depthwise form of the ternary convolution (the 3x3 layers of MobileNet, one of the
+ * networks of the paper's ImageNet table): every channel is convolved with its own
+ * k x k ternary filter, so one dot product has length K = k*k.  The reparameterized
+ * output is the same four-term formula with everything per channel:
+ *   y[n][c][p] = aa*aw[c]*D + aa*bw[c]*Sa + ba*aw[c]*Sw + Kv*ba*bw[c],
+ * D = sum over in-bounds taps of t_a*t_w,  Sa = sum of t_a,  Sw = sum of t_w over the
+ * in-bounds taps (zero padding of the reparameterized activation) or over all taps
+ * with Kv = k*k (code-zero padding), Kv = number of in-bounds taps.
+ * ta: [Nb][C][H][W], tw: [C][KH][KW]; y: [Nb][C][OH][OW] (fp64 evaluation, one rounding) */
+void orc_dwconv(const int8_t *ta, const int8_t *tw, int64_t Nb, int64_t C, int64_t H, int64_t W,
+                int64_t KH, int64_t KW, int64_t stride, int64_t pad, int pad_true_zero, float aa, float ba,
+                const float *aw, const float *bw, int stride_w, int relu, const float *bn_scale,
+                const float *bn_shift, int32_t *D, float *y)
+{
+    int64_t OH = (H + 2 * pad - KH) / stride + 1, OW = (W + 2 * pad - KW) / stride + 1;
+#pragma omp parallel for
+    for (int64_t nb = 0; nb < Nb; ++nb)
+        for (int64_t c = 0; c < C; ++c)
+            for (int64_t oh = 0; oh < OH; ++oh)
+                for (int64_t ow = 0; ow < OW; ++ow) {
+                    int64_t d = 0, sa = 0, sw = 0, kv = 0;
+                    for (int64_t kh = 0; kh < KH; ++kh)
+                        for (int64_t kw = 0; kw < KW; ++kw) {
+                            int64_t ih = oh * stride - pad + kh, iw = ow * stride - pad + kw;
+                            int inb = ih >= 0 && ih < H && iw >= 0 && iw < W;
+                            int w_ = tw[(c * KH + kh) * KW + kw];
+                            if (inb) {
+                                int a_ = ta[((nb * C + c) * H + ih) * W + iw];
+                                d += a_ * w_;
+                                sa += a_;
+                            }
+                            if (inb || !pad_true_zero) {
+                                sw += w_;
+                                kv += 1;
+                            }
+                        }
+                    int64_t i = ((nb * C + c) * OH + oh) * OW + ow;
+                    double a_w = aw[c * stride_w], b_w = bw ? bw[c * stride_w] : 0.0;
+                    double v = (double)aa * a_w * (double)d + (double)aa * b_w * (double)sa +
+                               (double)ba * a_w * (double)sw + (double)kv * (double)ba * b_w;
+                    if (D) D[i] = (int32_t)d;
+                    if (y) y[i] = (float)apply_tail(v, relu, bn_scale, bn_shift, c);
+                }
+}
+
 /* FP4 nibbles that hold small integers (0..3 are code points of E2M1 too): decoded values,
  * and the number of nibbles whose value is not an integer in [-6, 6] */
 int64_t orc_decode_fp4_int(const uint8_t *codes, int64_t rows, int64_t K, int64_t Kpad, int8_t *v)

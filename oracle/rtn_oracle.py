@@ -460,3 +460,21 @@ def decode_fp4_int(codes, K):
     f.restype = C.c_int64
     bad = f(_p(codes), _i64(rows), _i64(K), _i64(2 * half), _p(v))
     return v, int(bad)
+
+
+def dwconv(ta, tw, stride, pad, alpha_a, beta_a, alpha_w, beta_w=None, pad_true_zero=True, relu=False,
+           bn_scale=None, bn_shift=None):
+    """O13: depthwise ternary conv.  ta int8 [Nb,C,H,W], tw int8 [C,KH,KW] -> (D int32, y float32) [Nb,C,OH,OW]."""
+    ta, tw = _c(ta, np.int8), _c(tw, np.int8)
+    Nb, Cc, H, W = ta.shape
+    KH, KW = tw.shape[1:]
+    OH, OW = conv_out_shape(H, W, KH, KW, stride, pad)
+    aw, sw_ = _gran(alpha_w, Cc)
+    bw = None if beta_w is None else _gran(beta_w, Cc)[0]
+    bs, bh = _c(bn_scale, np.float32), _c(bn_shift, np.float32)
+    D = np.empty((Nb, Cc, OH, OW), dtype=np.int32)
+    y = np.empty((Nb, Cc, OH, OW), dtype=np.float32)
+    lib().orc_dwconv(_p(ta), _p(tw), _i64(Nb), _i64(Cc), _i64(H), _i64(W), _i64(KH), _i64(KW), _i64(stride),
+                     _i64(pad), C.c_int(int(pad_true_zero)), _f32(float(alpha_a)), _f32(float(beta_a)), _p(aw),
+                     _p(bw), C.c_int(sw_), C.c_int(int(relu)), _p(bs), _p(bh), _p(D), _p(y))
+    return D, y

@@ -732,3 +732,30 @@ def test_quantize4_thresholds_and_fp4_storage_of_quaternary_values():
     back, bad = orc.decode_fp4_int(enc, 77)
     assert bad == 0 and (back == qq).all()
     assert set(np.unique(enc & 15)) <= {0x0, 0x2, 0x4, 0x5}
+
+
+# ------------------------------------------------ O13: depthwise ternary conv ----
+@pytest.mark.parametrize("true_zero", [True, False])
+def test_depthwise_conv_equals_grouped_framework_conv_of_the_values(true_zero):
+    """D against torch's grouped conv on the float codes (exact: small integers), and the
+    four-term output against the direct depthwise conv of the reparameterized values, padded
+    with zeros (true-zero mode) or with beta_a (code-zero mode)."""
+    rng = np.random.default_rng(31)
+    for (C, H, W, k, s, p) in [(5, 9, 7, 3, 1, 1), (6, 10, 10, 3, 2, 1), (3, 6, 8, 5, 1, 2), (4, 5, 5, 1, 1, 0)]:
+        ta, tw = _rand_t(rng, (2, C, H, W)), _rand_t(rng, (C, k, k))
+        aw = rng.uniform(0.5, 1.5, C).astype(np.float32)
+        bw = rng.uniform(-0.2, 0.2, C).astype(np.float32)
+        aa, ba = np.float32(1.3), np.float32(-0.12)
+        D, y = orc.dwconv(ta, tw, s, p, aa, ba, aw, bw, true_zero)
+        lib = torch.nn.functional.conv2d(torch.from_numpy(ta.astype(np.float64)),
+                                         torch.from_numpy(tw.astype(np.float64))[:, None], stride=s, padding=p, groups=C)
+        assert (D == lib.numpy()).all()
+        va = torch.from_numpy(float(aa) * ta.astype(np.float64) + float(ba))
+        va = torch.nn.functional.pad(va, (p, p, p, p), value=0.0 if true_zero else float(ba))
+        vw = torch.from_numpy(aw.astype(np.float64)[:, None, None] * tw + bw.astype(np.float64)[:, None, None])
+        direct = torch.nn.functional.conv2d(va, vw[:, None], stride=s, padding=0, groups=C).numpy()
+        assert np.abs(y - direct).max() < 1e-5
+    # tail order: ReLU, then the BN affine
+    D, y = orc.dwconv(np.array([[[[1]], [[-1]]]], np.int8), np.ones((2, 1, 1), np.int8), 1, 0, 1.0, 0.0, 1.0, None,
+                      True, relu=True, bn_scale=np.array([2, 2], np.float32), bn_shift=np.array([0.5, 0.5], np.float32))
+    assert D.ravel().tolist() == [1, -1] and y.ravel().tolist() == [2.5, 0.5]
