@@ -41,7 +41,7 @@ def main():
     ap.add_argument("--workload", default="resnet18_ternary_convs",
                     choices=["resnet18_ternary_convs", "gemm4096", "wgemm4096", "resnet18_weight_only_convs",
                              "act_backward", "weight_backward", "gemm_sweep", "peaks", "config1",
-                             "resnet18_full_forward", "quaternary_gemm"])
+                             "resnet18_full_forward", "quaternary_gemm", "mobilenet_layers"])
     ap.add_argument("--tile", type=int, default=-1, help="force an MFMA tile configuration (tuning)")
     ap.add_argument("--format", default="fp4", choices=["fp4", "i8"],
                     help="storage of the ternary codes on the matrix-core path: FP4 (E2M1) nibbles on the FP4 "
@@ -308,6 +308,62 @@ def main():
             "cpu_baseline": None, "paths": rowsq,
             "context": "the paper's circuits: ternary 22.17 uW / 199.43 um^2 against quaternary 76.09 uW / 831.62 um^2 "
                        "(3.43x power, 4.17x area; FPGA / 45 nm flow, Table 3)"}))
+        return
+
+
+    if args.workload == "mobilenet_layers":
+        # MobileNet's ternary layers (the paper's third ImageNet network): 13 depthwise 3x3 convs (K = 9,
+        # streaming kernel) and 13 pointwise 1x1 convs (matrix cores), each with its pack, batch 256
+        cfgs = [(32, 112, 1, 64), (64, 112, 2, 128), (128, 56, 1, 128), (128, 56, 2, 256), (256, 28, 1, 256),
+                (256, 28, 2, 512)] + [(512, 14, 1, 512)] * 5 + [(512, 14, 2, 1024), (1024, 7, 1, 1024)]
+        rows_, tot_s, tot_macs = [], 0.0, 0.0
+        rng = np.random.Generator(np.random.PCG64(9))
+        for (Cc, H, st_, Op) in cfgs:
+            OH = (H + 2 - 3) // st_ + 1
+            x = torch.randn((args.batch, Cc, H, H), device=dev)
+            wd = to_dev((rng.standard_normal((Cc, 9)) * 0.3).astype(np.float32))
+            cwd, _ = B.ternarize_pack(wd, -0.2, 0.2, want_sum=False)
+            aw = to_dev(rng.uniform(0.5, 1.5, Cc).astype(np.float32))
+            epd = B.Epilogue(1.1, 0.1, aw, None, None, None, relu=True)
+            ca = torch.empty((args.batch, H, H, B.padded_k(Cc)), dtype=torch.int8, device=dev)
+            yd = torch.empty((args.batch, Cc, OH, OH), dtype=torch.float32, device=dev)
+            ms_pack = timed(lambda: B.ternarize_pack(x, -0.5, 0.5, codes=ca, want_sum=False), 5)
+            ms_dw = timed(lambda: B.ternary_depthwise_conv2d(ca, cwd, args.batch, Cc, H, H, 3, 3, st_, 1, ep=epd, y_out=yd), 5)
+            dw_bytes = ca.numel() + yd.numel() * 4
+            # pointwise conv on the depthwise output
+            shp = wl.ConvShape("pw", Cc, OH, Op, 1, 1, 0)
+            case = wl.conv_case(shp, batch=1, seed=Cc, per_channel=True, bn=True)
+            dwp = np.asarray(case["delta_w"])
+            cwp, pwp = B.ternarize_pack(to_dev(case["w"]), garg(-dwp), garg(dwp), FMT)
+            epp = B.Epilogue(garg(case["alpha_a"]), garg(case["beta_a"]), garg(case["alpha_w"]), garg(case["beta_w"]),
+                             None, pwp, relu=True, bn_scale=to_dev(case["bn_scale"]), bn_shift=to_dev(case["bn_shift"]))
+            wsp = B.conv2d_prepare_constants(Cc, Op, 1, 1, 0, epp)
+            cap = code_tensor(args.batch, OH, Cc)
+            yp = torch.empty((args.batch, Op, OH, OH), dtype=torch.float32, device=dev)
+            ms_pack2 = timed(lambda: B.ternarize_pack(yd, -0.5, 0.5, FMT, codes=cap, want_sum=False), 5)
+            ms_pw = timed(lambda: B.ternary_conv2d(cap, cwp, args.batch, Cc, OH, OH, Op, 1, 1, 1, 0, ep=epp, y_out=yp,
+                                                   workspace=wsp, fmt=FMT), 5)
+            macs_dw = args.batch * Cc * OH * OH * 9.0
+            macs_pw = args.batch * Op * OH * OH * float(Cc)
+            rows_.append(dict(layer="dw %d@%d s%d -> pw %d" % (Cc, H, st_, Op), dw_us=round(ms_dw * 1e3, 1),
+                              dw_gbs=round(dw_bytes / ms_dw / 1e6, 0), dw_pct_hbm=round(100 * dw_bytes / ms_dw / 1e6 / HBM_PEAK_GBS, 1),
+                              pack_dw_us=round(ms_pack * 1e3, 1), pw_us=round(ms_pw * 1e3, 1), pack_pw_us=round(ms_pack2 * 1e3, 1),
+                              pw_tmacs=round(macs_pw / ms_pw / 1e9, 1)))
+            tot_s += (ms_pack + ms_dw + ms_pack2 + ms_pw) * 1e-3
+            tot_macs += macs_dw + macs_pw
+            del x, ca, yd, cap, yp
+        dwb = sum(r["dw_gbs"] * r["dw_us"] for r in rows_) / sum(r["dw_us"] for r in rows_)
+        print(json.dumps({
+            "metric": "effective ternary MAC/s, MobileNet's 13 depthwise + 13 pointwise ternary layers, each with its pack",
+            "value": round(tot_macs / tot_s / 1e12, 3), "unit": "TMAC/s", "n_gpus": 1, "steps": 5, "warmup": 2,
+            "ms_per_step": round(tot_s * 1e3, 4), "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+            "dtype": args.format, "data": "synthetic",
+            "config": {"workload": "MobileNet ternary layers (depthwise 3x3 + pointwise 1x1), batch %d" % args.batch,
+                       "batch": args.batch, "format": args.format},
+            "roofline": {"bound": "hbm", "kernel": "k_dwconv (depthwise 3x3, int8 codes in, fp32 out)",
+                         "achieved": round(dwb, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": round(dwb / HBM_PEAK_GBS, 4),
+                         "traffic": None},
+            "cpu_baseline": None, "layers": rows_}))
         return
 
     if args.workload == "gemm_sweep":

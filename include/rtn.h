@@ -336,6 +336,25 @@ int rtn_weight_backward(const float *w, const float *grad_out, int64_t O, int64_
                         const float *thr_lo, const float *thr_hi, const float *k_w, const float *b_w,
                         const float *alpha, float *grad_w, double *grad_params, void *stream);
 
+/* Depthwise ternary convolution (the 3x3 layers of MobileNet, one of the networks of
+ * the paper's ImageNet table): channel c of the input is convolved with its own KH x KW
+ * ternary filter, so a dot product has K = KH*KW terms, and the four-term formula of
+ * rtn_epilogue holds per channel with Sa, Sw, Kv taken over the taps of that channel's
+ * window (in-bounds taps only for RTN_PAD_TRUE_ZERO).
+ *   a_codes: RTN_CODE_I8 [Nb][H][W][rtn_padded_k(C)], as rtn_ternarize_pack(RTN_NCHW) writes.
+ *   w_codes: RTN_CODE_I8 [C][rtn_padded_k(KH*KW)], one row of tap codes (kh*KW + kw) per
+ *     channel: rtn_ternarize_pack(RTN_ROWS_K_CONTIG) of the filters [C][KH*KW], which
+ *     allows one threshold pair per filter.
+ *   acc_out: int32 [Nb][C][OH][OW] or NULL; ep + y_out: fp32 [Nb][C][OH][OW] or both NULL.
+ *   ep: alpha_a, beta_a RTN_SCALAR; alpha_w, beta_w (nullable) RTN_SCALAR or RTN_VECTOR
+ *   over the C channels; relu, bn_scale, bn_shift as everywhere; sum_ta and sum_tw are
+ *   not read (the kernel forms the sums itself).  Geometry limits as for
+ *   rtn_ternary_conv2d_implicit_gemm; needs no workspace.                         */
+int rtn_ternary_depthwise_conv2d(const void *a_codes, const void *w_codes, int64_t Nb, int64_t C,
+                                 int64_t H, int64_t W, int KH, int KW, int stride, int pad,
+                                 rtn_pad_mode pad_mode, int32_t *acc_out, const rtn_epilogue *ep,
+                                 float *y_out, void *stream);
+
 /* The paper's comparison system: 2-bit quaternary weights and activations, values
  * q in {0,1,2,3} = 2*(1st bit) + (2nd bit) (Table 1, last column), and their dot
  * product D[m][n] = sum_k qa[m][k]*qw[n][k] (Section "How to Compute Dot Product

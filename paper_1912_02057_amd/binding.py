@@ -31,7 +31,8 @@ EXPORTS = ["rtn_status_string", "rtn_last_hip_error", "rtn_num_tile_configs", "r
            "rtn_activation_backward_workspace_bytes", "rtn_activation_backward",
            "rtn_activation_backward_static_max_n", "rtn_activation_backward_static", "rtn_weight_backward",
            "rtn_epilogue_reparam",
-           "rtn_epilogue_reparam_conv2d", "rtn_quaternary_pack", "rtn_quaternary_gemm"]
+           "rtn_epilogue_reparam_conv2d", "rtn_quaternary_pack", "rtn_quaternary_gemm",
+           "rtn_ternary_depthwise_conv2d"]
 
 
 class RtnEpilogue(C.Structure):
@@ -104,6 +105,8 @@ def lib():
         L.rtn_activation_backward_static.argtypes = [vp, vp, i64, vp, vp, vp, vp, vp, vp]
         L.rtn_weight_backward.restype = ci
         L.rtn_weight_backward.argtypes = [vp, vp, i64, i64, vp, vp, vp, vp, vp, vp, vp, vp]
+        L.rtn_ternary_depthwise_conv2d.restype = ci
+        L.rtn_ternary_depthwise_conv2d.argtypes = [vp, vp, i64, i64, i64, i64, ci, ci, ci, ci, ci, vp, vp, vp, vp]
         L.rtn_quaternary_pack.restype = ci
         L.rtn_quaternary_pack.argtypes = [vp, i64, i64, C.c_float, C.c_float, C.c_float, ci, vp, vp]
         L.rtn_quaternary_gemm.restype = ci
@@ -202,7 +205,7 @@ class Epilogue:
         self._tensors = (alpha_a, beta_a, alpha_w, beta_w, sum_ta, sum_tw, bn_scale, bn_shift)
         self.s = RtnEpilogue(self._a.ptr, self._b.ptr, self._a.gran, self._c.ptr, self._d.ptr,
                              self._c.gran, None if sum_ta is None else _dev(sum_ta, torch.int32),
-                             _dev(sum_tw, torch.int32),
+                             None if sum_tw is None else _dev(sum_tw, torch.int32),
                              int(bool(relu)),
                              None if bn_scale is None else _dev(bn_scale, torch.float32),
                              None if bn_shift is None else _dev(bn_shift, torch.float32))
@@ -457,3 +460,22 @@ def quaternary_gemm(a_codes, w_codes, M, N, K, fmt=RTN_CODE_I8, path=RTN_PATH_AU
                                    _dev(acc_out, torch.int32), _stream())
     _check(rc, "rtn_quaternary_gemm")
     return acc_out
+
+
+def ternary_depthwise_conv2d(a_codes, w_codes, Nb, Cc, H, W, KH, KW, stride, pad, pad_mode=RTN_PAD_TRUE_ZERO, ep=None,
+                             want_acc=False, acc_out=None, y_out=None):
+    """a_codes int8 [Nb,H,W,Cpad]; w_codes int8 [C, padded_k(KH*KW)].  Returns (acc, y) in NCHW."""
+    _check_codes(a_codes, Nb * H * W, Cc, RTN_CODE_I8, "a_codes")
+    _check_codes(w_codes, Cc, KH * KW, RTN_CODE_I8, "w_codes")
+    OH, OW = conv_out_hw(H, W, KH, KW, stride, pad)
+    dev = a_codes.device
+    if want_acc and acc_out is None:
+        acc_out = torch.empty((Nb, Cc, OH, OW), dtype=torch.int32, device=dev)
+    if ep is not None and y_out is None:
+        y_out = torch.empty((Nb, Cc, OH, OW), dtype=torch.float32, device=dev)
+    rc = lib().rtn_ternary_depthwise_conv2d(
+        C.c_void_p(a_codes.data_ptr()), C.c_void_p(w_codes.data_ptr()), Nb, Cc, H, W, KH, KW, stride, pad, pad_mode,
+        None if acc_out is None else _dev(acc_out, torch.int32), None if ep is None else ep.ref(),
+        None if y_out is None else _dev(y_out, torch.float32), _stream())
+    _check(rc, "rtn_ternary_depthwise_conv2d")
+    return acc_out, y_out

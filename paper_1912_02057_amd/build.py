@@ -10,7 +10,7 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librtn.so")
 PEAKS_LIB = os.path.join(HERE, "librtn_peaks.so")     # measurement aids for bench.py, not the product
-SOURCES = ["rtn_api.hip", "ternarize_pack.hip", "tgemm_popc.hip", "quaternary.hip", "tmm_mfma.hip", "tmm_inst_gemm.hip",
+SOURCES = ["rtn_api.hip", "ternarize_pack.hip", "tgemm_popc.hip", "quaternary.hip", "dwconv.hip", "tmm_mfma.hip", "tmm_inst_gemm.hip",
            "tmm_inst_conv.hip", "tmm_inst_tern1.hip", "tmm_inst_tern2.hip", "tmm_inst_bf16.hip",
            "tmm_inst_gemm_fp4.hip", "tmm_inst_conv_fp4.hip", "tmm_inst_tern1_fp4.hip", "tmm_inst_tern2_fp4.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall", "-Wextra",

@@ -475,6 +475,39 @@ int rtn_weight_backward(const float* w, const float* grad_out, int64_t O, int64_
     return he == hipSuccess ? RTN_OK : hip_fail(he);
 }
 
+int rtn_ternary_depthwise_conv2d(const void* a_codes, const void* w_codes, int64_t Nb, int64_t C, int64_t H,
+                                 int64_t W, int KH, int KW, int stride, int pad, rtn_pad_mode pad_mode,
+                                 int32_t* acc_out, const rtn_epilogue* ep, float* y_out, void* stream)
+{
+    if (!a_codes || !w_codes) return RTN_ERR_NULL;
+    if ((ep == nullptr) != (y_out == nullptr)) return RTN_ERR_NULL;
+    if (!acc_out && !y_out) return RTN_ERR_NULL;
+    rtn::DwConvArgs d = {};
+    int rc = make_geom(Nb, C, H, W, C, KH, KW, stride, pad, pad_mode, d.g);
+    if (rc != RTN_OK) return rc;
+    if (!aligned(a_codes, 16) || !aligned(w_codes, 16) || !aligned(acc_out, 4) || !aligned(y_out, 4)) return RTN_ERR_ALIGN;
+    if (ep) {
+        if (ep->gran_a != RTN_SCALAR) return RTN_ERR_UNSUPPORTED;
+        if (ep->gran_w != RTN_SCALAR && ep->gran_w != RTN_VECTOR) return RTN_ERR_UNSUPPORTED;
+        if ((rc = make_param(ep->alpha_a, ep->gran_a, false, d.ep.alpha_a)) != RTN_OK) return rc;
+        if ((rc = make_param(ep->beta_a, ep->gran_a, false, d.ep.beta_a)) != RTN_OK) return rc;
+        if ((rc = make_param(ep->alpha_w, ep->gran_w, false, d.ep.alpha_w)) != RTN_OK) return rc;
+        if ((rc = make_param(ep->beta_w, ep->gran_w, true, d.ep.beta_w)) != RTN_OK) return rc;
+        if (ep->bn_shift && !ep->bn_scale) return RTN_ERR_NULL;
+        if (!aligned(ep->bn_scale, 4) || !aligned(ep->bn_shift, 4)) return RTN_ERR_ALIGN;
+        d.ep.relu = ep->relu != 0;
+        d.ep.bn_scale = ep->bn_scale;
+        d.ep.bn_shift = ep->bn_shift;
+    }
+    d.a = (const int8_t*)a_codes;
+    d.w = (const int8_t*)w_codes;
+    d.Kp = pad64((int64_t)KH * KW);
+    d.acc = acc_out;
+    d.y = y_out;
+    const hipError_t he = rtn::launch_dwconv(d, (hipStream_t)stream);
+    return he == hipSuccess ? RTN_OK : hip_fail(he);
+}
+
 int rtn_quaternary_pack(const float* x, int64_t rows, int64_t K, float t1, float t2, float t3,
                         rtn_code_format fmt, void* codes, void* stream)
 {

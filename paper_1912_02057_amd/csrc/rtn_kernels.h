@@ -188,6 +188,19 @@ struct QPopcArgs {
 };
 hipError_t launch_qgemm_popc(const QPopcArgs& a, hipStream_t st);
 
+// Depthwise ternary conv: a int8 [Nb][H][W][Cpad], w int8 [C][Kp] (one row of KH*KW tap codes per
+// channel), outputs [Nb][C][OH][OW]; ep: alpha_a / beta_a scalar, alpha_w / beta_w per channel
+struct DwConvArgs {
+    const int8_t* a;
+    const int8_t* w;
+    int64_t Kp;
+    ConvGeom g;  // O = C
+    int32_t* acc;
+    float* y;
+    EpiArgs ep;
+};
+hipError_t launch_dwconv(const DwConvArgs& a, hipStream_t st);
+
 hipError_t launch_epilogue_gemm(const int32_t* acc, int64_t M, int64_t N, int64_t K,
                                 const EpiArgs& ep, float* y, hipStream_t st);
 hipError_t launch_epilogue_conv(const int32_t* acc, const ConvGeom& g, const EpiArgs& ep, float* y,

@@ -334,6 +334,24 @@ def test_quaternary_rejects(L):
     assert gemm(B.RTN_CODE_BITPLANE, B.RTN_PATH_AUTO, FAKE, ODD, 8, 8, 64, FAKE, None) == B.RTN_ERR_ALIGN
 
 
+def test_depthwise_rejects(L):
+    call = L.rtn_ternary_depthwise_conv2d
+    ok = [FAKE, FAKE, 2, 64, 8, 8, 3, 3, 1, 1, 0, FAKE, None, None, None]
+
+    def with_(**kw):
+        a = list(ok)
+        for i, v in kw.items():
+            a[int(i[1:])] = v
+        return call(*a)
+    assert with_(_0=None) == B.RTN_ERR_NULL
+    assert with_(_11=None) == B.RTN_ERR_NULL                 # neither accumulators nor y
+    assert with_(_13=FAKE) == B.RTN_ERR_NULL                 # y without an epilogue
+    assert with_(_3=0) == B.RTN_ERR_SHAPE
+    assert with_(_6=9) == B.RTN_ERR_UNSUPPORTED              # kernel size
+    assert with_(_9=3) == B.RTN_ERR_UNSUPPORTED              # pad >= kernel size
+    assert with_(_1=ODD) == B.RTN_ERR_ALIGN
+
+
 def test_fp4_format_rejects(L):
     lo, hi = _f(-0.5), _f(0.5)
     assert L.rtn_padded_k_format(B.RTN_CODE_FP4, 1) == 128 and L.rtn_padded_k_format(B.RTN_CODE_I8, 65) == 128

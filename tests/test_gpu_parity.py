@@ -1391,3 +1391,74 @@ def test_quaternary_extreme_sum_is_exact_on_the_fp4_path():
     got = B.quaternary_gemm(c, c, 64, 64, K, B.RTN_CODE_FP4)
     torch.cuda.synchronize()
     assert (got.cpu().numpy() == 9 * K).all()
+
+
+# ------------------- other networks' layer shapes (MobileNet, AlexNet, NIN) -------------------
+def _dw_check(C, H, k, stride, pad, batch, seed, true_zero=True, W=None):
+    rng = np.random.default_rng(seed)
+    W = H if W is None else W
+    x = rng.standard_normal((batch, C, H, W)).astype(np.float32)
+    w = (rng.standard_normal((C, k * k)) * 0.3).astype(np.float32)
+    dw = wl.twn_threshold(w, axis=0)
+    da = wl.twn_threshold(x)
+    aw = rng.uniform(0.5, 1.5, C).astype(np.float32)
+    bw = rng.uniform(-0.2, 0.2, C).astype(np.float32)
+    bs = rng.uniform(0.5, 1.5, C).astype(np.float32)
+    bh = rng.normal(0, 0.1, C).astype(np.float32)
+    aa, ba = np.float32(1.2), np.float32(0.15)
+    ta = orc.ternarize(x, -da, da)
+    tw = orc.ternarize(w, -dw, dw)
+    D, y = orc.dwconv(ta, tw.reshape(C, k, k), stride, pad, aa, ba, aw, bw, true_zero, relu=True, bn_scale=bs, bn_shift=bh)
+    ca, _ = B.ternarize_pack(T.dev(x), float(-da), float(da), want_sum=False)
+    cw, _ = B.ternarize_pack(T.dev(w), T.dev(-dw), T.dev(dw), want_sum=False)      # rows: one filter per row
+    ep = B.Epilogue(float(aa), float(ba), T.dev(aw), T.dev(bw), None, None, relu=True, bn_scale=T.dev(bs), bn_shift=T.dev(bh))
+    pm = B.RTN_PAD_TRUE_ZERO if true_zero else B.RTN_PAD_CODE_ZERO
+    acc = torch.full(D.shape, -7777, dtype=torch.int32, device=T.DEV)
+    yy = torch.full(D.shape, float("nan"), dtype=torch.float32, device=T.DEV)
+    B.ternary_depthwise_conv2d(ca, cw, batch, C, H, W, k, k, stride, pad, pm, ep=ep, acc_out=acc, y_out=yy)
+    torch.cuda.synchronize()
+    assert (acc.cpu().numpy() == D).all()
+    T.assert_y_close(yy.cpu().numpy(), y, "depthwise y")
+
+
+@pytest.mark.parametrize("C,H,k,stride,pad,batch", [(5, 9, 3, 1, 1, 2), (64, 12, 3, 1, 1, 3), (66, 11, 3, 2, 1, 3),
+                                                     (130, 7, 3, 1, 1, 5), (32, 10, 5, 1, 2, 2), (16, 6, 1, 1, 0, 4),
+                                                     (3, 2, 3, 1, 1, 1)])
+def test_depthwise_conv_vs_oracle(C, H, k, stride, pad, batch):
+    _say("depthwise conv C=%d H=%d k=%d s=%d p=%d" % (C, H, k, stride, pad))
+    _dw_check(C, H, k, stride, pad, batch, seed=C + H, true_zero=True)
+    _dw_check(C, H, k, stride, pad, batch, seed=C + H + 1, true_zero=False, W=H + 3)
+
+
+@pytest.mark.parametrize("C,H,stride", [(32, 112, 1), (64, 112, 2), (128, 56, 1), (256, 28, 2), (512, 14, 1), (1024, 7, 1)])
+def test_mobilenet_depthwise_layers(C, H, stride):
+    """MobileNet's 3x3 depthwise layer shapes (batch 4 here)."""
+    _say("mobilenet depthwise %d@%d s%d" % (C, H, stride))
+    _dw_check(C, H, 3, stride, 1, 4, seed=C)
+
+
+OTHER_NET_CONVS = [
+    # MobileNet pointwise (1x1) layers, AlexNet's 5x5 and 3x3 layers (first layer stays fp32), NIN's 5x5 / 1x1
+    wl.ConvShape("mobilenet.pw.64x128@56", 64, 56, 128, 1, 1, 0),
+    wl.ConvShape("mobilenet.pw.512x512@14", 512, 14, 512, 1, 1, 0),
+    wl.ConvShape("mobilenet.pw.1024x1024@7", 1024, 7, 1024, 1, 1, 0),
+    wl.ConvShape("alexnet.conv2.5x5", 96, 27, 256, 5, 1, 2),
+    wl.ConvShape("alexnet.conv3.3x3", 256, 13, 384, 3, 1, 1),
+    wl.ConvShape("alexnet.conv4.3x3", 384, 13, 384, 3, 1, 1),
+    wl.ConvShape("nin.conv2.5x5", 96, 16, 192, 5, 1, 2),
+    wl.ConvShape("nin.cccp.1x1", 192, 16, 160, 1, 1, 0),
+    wl.ConvShape("nin.conv3.3x3", 192, 8, 192, 3, 1, 1),
+]
+
+
+@pytest.mark.parametrize("shape", OTHER_NET_CONVS, ids=lambda s: s.name)
+def test_other_networks_conv_layers(shape):
+    """Layer shapes of the other networks of the paper's tables through the ternary conv, on
+    both matrix paths (batch 4)."""
+    _say("other nets %s" % (shape,))
+    case = wl.conv_case(shape, batch=4, seed=len(shape.name), per_channel=True, bn=True)
+    ref = T.oracle_conv(case, True, relu=True)
+    for fmt in (B.RTN_CODE_FP4, B.RTN_CODE_I8):
+        got = T.hip_conv(case, True, relu=True, fmt=fmt)
+        assert (got["D"].cpu().numpy() == ref["D"]).all()
+        T.assert_y_close(got["y"].cpu().numpy(), ref["y"], shape.name)
