@@ -1462,3 +1462,69 @@ def test_other_networks_conv_layers(shape):
         got = T.hip_conv(case, True, relu=True, fmt=fmt)
         assert (got["D"].cpu().numpy() == ref["D"]).all()
         T.assert_y_close(got["y"].cpu().numpy(), ref["y"], shape.name)
+
+
+# ------------------------------------------ guard bytes around every output buffer ------
+def test_outputs_stay_inside_their_buffers():
+    """Ragged problems with every output carved out of a larger poisoned allocation: the guard
+    regions before and after each output must be untouched (pack, GEMM, conv on both matrix
+    paths, ternarizing conv, depthwise conv)."""
+    _say("guard regions around outputs")
+    G = 4096
+
+    def carve(shape, dtype, fill):
+        n = int(np.prod(shape))
+        esz = torch.empty(0, dtype=dtype).element_size()
+        raw = torch.full((n * esz + 2 * G,), 0x5A, dtype=torch.uint8, device=T.DEV)
+        view = raw[G:G + n * esz].view(dtype).view(*shape)
+        view.fill_(fill)
+        return raw, view
+
+    def check(raw, what):
+        r = raw.cpu().numpy()
+        assert (r[:G] == 0x5A).all() and (r[-G:] == 0x5A).all(), what + ": wrote outside its buffer"
+
+    shape = wl.ConvShape("g", 70, 9, 77, 3, 1, 1)
+    case = wl.conv_case(shape, batch=3, seed=5, bn=True, Wx=11)
+    x, w = T.dev(case["x"]), T.dev(case["w"])
+    dw = np.asarray(case["delta_w"])
+    for fmt in (B.RTN_CODE_FP4, B.RTN_CODE_I8):
+        rowb = B.padded_k(70, fmt) // (2 if fmt == B.RTN_CODE_FP4 else 1)
+        cdt = torch.uint8 if fmt == B.RTN_CODE_FP4 else torch.int8
+        rc, codes = carve((3, 9, 11, rowb), cdt, 0)
+        rs, sums = carve((3, 9, 11), torch.int32, 0)
+        B.ternarize_pack(x, -float(case["delta_a"]), float(case["delta_a"]), fmt, codes=codes, sum_t=sums)
+        cw, pw = B.ternarize_pack(w, T.thr_arg(-dw), T.thr_arg(dw), fmt)
+        ep = B.Epilogue(T.gran_arg(case["alpha_a"]), T.gran_arg(case["beta_a"]), T.gran_arg(case["alpha_w"]),
+                        T.gran_arg(case["beta_w"]), sums, pw, relu=True, bn_scale=T.dev(case["bn_scale"]),
+                        bn_shift=T.dev(case["bn_shift"]))
+        ra, acc = carve((3, 77, 9, 11), torch.int32, 0)
+        ry, y = carve((3, 77, 9, 11), torch.float32, 0.0)
+        B.ternary_conv2d(codes, cw, 3, 70, 9, 11, 77, 3, 3, 1, 1, ep=ep, acc_out=acc, want_acc=True, y_out=y, fmt=fmt)
+        orow = B.padded_k(77, fmt) // (2 if fmt == B.RTN_CODE_FP4 else 1)
+        rz, zc = carve((3, 9, 11, orow), cdt, 0)
+        ry2, y2 = carve((3, 77, 9, 11), torch.float32, 0.0)
+        B.ternary_conv2d_ternarize(codes, cw, 3, 70, 9, 11, 77, 3, 3, 1, 1, ep, -0.4, 0.6, codes_out=zc, residual=y,
+                                   relu_out=True, y_out=y2, fmt=fmt)
+        torch.cuda.synchronize()
+        for raw, what in ((rc, "pack codes"), (rs, "pack sums"), (ra, "conv acc"), (ry, "conv y"), (rz, "codes out"),
+                          (ry2, "block-tail y")):
+            check(raw, "%s (format %d)" % (what, fmt))
+        g = wl.gemm_case(131, 77, 200, seed=3)
+        ca, sa = B.ternarize_pack(T.dev(g["xa"]), -0.5, 0.5, fmt)
+        cb, sb = B.ternarize_pack(T.dev(g["xw"]), -0.5, 0.5, fmt)
+        epg = B.Epilogue(T.dev(g["alpha_a"]), T.dev(g["beta_a"]), T.dev(g["alpha_w"]), T.dev(g["beta_w"]), sa, sb)
+        rga, gacc = carve((131, 77), torch.int32, 0)
+        rgy, gy = carve((131, 77), torch.float32, 0.0)
+        B.ternary_gemm(ca, cb, 131, 77, 200, fmt=fmt, ep=epg, acc_out=gacc, want_acc=True, y_out=gy)
+        torch.cuda.synchronize()
+        check(rga, "gemm acc"), check(rgy, "gemm y")
+    ca8, _ = B.ternarize_pack(x, -0.5, 0.5, want_sum=False)
+    wd = T.dev((np.random.default_rng(1).standard_normal((70, 9)) * 0.3).astype(np.float32))
+    cwd, _ = B.ternarize_pack(wd, -0.2, 0.2, want_sum=False)
+    rd, dacc = carve((3, 70, 9, 11), torch.int32, 0)
+    rdy, dy = carve((3, 70, 9, 11), torch.float32, 0.0)
+    epd = B.Epilogue(1.0, 0.1, 1.2, None, None, None)
+    B.ternary_depthwise_conv2d(ca8, cwd, 3, 70, 9, 11, 3, 3, 1, 1, ep=epd, acc_out=dacc, y_out=dy)
+    torch.cuda.synchronize()
+    check(rd, "depthwise acc"), check(rdy, "depthwise y")

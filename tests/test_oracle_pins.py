@@ -759,3 +759,17 @@ def test_depthwise_conv_equals_grouped_framework_conv_of_the_values(true_zero):
     D, y = orc.dwconv(np.array([[[[1]], [[-1]]]], np.int8), np.ones((2, 1, 1), np.int8), 1, 0, 1.0, 0.0, 1.0, None,
                       True, relu=True, bn_scale=np.array([2, 2], np.float32), bn_shift=np.array([0.5, 0.5], np.float32))
     assert D.ravel().tolist() == [1, -1] and y.ravel().tolist() == [2.5, 0.5]
+
+
+# ----------------------------------------------------------- sanitizer run ----
+def test_oracle_is_clean_under_address_and_undefined_behaviour_sanitizers(tmp_path):
+    """oracle/sanitize_check.c calls every oracle routine on exactly-sized heap buffers with
+    ragged shapes; built with -fsanitize=address,undefined it must finish without a report."""
+    import subprocess
+    src = os.path.join(os.path.dirname(GOLD), "..", "oracle", "sanitize_check.c")
+    exe = str(tmp_path / "sanitize_check")
+    subprocess.check_call(["gcc", "-O1", "-g", "-fsanitize=address,undefined", "-fno-sanitize-recover=all",
+                           "-fopenmp", "-o", exe, src, "-lm"])
+    env = dict(os.environ, ASAN_OPTIONS="detect_leaks=0", OMP_NUM_THREADS="4")
+    out = subprocess.run([exe], env=env, stdout=subprocess.PIPE, stderr=subprocess.STDOUT, text=True, timeout=120)
+    assert out.returncode == 0 and "sanitize_check ok" in out.stdout, out.stdout[-2000:]
