@@ -99,6 +99,7 @@ typedef int v4i __attribute__((ext_vector_type(4)));
 typedef int v8i __attribute__((ext_vector_type(8)));
 typedef int v16i __attribute__((ext_vector_type(16)));
 typedef float v16f __attribute__((ext_vector_type(16)));
+typedef float v4f __attribute__((ext_vector_type(4)));
 typedef __bf16 v8bf __attribute__((ext_vector_type(8)));
 
 // 16 zero bytes every out-of-image tap reads from.
@@ -452,9 +453,22 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
     // bytes), i.e. of the Q fragments this lane multiplies anyway: 4 byte-sum dot
     // products per fragment, added up beside the MFMAs.  A lane holds half of a
     // row's bytes (the other k-chunks sit in lane ^ 32); the halves meet in the epilogue.
-    int sa_part[TQ], sa_neg[TQ];  // DT = 2: signed and unsigned sums of the nibbles
+    // FP4 codes: the row sums come from the matrix cores as well, which have cycles to spare
+    // while the vector ALU does not: one 16x16x128 FP4 MFMA per Q fragment with a constant
+    // operand of +1 codes.  That instruction reads lane l's 16 bytes as row l & 15, k-block
+    // l >> 4, whereas the fragment holds pixel l & 31, k-chunk l >> 5: k-blocks 0 and 2 are
+    // the two chunks of pixel l & 15, k-blocks 1 and 3 those of pixel 16 + (l & 15).  With
+    // ones in row 0 over k-blocks 0, 2 and in row 1 over k-blocks 1, 3, output row 0 is the
+    // sum of pixels 0..15 and row 1 that of pixels 16..31 (registers 0 and 1 of lanes 0..15).
+    int sa_part[TQ];
+    v4f sa_acc[DT == 2 ? TQ : 1];
 #pragma unroll
-    for (int j = 0; j < TQ; ++j) sa_part[j] = sa_neg[j] = 0;
+    for (int j = 0; j < TQ; ++j) sa_part[j] = 0;
+#pragma unroll
+    for (int j = 0; j < (DT == 2 ? TQ : 1); ++j) sa_acc[j] = v4f{0.f, 0.f, 0.f, 0.f};
+    const int sa_ones = ((lane & 15) < 2 && ((lane >> 4) & 1) == (lane & 15)) ? 0x22222222 : 0;
+    const v8i SA8 = {sa_ones, sa_ones, sa_ones, sa_ones, 0, 0, 0, 0};
+    (void)SA8;
     using AccV = std::conditional_t<DT != 0, v16f, v16i>;
     AccV acc[TP][TQ];
 #pragma unroll
@@ -484,6 +498,8 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
                 const v8i A8 = {pa[0], pa[1], pa[2], pa[3], 0, 0, 0, 0}, B8 = {pb[0], pb[1], pb[2], pb[3], 0, 0, 0, 0};
                 acc[n / TQ][n % TQ] = __builtin_amdgcn_mfma_scale_f32_32x32x64_f8f6f4(A8, B8, acc[n / TQ][n % TQ], 4, 4, 0,
                                                                                       0, 0, 0);
+                if (CONV && n < TQ)
+                    sa_acc[n] = __builtin_amdgcn_mfma_scale_f32_16x16x128_f8f6f4(SA8, B8, sa_acc[n], 4, 4, 0, 0, 0, 0);
             } else
                 acc[n / TQ][n % TQ] = __builtin_amdgcn_mfma_i32_32x32x32_i8(fa[ks][n / TQ], fb[ks][n % TQ],
                                                                             acc[n / TQ][n % TQ], 0, 0, 0);
@@ -505,19 +521,6 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
             for (int j = 0; j < TQ; ++j)
 #pragma unroll
                 for (int e = 0; e < 4; ++e) sa_part[j] = __builtin_amdgcn_sdot4(fb[ks][j][e], 0x01010101, sa_part[j], false);
-        }
-        if (CONV && DT == 2) {
-            // FP4 nibbles read as 4-bit integers: +1 (0x2) is 2 signed and unsigned, -1 (0xA) is
-            // -6 signed and 10 unsigned.  Two 8-way nibble dot products per dword accumulate
-            // S = 2 pos - 6 neg and U = 2 pos + 10 neg; the epilogue solves for pos - neg.
-#pragma unroll
-            for (int j = 0; j < TQ; ++j)
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const unsigned w = (unsigned)fb[ks][j][e];
-                    sa_part[j] = __builtin_amdgcn_sdot8((int)w, 0x11111111, sa_part[j], false);
-                    sa_neg[j] = (int)__builtin_amdgcn_udot8(w, 0x11111111u, (unsigned)sa_neg[j], false);
-                }
         }
     };
     const std::true_type yes{};
@@ -792,12 +795,13 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
         int sa_full[TQ];
 #pragma unroll
         for (int j = 0; j < TQ; ++j) {
-            int mine = sa_part[j];
-            if (DT == 2) {
-                const int neg = (sa_neg[j] - sa_part[j]) >> 4, pos = (sa_part[j] + 6 * neg) >> 1;
-                mine = pos - neg;
+            if constexpr (DT == 2) {
+                const float s0 = __shfl(sa_acc[j][0], lane & 15, 64), s1 = __shfl(sa_acc[j][1], lane & 15, 64);
+                sa_full[j] = (int)((lane & 16) ? s1 : s0);
+            } else {
+                const int mine = sa_part[j];
+                sa_full[j] = mine + __shfl_xor(mine, 32, 64);
             }
-            sa_full[j] = mine + __shfl_xor(mine, 32, 64);
         }
         if constexpr (TERN) {
             // Ternarizing epilogue (Eq.1 / Eq.3 applied to the activation of Eq.9): the
