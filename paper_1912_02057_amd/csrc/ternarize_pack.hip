@@ -6,6 +6,7 @@
 // cross-lane adds).  They are HBM-bound: 4 B read per element, 1 B (int8) or
 // 0.25 B (two bit planes) written.
 #include <mutex>
+#include <type_traits>
 
 #include "rtn_kernels.h"
 
@@ -324,6 +325,135 @@ __global__ __launch_bounds__(256) void k_pack_nchw_i8_v4(PackArgs a)
     }
 }
 
+// ---- NCHW layout, the common case in straight-line form ------------------------
+// The kernel above spends more time in the vector ALU than in memory (bounds
+// selects and 64-bit address arithmetic per element).  This one is for tensors
+// where none of that is needed: H*W % 4 == 0, C a multiple of the block's channel
+// group CG = 64*SUBS, the whole tensor below 4 GiB (a lane's byte offset fits 32
+// bits and is added to a wave-uniform base, so a load costs no vector instruction
+// besides itself).  Same tiling and LDS image as above.  Per element: two
+// compares, two selects and an OR into the code word when the thresholds are
+// ordered (ORDERED: scalar thresholds, lo <= hi checked by the entry point, so
+// x > hi and x < lo exclude each other), else the subtract form.  The side sum is
+// taken from the packed words (SUM).  An FP4 row whose padding exceeds the last
+// group (C % 128 == 64) gets its zero half written directly.
+template <int LPR, bool FP4, bool SUM, bool ORDERED>
+__global__ __launch_bounds__(256) void k_pack_nchw_fast(PackArgs a)
+{
+    constexpr int SUBS = 64 / LPR, PB = 4 * LPR, SLOT = FP4 ? 8 : 16, NSLOT = 4 * SUBS, RB = SLOT * NSLOT;
+    constexpr int CG = 64 * SUBS;
+    constexpr int NW = FP4 ? 2 : 4;  // code words per pixel and lane
+    __shared__ __attribute__((aligned(16))) uint8_t tile[PB * RB];
+    __shared__ int part[SUM ? 4 * SUBS : 1][SUM ? PB : 1];
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int quad = lane % LPR, cblk = wave * SUBS + lane / LPR;
+    const int64_t total = a.N * a.HW;
+    const int64_t q0 = (int64_t)blockIdx.x * PB;
+    int64_t q = q0 + 4 * quad;
+    q = q < total ? q : total - 4;  // total % 4 == 0; lanes past the end redo the last quad, never stored
+    const int HW = (int)a.HW, K = (int)a.K;
+    const int n = (int)(q / HW), p = (int)(q - (int64_t)n * HW);
+    const float lo = thr(a.lo, n), hi = thr(a.hi, n);
+    const uint32_t off = (uint32_t)((((int64_t)n * K + cblk * 16) * HW + p) * 4);
+    const int ngroup = K / CG;
+    const int64_t valid = total - q0 < PB ? total - q0 : PB;
+    const int rowb = (int)(FP4 ? a.Kpad >> 1 : a.Kpad);
+    uint8_t* out = (uint8_t*)a.codes + q0 * rowb;
+    int sum[4] = {0, 0, 0, 0}, usum[4] = {0, 0, 0, 0};
+    (void)usum;
+    for (int cg = 0; cg < ngroup; ++cg) {
+        float4 v[16];
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const float* base = a.x + (int64_t)(cg * CG + j) * HW;  // wave-uniform
+            v[j] = *(const float4*)((const char*)base + off);
+        }
+        uint32_t w[4][NW];
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int k = 0; k < NW; ++k) w[i][k] = 0;
+#pragma unroll
+        for (int j = 0; j < 16; ++j) {
+            const float e[4] = {v[j].x, v[j].y, v[j].z, v[j].w};
+            const int sh = FP4 ? 4 * (j & 7) : 8 * (j & 3);
+            const uint32_t cp = (FP4 ? 0x2u : 0x01u) << sh, cn = (FP4 ? 0xAu : 0xFFu) << sh;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                uint32_t c;
+                if (ORDERED) {
+                    c = e[i] > hi ? cp : 0u;
+                    c = e[i] < lo ? cn : c;
+                } else {
+                    // t in {-1, 0, 1}: the int8 code is t's low byte, the FP4 code (t << 1) & 0xA
+                    c = ((uint32_t)tern(e[i], lo, hi) << (FP4 ? sh + 1 : sh)) & cn;
+                }
+                w[i][FP4 ? j >> 3 : j >> 2] |= c;
+            }
+        }
+        if (SUM) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+#pragma unroll
+                for (int k = 0; k < NW; ++k) {
+                    if (FP4) {
+                        sum[i] = __builtin_amdgcn_sdot8((int)w[i][k], 0x11111111, sum[i], false);
+                        usum[i] = (int)__builtin_amdgcn_udot8(w[i][k], 0x11111111u, (unsigned)usum[i], false);
+                    } else {
+                        sum[i] = __builtin_amdgcn_sdot4((int)w[i][k], 0x01010101, sum[i], false);
+                    }
+                }
+        }
+        if (cg > 0) __syncthreads();  // previous group fully streamed out
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            uint8_t* slot = tile + (4 * quad + i) * RB + (cblk ^ (quad & (NSLOT - 1))) * SLOT;
+            if (FP4)
+                *(uint2*)slot = make_uint2(w[i][0], w[i][1]);
+            else
+                *(uint4*)slot = make_uint4(w[i][0], w[i][1], w[i][2], w[i][3]);
+        }
+        __syncthreads();
+#pragma unroll
+        for (int k = 0; k < PB * NSLOT / 256; ++k) {
+            const int e = tid + 256 * k, px = e / NSLOT, pp = e % NSLOT;
+            const int logical = pp ^ ((px >> 2) & (NSLOT - 1));
+            const int cbyte = cg * RB + logical * SLOT;
+            if (px < valid) {
+                if (FP4)
+                    *(uint2*)(out + (size_t)px * rowb + cbyte) = *(const uint2*)(tile + e * SLOT);
+                else
+                    *(uint4*)(out + (size_t)px * rowb + cbyte) = *(const uint4*)(tile + e * SLOT);
+            }
+        }
+    }
+    // the zero codes behind the last group (FP4 rows are padded to 128 codes)
+    const int donebytes = ngroup * RB, padu = (rowb - donebytes) >> 4;  // 16-byte units per pixel
+    for (int e = tid; e < PB * padu; e += 256) {
+        const int px = e / padu, u = e - px * padu;
+        if (px < valid) *(uint4*)(out + (size_t)px * rowb + donebytes + 16 * u) = make_uint4(0, 0, 0, 0);
+    }
+    if (SUM) {
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            int t = sum[i];
+            if (FP4) {
+                // nibbles as integers: +1 is 2 signed and unsigned, -1 is -6 signed and 10 unsigned
+                const int neg = (usum[i] - sum[i]) >> 4, pos = (sum[i] + 6 * neg) >> 1;
+                t = pos - neg;
+            }
+            part[cblk][4 * quad + i] = t;
+        }
+        __syncthreads();
+        if (tid < valid && tid < PB) {
+            int s = 0;
+#pragma unroll
+            for (int b = 0; b < 4 * SUBS; ++b) s += part[b][tid];
+            a.sum_t[q0 + tid] = s;
+        }
+    }
+}
+
 // ---- NCHW layout, int8 codes, small images whose H*W is not a multiple of 4 ---
 // One 1024-thread block per image.  The image's C*H*W floats are one contiguous,
 // 16-byte aligned run (C*H*W % 4 == 0), read with 16-byte loads regardless of
@@ -493,6 +623,32 @@ hipError_t launch_pack_nchw_codes(const PackArgs& a, hipStream_t st)
                                            hipFuncAttributeMaxDynamicSharedMemorySize, 128 * 1024);
         if (e != hipSuccess) return e;
         attr_done = true;
+    }
+    if (a.HW % 4 == 0 && ((uintptr_t)a.x) % 16 == 0 && a.K % 64 == 0 && a.N * a.K * a.HW < ((int64_t)1 << 30)) {
+        // straight-line kernel; the widest pixel runs that still give every CU several blocks
+        const int64_t px = a.N * a.HW;
+        const int lpr = (a.K % 256 == 0 && px < 2048 * 256) ? 16 : (a.K % 128 == 0 && px < 4096 * 256) ? 32 : 64;
+        const bool ordered = !a.lo.ptr && !a.hi.ptr, sum = a.sum_t != nullptr;
+        const dim3 grid((unsigned)((px + 4 * lpr - 1) / (4 * lpr)));
+        auto go = [&](auto L, auto S, auto O) {
+            hipLaunchKernelGGL((k_pack_nchw_fast<decltype(L)::value, FP4, decltype(S)::value, decltype(O)::value>), grid,
+                               dim3(256), 0, st, a);
+        };
+        auto go2 = [&](auto L) {
+            using T = std::true_type;
+            using F = std::false_type;
+            if (sum)
+                ordered ? go(L, T{}, T{}) : go(L, T{}, F{});
+            else
+                ordered ? go(L, F{}, T{}) : go(L, F{}, F{});
+        };
+        if (lpr == 16)
+            go2(std::integral_constant<int, 16>{});
+        else if (lpr == 32)
+            go2(std::integral_constant<int, 32>{});
+        else
+            go2(std::integral_constant<int, 64>{});
+        return hipGetLastError();
     }
     if (a.HW % 4 == 0 && ((uintptr_t)a.x) % 16 == 0) {
         // widest pixel runs that still give every CU several blocks and one pass over
