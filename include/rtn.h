@@ -284,6 +284,35 @@ int rtn_ternary_weight_conv2d(const float *x, const void *w_codes, int64_t Nb, i
                               const float *bn_shift, float *y_out, void *workspace,
                               size_t workspace_bytes, void *stream);
 
+/* Weight side of the weight-only layer, done once per layer and off the timed path
+ * (the offline preparation of the weights the paper's "Inference" paragraph describes:
+ * everything that depends only on the trained filters is stored ahead of time).
+ *   rtn_weight_gemm_prepare: the codes [N][rtn_padded_k(K)] as bf16 values.
+ *   rtn_weight_conv2d_prepare: the codes [O][KH][KW][rtn_padded_k(C)] as bf16 values,
+ *   then the per-filter epilogue table (alpha_w and the BN affine; nullable BN as above).
+ * prepared: DEVICE, 16-byte aligned, at least rtn_weight_*_prepared_bytes(...) bytes;
+ * it is only read by the *_prepared calls below, so one buffer serves any number of
+ * calls, batch sizes and image sizes.  Those calls compute exactly what
+ * rtn_ternary_weight_gemm / rtn_ternary_weight_conv2d compute (same kernels, same
+ * bits); their workspace (same size functions as above) then holds only the split
+ * activations.  The conv takes alpha_w and the BN affine from the prepared table. */
+size_t rtn_weight_gemm_prepared_bytes(int64_t N, int64_t K);
+int rtn_weight_gemm_prepare(const void *w_codes, int64_t N, int64_t K, void *prepared,
+                            size_t prepared_bytes, void *stream);
+int rtn_ternary_weight_gemm_prepared(const float *x, const void *prepared, int64_t M, int64_t N,
+                                     int64_t K, const float *alpha_w, rtn_gran gran_w, int relu,
+                                     const float *bn_scale, const float *bn_shift, float *y_out,
+                                     void *workspace, size_t workspace_bytes, void *stream);
+size_t rtn_weight_conv2d_prepared_bytes(int64_t C, int64_t O, int KH, int KW, int pad);
+int rtn_weight_conv2d_prepare(const void *w_codes, int64_t C, int64_t O, int KH, int KW, int pad,
+                              const float *alpha_w, rtn_gran gran_w, const float *bn_scale,
+                              const float *bn_shift, void *prepared, size_t prepared_bytes,
+                              void *stream);
+int rtn_ternary_weight_conv2d_prepared(const float *x, const void *prepared, int64_t Nb, int64_t C,
+                                       int64_t H, int64_t W, int64_t O, int KH, int KW, int stride,
+                                       int pad, int relu, float *y_out, void *workspace,
+                                       size_t workspace_bytes, void *stream);
+
 /* Backward of the reparameterized ternary activation Abar^t = gamma*Q(Abar) + beta
  * (Section "Backward Update in Reparameterized Ternarization"), for n elements:
  *   grad_gamma_beta[0] = sum_i t_i * g_i,  grad_gamma_beta[1] = sum_i g_i      (Eq.6)

@@ -28,6 +28,8 @@ EXPORTS = ["rtn_status_string", "rtn_last_hip_error", "rtn_num_tile_configs", "r
            "rtn_ternary_conv2d_implicit_gemm", "rtn_ternary_conv2d_ternarize",
            "rtn_weight_gemm_workspace_bytes", "rtn_ternary_weight_gemm",
            "rtn_weight_conv2d_workspace_bytes", "rtn_ternary_weight_conv2d",
+           "rtn_weight_gemm_prepared_bytes", "rtn_weight_gemm_prepare", "rtn_ternary_weight_gemm_prepared",
+           "rtn_weight_conv2d_prepared_bytes", "rtn_weight_conv2d_prepare", "rtn_ternary_weight_conv2d_prepared",
            "rtn_activation_backward_workspace_bytes", "rtn_activation_backward",
            "rtn_activation_backward_static_max_n", "rtn_activation_backward_static", "rtn_weight_backward",
            "rtn_epilogue_reparam",
@@ -90,6 +92,19 @@ def lib():
         L.rtn_weight_gemm_workspace_bytes.argtypes = [i64, i64, i64]
         L.rtn_ternary_weight_gemm.restype = ci
         L.rtn_ternary_weight_gemm.argtypes = [vp, vp, i64, i64, i64, vp, ci, ci, vp, vp, vp, vp, C.c_size_t, vp]
+        L.rtn_weight_gemm_prepared_bytes.restype = C.c_size_t
+        L.rtn_weight_gemm_prepared_bytes.argtypes = [i64, i64]
+        L.rtn_weight_gemm_prepare.restype = ci
+        L.rtn_weight_gemm_prepare.argtypes = [vp, i64, i64, vp, C.c_size_t, vp]
+        L.rtn_ternary_weight_gemm_prepared.restype = ci
+        L.rtn_ternary_weight_gemm_prepared.argtypes = [vp, vp, i64, i64, i64, vp, ci, ci, vp, vp, vp, vp, C.c_size_t, vp]
+        L.rtn_weight_conv2d_prepared_bytes.restype = C.c_size_t
+        L.rtn_weight_conv2d_prepared_bytes.argtypes = [i64, i64, ci, ci, ci]
+        L.rtn_weight_conv2d_prepare.restype = ci
+        L.rtn_weight_conv2d_prepare.argtypes = [vp, i64, i64, ci, ci, ci, vp, ci, vp, vp, vp, C.c_size_t, vp]
+        L.rtn_ternary_weight_conv2d_prepared.restype = ci
+        L.rtn_ternary_weight_conv2d_prepared.argtypes = [vp, vp, i64, i64, i64, i64, i64, ci, ci, ci, ci, ci, vp, vp,
+                                                         C.c_size_t, vp]
         L.rtn_weight_conv2d_workspace_bytes.restype = C.c_size_t
         L.rtn_weight_conv2d_workspace_bytes.argtypes = [i64, i64, i64, i64, i64, ci, ci, ci]
         L.rtn_ternary_weight_conv2d.restype = ci
@@ -323,18 +338,30 @@ def ternary_conv2d_ternarize(a_codes, w_codes, Nb, Cc, H, W, O, KH, KW, stride, 
     return codes_out
 
 
+def weight_gemm_prepare(w_codes, N, K):
+    """Weight side of the weight-only GEMM, once per layer: returns the prepared buffer (cuda uint8)."""
+    prepared = torch.empty(lib().rtn_weight_gemm_prepared_bytes(N, K), dtype=torch.uint8, device=w_codes.device)
+    rc = lib().rtn_weight_gemm_prepare(C.c_void_p(w_codes.data_ptr()), N, K, C.c_void_p(prepared.data_ptr()),
+                                       prepared.numel(), _stream())
+    _check(rc, "rtn_weight_gemm_prepare")
+    return prepared
+
+
 def ternary_weight_gemm(x, w_codes, M, N, K, alpha_w, relu=False, bn_scale=None, bn_shift=None, y_out=None,
-                        workspace=None):
-    """Weight-only ternary GEMM: x cuda float32 [M,K], w_codes int8 [N,Kpad]; alpha_w python
-    float or cuda float32 [N].  Returns y float32 [M,N]."""
+                        workspace=None, prepared=None):
+    """Weight-only ternary GEMM: x cuda float32 [M,K], w_codes int8 [N,Kpad] (or None with
+    prepared = weight_gemm_prepare(...)); alpha_w python float or cuda float32 [N].
+    Returns y float32 [M,N]."""
     if y_out is None:
         y_out = torch.empty((M, N), dtype=torch.float32, device=x.device)
     if workspace is None:
         workspace = torch.empty(lib().rtn_weight_gemm_workspace_bytes(M, N, K), dtype=torch.uint8,
                                 device=x.device)
     ga = _Gran(alpha_w)
-    rc = lib().rtn_ternary_weight_gemm(
-        _dev(x, torch.float32), C.c_void_p(w_codes.data_ptr()), M, N, K, ga.ptr, ga.gran, int(bool(relu)),
+    fn = lib().rtn_ternary_weight_gemm if prepared is None else lib().rtn_ternary_weight_gemm_prepared
+    wsrc = w_codes if prepared is None else prepared
+    rc = fn(
+        _dev(x, torch.float32), C.c_void_p(wsrc.data_ptr()), M, N, K, ga.ptr, ga.gran, int(bool(relu)),
         None if bn_scale is None else _dev(bn_scale, torch.float32),
         None if bn_shift is None else _dev(bn_shift, torch.float32), _dev(y_out, torch.float32),
         C.c_void_p(workspace.data_ptr()), workspace.numel(), _stream())
@@ -342,10 +369,25 @@ def ternary_weight_gemm(x, w_codes, M, N, K, alpha_w, relu=False, bn_scale=None,
     return y_out
 
 
-def ternary_weight_conv2d(x, w_codes, O, KH, KW, stride, pad, alpha_w, relu=False, bn_scale=None,
-                          bn_shift=None, y_out=None, workspace=None):
+def weight_conv2d_prepare(w_codes, Cc, O, KH, KW, pad, alpha_w, bn_scale=None, bn_shift=None):
+    """Weight side of the weight-only conv, once per layer (bf16 weights + epilogue table)."""
+    prepared = torch.empty(lib().rtn_weight_conv2d_prepared_bytes(Cc, O, KH, KW, pad), dtype=torch.uint8,
+                           device=w_codes.device)
+    ga = _Gran(alpha_w)
+    rc = lib().rtn_weight_conv2d_prepare(
+        C.c_void_p(w_codes.data_ptr()), Cc, O, KH, KW, pad, ga.ptr, ga.gran,
+        None if bn_scale is None else _dev(bn_scale, torch.float32),
+        None if bn_shift is None else _dev(bn_shift, torch.float32), C.c_void_p(prepared.data_ptr()),
+        prepared.numel(), _stream())
+    _check(rc, "rtn_weight_conv2d_prepare")
+    return prepared
+
+
+def ternary_weight_conv2d(x, w_codes, O, KH, KW, stride, pad, alpha_w=None, relu=False, bn_scale=None,
+                          bn_shift=None, y_out=None, workspace=None, prepared=None):
     """conv form of the weight-only ternary layer: x cuda float32 [Nb,C,H,W], w_codes int8
-    [O,KH,KW,Cpad].  Returns y float32 [Nb,O,OH,OW]."""
+    [O,KH,KW,Cpad]; or w_codes None and prepared = weight_conv2d_prepare(...), which already
+    holds alpha_w and the BN affine.  Returns y float32 [Nb,O,OH,OW]."""
     Nb, Cc, H, W = x.shape
     OH, OW = conv_out_hw(H, W, KH, KW, stride, pad)
     if y_out is None:
@@ -353,6 +395,13 @@ def ternary_weight_conv2d(x, w_codes, O, KH, KW, stride, pad, alpha_w, relu=Fals
     if workspace is None:
         workspace = torch.empty(lib().rtn_weight_conv2d_workspace_bytes(Nb, Cc, H, W, O, KH, KW, pad),
                                 dtype=torch.uint8, device=x.device)
+    if prepared is not None:
+        rc = lib().rtn_ternary_weight_conv2d_prepared(
+            _dev(x, torch.float32), C.c_void_p(prepared.data_ptr()), Nb, Cc, H, W, O, KH, KW, stride, pad,
+            int(bool(relu)), _dev(y_out, torch.float32), C.c_void_p(workspace.data_ptr()), workspace.numel(),
+            _stream())
+        _check(rc, "rtn_ternary_weight_conv2d_prepared")
+        return y_out
     ga = _Gran(alpha_w)
     rc = lib().rtn_ternary_weight_conv2d(
         _dev(x, torch.float32), C.c_void_p(w_codes.data_ptr()), Nb, Cc, H, W, O, KH, KW, stride, pad, ga.ptr,

@@ -332,17 +332,17 @@ size_t rtn_weight_gemm_workspace_bytes(int64_t M, int64_t N, int64_t K)
     return (size_t)(3 * M + N) * (size_t)pad64(K) * 2u;
 }
 
-int rtn_ternary_weight_gemm(const float* x, const void* w_codes, int64_t M, int64_t N, int64_t K,
+static int weight_gemm_impl(const float* x, const void* w_codes, const void* prepared, int64_t M, int64_t N, int64_t K,
                             const float* alpha_w, rtn_gran gran_w, int relu, const float* bn_scale,
                             const float* bn_shift, float* y_out, void* workspace, size_t workspace_bytes,
                             void* stream)
 {
-    if (!x || !w_codes || !alpha_w || !y_out) return RTN_ERR_NULL;
+    if (!x || (!w_codes && !prepared) || !alpha_w || !y_out) return RTN_ERR_NULL;
     if (bn_shift && !bn_scale) return RTN_ERR_NULL;
     if (M <= 0 || N <= 0 || K <= 0 || M > kMaxDim || N > kMaxDim || K > kMaxK) return RTN_ERR_SHAPE;
     // the three bf16 terms of a row sit side by side: 6 * Kpad bytes per row must stay below 2^31
     if (3 * pad64(K) * 2 * 256 > kMaxDim || M * pad64(K) > (int64_t)1 << 40) return RTN_ERR_SHAPE;
-    if (!aligned(x, 4) || !aligned(w_codes, 16) || !aligned(y_out, 4) || !aligned(bn_scale, 4) ||
+    if (!aligned(x, 4) || !aligned(w_codes, 16) || !aligned(prepared, 16) || !aligned(y_out, 4) || !aligned(bn_scale, 4) ||
         !aligned(bn_shift, 4))
         return RTN_ERR_ALIGN;
     rtn::WGemmArgs a = {};
@@ -360,8 +360,45 @@ int rtn_ternary_weight_gemm(const float* x, const void* w_codes, int64_t M, int6
     a.M = M, a.N = N, a.K = K, a.Kpad = pad64(K);
     a.y = y_out;
     a.workspace = workspace;
+    a.prepared = prepared;
     const hipError_t he = rtn::launch_wgemm(a, (hipStream_t)stream);
     return he == hipSuccess ? RTN_OK : hip_fail(he);
+}
+
+int rtn_ternary_weight_gemm(const float* x, const void* w_codes, int64_t M, int64_t N, int64_t K,
+                            const float* alpha_w, rtn_gran gran_w, int relu, const float* bn_scale,
+                            const float* bn_shift, float* y_out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!w_codes) return RTN_ERR_NULL;
+    return weight_gemm_impl(x, w_codes, nullptr, M, N, K, alpha_w, gran_w, relu, bn_scale, bn_shift, y_out, workspace,
+                            workspace_bytes, stream);
+}
+
+size_t rtn_weight_gemm_prepared_bytes(int64_t N, int64_t K)
+{
+    if (N <= 0 || K <= 0 || N > kMaxDim || K > kMaxK) return 0;
+    return (size_t)N * (size_t)pad64(K) * 2u;
+}
+
+int rtn_weight_gemm_prepare(const void* w_codes, int64_t N, int64_t K, void* prepared, size_t prepared_bytes,
+                            void* stream)
+{
+    if (!w_codes || !prepared) return RTN_ERR_NULL;
+    if (N <= 0 || K <= 0 || N > kMaxDim || K > kMaxK) return RTN_ERR_SHAPE;
+    if (!aligned(w_codes, 16) || !aligned(prepared, 16)) return RTN_ERR_ALIGN;
+    if (prepared_bytes < rtn_weight_gemm_prepared_bytes(N, K)) return RTN_ERR_WORKSPACE;
+    const hipError_t he = rtn::launch_wgemm_prepare((const int8_t*)w_codes, N, pad64(K), prepared, (hipStream_t)stream);
+    return he == hipSuccess ? RTN_OK : hip_fail(he);
+}
+
+int rtn_ternary_weight_gemm_prepared(const float* x, const void* prepared, int64_t M, int64_t N, int64_t K,
+                                     const float* alpha_w, rtn_gran gran_w, int relu, const float* bn_scale,
+                                     const float* bn_shift, float* y_out, void* workspace, size_t workspace_bytes,
+                                     void* stream)
+{
+    if (!prepared) return RTN_ERR_NULL;
+    return weight_gemm_impl(x, nullptr, prepared, M, N, K, alpha_w, gran_w, relu, bn_scale, bn_shift, y_out, workspace,
+                            workspace_bytes, stream);
 }
 
 size_t rtn_weight_conv2d_workspace_bytes(int64_t Nb, int64_t C, int64_t H, int64_t W, int64_t O, int KH, int KW,
@@ -375,12 +412,12 @@ size_t rtn_weight_conv2d_workspace_bytes(int64_t Nb, int64_t C, int64_t H, int64
            rtn_conv2d_workspace_bytes(O, KH, KW, pad);
 }
 
-int rtn_ternary_weight_conv2d(const float* x, const void* w_codes, int64_t Nb, int64_t C, int64_t H, int64_t W,
+static int weight_conv_impl(const float* x, const void* w_codes, const void* prepared, int64_t Nb, int64_t C, int64_t H, int64_t W,
                               int64_t O, int KH, int KW, int stride, int pad, const float* alpha_w,
                               rtn_gran gran_w, int relu, const float* bn_scale, const float* bn_shift,
                               float* y_out, void* workspace, size_t workspace_bytes, void* stream)
 {
-    if (!x || !w_codes || !alpha_w || !y_out) return RTN_ERR_NULL;
+    if (!x || (!w_codes && !prepared) || (!alpha_w && !prepared) || !y_out) return RTN_ERR_NULL;
     if (bn_shift && !bn_scale) return RTN_ERR_NULL;
     rtn::WConvArgs a = {};
     int rc = make_geom(Nb, C, H, W, O, KH, KW, stride, pad, RTN_PAD_TRUE_ZERO, a.g);
@@ -388,11 +425,11 @@ int rtn_ternary_weight_conv2d(const float* x, const void* w_codes, int64_t Nb, i
     // three planes of K bytes each are walked by 32-bit offsets
     if (3 * (int64_t)a.g.Cpad * 2 * KH * KW > kMaxK || Nb * H * W * (int64_t)a.g.Cpad > (int64_t)1 << 36)
         return RTN_ERR_SHAPE;
-    if (!aligned(x, 4) || !aligned(w_codes, 16) || !aligned(y_out, 4) || !aligned(bn_scale, 4) ||
+    if (!aligned(x, 4) || !aligned(w_codes, 16) || !aligned(prepared, 16) || !aligned(y_out, 4) || !aligned(bn_scale, 4) ||
         !aligned(bn_shift, 4))
         return RTN_ERR_ALIGN;
     if (gran_w != RTN_SCALAR && gran_w != RTN_VECTOR) return RTN_ERR_UNSUPPORTED;
-    if ((rc = make_param(alpha_w, gran_w, false, a.ep.alpha_w)) != RTN_OK) return rc;
+    if (!prepared && (rc = make_param(alpha_w, gran_w, false, a.ep.alpha_w)) != RTN_OK) return rc;
     if (!workspace || workspace_bytes < rtn_weight_conv2d_workspace_bytes(Nb, C, H, W, O, KH, KW, pad))
         return RTN_ERR_WORKSPACE;
     if (!aligned(workspace, 16)) return RTN_ERR_ALIGN;
@@ -404,8 +441,57 @@ int rtn_ternary_weight_conv2d(const float* x, const void* w_codes, int64_t Nb, i
     a.w = (const int8_t*)w_codes;
     a.y = y_out;
     a.workspace = workspace;
+    a.prepared = prepared;
     const hipError_t he = rtn::launch_wconv(a, (hipStream_t)stream);
     return he == hipSuccess ? RTN_OK : hip_fail(he);
+}
+
+int rtn_ternary_weight_conv2d(const float* x, const void* w_codes, int64_t Nb, int64_t C, int64_t H, int64_t W,
+                              int64_t O, int KH, int KW, int stride, int pad, const float* alpha_w,
+                              rtn_gran gran_w, int relu, const float* bn_scale, const float* bn_shift,
+                              float* y_out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!w_codes) return RTN_ERR_NULL;
+    return weight_conv_impl(x, w_codes, nullptr, Nb, C, H, W, O, KH, KW, stride, pad, alpha_w, gran_w, relu, bn_scale,
+                            bn_shift, y_out, workspace, workspace_bytes, stream);
+}
+
+size_t rtn_weight_conv2d_prepared_bytes(int64_t C, int64_t O, int KH, int KW, int pad)
+{
+    rtn::ConvGeom g = {};
+    if (make_geom(1, C, KH, KW, O, KH, KW, 1, pad, RTN_PAD_TRUE_ZERO, g) != RTN_OK) return 0;
+    return (size_t)O * KH * KW * (size_t)pad64(C) * 2u + 16u + rtn_conv2d_workspace_bytes(O, KH, KW, pad);
+}
+
+int rtn_weight_conv2d_prepare(const void* w_codes, int64_t C, int64_t O, int KH, int KW, int pad,
+                              const float* alpha_w, rtn_gran gran_w, const float* bn_scale, const float* bn_shift,
+                              void* prepared, size_t prepared_bytes, void* stream)
+{
+    if (!w_codes || !alpha_w || !prepared) return RTN_ERR_NULL;
+    if (bn_shift && !bn_scale) return RTN_ERR_NULL;
+    rtn::ConvGeom g = {};
+    int rc = make_geom(1, C, KH, KW, O, KH, KW, 1, pad, RTN_PAD_TRUE_ZERO, g);
+    if (rc != RTN_OK) return rc;
+    if (!aligned(w_codes, 16) || !aligned(prepared, 16) || !aligned(bn_scale, 4) || !aligned(bn_shift, 4))
+        return RTN_ERR_ALIGN;
+    if (gran_w != RTN_SCALAR && gran_w != RTN_VECTOR) return RTN_ERR_UNSUPPORTED;
+    if (prepared_bytes < rtn_weight_conv2d_prepared_bytes(C, O, KH, KW, pad)) return RTN_ERR_WORKSPACE;
+    rtn::EpiArgs ep = {};
+    if ((rc = make_param(alpha_w, gran_w, false, ep.alpha_w)) != RTN_OK) return rc;
+    ep.alpha_a.s = 1.0f;
+    ep.bn_scale = bn_scale;
+    ep.bn_shift = bn_shift;
+    const hipError_t he = rtn::launch_wconv_prepare((const int8_t*)w_codes, g, ep, prepared, (hipStream_t)stream);
+    return he == hipSuccess ? RTN_OK : hip_fail(he);
+}
+
+int rtn_ternary_weight_conv2d_prepared(const float* x, const void* prepared, int64_t Nb, int64_t C, int64_t H,
+                                       int64_t W, int64_t O, int KH, int KW, int stride, int pad, int relu,
+                                       float* y_out, void* workspace, size_t workspace_bytes, void* stream)
+{
+    if (!prepared) return RTN_ERR_NULL;
+    return weight_conv_impl(x, nullptr, prepared, Nb, C, H, W, O, KH, KW, stride, pad, nullptr, RTN_SCALAR, relu, nullptr,
+                            nullptr, y_out, workspace, workspace_bytes, stream);
 }
 
 size_t rtn_activation_backward_workspace_bytes(int64_t n)

@@ -140,8 +140,11 @@ struct WGemmArgs {
     float* y;          // [M][N]
     void* workspace;   // (3 M + N) * Kpad bf16
     EpiArgs ep;        // alpha_a = 1, beta_a = 0, beta_w = 0; alpha_w, relu, bn as given
+    const void* prepared;  // nullable: the weights as bf16, written by launch_wgemm_prepare (then w is unused)
 };
 hipError_t launch_wgemm(const WGemmArgs& a, hipStream_t st);
+// weight side of the above, once per layer: int8 codes [N][Kpad] -> bf16 [N][Kpad]
+hipError_t launch_wgemm_prepare(const int8_t* w, int64_t N, int64_t Kpad, void* prepared, hipStream_t st);
 
 // conv form: x fp32 NCHW, w int8 [O][KH][KW][Cpad] (g.Cpad in elements), y fp32 NCHW;
 // workspace: 3 activation planes + weights as bf16, then the epilogue table
@@ -152,8 +155,12 @@ struct WConvArgs {
     float* y;
     void* workspace;
     EpiArgs ep;
+    const void* prepared;  // nullable: bf16 weights + epilogue table, written by launch_wconv_prepare
 };
 hipError_t launch_wconv(const WConvArgs& a, hipStream_t st);
+// weight side of the above, once per layer (g: C, Cpad, O, KH, KW, pad are read): bf16
+// weights [O][KH][KW][Cpad], then (16-byte aligned) the epilogue table
+hipError_t launch_wconv_prepare(const int8_t* w, const ConvGeom& g, const EpiArgs& ep, void* prepared, hipStream_t st);
 hipError_t launch_conv_mfma(const ConvArgs& a, hipStream_t st);
 // Tile configuration override for tuning and tests (-1 = heuristic).
 int tile_config_count();

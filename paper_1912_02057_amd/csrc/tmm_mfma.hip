@@ -248,22 +248,33 @@ __global__ __launch_bounds__(256) void k_split_nchw_bf16x3(const float* x, int64
     }
 }
 
+// table position behind wn bf16 weights
+static double* wconv_table(uint16_t* wb, int64_t wn) { return (double*)(((uintptr_t)(wb + wn) + 15) & ~(uintptr_t)15); }
+
+hipError_t launch_wconv_prepare(const int8_t* w, const ConvGeom& g0, const EpiArgs& ep, void* prepared, hipStream_t st)
+{
+    uint16_t* wb = (uint16_t*)prepared;
+    const int64_t wn = (int64_t)g0.O * g0.KH * g0.KW * g0.Cpad;
+    hipLaunchKernelGGL(k_codes_to_bf16, dim3((unsigned)((wn / 16 + 255) / 256)), dim3(256), 0, st, w, wn / 16, wb);
+    ConvArgs c = {};
+    c.g = g0;
+    c.ep = ep;
+    return launch_conv_class_consts(c, wconv_table(wb, wn), st);  // g1 = alpha_w, BN rows; the class constants are 0
+}
+
 hipError_t launch_wconv(const WConvArgs& a, hipStream_t st)
 {
     const ConvGeom& g0 = a.g;  // Cpad in elements here
     const int64_t npix = (int64_t)g0.Nb * g0.H * g0.W;
     const int64_t plane = npix * g0.Cpad;
     uint16_t* a3 = (uint16_t*)a.workspace;
-    uint16_t* wb = a3 + 3 * plane;
+    uint16_t* wb = a.prepared ? (uint16_t*)a.prepared : a3 + 3 * plane;
     const int64_t wn = (int64_t)g0.O * g0.KH * g0.KW * g0.Cpad;
-    double* tab = (double*)(((uintptr_t)(wb + wn) + 15) & ~(uintptr_t)15);
+    double* tab = wconv_table(wb, wn);
     hipLaunchKernelGGL(k_split_nchw_bf16x3, dim3((unsigned)((npix + 63) / 64), (unsigned)(g0.Cpad / 64)), dim3(256), 0,
                        st, a.x, (int64_t)g0.Nb, g0.C, g0.Cpad, g0.H * g0.W, plane, a3);
-    hipLaunchKernelGGL(k_codes_to_bf16, dim3((unsigned)((wn / 16 + 255) / 256)), dim3(256), 0, st, a.w, wn / 16, wb);
-    ConvArgs c = {};
-    c.g = g0;
-    c.ep = a.ep;
-    hipError_t e = launch_conv_class_consts(c, tab, st);  // g1 = alpha_w, BN rows; the class constants are 0
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess && !a.prepared) e = launch_wconv_prepare(a.w, g0, a.ep, wb, st);
     if (e != hipSuccess) return e;
     TmmParams prm = {};
     prm.g = g0;
@@ -294,15 +305,22 @@ hipError_t launch_wconv(const WConvArgs& a, hipStream_t st)
     return e;
 }
 
+hipError_t launch_wgemm_prepare(const int8_t* w, int64_t N, int64_t Kpad, void* prepared, hipStream_t st)
+{
+    const int64_t nw = N * Kpad / 16;
+    hipLaunchKernelGGL(k_codes_to_bf16, dim3((unsigned)((nw + 255) / 256)), dim3(256), 0, st, w, nw, (uint16_t*)prepared);
+    return hipGetLastError();
+}
+
 hipError_t launch_wgemm(const WGemmArgs& a, hipStream_t st)
 {
     uint16_t* a3 = (uint16_t*)a.workspace;
-    uint16_t* wb = a3 + (size_t)a.M * 3 * a.Kpad;
-    const int64_t na = a.M * a.Kpad / 8, nw = a.N * a.Kpad / 16;
+    uint16_t* wb = a.prepared ? (uint16_t*)a.prepared : a3 + (size_t)a.M * 3 * a.Kpad;
+    const int64_t na = a.M * a.Kpad / 8;
     hipLaunchKernelGGL(k_split_bf16x3, dim3((unsigned)((na + 255) / 256)), dim3(256), 0, st, a.x, a.M, (int)a.K,
                        (int)a.Kpad, a3);
-    hipLaunchKernelGGL(k_codes_to_bf16, dim3((unsigned)((nw + 255) / 256)), dim3(256), 0, st, a.w, nw, wb);
     hipError_t e = hipGetLastError();
+    if (e == hipSuccess && !a.prepared) e = launch_wgemm_prepare(a.w, a.N, a.Kpad, wb, st);
     if (e != hipSuccess) return e;
     TmmParams prm = {};
     prm.P = (const int8_t*)a3;

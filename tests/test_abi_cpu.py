@@ -253,6 +253,47 @@ def test_weight_conv_rejects(L):
     assert with_(_17=ODD) == B.RTN_ERR_ALIGN
 
 
+def test_weight_prepare_rejects(L):
+    a1 = _f(1.0)
+    assert L.rtn_weight_gemm_prepared_bytes(8, 65) == 8 * 128 * 2
+    assert L.rtn_weight_gemm_prepared_bytes(0, 64) == 0
+    gp = L.rtn_weight_gemm_prepare
+    assert gp(None, 8, 64, FAKE, 1 << 20, None) == B.RTN_ERR_NULL
+    assert gp(FAKE, 8, 64, None, 1 << 20, None) == B.RTN_ERR_NULL
+    assert gp(FAKE, 0, 64, FAKE, 1 << 20, None) == B.RTN_ERR_SHAPE
+    assert gp(ODD, 8, 64, FAKE, 1 << 20, None) == B.RTN_ERR_ALIGN
+    assert gp(FAKE, 8, 64, FAKE, 8 * 64 * 2 - 1, None) == B.RTN_ERR_WORKSPACE
+    run = L.rtn_ternary_weight_gemm_prepared
+    assert run(FAKE, None, 8, 8, 64, a1, B.RTN_SCALAR, 0, None, None, FAKE, FAKE, 1 << 20, None) == B.RTN_ERR_NULL
+    assert run(FAKE, ODD, 8, 8, 64, a1, B.RTN_SCALAR, 0, None, None, FAKE, FAKE, 1 << 20, None) == B.RTN_ERR_ALIGN
+    assert run(FAKE, FAKE, 8, 8, 64, a1, B.RTN_SCALAR, 0, None, None, FAKE, FAKE, 100, None) == B.RTN_ERR_WORKSPACE
+    pb = L.rtn_weight_conv2d_prepared_bytes
+    assert pb(64, 64, 3, 3, 1) == 64 * 9 * 64 * 2 + 16 + L.rtn_conv2d_workspace_bytes(64, 3, 3, 1)
+    assert pb(64, 64, 3, 3, 3) == 0
+    cp = L.rtn_weight_conv2d_prepare
+    ok = [FAKE, 64, 64, 3, 3, 1, a1, B.RTN_SCALAR, None, None, FAKE, 1 << 24, None]
+
+    def with_(**kw):
+        a = list(ok)
+        for i, v in kw.items():
+            a[int(i[1:])] = v
+        return cp(*a)
+    assert with_(_0=None) == B.RTN_ERR_NULL
+    assert with_(_6=None) == B.RTN_ERR_NULL                     # alpha_w
+    assert with_(_10=None) == B.RTN_ERR_NULL
+    assert with_(_9=FAKE) == B.RTN_ERR_NULL                     # bn_shift without bn_scale
+    assert with_(_5=3) == B.RTN_ERR_UNSUPPORTED                 # pad >= kernel
+    assert with_(_0=ODD) == B.RTN_ERR_ALIGN
+    assert with_(_7=5) == B.RTN_ERR_UNSUPPORTED
+    assert with_(_11=100) == B.RTN_ERR_WORKSPACE
+    crun = L.rtn_ternary_weight_conv2d_prepared
+    okr = [FAKE, FAKE, 1, 64, 8, 8, 64, 3, 3, 1, 1, 0, FAKE, FAKE, 1 << 24, None]
+    assert crun(*okr[:1], None, *okr[2:]) == B.RTN_ERR_NULL
+    assert crun(*okr[:12], None, *okr[13:]) == B.RTN_ERR_NULL   # y_out
+    assert crun(*okr[:1], ODD, *okr[2:]) == B.RTN_ERR_ALIGN
+    assert crun(*okr[:14], 100, None) == B.RTN_ERR_WORKSPACE
+
+
 def test_weight_backward_rejects(L):
     call = L.rtn_weight_backward
     lo, hi = _f(-0.5), _f(0.5)

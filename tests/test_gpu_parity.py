@@ -1118,7 +1118,12 @@ def _wgemm_check(M, N, K, seed, vector_alpha=True, relu=False, bn=False, rows=No
     y = B.ternary_weight_gemm(T.dev(x), cw, M, N, K, T.thr_arg(aw), relu=relu,
                               bn_scale=None if bs is None else T.dev(bs),
                               bn_shift=None if bh is None else T.dev(bh))
+    # the same call with the weight side prepared ahead of time: same kernels, same bits
+    y2 = B.ternary_weight_gemm(T.dev(x), None, M, N, K, T.thr_arg(aw), relu=relu,
+                               bn_scale=None if bs is None else T.dev(bs),
+                               bn_shift=None if bh is None else T.dev(bh), prepared=B.weight_gemm_prepare(cw, N, K))
     torch.cuda.synchronize()
+    assert torch.equal(y, y2), "prepared weight-only GEMM differs from the one-call form"
     y = y.cpu().numpy()
     sel = np.arange(M) if rows is None else rows
     ref = orc.wgemm(x[sel], tw, aw, relu=relu, bn_scale=bs, bn_shift=bh).astype(np.float64)
@@ -1201,7 +1206,13 @@ def _wconv_check(shape, batch, seed, relu=False, bn=False, Wx=None, images=None,
     y = B.ternary_weight_conv2d(T.dev(x), cw, shape.O, shape.k, shape.k, shape.stride, shape.pad, T.dev(aw),
                                 relu=relu, bn_scale=None if bs is None else T.dev(bs),
                                 bn_shift=None if bh is None else T.dev(bh))
+    prep = B.weight_conv2d_prepare(cw, shape.C, shape.O, shape.k, shape.k, shape.pad, T.dev(aw),
+                                   bn_scale=None if bs is None else T.dev(bs),
+                                   bn_shift=None if bh is None else T.dev(bh))
+    y2 = B.ternary_weight_conv2d(T.dev(x), None, shape.O, shape.k, shape.k, shape.stride, shape.pad, relu=relu,
+                                 prepared=prep)
     torch.cuda.synchronize()
+    assert torch.equal(y, y2), "prepared weight-only conv differs from the one-call form"
     y = y.cpu().numpy()
     sel = list(range(batch)) if images is None else images
     ref = orc.wconv(x[sel], tw, shape.stride, shape.pad, aw, relu=relu, bn_scale=bs, bn_shift=bh).astype(np.float64)
