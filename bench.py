@@ -28,8 +28,13 @@ INT8_PEAK_TOPS = 5000.0   # MI355X dense int8 MFMA, TOP/s (2 ops per MAC)
 FP4_PEAK_TFLOPS = 10100.0  # MI355X dense FP4 MFMA (the path the FP4 code storage runs on)
 BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA
 HBM_PEAK_GBS = 8000.0
-# rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE on this file's default run (see profiles/)
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 129.6e6
+# HBM bytes per k_tmm launch of the default run (FP4 codes, batch 256): rocprofv3 --pmc FETCH_SIZE and
+# WRITE_SIZE passes summarised in profiles/k_tmm_conv_resnet18_b256.md, (2 * FETCH_SIZE + WRITE_SIZE) KiB
+# averaged over the 19 launches of a step.  Measured 2026-11-28 on the kernels of commit 6a61329 (the
+# conv's loads and stores have not changed since); a constant, not a live reading: the counters need the
+# profiler.  It only applies to the default format, batch and tile choice.
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = 109.3e6
+MEASURED_TRAFFIC_STAMP = "rocprofv3 FETCH_SIZE/WRITE_SIZE, 2026-11-28, kernels of commit 6a61329"
 
 
 def main():
@@ -823,7 +828,7 @@ def main():
         alg_bytes_launch = tot_bytes_conv / nlaunch
         achieved_gbs = tot_bytes_conv / conv_total_s / 1e9
         traffic = None
-        if args.batch == 256 and args.tile < 0:
+        if args.batch == 256 and args.tile < 0 and args.format == "fp4":
             # HBM bytes per k_tmm launch from the FETCH_SIZE / WRITE_SIZE counter passes
             # summarised in profiles/k_tmm_conv_resnet18_b256.md (2 * FETCH_SIZE + WRITE_SIZE,
             # in KiB per dispatch, averaged over the 19 launches of a step)
@@ -831,6 +836,7 @@ def main():
         roofline = dict(bound="hbm", kernel="k_tmm (%s MFMA implicit-GEMM conv + fused epilogue)" % args.format,
                         achieved=round(achieved_gbs, 1), peak=HBM_PEAK_GBS, unit="GB/s",
                         frac=round(achieved_gbs / HBM_PEAK_GBS, 4), traffic=traffic,
+                        traffic_source=MEASURED_TRAFFIC_STAMP if traffic else None,
                         launches_per_step=nlaunch, avg_launch_us=round(conv_total_s / nlaunch * 1e6, 1),
                         bytes_per_launch=round(alg_bytes_launch, 0),
                         mfma_tops=round(achieved_tops, 1), mfma_frac=round(achieved_tops / INT8_PEAK_TOPS, 4))
