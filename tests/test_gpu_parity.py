@@ -116,6 +116,35 @@ def test_pack_nchw(shape, per_lead):
     assert (s3.cpu().numpy() == orc.pixel_sums(t)).all()
 
 
+@pytest.mark.parametrize("shape", [(3, 192, 12, 12), (2, 320, 8, 8), (6, 256, 6, 6), (2, 64, 30, 30),
+                                   (7, 128, 2, 2), (1, 1024, 4, 4)])
+def test_pack_nchw_straight_line_kernel(shape):
+    """The NCHW pack's straight-line kernel (H*W % 4 == 0, C % 64 == 0) in its four forms: with and
+    without the side sum, scalar (ordered) thresholds and per-image ones, one of which has lo > hi
+    (x between them is then +1 and -1 at once, i.e. 0)."""
+    _say("pack_nchw straight-line %s" % (shape,))
+    rng = np.random.default_rng(11 + sum(shape))
+    x = rng.standard_normal(shape).astype(np.float32)
+    x.flat[5] = np.nan
+    x.flat[6] = np.inf
+    x.flat[7] = -np.inf
+    hi_v = rng.uniform(0.1, 1.0, shape[0]).astype(np.float32)
+    lo_v = -hi_v
+    lo_v[-1], hi_v[-1] = np.float32(0.3), np.float32(-0.2)          # unordered pair on the last image
+    x[:, 0, 0, 0] = hi_v
+    xd = T.dev(x)
+    for lo, hi in ((np.float32(-0.9), np.float32(0.4)), (lo_v, hi_v)):
+        t = orc.ternarize(x, lo, hi)
+        nhwc = orc.nchw_to_nhwc_i8(t, shape[1])
+        for fmt in (B.RTN_CODE_FP4, B.RTN_CODE_I8):
+            want = T.fp4_rows(nhwc) if fmt == B.RTN_CODE_FP4 else orc.nchw_to_nhwc_i8(t, (shape[1] + 63) // 64 * 64)
+            codes, s = B.ternarize_pack(xd, T.thr_arg(lo), T.thr_arg(hi), fmt)
+            assert (codes.cpu().numpy() == want).all()
+            assert (s.cpu().numpy() == orc.pixel_sums(t)).all()
+            codes2, s2 = B.ternarize_pack(xd, T.thr_arg(lo), T.thr_arg(hi), fmt, want_sum=False)
+            assert s2 is None and (codes2.cpu().numpy() == want).all()
+
+
 # ------------------------------------------------------ S2 + S4: GEMM -------
 GEMM_SHAPES = [(1, 1, 1), (37, 19, 131), (64, 64, 64), (65, 33, 64), (300, 200, 576), (129, 257, 1000),
                (512, 384, 2048), (1024, 1024, 512)]
