@@ -205,6 +205,7 @@ struct DwConvArgs {
     int32_t* acc;
     float* y;
     EpiArgs ep;
+    int tiles_per_block;  // set by launch_dwconv: consecutive pixel tiles a block of the 3 x 3 kernel walks
 };
 hipError_t launch_dwconv(const DwConvArgs& a, hipStream_t st);
 
