@@ -1459,6 +1459,13 @@ def _dw_check(C, H, k, stride, pad, batch, seed, true_zero=True, W=None):
     torch.cuda.synchronize()
     assert (acc.cpu().numpy() == D).all()
     T.assert_y_close(yy.cpu().numpy(), y, "depthwise y")
+    # one output at a time (the kernel then keeps one tile instead of two): same bits
+    acc2 = torch.full(D.shape, -7777, dtype=torch.int32, device=T.DEV)
+    y2 = torch.full(D.shape, float("nan"), dtype=torch.float32, device=T.DEV)
+    B.ternary_depthwise_conv2d(ca, cw, batch, C, H, W, k, k, stride, pad, pm, acc_out=acc2)
+    B.ternary_depthwise_conv2d(ca, cw, batch, C, H, W, k, k, stride, pad, pm, ep=ep, y_out=y2)
+    torch.cuda.synchronize()
+    assert torch.equal(acc, acc2) and torch.equal(yy, y2)
 
 
 @pytest.mark.parametrize("C,H,k,stride,pad,batch", [(5, 9, 3, 1, 1, 2), (64, 12, 3, 1, 1, 3), (66, 11, 3, 2, 1, 3),
@@ -1475,6 +1482,14 @@ def test_mobilenet_depthwise_layers(C, H, stride):
     """MobileNet's 3x3 depthwise layer shapes (batch 4 here)."""
     _say("mobilenet depthwise %d@%d s%d" % (C, H, stride))
     _dw_check(C, H, 3, stride, 1, 4, seed=C)
+
+
+@pytest.mark.parametrize("C,H,stride,batch", [(512, 14, 1, 256), (128, 56, 1, 96), (32, 112, 1, 40)])
+def test_depthwise_layers_at_bench_sizes(C, H, stride, batch):
+    """Sizes at which a block of the 3x3 kernel walks several pixel tiles and, for the two
+    larger ones, the fp32 output is stored with the non-temporal hint (above 128 MiB)."""
+    _say("depthwise at size %d@%d s%d batch %d" % (C, H, stride, batch))
+    _dw_check(C, H, 3, stride, 1, batch, seed=C + batch)
 
 
 OTHER_NET_CONVS = [
