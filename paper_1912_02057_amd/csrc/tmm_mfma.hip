@@ -387,6 +387,13 @@ hipError_t launch_conv_mfma(const ConvArgs& a, hipStream_t st)
     // the block-tail epilogue prefetches its residual values only for the tiles with
     // 64 accumulators per lane: prefer 128x128 over 128x256 there
     if (tail && g_forced_tile < 0 && cfg == 13) cfg = 12;
+    // FP4 block tails, from a sweep over all configurations on the ResNet-18 shapes: the pixel-run
+    // tile with the whole 9-step weight slab resident (123.5 against 126.9 us on the 64-filter
+    // layers), and the two-stage 128 x 128 ring on the 512-filter layers (40.6 against 42.4 us)
+    if (tail && a.fp4 && g_forced_tile < 0) {
+        if (cfg == 15 && prm.nk <= 9) cfg = 14;
+        if (cfg == 1 && nblocks(g.O, prm.RQ, 128, 128) >= 256) cfg = 12;
+    }
     if (a.fp4) return tail ? launch_index<true, 2, 2>(cfg, prm, st) : launch_index<true, 1, 2>(cfg, prm, st);
     return tail ? launch_index<true, 2>(cfg, prm, st) : launch_index<true, 1>(cfg, prm, st);
 }
