@@ -700,7 +700,11 @@ __device__ __forceinline__ double wave_sum(double v)
     return v;
 }
 
-template <bool VEC>
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+
+// NT: the gradient tensor is stored with the non-temporal hint (tensors above 128 MiB, which
+// the memory-side cache cannot keep for the next kernel anyway)
+template <bool VEC, bool NT = false>
 __global__ __launch_bounds__(256) void k_act_backward(ActBwdArgs p)
 {
     __shared__ double red[2][4];
@@ -722,7 +726,12 @@ __global__ __launch_bounds__(256) void k_act_backward(ActBwdArgs p)
                 const float4 a = *(const float4*)(p.a + e), g = *(const float4*)(p.g + e);
                 float4 d;
                 one(a.x, g.x, d.x), one(a.y, g.y, d.y), one(a.z, g.z, d.z), one(a.w, g.w, d.w);
-                if (p.da) *(float4*)(p.da + e) = d;
+                if (p.da) {
+                    if (NT)
+                        __builtin_nontemporal_store(f32x4{d.x, d.y, d.z, d.w}, (f32x4*)(p.da + e));
+                    else
+                        *(float4*)(p.da + e) = d;
+                }
             } else {
                 for (int64_t k = e; k < p.n; ++k) {
                     float d;
@@ -837,7 +846,9 @@ hipError_t launch_act_backward(const ActBwdArgs& p, hipStream_t st)
 {
     const int64_t nb = act_backward_blocks(p.n);
     const bool vec = (((uintptr_t)p.a | (uintptr_t)p.g | (uintptr_t)p.da) & 15) == 0;
-    if (vec)
+    if (vec && p.da && p.n * 4 > ((int64_t)128 << 20))
+        hipLaunchKernelGGL((k_act_backward<true, true>), dim3((unsigned)nb), dim3(256), 0, st, p);
+    else if (vec)
         hipLaunchKernelGGL(k_act_backward<true>, dim3((unsigned)nb), dim3(256), 0, st, p);
     else
         hipLaunchKernelGGL(k_act_backward<false>, dim3((unsigned)nb), dim3(256), 0, st, p);
