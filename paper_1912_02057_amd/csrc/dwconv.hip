@@ -252,9 +252,12 @@ __global__ __launch_bounds__(256) void k_dwconv3(DwConvArgs a)
     for (int tt = 0; tt < a.tiles_per_block; ++tt) {
     const int64_t m0 = ((int64_t)blockIdx.x * a.tiles_per_block + tt) * PXB;
     if (m0 >= total) break;  // block-uniform
-    // ---- phase 0: per-pixel preparation ---------------------------------------------------
-    if (tid < PXB) {
-        int64_t m = m0 + tid;
+    // ---- phase 0: per-pixel preparation, the nine taps of a pixel dealt out over the block's
+    // wave groups (so that the work spreads over the CU's four SIMDs) -----------------------
+    {
+        constexpr int PARTS = 256 / PXB;
+        const int px = tid % PXB, part = tid / PXB;
+        int64_t m = m0 + px;
         m = m < total ? m : total - 1;  // pixels past the end repeat the last one; never stored
         const int nb = (int)fastdiv((uint32_t)m, g.div_ohw), pix = (int)(m - (int64_t)nb * ohw);
         const int oh = (int)fastdiv((uint32_t)pix, g.div_ow), ow = pix - oh * g.OW;
@@ -267,17 +270,20 @@ __global__ __launch_bounds__(256) void k_dwconv3(DwConvArgs a)
         }
         // a tap outside the image gets an offset past the end of the buffer: the buffer load
         // returns 0 for it (no clamping, no masking of the loaded word)
+        const unsigned corner = (unsigned)(((nb * g.H + ih0) * g.W + iw0) * g.Cpad);
 #pragma unroll
         for (int t = 0; t < 9; ++t) {
+            if (t % PARTS != part) continue;
             const int kh = t / 3, kw = t % 3;
             const bool inb = ((rowin >> kh) & (colin >> kw) & 1u) != 0;
-            po[tid][t] = inb ? (unsigned)(((nb * g.H + ih0 + kh) * g.W + iw0 + kw) * g.Cpad) : 0x80000000u;
+            po[px][t] = inb ? corner + (unsigned)((kh * g.W + kw) * g.Cpad) : 0x80000000u;
         }
-        // pad <= 1: only the first or the last window row / column can be outside
-        const unsigned rc = ((rowin & 1u) ^ 1u) | (((rowin >> 2) & 1u) ^ 1u) << 1;
-        const unsigned cc = ((colin & 1u) ^ 1u) | (((colin >> 2) & 1u) ^ 1u) << 1;
-        const unsigned cls = g.code_zero_pad ? 0u : rc * 4u + cc;
-        pm[tid] = (int)cls;
+        if (part == 0) {
+            // pad <= 1: only the first or the last window row / column can be outside
+            const unsigned rc = ((rowin & 1u) ^ 1u) | (((rowin >> 2) & 1u) ^ 1u) << 1;
+            const unsigned cc = ((colin & 1u) ^ 1u) | (((colin >> 2) & 1u) ^ 1u) << 1;
+            pm[px] = (int)(g.code_zero_pad ? 0u : rc * 4u + cc);
+        }
     }
     __syncthreads();
     // ---- phase 1: 4 pixels x 4 channels per thread ---------------------------------------
