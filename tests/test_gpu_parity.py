@@ -1433,6 +1433,45 @@ def test_quaternary_extreme_sum_is_exact_on_the_fp4_path():
     assert (got.cpu().numpy() == 9 * K).all()
 
 
+@pytest.mark.parametrize("fmt", [B.RTN_CODE_FP4, B.RTN_CODE_I8], ids=["fp4", "i8"])
+def test_gemm_extreme_sums_at_the_maximum_k(fmt):
+    """K = 2^22, the largest the library accepts: accumulators of +-K, the largest magnitude there
+    is (on the FP4 path an fp32 sum of integers that must stay exact), and of 0 from full
+    cancellation.  Expected values are closed forms; the four-term output is compared with the
+    oracle's epilogue on those accumulators."""
+    _say("gemm at K = 2^22, fmt %d" % fmt)
+    K, M, N = 1 << 22, 64, 64
+    xa = torch.ones((M, K), dtype=torch.float32, device=T.DEV)
+    xa[1].fill_(-1.0)
+    xa[2, ::2] = -1.0                                    # alternating: sums to 0 against ones
+    xw = torch.ones((N, K), dtype=torch.float32, device=T.DEV)
+    xw[3].fill_(-1.0)
+    xw[5, 1::2] = 0.0                                    # every other weight zero
+    ca, sa = B.ternarize_pack(xa, -0.5, 0.5, fmt)
+    cw, sw = B.ternarize_pack(xw, -0.5, 0.5, fmt)
+    ra = np.full(M, K, np.int64); ra[1] = -K; ra[2] = 0                 # row sums of t_a
+    rw = np.full(N, K, np.int64); rw[3] = -K; rw[5] = K // 2            # row sums of t_w
+    assert (sa.cpu().numpy() == ra).all() and (sw.cpu().numpy() == rw).all()
+    D = np.empty((M, N), np.int64)
+    for m in range(M):
+        for n in range(N):
+            if m == 2:
+                # alternating signs cancel, except against the filter that keeps only the even taps
+                D[m, n] = -(K // 2) if n == 5 else 0
+            else:
+                base = K if n != 5 else K // 2
+                D[m, n] = base * (-1 if m == 1 else 1) * (-1 if n == 3 else 1)
+    aa, ba, aw, bw = np.float32(0.75), np.float32(-0.1), np.float32(1.25), np.float32(0.05)
+    ep = B.Epilogue(float(aa), float(ba), float(aw), float(bw), sa, sw)
+    acc = torch.empty((M, N), dtype=torch.int32, device=T.DEV)
+    y = torch.empty((M, N), dtype=torch.float32, device=T.DEV)
+    B.ternary_gemm(ca, cw, M, N, K, fmt=fmt, ep=ep, acc_out=acc, y_out=y)
+    torch.cuda.synchronize()
+    assert (acc.cpu().numpy() == D).all()
+    ref = orc.gemm_epilogue(D.astype(np.int32), K, ra.astype(np.int32), rw.astype(np.int32), aa, ba, aw, bw)
+    T.assert_y_close(y.cpu().numpy(), ref, "y at K = 2^22")
+
+
 # ------------------- other networks' layer shapes (MobileNet, AlexNet, NIN) -------------------
 def _dw_check(C, H, k, stride, pad, batch, seed, true_zero=True, W=None):
     rng = np.random.default_rng(seed)
