@@ -365,8 +365,7 @@ hipError_t launch_conv_mfma(const ConvArgs& a, hipStream_t st)
     // outputs beyond what stays in the memory-side cache take the non-temporal hint
     {
         const int64_t out_bytes = (int64_t)g.Nb * g.O * g.OH * g.OW * 4 * ((a.acc ? 1 : 0) + (a.y ? 1 : 0));
-        const char* force = getenv("RTN_CONV_NT");
-        prm.nt_out = force ? atoi(force) : out_bytes > (int64_t)128 << 20;
+        prm.nt_out = out_bytes > (int64_t)128 << 20;
     }
     int cfg = g_forced_tile >= 0 ? g_forced_tile : pick_tile(g.O, prm.RQ, true);
     // a 64-filter layer with a centred stride-1 window: the variant that keeps the
