@@ -328,22 +328,31 @@ __global__ __launch_bounds__(256, MINW) void k_tmm(TmmParams prm)
     const int8_t* zero_page = (const int8_t*)g_zero16;
 
     int64_t l_plane = 0;  // DT = 1 conv: byte offset of the activation plane being walked
+    int64_t l_koff = 0;   // conv: running byte offset of the step being issued within the window
+    const int64_t l_rowskip = CONV ? (int64_t)(g.W - g.KW) * g.Cpad : 0;
     auto issue_begin = [&](int kt) {
         is_sbase = lds0 + (unsigned)(roff + (kt % NS) * STAGE);
         is_koffP = (int64_t)kt * 64;
         if (CONV && DT == 1) is_koffP = (int64_t)((unsigned)is_koffP % prm.wwrap);
         if (CONV && !HALO) {
+            // byte offset of tap (kh, kw), channel chunk cc from a pixel's tap (0, 0):
+            // (kh W + kw) Cpad + cc, kept as a running sum (scalar multiplies in this loop cost
+            // matrix-core time): + 64 per step, which also carries over from the last chunk of a
+            // tap to the next tap of the row, and + (W - KW) Cpad at the end of a window row
             is_kh = l_kh;
             is_kw = l_kw;
-            is_koffQ = ((int64_t)l_kh * g.W + l_kw) * g.Cpad + l_cc + l_plane;
+            is_koffQ = l_koff + l_plane;
+            l_koff += 64;
             l_cc += 64;
             if (l_cc == g.Cpad) {
                 l_cc = 0;
                 if (++l_kw == g.KW) {
                     l_kw = 0;
                     ++l_kh;
+                    l_koff += l_rowskip;
                     if (DT == 1 && l_kh == g.KH) {
                         l_kh = 0;
+                        l_koff = 0;
                         l_plane += prm.qplane;
                     }
                 }
